@@ -1,0 +1,269 @@
+/*
+ * LASAD CPU oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, fp64 implementation of linear attention with Spatial-Aware
+ * Decay (SAD) written directly from the paper's Section 3.4 recurrence and
+ * Algorithm 1.  Only tests, the smoke check and the benchmark's CPU-baseline
+ * leg may call it; it shares no code with the HIP library and the HIP library
+ * never calls it.
+ *
+ * Reading used for the decay (one scalar base decay gamma_h per head, the
+ * "constant lambda" case of Section 3.3, with the row-boundary rule of
+ * Section 3.4 on top):
+ *     lambda_t = 1        if t is a row-boundary position
+ *              = gamma_h  otherwise,                 t = 1..N (1-indexed)
+ * where the paper's rule (Section 3.4, second equation; Algorithm 1) makes
+ * t a boundary when t mod w == 0 (the last token of a grid row).  Two other
+ * rules are selectable for comparison: boundary at the first token of a row
+ * ((t-1) mod w == 0) and no boundary at all (Section 3.3 plain decay).
+ *
+ * All tensors here are dense, fp64, in [B][Hh][n][d] order ("head-major");
+ * states are [B][Hh][dk][dv] with dv contiguous: S[i][j] = sum_t k_t[i] v_t[j].
+ *
+ * Every function below is pinned by the CPU test-suite against values fixed by
+ * the paper's equations (hand-worked recurrences, geometric-series closed
+ * forms, the gamma = 1 reduction to plain causal linear attention of
+ * Section 3.2, brute force); none is "parity unpinned".
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_RESET_LAST_COL = 0, ORACLE_RESET_FIRST_COL = 1, ORACLE_RESET_NONE = 2 };
+
+/* Section 3.4, second equation / Algorithm 1 "if (t mod w) = 0": is the
+ * 1-indexed raster position t one where the decay is switched off? */
+static int is_boundary(int64_t t, int grid_w, int mode)
+{
+    if (mode == ORACLE_RESET_LAST_COL)  return (t % grid_w) == 0;
+    if (mode == ORACLE_RESET_FIRST_COL) return ((t - 1) % grid_w) == 0;
+    return 0;
+}
+
+/*
+ * Decay table (Section 3.4 second equation, Algorithm 1 boundary branch).
+ *   lam_out[h*n + i]  = lambda of position t = start_pos + 1 + i for head h
+ *                       (the fp32 gamma copied unchanged, or exactly 1.0f)
+ *   cum_out[i]        = E(start_pos + i), i = 0..n, where E(t) counts the
+ *                       positions s in 1..t that are NOT boundaries, so that
+ *                       prod_{s=j+1..i} lambda_s = gamma^(E(i) - E(j)).
+ * E is obtained by literally walking t = 1, 2, ... and counting.
+ * Returns 0, or 1 on invalid arguments.
+ */
+int lasad_oracle_decay_factors(const float *gamma, int n_heads, int grid_h, int grid_w,
+                               int start_pos, int n, int mode,
+                               float *lam_out, int32_t *cum_out)
+{
+    if (!gamma || n_heads < 1 || grid_h < 1 || grid_w < 1 || start_pos < 0 || n < 0) return 1;
+    if ((int64_t)start_pos + n > (int64_t)grid_h * grid_w) return 1;
+    if (mode < 0 || mode > 2) return 1;
+    if (lam_out) {
+        for (int h = 0; h < n_heads; ++h)
+            for (int i = 0; i < n; ++i) {
+                int64_t t = (int64_t)start_pos + 1 + i;
+                lam_out[(size_t)h * n + i] = is_boundary(t, grid_w, mode) ? 1.0f : gamma[h];
+            }
+    }
+    if (cum_out) {
+        int32_t e = 0;
+        if (start_pos == 0) cum_out[0] = 0;
+        for (int64_t t = 1; t <= (int64_t)start_pos + n; ++t) {
+            if (!is_boundary(t, grid_w, mode)) e += 1;
+            if (t >= start_pos) cum_out[t - start_pos] = e;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Parallel ("full mask") form.  Unrolling s_t = lambda_t s_{t-1} + k_t v_t^T,
+ * o_t^T = q_t^T s_t (Section 3.4 first equation) gives
+ *     o_i = sum_{j<=i} M[i][j] (q_i . k_j) v_j,   M[i][j] = prod_{s=j+1..i} lambda_s
+ * with M[i][i] = 1 (empty product) and M[i][j] = 0 for j > i.  The full n x n
+ * M is materialised, then A = q_scale * Q K^T, P = A (.) M, O = P V.
+ *
+ * With a carried state S0 (the state after the tokens that precede this
+ * call) the recurrence adds  (prod_{s=first..i} lambda_s) q_i^T S0  to o_i and
+ *     S_out = (prod_{s=first..last} lambda_s) S0 + sum_j M[last][j] k_j v_j^T.
+ *
+ * lam is [Hh][n] (lambda of the n positions of this call), s0/s_out may be
+ * NULL.  Returns 0, 1 on bad arguments, 2 when out of memory.
+ */
+int lasad_oracle_forward_fullmask(const double *q, const double *k, const double *v,
+                                  const double *lam, double q_scale,
+                                  const double *s0, double *o, double *s_out,
+                                  int B, int n_heads, int n, int d)
+{
+    if (!q || !k || !v || !lam || !o || B < 1 || n_heads < 1 || n < 0 || d < 1) return 1;
+    int status = 0;
+    const int64_t n_seq = (int64_t)B * n_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < n_seq; ++bh) {
+        const int h = (int)(bh % n_heads);
+        const double *lm = lam + (size_t)h * n;
+        const double *Q = q + (size_t)bh * n * d, *K = k + (size_t)bh * n * d;
+        const double *V = v + (size_t)bh * n * d;
+        double *O = o + (size_t)bh * n * d;
+        double *M = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * (size_t)(n > 0 ? n : 1));
+        double *p = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        double *pre = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        if (!M || !p || !pre) {
+#pragma omp atomic write
+            status = 2;
+            free(M); free(p); free(pre);
+            continue;
+        }
+        /* M[i][j] = lambda_{j+1} * ... * lambda_i, multiplied in increasing s. */
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                double m;
+                if (j > i) m = 0.0;
+                else if (j == i) m = 1.0;
+                else m = M[(size_t)(i - 1) * n + j] * lm[i];
+                M[(size_t)i * n + j] = m;
+            }
+        /* pre[i] = lambda_first * ... * lambda_i : what multiplies S0 at step i. */
+        for (int i = 0; i < n; ++i) pre[i] = (i == 0 ? 1.0 : pre[i - 1]) * lm[i];
+
+        for (int i = 0; i < n; ++i) {
+            for (int j = 0; j < n; ++j) {            /* row i of P = (q_scale Q K^T) (.) M */
+                double a = 0.0;
+                for (int c = 0; c < d; ++c) a += Q[(size_t)i * d + c] * K[(size_t)j * d + c];
+                p[j] = (q_scale * a) * M[(size_t)i * n + j];
+            }
+            for (int c = 0; c < d; ++c) {            /* row i of O = P V */
+                double acc = 0.0;
+                for (int j = 0; j < n; ++j) acc += p[j] * V[(size_t)j * d + c];
+                O[(size_t)i * d + c] = acc;
+            }
+            if (s0) {                                /* carried-state term */
+                const double *S0 = s0 + (size_t)bh * d * d;
+                for (int c = 0; c < d; ++c) {
+                    double acc = 0.0;
+                    for (int r = 0; r < d; ++r) acc += Q[(size_t)i * d + r] * S0[(size_t)r * d + c];
+                    O[(size_t)i * d + c] += pre[i] * (q_scale * acc);
+                }
+            }
+        }
+        if (s_out) {
+            double *S = s_out + (size_t)bh * d * d;
+            for (int r = 0; r < d; ++r)
+                for (int c = 0; c < d; ++c) {
+                    double acc = 0.0;
+                    for (int j = 0; j < n; ++j)
+                        acc += M[(size_t)(n - 1) * n + j] * K[(size_t)j * d + r] * V[(size_t)j * d + c];
+                    if (s0) acc += (n > 0 ? pre[n - 1] : 1.0) * s0[(size_t)bh * d * d + (size_t)r * d + c];
+                    S[(size_t)r * d + c] = acc;
+                }
+        }
+        free(M); free(p); free(pre);
+    }
+    return status;
+}
+
+/*
+ * Sequential form: the loop of Algorithm 1 (recurrence lines only; the
+ * projections, activations and Norm of the surrounding layer are outside this
+ * path), state kept in fp64.  s_t = lambda_t s_{t-1} + k_t v_t^T, then
+ * o_t^T = q_scale * q_t^T s_t (the state that already contains token t).
+ * s0 NULL means s_0 = 0; s_out (may alias nothing else) receives s_n.
+ */
+int lasad_oracle_recurrent(const double *q, const double *k, const double *v,
+                           const double *lam, double q_scale,
+                           const double *s0, double *o, double *s_out,
+                           int B, int n_heads, int n, int d)
+{
+    if (!q || !k || !v || !lam || !o || B < 1 || n_heads < 1 || n < 0 || d < 1) return 1;
+    int status = 0;
+    const int64_t n_seq = (int64_t)B * n_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < n_seq; ++bh) {
+        const int h = (int)(bh % n_heads);
+        double *S = (double *)malloc(sizeof(double) * (size_t)d * d);
+        if (!S) {
+#pragma omp atomic write
+            status = 2;
+            continue;
+        }
+        if (s0) memcpy(S, s0 + (size_t)bh * d * d, sizeof(double) * (size_t)d * d);
+        else    memset(S, 0, sizeof(double) * (size_t)d * d);
+        for (int t = 0; t < n; ++t) {
+            const double l = lam[(size_t)h * n + t];
+            const double *qt = q + ((size_t)bh * n + t) * d;
+            const double *kt = k + ((size_t)bh * n + t) * d;
+            const double *vt = v + ((size_t)bh * n + t) * d;
+            double *ot = o + ((size_t)bh * n + t) * d;
+            for (int r = 0; r < d; ++r)
+                for (int c = 0; c < d; ++c)
+                    S[(size_t)r * d + c] = l * S[(size_t)r * d + c] + kt[r] * vt[c];
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < d; ++r) acc += qt[r] * S[(size_t)r * d + c];
+                ot[c] = q_scale * acc;
+            }
+        }
+        if (s_out) memcpy(s_out + (size_t)bh * d * d, S, sizeof(double) * (size_t)d * d);
+        free(S);
+    }
+    return status;
+}
+
+/*
+ * One decode step for every (batch, head): the body of Algorithm 1's loop for
+ * a single position whose decay is lam_t[h].  state [B][Hh][d][d] is updated
+ * in place; q, k, v, o are [B][Hh][d].
+ */
+int lasad_oracle_decode_step(const double *q, const double *k, const double *v,
+                             const double *lam_t, double q_scale,
+                             double *state, double *o, int B, int n_heads, int d)
+{
+    if (!q || !k || !v || !lam_t || !state || !o || B < 1 || n_heads < 1 || d < 1) return 1;
+    const int64_t n_seq = (int64_t)B * n_heads;
+#pragma omp parallel for schedule(static)
+    for (int64_t bh = 0; bh < n_seq; ++bh) {
+        const double l = lam_t[bh % n_heads];
+        double *S = state + (size_t)bh * d * d;
+        const double *qt = q + (size_t)bh * d, *kt = k + (size_t)bh * d, *vt = v + (size_t)bh * d;
+        for (int r = 0; r < d; ++r)
+            for (int c = 0; c < d; ++c)
+                S[(size_t)r * d + c] = l * S[(size_t)r * d + c] + kt[r] * vt[c];
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int r = 0; r < d; ++r) acc += qt[r] * S[(size_t)r * d + c];
+            o[(size_t)bh * d + c] = q_scale * acc;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Brute force for tiny inputs: every (i, j) pair separately, the decay
+ * product formed by its own loop over s = j+1..i, no table, no state.
+ * Single sequence (one batch, one head): q, k, v, o are [n][d], lam is [n].
+ */
+int lasad_oracle_bruteforce(const double *q, const double *k, const double *v,
+                            const double *lam, double q_scale, double *o, int n, int d)
+{
+    if (!q || !k || !v || !lam || !o || n < 0 || d < 1) return 1;
+    for (int i = 0; i < n; ++i)
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j <= i; ++j) {
+                double decay = 1.0;
+                for (int s = j + 1; s <= i; ++s) decay *= lam[s];
+                double dot = 0.0;
+                for (int r = 0; r < d; ++r) dot += q[(size_t)i * d + r] * k[(size_t)j * d + r];
+                acc += decay * (q_scale * dot) * v[(size_t)j * d + c];
+            }
+            o[(size_t)i * d + c] = acc;
+        }
+    return 0;
+}
+
+/* Threads the OpenMP loops above will use (reported by the benchmark). */
+#ifdef _OPENMP
+#include <omp.h>
+int lasad_oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int lasad_oracle_num_threads(void) { return 1; }
+#endif

@@ -1,0 +1,148 @@
+"""ctypes front-end of the LASAD CPU oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+module.  It compiles ``lasad_oracle.c`` with gcc (fp64, OpenMP, no BLAS) into
+``liblasad_oracle.so`` next to the source and marshals numpy arrays; every bit
+of arithmetic is in the C file.  It imports nothing from the HIP package.
+
+Array convention at this level: q, k, v, o are ``[B, n, Hh, d]`` (what a
+projection producing model width Hh*d yields, Algorithm 1 input X[B, N, D]);
+states are ``[B, Hh, d, d]`` with S[i, j] = sum_t k_t[i] v_t[j].
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lasad_oracle.c")
+_LIB = os.path.join(_HERE, "liblasad_oracle.so")
+
+RESET_LAST_COL, RESET_FIRST_COL, RESET_NONE = 0, 1, 2
+
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the C oracle (gcc -O2 -fopenmp).  Returns the library path.
+
+    With force=False an existing library is kept as it is (the loader's case:
+    it only compiles when nothing has been built yet)."""
+    if force or not os.path.exists(_LIB):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build(force=False))
+        dp = ctypes.POINTER(ctypes.c_double)
+        fp = ctypes.POINTER(ctypes.c_float)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        ci = ctypes.c_int
+        lib.lasad_oracle_decay_factors.argtypes = [fp, ci, ci, ci, ci, ci, ci, fp, ip]
+        lib.lasad_oracle_decay_factors.restype = ci
+        for name in ("lasad_oracle_forward_fullmask", "lasad_oracle_recurrent"):
+            f = getattr(lib, name)
+            f.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp, ci, ci, ci, ci]
+            f.restype = ci
+        lib.lasad_oracle_decode_step.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, ci, ci, ci]
+        lib.lasad_oracle_decode_step.restype = ci
+        lib.lasad_oracle_bruteforce.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, ci, ci]
+        lib.lasad_oracle_bruteforce.restype = ci
+        lib.lasad_oracle_num_threads.argtypes = []
+        lib.lasad_oracle_num_threads.restype = ci
+        _lib = lib
+    return _lib
+
+
+def _dptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64c(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def num_threads() -> int:
+    return int(_load().lasad_oracle_num_threads())
+
+
+def decay_factors(gamma, grid_h, grid_w, start_pos, n_tokens, mode=RESET_LAST_COL):
+    """Return (lam[Hh, n] float32, cum_exp[n+1] int32) for positions start_pos+1..start_pos+n."""
+    g = np.ascontiguousarray(np.asarray(gamma, dtype=np.float32))
+    lam = np.empty((g.shape[0], n_tokens), dtype=np.float32)
+    cum = np.empty((n_tokens + 1,), dtype=np.int32)
+    rc = _load().lasad_oracle_decay_factors(
+        g.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), g.shape[0], grid_h, grid_w,
+        start_pos, n_tokens, mode,
+        lam.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+        cum.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    if rc != 0:
+        raise ValueError(f"lasad_oracle_decay_factors: bad arguments (rc={rc})")
+    return lam, cum
+
+
+def _sequence_call(fn_name, q, k, v, lam, q_scale, s0, want_state):
+    q, k, v = (np.asarray(x, dtype=np.float64) for x in (q, k, v))
+    B, n, Hh, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape
+    lam = _f64c(lam)
+    assert lam.shape == (Hh, n), (lam.shape, (Hh, n))
+    # [B, n, Hh, d] -> [B, Hh, n, d]
+    qh, kh, vh = (np.ascontiguousarray(x.transpose(0, 2, 1, 3)) for x in (q, k, v))
+    oh = np.empty_like(qh)
+    s0c = None if s0 is None else _f64c(s0)
+    if s0c is not None:
+        assert s0c.shape == (B, Hh, d, d)
+    s_out = np.empty((B, Hh, d, d), dtype=np.float64) if want_state else None
+    rc = getattr(_load(), fn_name)(_dptr(qh), _dptr(kh), _dptr(vh), _dptr(lam), float(q_scale),
+                                   _dptr(s0c), _dptr(oh), _dptr(s_out), B, Hh, n, d)
+    if rc != 0:
+        raise RuntimeError(f"{fn_name} failed (rc={rc})")
+    o = np.ascontiguousarray(oh.transpose(0, 2, 1, 3))
+    return (o, s_out) if want_state else o
+
+
+def forward_fullmask(q, k, v, lam, q_scale=1.0, s0=None, want_state=False):
+    """O = (q_scale QK^T (.) M) V with the full n x n decay mask (plus carried-state terms)."""
+    return _sequence_call("lasad_oracle_forward_fullmask", q, k, v, lam, q_scale, s0, want_state)
+
+
+def recurrent(q, k, v, lam, q_scale=1.0, s0=None, want_state=False):
+    """The sequential recurrence of Algorithm 1 in fp64."""
+    return _sequence_call("lasad_oracle_recurrent", q, k, v, lam, q_scale, s0, want_state)
+
+
+def decode_step(q, k, v, lam_t, state, q_scale=1.0):
+    """One token for every (b, h).  q, k, v: [B, Hh, d]; state [B, Hh, d, d] fp64 updated IN PLACE."""
+    q, k, v = (_f64c(x) for x in (q, k, v))
+    B, Hh, d = q.shape
+    lam_t = _f64c(lam_t)
+    assert lam_t.shape == (Hh,)
+    assert state.dtype == np.float64 and state.flags.c_contiguous and state.shape == (B, Hh, d, d)
+    o = np.empty_like(q)
+    rc = _load().lasad_oracle_decode_step(_dptr(q), _dptr(k), _dptr(v), _dptr(lam_t), float(q_scale),
+                                          _dptr(state), _dptr(o), B, Hh, d)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_decode_step failed (rc={rc})")
+    return o
+
+
+def bruteforce(q, k, v, lam, q_scale=1.0):
+    """Per-pair sums for ONE sequence: q, k, v [n, d], lam [n]."""
+    q, k, v, lam = (_f64c(x) for x in (q, k, v, lam))
+    n, d = q.shape
+    assert lam.shape == (n,)
+    o = np.empty_like(q)
+    rc = _load().lasad_oracle_bruteforce(_dptr(q), _dptr(k), _dptr(v), _dptr(lam), float(q_scale),
+                                         _dptr(o), n, d)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_bruteforce failed (rc={rc})")
+    return o
