@@ -1,0 +1,142 @@
+/*
+ * liblasad -- linear attention with Spatial-Aware Decay (SAD) for AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Autoregressive Image Generation with Linear
+ * Complexity: A Spatial-Aware Decay Perspective" (LASAD): causal linear
+ * attention over an H x W grid of image tokens flattened in raster order, with a
+ * per-head base decay gamma_h that is switched off (factor 1) at row-boundary
+ * positions, so that the decay between two tokens follows their true
+ * (row, column) locations.
+ *
+ * Notation.  Grid H x W (the paper's h x w, Section 3.1), N = H*W, 1-indexed
+ * raster position t = r*W + c + 1 for 0-indexed row r and column c.  Head dim d
+ * (dk = dv = d; Section 3.4: s_t in R^{d x d}).  Per-head scalar base decay
+ * gamma_h in [0, 1] (the constant-lambda case of Section 3.3).
+ *
+ *   lambda_t = 1        if t is a boundary position of the chosen rule,
+ *            = gamma_h  otherwise                     (Section 3.4, 2nd equation;
+ *                                                      Algorithm 1 boundary branch)
+ *   s_t = lambda_t s_{t-1} + k_t v_t^T,   o_t^T = q_scale * q_t^T s_t
+ *                                                     (Section 3.4, 1st equation)
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers unless stated otherwise.  The caller
+ *    owns every buffer; the library allocates no device memory and keeps no
+ *    state between calls.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream).  No call synchronises; buffers must stay alive until
+ *    the stream has run the work.
+ *  - Return value: LASAD_OK or an error code.  Arguments are validated on the
+ *    host before anything is launched; nothing is launched on error.  A
+ *    human-readable reason is available from lasad_last_error().
+ *  - gfx950 only.  There is no CPU path.
+ */
+#ifndef LASAD_H
+#define LASAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LASAD_OK = 0,
+    LASAD_ERR_INVALID_ARG = 1,   /* null pointer, bad size, bad enum, misaligned pointer */
+    LASAD_ERR_UNSUPPORTED = 2,   /* valid request the library has no kernel for */
+    LASAD_ERR_WORKSPACE = 3,     /* workspace missing or smaller than the size query says */
+    LASAD_ERR_HIP = 4            /* the HIP runtime refused the launch */
+} lasad_status_t;
+
+typedef enum { LASAD_F32 = 0, LASAD_BF16 = 1 } lasad_dtype_t;
+
+/* Which positions get lambda_t = 1. */
+typedef enum {
+    LASAD_RESET_LAST_COL = 0,    /* the paper's rule: t mod W == 0, the last token of a row */
+    LASAD_RESET_FIRST_COL = 1,   /* (t-1) mod W == 0, the first token of a row            */
+    LASAD_RESET_NONE = 2         /* plain 1-D decay (Section 3.3), no boundary             */
+} lasad_boundary_t;
+
+/* Element strides of a [B, n_tokens, Hh, d] tensor; the stride of d is 1.
+ * [B, N, Hh, d] contiguous: {N*Hh*d, Hh*d, d};  [B, Hh, N, d] contiguous: {Hh*N*d, d, N*d}. */
+typedef struct {
+    int64_t stride_b;
+    int64_t stride_n;
+    int64_t stride_h;
+} lasad_layout_t;
+
+/*
+ * Decay table (Section 3.4, second equation; Algorithm 1 boundary branch).
+ *   gamma      [n_heads] fp32, device.
+ *   lambda_out [n_heads, n_tokens] fp32, device, or NULL: lambda_out[h, i] is the
+ *              factor of position t = start_pos + 1 + i: the bits of gamma[h]
+ *              copied unchanged, or exactly 1.0f.
+ *   cum_exp_out [n_tokens + 1] int32, device, or NULL: cum_exp_out[i] =
+ *              E(start_pos + i) where E(t) is the number of non-boundary positions
+ *              among 1..t, so that prod_{s=j+1..i} lambda_s = gamma^(E(i) - E(j)).
+ *   start_pos  tokens of the grid already consumed, 0 <= start_pos,
+ *              start_pos + n_tokens <= grid_h * grid_w.  n_tokens may be 0.
+ */
+int lasad_decay_factors(const float *gamma, int n_heads, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode,
+                        float *lambda_out, int32_t *cum_exp_out, void *hip_stream);
+
+/* Bytes of device workspace lasad_forward_chunked needs for these sizes (may be 0). */
+size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype);
+
+/*
+ * Chunked parallel forward (prefill / teacher-forced pass) over positions
+ * start_pos+1 .. start_pos+n_tokens of every (batch, head) sequence.  Computes
+ * exactly what the recurrence of Section 3.4 gives, chunk by chunk: inside a
+ * chunk the decay-masked (Q K^T (.) D) V product, across chunks a d x d state.
+ *
+ *   q, k, v   [B, n_tokens, n_heads, d] with strides `qkv_layout`, type io_dtype.
+ *   o         same logical shape with strides `o_layout`, type out_dtype; must not
+ *             alias q, k or v.
+ *   io_dtype  LASAD_F32 (then out_dtype must be LASAD_F32) or LASAD_BF16 (out_dtype
+ *             LASAD_BF16 or LASAD_F32).  Accumulation is fp32 in every case.
+ *   d         32, 64 or 128 (generic kernel); bf16 with d = 64 takes the MFMA kernel.
+ *   gamma     [n_heads] fp32, each in [0, 1].
+ *   state_in  [B, n_heads, d, d] fp32, S[i][j] = sum_t (decay) k_t[i] v_t[j] (dv
+ *             contiguous), the state after position start_pos; NULL means zeros.
+ *   state_out [B, n_heads, d, d] fp32 or NULL; may equal state_in.
+ *   workspace device scratch of at least lasad_forward_workspace_bytes(...) bytes;
+ *             may be NULL when that is 0.
+ * Pointers must be aligned to 16 bytes and strides multiples of 8 elements for the
+ * bf16 kernels (4 for fp32).  n_tokens may be 0 (then state_out = state_in).
+ */
+int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
+                          const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
+                          int io_dtype, int out_dtype,
+                          int B, int n_heads, int d, int grid_h, int grid_w,
+                          int start_pos, int n_tokens,
+                          const float *gamma, int boundary_mode, float q_scale,
+                          const float *state_in, float *state_out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Recurrent decode step (Algorithm 1 loop body; Section 3.4 first equation):
+ * one token for every (batch, head):  S <- lambda S + k v^T,  o = q_scale * S^T q
+ * with lambda = 1 if `pos` is a boundary position, else gamma[h].
+ *   q, k, v   [B, n_heads, d] contiguous, type io_dtype; o same shape, out_dtype.
+ *   pos       0-indexed raster index of THIS token (t = pos + 1), 0 <= pos < H*W.
+ *   state     [B, n_heads, d, d] fp32, dv contiguous, updated IN PLACE.
+ *   d         32, 64 or 128.
+ */
+int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
+                      int io_dtype, int out_dtype, int B, int n_heads, int d,
+                      int grid_h, int grid_w, int pos,
+                      const float *gamma, int boundary_mode, float q_scale,
+                      float *state, void *hip_stream);
+
+/* Reason for the last non-OK status returned on this thread (static storage). */
+const char *lasad_last_error(void);
+
+/* Library version string, e.g. "lasad 0.1 gfx950". */
+const char *lasad_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LASAD_H */

@@ -1,0 +1,193 @@
+"""Thin ctypes binding of liblasad's C ABI (see include/lasad.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch supplies device memory (``tensor.data_ptr()``) and the stream; there is
+no CPU fallback -- a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblasad.so")
+
+F32, BF16 = 0, 1
+RESET_LAST_COL, RESET_FIRST_COL, RESET_NONE = 0, 1, 2
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
+
+EXPORTS = (
+    "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
+    "lasad_decode_step", "lasad_last_error", "lasad_version",
+)
+
+
+class LasadError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"liblasad status {status}: {message}")
+        self.status = status
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [("stride_b", ctypes.c_int64), ("stride_n", ctypes.c_int64), ("stride_h", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Open liblasad.so (built in-tree by ``paper_2507_01652_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2507_01652_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lp = ctypes.POINTER(Layout)
+    lib.lasad_decay_factors.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
+    lib.lasad_decay_factors.restype = ci
+    lib.lasad_forward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.lasad_forward_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_forward_chunked.argtypes = [vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                          vp, ci, cf, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.lasad_forward_chunked.restype = ci
+    lib.lasad_decode_step.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, cf, vp, vp]
+    lib.lasad_decode_step.restype = ci
+    lib.lasad_last_error.argtypes = []
+    lib.lasad_last_error.restype = ctypes.c_char_p
+    lib.lasad_version.argtypes = []
+    lib.lasad_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != OK:
+        raise LasadError(status, load().lasad_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _layout(t: torch.Tensor) -> Layout:
+    """Strides of a logical [B, n, Hh, d] tensor (any permutation with unit d stride)."""
+    if t.dim() != 4 or (t.shape[3] > 1 and t.stride(3) != 1):
+        raise ValueError("expected a [B, n_tokens, Hh, d] tensor with unit stride along d")
+    return Layout(t.stride(0), t.stride(1), t.stride(2))
+
+
+def version() -> str:
+    return load().lasad_version().decode()
+
+
+def lasad_decay_factors(gamma: torch.Tensor, grid_h: int, grid_w: int, start_pos: int, n_tokens: int,
+                        boundary_mode: int = RESET_LAST_COL, want_lambda: bool = True,
+                        want_cum_exp: bool = True, stream=None):
+    """Decay table: returns (lambda[Hh, n] fp32 or None, cum_exp[n+1] int32 or None) on gamma's device."""
+    assert gamma.dtype == torch.float32 and gamma.is_contiguous() and gamma.dim() == 1
+    Hh = gamma.shape[0]
+    lam = torch.empty((Hh, max(n_tokens, 0)), dtype=torch.float32, device=gamma.device) if want_lambda else None
+    cum = torch.empty((max(n_tokens, 0) + 1,), dtype=torch.int32, device=gamma.device) if want_cum_exp else None
+    _check(load().lasad_decay_factors(_ptr(gamma), Hh, grid_h, grid_w, start_pos, n_tokens, boundary_mode,
+                                      _ptr(lam), _ptr(cum), _stream(stream)))
+    return lam, cum
+
+
+def lasad_forward_workspace_bytes(B: int, n_heads: int, n_tokens: int, d: int, io_dtype: int) -> int:
+    return int(load().lasad_forward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype))
+
+
+def lasad_forward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: torch.Tensor,
+                          grid_h: int, grid_w: int, start_pos: int = 0,
+                          boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                          state_in: torch.Tensor | None = None, state_out: torch.Tensor | None = None,
+                          out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                          workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Chunked forward over positions start_pos+1 .. start_pos+n.  q, k, v: logical [B, n, Hh, d]
+    views sharing one set of strides; returns o (allocated like q unless `out` is given)."""
+    B, n, Hh, d = q.shape
+    if k.shape != q.shape or v.shape != q.shape or k.stride() != q.stride() or v.stride() != q.stride():
+        raise ValueError("q, k, v must share shape and strides")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share a dtype")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape:
+        raise ValueError("out has the wrong shape")
+    for s in (state_in, state_out):
+        if s is not None and (s.dtype != torch.float32 or not s.is_contiguous() or tuple(s.shape) != (B, Hh, d, d)):
+            raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
+    assert gamma.dtype == torch.float32 and gamma.is_contiguous() and tuple(gamma.shape) == (Hh,)
+    lq, lo = _layout(q), _layout(out)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().lasad_forward_chunked(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(out), ctypes.byref(lq), ctypes.byref(lo),
+        _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, start_pos, n,
+        _ptr(gamma), boundary_mode, q_scale, _ptr(state_in), _ptr(state_out),
+        _ptr(workspace), ws_bytes, _stream(stream)))
+    return out
+
+
+def lasad_decode_step(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: torch.Tensor,
+                      state: torch.Tensor, grid_h: int, grid_w: int, pos: int,
+                      boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                      out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                      stream=None) -> torch.Tensor:
+    """One decode step at 0-indexed raster position `pos`.  q, k, v: contiguous [B, Hh, d];
+    state: contiguous fp32 [B, Hh, d, d], updated in place.  Returns o [B, Hh, d]."""
+    B, Hh, d = q.shape
+    for t in (q, k, v):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("q, k, v must be contiguous [B, Hh, d] of one dtype")
+    if state.dtype != torch.float32 or not state.is_contiguous() or tuple(state.shape) != (B, Hh, d, d):
+        raise ValueError("state must be contiguous fp32 [B, Hh, d, d]")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hh, d]")
+    assert gamma.dtype == torch.float32 and gamma.is_contiguous() and tuple(gamma.shape) == (Hh,)
+    _check(load().lasad_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _dtype_code(q), _dtype_code(out),
+                                    B, Hh, d, grid_h, grid_w, pos, _ptr(gamma), boundary_mode, q_scale,
+                                    _ptr(state), _stream(stream)))
+    return out
+
+
+# ---- host <-> device helpers for seeded numpy inputs (no arithmetic) ---------
+
+def to_device(x, dtype: str, device="cuda"):
+    """Upload a float32 numpy array (values already storage-rounded) as an f32 or bf16 tensor,
+    keeping the numpy array's strides (so a transposed view stays a transposed view)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if not x.flags.c_contiguous:
+        # rebuild the same permutation on the device
+        order = sorted(range(x.ndim), key=lambda i: -x.strides[i])
+        t = torch.from_numpy(np.ascontiguousarray(x.transpose(order)))
+        inv = [order.index(i) for i in range(x.ndim)]
+        t = t.to(device).permute(inv)
+    else:
+        t = t.to(device)
+    if dtype == "bf16":
+        return t.to(torch.bfloat16)    # exact: the values are already bf16-representable
+    if dtype == "f32":
+        return t
+    raise ValueError(dtype)

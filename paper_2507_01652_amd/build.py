@@ -1,0 +1,43 @@
+"""Build liblasad.so (hand-written HIP, gfx950 only) in-tree with hipcc.
+
+Usage: ``python -m paper_2507_01652_amd.build``.  The library lands next to this
+file so that it travels with the source tree; nothing is JIT-compiled at import.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(_HERE, "csrc")
+LIB = os.path.join(_HERE, "liblasad.so")
+
+SOURCES = [
+    "lasad_api.hip",
+    "lasad_decay.hip",
+    "lasad_forward_generic.hip",
+    "lasad_forward_mfma.hip",
+    "lasad_decode.hip",
+]
+
+# Packed-fp32 instruction selection is switched off for every HIP translation unit.
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-command-line-argument",
+]
+
+
+def build(verbose: bool = False, extra_flags=()) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *FLAGS, *extra_flags, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(verbose=True, extra_flags=sys.argv[1:])
+    print("built", LIB)

@@ -1,0 +1,169 @@
+// C ABI of liblasad: argument validation on the host, then dispatch to the
+// kernel launchers.  Nothing here allocates device memory or synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "lasad_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(const char *what, hipError_t e)
+{
+    return fail(LASAD_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+bool supported_d(int d) { return d == 32 || d == 64 || d == 128; }
+
+bool force_generic()
+{
+    static const bool v = [] {
+        const char *e = getenv("LASAD_FORCE_GENERIC");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
+int check_grid(int grid_h, int grid_w, int mode)
+{
+    if (grid_h < 1 || grid_w < 1) return fail(LASAD_ERR_INVALID_ARG, "grid %d x %d: both sides must be >= 1", grid_h, grid_w);
+    if ((int64_t)grid_h * grid_w > (int64_t)1 << 30) return fail(LASAD_ERR_INVALID_ARG, "grid %d x %d is too large", grid_h, grid_w);
+    if (mode < 0 || mode > 2) return fail(LASAD_ERR_INVALID_ARG, "boundary_mode %d is not a lasad_boundary_t", mode);
+    return LASAD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *lasad_last_error(void) { return g_err; }
+
+const char *lasad_version(void) { return "lasad 0.1 gfx950"; }
+
+int lasad_decay_factors(const float *gamma, int n_heads, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode,
+                        float *lambda_out, int32_t *cum_exp_out, void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "n_heads = %d", n_heads);
+    if (start_pos < 0 || n_tokens < 0 || (int64_t)start_pos + n_tokens > (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "positions %d+1..%d+%d leave the %d x %d grid", start_pos, start_pos, n_tokens, grid_h, grid_w);
+    if (lambda_out && !gamma) return fail(LASAD_ERR_INVALID_ARG, "gamma is NULL");
+    hipError_t e = lasad::launch_decay_factors(gamma, n_heads, grid_w, start_pos, n_tokens, boundary_mode,
+                                               lambda_out, cum_exp_out, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_decay_factors launch", e);
+    return LASAD_OK;
+}
+
+size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype)
+{
+    (void)B; (void)n_heads; (void)n_tokens; (void)d; (void)io_dtype;
+    return 0;   // every kernel keeps its intermediates in registers and LDS
+}
+
+int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
+                          const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
+                          int io_dtype, int out_dtype,
+                          int B, int n_heads, int d, int grid_h, int grid_w,
+                          int start_pos, int n_tokens,
+                          const float *gamma, int boundary_mode, float q_scale,
+                          const float *state_in, float *state_out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
+    if (start_pos < 0 || n_tokens < 0 || (int64_t)start_pos + n_tokens > (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "positions %d+1..%d+%d leave the %d x %d grid", start_pos, start_pos, n_tokens, grid_h, grid_w);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (out_dtype != LASAD_F32 && out_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "out_dtype %d", out_dtype);
+    if (io_dtype == LASAD_F32 && out_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 output");
+    if (!gamma) return fail(LASAD_ERR_INVALID_ARG, "gamma is NULL");
+    if (!qkv_layout || !o_layout) return fail(LASAD_ERR_INVALID_ARG, "layout is NULL");
+    if (n_tokens > 0 && (!q || !k || !v || !o)) return fail(LASAD_ERR_INVALID_ARG, "q, k, v or o is NULL");
+    const int vec = io_dtype == LASAD_BF16 ? 8 : 4;   // elements per 16 bytes
+    const int ovec = out_dtype == LASAD_BF16 ? 8 : 4;
+    if (qkv_layout->stride_b % vec || qkv_layout->stride_n % vec || qkv_layout->stride_h % vec ||
+        qkv_layout->stride_b < 0 || qkv_layout->stride_n < 0 || qkv_layout->stride_h < 0)
+        return fail(LASAD_ERR_INVALID_ARG, "q/k/v strides must be non-negative multiples of %d elements", vec);
+    if (o_layout->stride_b % ovec || o_layout->stride_n % ovec || o_layout->stride_h % ovec ||
+        o_layout->stride_b < 0 || o_layout->stride_n < 0 || o_layout->stride_h < 0)
+        return fail(LASAD_ERR_INVALID_ARG, "o strides must be non-negative multiples of %d elements", ovec);
+    if (n_tokens > 0 && (qkv_layout->stride_n < d || o_layout->stride_n < d))
+        return fail(LASAD_ERR_INVALID_ARG, "token stride smaller than the head dim");
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) ||
+        !aligned(state_in, 16) || !aligned(state_out, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "q, k, v, o and the states must be 16-byte aligned");
+    if (n_tokens > 0 && (o == q || o == k || o == v)) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
+
+    lasad::ForwardArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o;
+    a.in = *qkv_layout; a.out = *o_layout;
+    a.io_dtype = io_dtype; a.out_dtype = out_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d;
+    a.grid_w = grid_w;
+    a.start_pos = start_pos; a.n_tokens = n_tokens;
+    a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
+    a.state_in = state_in; a.state_out = state_out;
+
+    if (n_tokens == 0 && (!state_out || state_out == state_in)) return LASAD_OK;   // nothing to do
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e;
+    if (io_dtype == LASAD_BF16 && d == 64 && n_tokens > 0 && !force_generic())
+        e = lasad::launch_forward_mfma(a, s);
+    else
+        e = lasad::launch_forward_generic(a, s);
+    if (e != hipSuccess) return hip_fail("lasad_forward_chunked launch", e);
+    return LASAD_OK;
+}
+
+int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
+                      int io_dtype, int out_dtype, int B, int n_heads, int d,
+                      int grid_h, int grid_w, int pos,
+                      const float *gamma, int boundary_mode, float q_scale,
+                      float *state, void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
+    if (pos < 0 || (int64_t)pos >= (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "pos %d is outside the %d x %d grid", pos, grid_h, grid_w);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (out_dtype != LASAD_F32 && out_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "out_dtype %d", out_dtype);
+    if (io_dtype == LASAD_F32 && out_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 output");
+    if (!q || !k || !v || !o || !gamma || !state) return fail(LASAD_ERR_INVALID_ARG, "a required pointer is NULL");
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(state, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "q, k, v, o and state must be 16-byte aligned");
+    if (o == q || o == k || o == v) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
+
+    lasad::DecodeArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o;
+    a.io_dtype = io_dtype; a.out_dtype = out_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d;
+    a.grid_w = grid_w; a.pos = pos;
+    a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
+    a.state = state;
+    hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_decode_step launch", e);
+    return LASAD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Internal declarations shared by the translation units of liblasad (gfx950 only).
+// Host-side launchers live next to their kernels; the C ABI in lasad_api.hip
+// validates arguments and calls them.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/lasad.h"
+
+namespace lasad {
+
+// Arguments of one forward call, already validated.
+struct ForwardArgs {
+    const void *q, *k, *v;
+    void *o;
+    lasad_layout_t in, out;      // element strides of q/k/v and of o
+    int io_dtype, out_dtype;
+    int B, Hh, d;
+    int grid_w;
+    int start_pos, n_tokens;
+    const float *gamma;
+    int mode;
+    float q_scale;
+    const float *state_in;
+    float *state_out;
+};
+
+struct DecodeArgs {
+    const void *q, *k, *v;
+    void *o;
+    int io_dtype, out_dtype;
+    int B, Hh, d;
+    int grid_w, pos;
+    const float *gamma;
+    int mode;
+    float q_scale;
+    float *state;
+};
+
+hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,
+                                int mode, float *lambda_out, int32_t *cum_out, hipStream_t s);
+hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s);
+// bf16 in, d == 64: MFMA chunked kernel.
+hipError_t launch_forward_mfma(const ForwardArgs &a, hipStream_t s);
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+
+// ---- device helpers -----------------------------------------------------------
+
+// Is 1-indexed raster position t one where the decay is switched off
+// (Section 3.4 second equation / Algorithm 1 boundary branch)?
+__host__ __device__ inline bool is_boundary(int t, int grid_w, int mode)
+{
+    if (mode == LASAD_RESET_LAST_COL) return (t % grid_w) == 0;
+    if (mode == LASAD_RESET_FIRST_COL) return ((t - 1) % grid_w) == 0;
+    return false;
+}
+
+// E(t): number of non-boundary positions among 1..t (t >= 0), closed form.
+__host__ __device__ inline int cum_exp(int t, int grid_w, int mode)
+{
+    if (mode == LASAD_RESET_LAST_COL) return t - t / grid_w;
+    if (mode == LASAD_RESET_FIRST_COL) return t - (t + grid_w - 1) / grid_w;
+    return t;
+}
+
+__device__ inline float bf16_bits_to_float(uint16_t b)
+{
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// float -> bf16 bits, round to nearest even (NaN kept quiet).
+__device__ inline uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+}  // namespace lasad

@@ -1,0 +1,96 @@
+"""Host-side checks of liblasad that need no GPU: the library loads, exports every symbol
+the header declares, and rejects invalid arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2507_01652_amd", "liblasad.so")
+HEADER = os.path.join(ROOT, "include", "lasad.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail(f"{LIB} not built: run `python -m paper_2507_01652_amd.build`")
+    lib = ctypes.CDLL(LIB)
+    lib.lasad_last_error.restype = ctypes.c_char_p
+    lib.lasad_version.restype = ctypes.c_char_p
+    lib.lasad_forward_workspace_bytes.restype = ctypes.c_size_t
+    return lib
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lasad_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = declared_functions()
+    assert {"lasad_decay_factors", "lasad_forward_chunked", "lasad_decode_step"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lasad.h but not exported"
+
+
+def test_binding_names_match_header():
+    import paper_2507_01652_amd.binding as b
+    assert sorted(b.EXPORTS) == declared_functions()
+    for n in ("lasad_decay_factors", "lasad_forward_chunked", "lasad_decode_step",
+              "lasad_forward_workspace_bytes"):
+        assert callable(getattr(b, n))
+
+
+def test_version_and_workspace(lib):
+    assert b"gfx950" in lib.lasad_version()
+    assert lib.lasad_forward_workspace_bytes(8, 12, 256, 64, 1) == 0
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [("b", ctypes.c_int64), ("n", ctypes.c_int64), ("h", ctypes.c_int64)]
+
+
+def _forward(lib, **kw):
+    a = dict(q=0x1000, k=0x2000, v=0x3000, o=0x4000, lq=Layout(64 * 4 * 2, 2 * 64, 64),
+             lo=Layout(64 * 4 * 2, 2 * 64, 64), io=1, out=1, B=1, Hh=2, d=64, gh=2, gw=2, sp=0, n=4,
+             gamma=0x5000, mode=0, qs=1.0, s_in=None, s_out=None)
+    a.update(kw)
+    vp = ctypes.c_void_p
+    return lib.lasad_forward_chunked(vp(a["q"]), vp(a["k"]), vp(a["v"]), vp(a["o"]),
+                                     ctypes.byref(a["lq"]), ctypes.byref(a["lo"]), a["io"], a["out"],
+                                     a["B"], a["Hh"], a["d"], a["gh"], a["gw"], a["sp"], a["n"],
+                                     vp(a["gamma"]), a["mode"], ctypes.c_float(a["qs"]),
+                                     vp(a["s_in"]), vp(a["s_out"]), None, ctypes.c_size_t(0), None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=48), 2), (dict(d=0), 2), (dict(B=0), 1), (dict(Hh=0), 1), (dict(gw=0), 1), (dict(mode=3), 1),
+    (dict(sp=2, n=3), 1), (dict(sp=-1), 1), (dict(n=-1), 1), (dict(io=2), 1), (dict(io=0, out=1), 2),
+    (dict(q=None), 1), (dict(gamma=None), 1), (dict(q=0x1004), 1), (dict(o=0x1000), 1),
+    (dict(lq=Layout(512, 127, 64)), 1), (dict(lq=Layout(512, 32, 64)), 1), (dict(s_in=0x6008), 1),
+])
+def test_forward_rejects_bad_arguments_before_launch(lib, kw, code):
+    """Every call here fails validation, so no kernel is launched (the pointers are fake)."""
+    assert _forward(lib, **kw) == code
+    assert len(lib.lasad_last_error()) > 0
+
+
+def test_decode_and_decay_reject_bad_arguments(lib):
+    vp, cf = ctypes.c_void_p, ctypes.c_float
+    dec = lambda **k: lib.lasad_decode_step(vp(k.get("q", 0x1000)), vp(0x2000), vp(0x3000), vp(k.get("o", 0x4000)),
+                                            k.get("io", 1), k.get("out", 1), k.get("B", 2), 2, k.get("d", 64), 4, 4,
+                                            k.get("pos", 0), vp(0x5000), k.get("mode", 0), cf(1.0),
+                                            vp(k.get("state", 0x6000)), None)
+    assert dec(d=40) == 2
+    assert dec(pos=16) == 1 and dec(pos=-1) == 1
+    assert dec(state=None) == 1 and dec(q=None) == 1
+    assert dec(io=0, out=1) == 2
+    assert dec(mode=7) == 1 and dec(B=0) == 1
+    assert dec(o=0x1000) == 1 and dec(state=0x6004) == 1
+    dk = lambda **k: lib.lasad_decay_factors(vp(k.get("gamma", 0x1000)), k.get("Hh", 2), 4, k.get("gw", 4),
+                                             k.get("sp", 0), k.get("n", 16), k.get("mode", 0),
+                                             vp(0x2000), vp(0x3000), None)
+    assert dk(sp=1) == 1 and dk(n=-2) == 1 and dk(gw=0) == 1 and dk(mode=-1) == 1
+    assert dk(Hh=0) == 1 and dk(gamma=None) == 1
