@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the LASAD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A prefill "step" is one lasad_forward_chunked call over the whole token grid of the chosen
+workload (the decay factors are computed inside the kernel from each token's position); the
+default workload is the base-size layer prefill (batch 8, 12 heads, d 64, 16x16 grid, bf16).
+A decode "step" is one lasad_decode_step call for the AR-decode workload (batch 256, 20 heads,
+fp32 64x64 states), walked over the 16x16 grid in raster order.  Inputs are seeded synthetic
+tensors resident in HBM before the timed region.  Every step works on a different buffer set
+(more than 1 GB in rotation) so that nothing is served from a cache left warm by the previous
+step.  The K timed steps are captured once into a HIP graph and replayed as one submission
+(the eager per-call figure is reported next to it).
+
+Prints ONE JSON line: whole-job prefill tokens/s as `value`, the roofline of the forward
+kernel, the CPU oracle timed on the host cores (`cpu_baseline`), and the decode leg under
+`decode` with its own roofline and CPU baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
+# None until a counter run for that workload has been recorded.
+MEASURED_TRAFFIC_BYTES = {
+    "base_prefill_16x16": None,
+    "large_prefill_24x24": None,
+    "highres_64x64": None,
+    "ar_decode_16x16": None,
+}
+
+PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
+                     "highres_prefill": "highres_64x64"}
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--workload", default="base_prefill", choices=sorted(PREFILL_WORKLOADS))
+    p.add_argument("--decode-walks", type=int, default=4, help="timed raster walks of 256 decode steps (0 = skip)")
+    p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    return p.parse_args()
+
+
+def time_region(torch, fn):
+    """Run fn() between two events on the current stream; returns milliseconds."""
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def capture(torch, fn):
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):     # launches go to the capturing stream (the binding reads the current stream)
+        fn()
+    torch.cuda.synchronize()
+    return g
+
+
+def bench_prefill(args, torch, lasad, wl):
+    import numpy as np
+    w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
+    q, k, v, gam = wl.prefill_inputs(w)
+    tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
+    tg = torch.from_numpy(gam).cuda()
+    token_heads = w.B * w.N * w.Hh
+    bytes_per_launch = token_heads * 4 * w.d * 2            # q, k, v read + o written, bf16
+    sets = max(4, min(96, -(-(1 << 30) // bytes_per_launch)))
+    bufs = [(tq, tk, tv, torch.empty_like(tq))]
+    for _ in range(sets - 1):
+        bufs.append((tq.clone(), tk.clone(), tv.clone(), torch.empty_like(tq)))
+
+    def step(i):
+        a, b, c, o = bufs[i % sets]
+        lasad.lasad_forward_chunked(a, b, c, tg, w.grid_h, w.grid_w, out=o)
+
+    def run(nsteps, first=0):
+        for i in range(nsteps):
+            step(first + i)
+
+    run(args.warmup)
+    eager_ms = time_region(torch, lambda: run(args.steps, args.warmup))
+    graph_ms = None
+    if not args.no_graph:
+        g = capture(torch, lambda: run(args.steps, args.warmup))
+        g.replay()
+        graph_ms = time_region(torch, g.replay)
+    total_ms = graph_ms if graph_ms is not None else eager_ms
+    ms_per_step = total_ms / args.steps
+    dur_s = ms_per_step * 1e-3
+    tokens_per_s = w.B * w.N / dur_s
+
+    C = 64
+    useful_flops = token_heads * (2 * w.d * (C + 1) + 4 * w.d * w.d)   # causal-useful, chunk 64
+    executed_flops = token_heads * (4 * C * w.d + 4 * w.d * w.d)
+    achieved_gbs = bytes_per_launch / dur_s / 1e9
+    res = {
+        "workload": w, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_s,
+        "eager_ms_per_step": eager_ms / args.steps, "graph_ms_per_step": None if graph_ms is None else graph_ms / args.steps,
+        "buffer_sets": sets,
+        "roofline": {"bound": "hbm", "kernel": "lasad_forward_chunked", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": bytes_per_launch,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+        "roofline_mfma": {"bound": "mfma", "achieved": useful_flops / dur_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                          "unit": "TFLOP/s", "frac": useful_flops / dur_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                          "flops_counted": "causal-useful, chunk 64",
+                          "executed_frac": executed_flops / dur_s / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "inputs": (q, k, v, gam),
+    }
+    return res
+
+
+def cpu_baseline_prefill(res, budget_s=20.0):
+    """The fp64 full-mask oracle on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import lasad_oracle as oracle
+    w = res["workload"]
+    q, k, v, gam = res["inputs"]
+    cores = oracle.num_threads()
+    # cost model: 4 N^2 d flops per sequence at roughly 1 GFLOP/s per core
+    per_seq = 4.0 * w.N * w.N * w.d / 1e9
+    n_seq = int(max(cores, min(w.B * w.Hh, budget_s * cores / max(per_seq, 1e-9))))
+    n_seq = min(n_seq, w.B * w.Hh)
+    pairs = [(i // w.Hh, i % w.Hh) for i in np.linspace(0, w.B * w.Hh - 1, n_seq).astype(int)]
+    gq, gk, gv = (np.stack([x[b, :, h, :] for b, h in pairs], axis=1)[None] for x in (q, k, v))
+    lam, _ = oracle.decay_factors(gam[[h for _, h in pairs]], w.grid_h, w.grid_w, 0, w.N)
+    t0 = time.perf_counter()
+    oracle.forward_fullmask(gq, gk, gv, lam)
+    dt = time.perf_counter() - t0
+    return {"value": n_seq * w.N / w.Hh / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_seq} of {w.B * w.Hh} (batch, head) sequences of the workload, full {w.N}x{w.N} mask, "
+                      f"{dt:.2f} s wall; tokens/s = sequences*N/heads/time"}
+
+
+def bench_decode(args, torch, lasad, wl):
+    w = wl.AR_DECODE
+    q, k, v, gam = wl.decode_inputs(w)
+    tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
+    tg = torch.from_numpy(gam).cuda()
+    L = args.decode_layers
+    states = [torch.zeros((w.B, w.Hh, w.d, w.d), dtype=torch.float32, device="cuda") for _ in range(L)]
+    outs = [torch.empty((w.B, w.Hh, w.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    n_steps = args.decode_walks * w.steps
+
+    def run(nsteps):
+        for i in range(nsteps):
+            t = i % w.steps
+            lasad.lasad_decode_step(tq[t], tk[t], tv[t], tg, states[i % L], w.grid_h, w.grid_w, t, out=outs[i % L])
+
+    run(w.steps)    # one untimed walk
+    eager_ms = time_region(torch, lambda: run(n_steps))
+    graph_ms = None
+    if not args.no_graph:
+        g = capture(torch, lambda: run(n_steps))
+        g.replay()
+        graph_ms = time_region(torch, g.replay)
+    total_ms = graph_ms if graph_ms is not None else eager_ms
+    dur_s = total_ms / n_steps * 1e-3
+    n_states = w.B * w.Hh
+    bytes_per_launch = n_states * (2 * w.d * w.d * 4 + 4 * w.d * 2)   # state read + write, q k v o bf16
+    achieved = bytes_per_launch / dur_s / 1e9
+    res = {
+        "workload": w.name, "value": 1.0 / dur_s, "unit": "steps/s", "tokens_per_s": w.B / dur_s,
+        "ms_per_step": dur_s * 1e3, "steps_timed": n_steps, "state_sets_in_rotation": L,
+        "eager_ms_per_step": eager_ms / n_steps, "graph_ms_per_step": None if graph_ms is None else graph_ms / n_steps,
+        "roofline": {"bound": "hbm", "kernel": "lasad_decode_step", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_per_launch,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import lasad_oracle as oracle
+        rows, steps = 32, 64    # bounded sample: 32 of 256 batch rows, 64 of 256 steps
+        state = np.zeros((rows, w.Hh, w.d, w.d))
+        t0 = time.perf_counter()
+        for t in range(steps):
+            lam_t, _ = oracle.decay_factors(gam, w.grid_h, w.grid_w, t, 1)
+            oracle.decode_step(q[t, :rows], k[t, :rows], v[t, :rows], lam_t[:, 0], state)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": steps / dt * rows / w.B, "unit": "steps/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{rows} of {w.B} batch rows, {steps} raster steps, {dt:.2f} s wall; "
+                                         "steps/s scaled by rows/batch to the full batch"}
+    return res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (single process, no collectives); "
+              f"--gpus {args.gpus} is not supported, use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2507_01652_amd import binding as lasad, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    lasad.load()
+
+    pre = bench_prefill(args, torch, lasad, wl)
+    w = pre["workload"]
+    line = {
+        "metric": "lasad_prefill_tokens_per_s", "value": pre["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": pre["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.B, "heads": w.Hh, "head_dim": w.d,
+                   "grid": [w.grid_h, w.grid_w], "tokens_per_step": w.B * w.N, "chunk": 64,
+                   "io": "bf16 q,k,v in, bf16 o out, fp32 accumulation",
+                   "timing": "HIP graph replay of the timed steps" if pre["graph_ms_per_step"] is not None else "eager launches",
+                   "buffer_sets_in_rotation": pre["buffer_sets"]},
+        "eager_ms_per_step": pre["eager_ms_per_step"],
+        "roofline": pre["roofline"], "roofline_mfma": pre["roofline_mfma"],
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline_prefill(pre)
+    if args.decode_walks > 0:
+        line["decode"] = bench_decode(args, torch, lasad, wl)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
