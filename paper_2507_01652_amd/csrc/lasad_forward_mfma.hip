@@ -2,45 +2,50 @@
 //
 // Unrolling Section 3.4's recurrence over a chunk of C tokens that starts after
 // position c0 gives, with e_i = E(i) - E(c0) (number of decaying steps between the
-// chunk start and token i; E is the integer prefix of the boundary rule):
+// chunk start and token i; E is the integer prefix of the boundary rule) and the
+// separable factors r_i = gamma^{e_i}, c_j = gamma^{-e_j}:
 //
-//   o_i   = gamma^{e_i} q_i^T S_prev  +  sum_{j<=i} gamma^{e_i - e_j} (q_i . k_j) v_j
-//   S_new = gamma^{e_C} S_prev        +  sum_j      gamma^{e_C - e_j}  k_j v_j^T
+//   o_i   = r_i   ( q_i^T S_prev + sum_{j<=i} c_j (q_i . k_j) v_j )
+//   S_new = r_end ( S_prev       + sum_j      c_j  k_j v_j^T )
 //
 // i.e. per chunk four 64x64x64 contractions: K Q^T, (masked P) V, Q S and K^T V.
 //
 // One workgroup of four wavefronts walks one (batch, head) sequence.  Wave (a, c)
-// owns query half a / key-channel half a and value-channel half c (32 x 32 tiles,
-// v_mfma_f32_32x32x16_bf16).  Layout choices, all to avoid shuffling data between
-// the MFMA accumulator layout and the MFMA operand layout:
+// owns key-channel half a and value-channel half c of the state and, in
+// alternating chunks, query half a or 1-a (the lower query half has half the
+// causal work) -- all 32 x 32 tiles of v_mfma_f32_32x32x16_bf16.  Layout choices,
+// all made so that nothing is shuffled between the MFMA accumulator layout and
+// the MFMA operand layout:
 //  * the score tile is computed transposed, P^T = K Q^T: a lane then holds, for
 //    its query column i, key rows j in groups of four consecutive -- which is
-//    exactly an A/B operand fragment of the next MFMA once the reduction index j
-//    is enumerated in that same (permuted) order on the V side;
+//    exactly an operand fragment of the next MFMA once the reduction index j is
+//    enumerated in that same (permuted) order on the V side;
 //  * the output tile is computed transposed, O^T = V^T P^T + S^T Q^T, so the
-//    per-query decay gamma^{e_i} is one scalar per lane and a lane owns four
-//    consecutive value channels of its query (8-byte LDS writes on the way out);
-//  * V and K are kept row-major (token, channel) in LDS, as they arrive from
-//    HBM; their token-major operand fragments (reduction over tokens) come from
-//    the LDS transpose read ds_read_b64_tr_b16;
+//    per-query factor r_i is one scalar per lane and a lane owns four consecutive
+//    value channels of its query (8-byte LDS writes on the way out);
+//  * K, V and the decayed keys c_j k_j are kept row-major (token, channel) in
+//    LDS, as they arrive from HBM; the token-major operand fragments (reduction
+//    over tokens) come from the LDS transpose read ds_read_b64_tr_b16;
+//  * Q fragments are loaded from global memory straight into operand layout;
 //  * the fp32 state stays in MFMA accumulators for the whole sequence; a bf16
 //    copy S^T goes through LDS once per chunk for the Q S product.
+//
 // Precision.  The matrix cores take bf16 operands, but rounding the computed
-// operands (masked scores P, state S, decayed values b (.) V) to one bf16 each
+// operands (masked scores P, state S, decayed keys c (.) K) to one bf16 each
 // costs about 2^-9 of the local output magnitude per site, which on heavy-tailed
 // outputs exceeds a 2e-2-of-RMS budget at the largest element.  Each computed
 // operand is therefore split into a bf16 pair hi + lo (lo = the rounding
 // residual) and multiplied with two MFMAs; q, k, v themselves are exact bf16.
-// The kernel is bound by HBM, not by the matrix cores, so the extra MFMAs hide
-// under the memory time.
+// The kernel is bound by instruction issue and HBM, not by the matrix cores, so
+// all elementwise work is done once per element (the decayed keys at staging
+// time by the thread that loaded them) and the extra MFMAs are cheap.
 //
-// Decay.  Powers of gamma are only ever formed for in-chunk exponent differences
-// (0..64).  For gamma > 0.5 the mask is separable, gamma^{e_i - e_j} =
-// gamma^{e_i} * gamma^{-e_j} with gamma^{-e_j} <= 2^64: the column factor is one
-// table lookup and multiply per score, the row factor one multiply per output.
-// For smaller gamma (where gamma^{-e_j} could overflow) every score gets its own
-// exp2((e_i - e_j) log2 gamma).
-#include "lasad_internal.h"
+// Decay.  Powers of gamma are only formed for in-chunk exponents (0..64), from
+// each token's (row, column) position.  The separable form needs c_j <= 2^64,
+// i.e. gamma > 0.5; a head with a smaller gamma is walked with the fp32
+// recurrence instead (lasad_recurrence.h), where its decay is applied step by
+// step.
+#include "lasad_recurrence.h"
 
 namespace lasad {
 
@@ -52,6 +57,14 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((__vector_size__(4 * sizeof(short))));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+#ifdef LASAD_PROFILE
+// Development aid: cycle stamps of workgroup 0 / wave 0 at phase boundaries of each chunk.
+__device__ long long g_prof[16 * 64];
+#define PROF(slot) do { if (blockIdx.x == 0 && tid == 0 && chunk < 64) g_prof[chunk * 16 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define PROF(slot) do { } while (0)
+#endif
 
 constexpr int C = 64;      // chunk length (tokens)
 constexpr int D = 64;      // head dim
@@ -88,29 +101,50 @@ __device__ inline void split2(float x0, float x1, uint32_t &hi, uint32_t &lo)
     lo = pack2(x0 - h0, x1 - h1);
 }
 
+// number of boundary positions among the x small offsets: floor(x / W), 0 <= x < W + 128
+__device__ inline int small_div(int x, int W, float rcpW)
+{
+    if (W > 128) return x >= W ? 1 : 0;
+    int q = (int)((float)x * rcpW);
+    const int r = x - q * W;
+    q += (r >= W) ? 1 : 0;
+    q -= (r < 0) ? 1 : 0;
+    return q;
+}
+
 template <int OUT_BF16>
 __global__ void __launch_bounds__(kThreads, 2)
 forward_mfma_kernel(ForwardArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t sQ[C * RS];
-    __shared__ __attribute__((aligned(16))) uint16_t sK[C * RS];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[C * VS];
-    __shared__ __attribute__((aligned(16))) uint16_t sSt[2][2][D * RS];   // [buffer][hi, lo] bf16 S^T [dv][dk]
-    __shared__ __attribute__((aligned(16))) uint16_t sO[OUT_BF16 ? C * RS : 8];   // bf16 output tile [token][dv]
-    __shared__ __attribute__((aligned(16))) float tabE[C];   // e_j as float
-    __shared__ __attribute__((aligned(16))) float tabC[C];   // gamma^{-e_j} (separable path)
-    __shared__ __attribute__((aligned(16))) float tabB[C];   // gamma^{e_end - e_j}, 0 for rows past the end
+    // LDS: K tile (16-byte reads), V and decayed-K hi/lo tiles (transpose reads), S^T hi/lo,
+    // the bf16 output tile, the table of c_j.  The fp32-recurrence fallback reuses the block.
+    constexpr int kLdsHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[kLdsHalfs];
+    __shared__ __attribute__((aligned(16))) float tabC[C];
+    static_assert(kLdsHalfs * 2 >= recurrence_lds_floats<D>() * 4, "fallback needs the LDS block");
+    uint16_t *sK = smem;
+    uint16_t *sV = sK + C * RS;
+    uint16_t *sKh = sV + C * VS;
+    uint16_t *sKl = sKh + C * VS;
+    uint16_t *sSh = sKl + C * VS;      // S^T hi [dv][dk]
+    uint16_t *sSl = sSh + D * RS;      // S^T lo
+    uint16_t *sO = sSl + D * RS;       // output tile [token][dv] bf16
+
+    const int bh = blockIdx.x;
+    const int b = bh / a.Hh, h = bh - b * a.Hh;
+    const float gamma = a.gamma[h];
+    const float lg = log2f(gamma);
+    if (!(lg * (float)C > -64.0f)) {   // gamma <= 0.5 (or 0): separable factors could overflow
+        recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);
+        return;
+    }
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int wa = wave >> 1, wc = wave & 1;     // query/key-channel half, value-channel half
+    const int wa = wave >> 1, wc = wave & 1;     // key-channel half, value-channel half
     const int l32 = lane & 31, g = lane >> 5;    // column inside the 32-wide tile, k-group
-    const int bh = blockIdx.x;
-    const int b = bh / a.Hh, h = bh - b * a.Hh;
-
-    const float gamma = a.gamma[h];
-    const float lg = log2f(gamma);               // -inf for gamma == 0 (guarded where used)
-    const bool separable = lg * (float)C > -64.0f;   // gamma^{-64} <= 2^64
+    const int W = a.grid_w;
+    const float rcpW = 1.0f / (float)W;
 
     const uint16_t *gq = (const uint16_t *)a.q + (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
     const uint16_t *gk = (const uint16_t *)a.k + (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
@@ -130,204 +164,201 @@ forward_mfma_kernel(ForwardArgs a)
         for (int r = 0; r < 16; ++r) accS[r] = 0.f;
     }
     // bf16 hi/lo copy of S^T for the Q S product of the next chunk
-    auto publish_state = [&](int buf) {
+    auto publish_state = [&]() {
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             uint2 hi, lo;
             split2(accS[4 * qd + 0], accS[4 * qd + 1], hi.x, lo.x);
             split2(accS[4 * qd + 2], accS[4 * qd + 3], hi.y, lo.y);
             const int off = (wc * 32 + l32) * RS + wa * 32 + 8 * qd + 4 * g;
-            *(uint2 *)&sSt[buf][0][off] = hi;
-            *(uint2 *)&sSt[buf][1][off] = lo;
+            *(uint2 *)&sSh[off] = hi;
+            *(uint2 *)&sSl[off] = lo;
         }
     };
-    if (have_state) publish_state(0);
+    if (have_state) publish_state();
 
     const int n_chunks = (a.n_tokens + C - 1) / C;
 
-    // global -> register staging: thread loads 16 B pieces (row = tid/8 + 32*it, piece = tid%8)
-    uint4 rq[2], rk[2], rv[2];
+    // Position bookkeeping: col0 = (tokens before the chunk) mod W.  The number of boundary
+    // positions among the first j+1 tokens of the chunk is floor((j + xoff) / W) with a small
+    // per-chunk offset xoff, so e_j = j + 1 - floor((j + xoff) / W).
+    int col0 = a.start_pos % W;
+
+    // global -> register staging of K and V: 16 B pieces (row = tid/8 + 32*it, piece = tid%8);
+    // Q: this lane's operand fragments of query row l32 of the wave's query half.
+    uint4 rk[2], rv[2];
+    Frag fqn[4];
+    // Loads are unconditional (the token index is clamped into the sequence): nothing
+    // touches the loaded registers until the next chunk is staged, so the loads stay in
+    // flight behind this chunk's arithmetic.  Rows past the end are zeroed at staging.
     auto prefetch = [&](int chunk) {
         const int t0 = chunk * C;
+        const int last = a.n_tokens - 1;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const int row = (tid >> 3) + 32 * it;
-            const int tok = t0 + row;
-            if (tok < a.n_tokens) {
-                const int64_t off = (int64_t)tok * a.in.stride_n + (tid & 7) * 8;
-                rq[it] = *(const uint4 *)(gq + off);
-                rk[it] = *(const uint4 *)(gk + off);
-                rv[it] = *(const uint4 *)(gv + off);
-            } else {
-                rq[it] = rk[it] = rv[it] = make_uint4(0, 0, 0, 0);
-            }
+            const int tok = t0 + (tid >> 3) + 32 * it;
+            const int64_t off = (int64_t)min(tok, last) * a.in.stride_n + (tid & 7) * 8;
+            rk[it] = *(const uint4 *)(gk + off);
+            rv[it] = *(const uint4 *)(gv + off);
         }
+        const int qtok = t0 + (wa ^ (chunk & 1)) * 32 + l32;
+        const uint16_t *p = gq + (int64_t)min(qtok, last) * a.in.stride_n + 8 * g;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);
     };
     prefetch(0);
 
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
         const int nt = min(C, a.n_tokens - t0);
-        const int c0 = a.start_pos + t0;                 // tokens before this chunk
-        const int cur = chunk & 1;
+        const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
 
-        // ---- stage tiles and per-chunk decay tables into LDS ----
+        PROF(0);
+        // ---- stage K, V and the decayed keys c_j K (hi + lo) into LDS ----
+        int xoff = 0;
+        if (a.mode == LASAD_RESET_LAST_COL) xoff = col0 + 1;
+        else if (a.mode == LASAD_RESET_FIRST_COL) xoff = col0 ? col0 : W;
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int row = (tid >> 3) + 32 * it;
             const int col = (tid & 7) * 8;
-            *(uint4 *)&sQ[row * RS + col] = rq[it];
+            if (row >= nt) rk[it] = rv[it] = make_uint4(0, 0, 0, 0);   // tail chunk only
+            const int nb = a.mode == LASAD_RESET_NONE ? 0 : small_div(row + xoff, W, rcpW);
+            const float cj = __builtin_amdgcn_exp2f(-(float)(row + 1 - nb) * lg);   // gamma^{-e_j}
+            if ((tid & 7) == 0) tabC[row] = cj;
+            const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2)
+                split2(__uint_as_float(kw[w2] << 16) * cj, __uint_as_float(kw[w2] & 0xffff0000u) * cj,
+                       hi[w2], lo[w2]);
             *(uint4 *)&sK[row * RS + col] = rk[it];
             *(uint4 *)&sV[row * VS + col] = rv[it];
+            *(uint4 *)&sKh[row * VS + col] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *(uint4 *)&sKl[row * VS + col] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         }
-        const int e_base = cum_exp(c0, a.grid_w, a.mode);
-        const int e_end = cum_exp(c0 + nt, a.grid_w, a.mode) - e_base;
-        if (tid < C) {
-            const int ej = cum_exp(c0 + 1 + tid, a.grid_w, a.mode) - e_base;
-            tabE[tid] = (float)ej;
-            tabC[tid] = separable ? __builtin_amdgcn_exp2f(-(float)ej * lg) : 0.f;
-            const int de = e_end - ej;
-            tabB[tid] = tid < nt ? (de == 0 ? 1.0f : __builtin_amdgcn_exp2f((float)de * lg)) : 0.0f;
+        Frag fq[4];
+        {
+            const uint32_t keep = (qa * 32 + l32) < nt ? 0xffffffffu : 0u;   // query rows past the end
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                fq[s].u = make_uint4(fqn[s].u.x & keep, fqn[s].u.y & keep, fqn[s].u.z & keep, fqn[s].u.w & keep);
         }
-        __syncthreads();                                  // (A) tiles, tables and S^T[cur] visible
+        // next chunk's col0
+        col0 += C;
+        if (W > 128) col0 -= col0 >= W ? W : 0;
+        else col0 -= W * small_div(col0, W, rcpW);
+
+        PROF(1);
+        __syncthreads();                                  // (A) tiles, c_j table and S^T visible
+        PROF(2);
         if (chunk + 1 < n_chunks) prefetch(chunk + 1);
 
-        // ---- Q fragments of this wave's query half: row i = wa*32 + l32, channels 16*s + 8*g .. +7 ----
-        Frag fq[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) fq[s].u = *(const uint4 *)&sQ[(wa * 32 + l32) * RS + 16 * s + 8 * g];
+        const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
+        const int trow = (lane & 15) >> 2;                // transpose reads: row inside the 4-row group
+        const int tsub = 16 * (l32 >> 4) + 4 * (lane & 3);
 
-        const int i_row = wa * 32 + l32;                  // this lane's query (column of the transposed tiles)
-        const float e_i = tabE[i_row];
-        const float r_i = (e_i == 0.f) ? 1.0f : __builtin_amdgcn_exp2f(e_i * lg);   // gamma^{e_i}
-
-        // ---- P^T[j][i] = sum_d K[j][d] Q[i][d]; key block 1 is fully masked for query half 0 ----
-        Frag fph[4], fpl[4];                              // bf16 hi / lo fragments of P, reduction index j permuted
+        // ---- scores of key block 0, P^T[j][i] = sum_d K[j][d] Q[i][d] ----
+        f32x16 acc0, acc1, accO;
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-            if (jb <= wa) {
-                f32x16 acc;
+        for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = accO[r] = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    Frag fk;
-                    fk.u = *(const uint4 *)&sK[(jb * 32 + l32) * RS + 16 * s + 8 * g];
-                    acc = mfma(fk, fq[s], acc);
-                }
-                // decay + causal mask on the fp32 scores, then split to bf16 hi + lo
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    const int j0 = jb * 32 + 8 * qd + 4 * g;
-                    float p[4];
-                    if (separable) {
-                        const float4 c4 = *(const float4 *)&tabC[j0];
-                        p[0] = acc[4 * qd + 0] * c4.x; p[1] = acc[4 * qd + 1] * c4.y;
-                        p[2] = acc[4 * qd + 2] * c4.z; p[3] = acc[4 * qd + 3] * c4.w;
-                    } else {
-                        const float4 ej4 = *(const float4 *)&tabE[j0];
-                        const float ej[4] = {ej4.x, ej4.y, ej4.z, ej4.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float de = e_i - ej[e];
-                            p[e] = acc[4 * qd + e] * ((de == 0.f) ? 1.0f : __builtin_amdgcn_exp2f(de * lg));
-                        }
-                    }
-                    if (jb == wa) {                       // diagonal block: causal mask
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) p[e] = (j0 + e <= i_row) ? p[e] : 0.f;
-                    }
-                    // fragment for k-step s = 2*jb + qd/2, half qd%2
-                    uint2 hi, lo;
-                    split2(p[0], p[1], hi.x, lo.x);
-                    split2(p[2], p[3], hi.y, lo.y);
-                    fph[2 * jb + qd / 2].h[qd % 2] = hi;
-                    fpl[2 * jb + qd / 2].h[qd % 2] = lo;
-                }
-            } else {
-                fph[2 * jb].u = fph[2 * jb + 1].u = make_uint4(0, 0, 0, 0);
-                fpl[2 * jb].u = fpl[2 * jb + 1].u = make_uint4(0, 0, 0, 0);
-            }
+        for (int s = 0; s < 4; ++s) {
+            Frag fk;
+            fk.u = *(const uint4 *)&sK[l32 * RS + 16 * s + 8 * g];
+            acc0 = mfma(fk, fq[s], acc0);
         }
-
-        // ---- O^T[n][i] = gamma^{e_i} sum_dk S^T[n][dk] Q[i][dk]  +  sum_j V[j][n] P[i][j] ----
-        // (separable path: P lacks the row factor gamma^{e_i}, applied to the whole sum at the end)
-        f32x16 accO;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) accO[r] = 0.f;
+        // ---- O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk]  (independent of the scores) ----
         if (have_state) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 Frag fs;
-                fs.u = *(const uint4 *)&sSt[cur][0][(wc * 32 + l32) * RS + 16 * s + 8 * g];
+                fs.u = *(const uint4 *)&sSh[(wc * 32 + l32) * RS + 16 * s + 8 * g];
                 accO = mfma(fs, fq[s], accO);
-                fs.u = *(const uint4 *)&sSt[cur][1][(wc * 32 + l32) * RS + 16 * s + 8 * g];
+                fs.u = *(const uint4 *)&sSl[(wc * 32 + l32) * RS + 16 * s + 8 * g];
                 accO = mfma(fs, fq[s], accO);
-            }
-            if (!separable) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) accO[r] *= r_i;
             }
         }
-        // V fragments: value channel n = wc*32 + l32, token rows 16*s + 4*g + {0..3} and + 8
-        Frag fv[4];
-        {
-            const int trow = (lane & 15) >> 2;                       // row inside the 4-row group this lane points at
-            const int tcol = wc * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
+        // ---- scores of key block 1 (all masked for the lower query half) ----
+        if (qa == 1) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                fv[s].h[0] = tr_read(&sV[(16 * s + 4 * g + trow) * VS + tcol]);
-                fv[s].h[1] = tr_read(&sV[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+                Frag fk;
+                fk.u = *(const uint4 *)&sK[(32 + l32) * RS + 16 * s + 8 * g];
+                acc1 = mfma(fk, fq[s], acc1);
             }
         }
-        const int s_max = wa == 0 ? 2 : 4;               // key rows 32..63 carry zero P for query half 0
+        // ---- V fragments: value channel n = wc*32 + l32, token rows 16*s + 4*g + {0..3} and + 8 ----
+        Frag fv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            if (s < s_max) {
-                accO = mfma(fv[s], fph[s], accO);
-                accO = mfma(fv[s], fpl[s], accO);
-            }
-        {
-            const float osc = separable ? a.q_scale * r_i : a.q_scale;
+        for (int s = 0; s < 4; ++s) {
+            fv[s].h[0] = tr_read(&sV[(16 * s + 4 * g + trow) * VS + wc * 32 + tsub]);
+            fv[s].h[1] = tr_read(&sV[(16 * s + 8 + 4 * g + trow) * VS + wc * 32 + tsub]);
+        }
+        // ---- state: S[dk][dv] += sum_j (c_j K[j][dk]) V[j][dv]  (independent of the scores) ----
 #pragma unroll
-            for (int r = 0; r < 16; ++r) accO[r] *= osc;
+        for (int s = 0; s < 4; ++s) {
+            Frag fkt;
+            fkt.h[0] = tr_read(&sKh[(16 * s + 4 * g + trow) * VS + wa * 32 + tsub]);
+            fkt.h[1] = tr_read(&sKh[(16 * s + 8 + 4 * g + trow) * VS + wa * 32 + tsub]);
+            accS = mfma(fkt, fv[s], accS);
+            fkt.h[0] = tr_read(&sKl[(16 * s + 4 * g + trow) * VS + wa * 32 + tsub]);
+            fkt.h[1] = tr_read(&sKl[(16 * s + 8 + 4 * g + trow) * VS + wa * 32 + tsub]);
+            accS = mfma(fkt, fv[s], accS);
         }
 
-        // ---- state update: S <- gamma^{e_end} S + K^T (b (.) V) ----
-        {
-            const float gtot = (e_end == 0) ? 1.0f : __builtin_amdgcn_exp2f((float)e_end * lg);
+        PROF(3);
+        // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
+        // slot e of quad qd of key block jb is key j = jb*32 + 8*qd + 4*g + e; it lands in the
+        // fragment of k-step s = 2*jb + qd/2, half qd%2.
+        auto mask_split = [&](const f32x16 &acc, int jb, bool diagonal, Frag *ph, Frag *pl) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) accS[r] *= gtot;
-            const int trow = (lane & 15) >> 2;
-            const int tcol = wa * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                Frag fkt, fvh, fvl;
-                fkt.h[0] = tr_read(&sK[(16 * s + 4 * g + trow) * RS + tcol]);
-                fkt.h[1] = tr_read(&sK[(16 * s + 8 + 4 * g + trow) * RS + tcol]);
-                // scale V rows by b_j (slot e <-> token 16*s + 8*(e/4) + 4*g + e%4), split hi + lo
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const float4 b4 = *(const float4 *)&tabB[16 * s + 8 * hh + 4 * g];
-                    const uint2 raw = fv[s].h[hh];
-                    const float v0 = __uint_as_float(raw.x << 16) * b4.x;
-                    const float v1 = __uint_as_float(raw.x & 0xffff0000u) * b4.y;
-                    const float v2 = __uint_as_float(raw.y << 16) * b4.z;
-                    const float v3 = __uint_as_float(raw.y & 0xffff0000u) * b4.w;
-                    uint2 hi, lo;
-                    split2(v0, v1, hi.x, lo.x);
-                    split2(v2, v3, hi.y, lo.y);
-                    fvh.h[hh] = hi;
-                    fvl.h[hh] = lo;
+            for (int qd = 0; qd < 4; ++qd) {
+                const int j0 = jb * 32 + 8 * qd + 4 * g;
+                const float4 c4 = *(const float4 *)&tabC[j0];
+                float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
+                float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
+                if (diagonal) {
+                    p0 = (j0 + 0 <= i_row) ? p0 : 0.f; p1 = (j0 + 1 <= i_row) ? p1 : 0.f;
+                    p2 = (j0 + 2 <= i_row) ? p2 : 0.f; p3 = (j0 + 3 <= i_row) ? p3 : 0.f;
                 }
-                accS = mfma(fkt, fvh, accS);             // S[dk][dv] += sum_j K[j][dk] * (b_j V[j][dv])
-                accS = mfma(fkt, fvl, accS);
+                uint2 hi, lo;
+                split2(p0, p1, hi.x, lo.x);
+                split2(p2, p3, hi.y, lo.y);
+                ph[qd / 2].h[qd % 2] = hi;
+                pl[qd / 2].h[qd % 2] = lo;
             }
+        };
+        {
+            Frag ph[2], pl[2];
+            mask_split(acc0, 0, qa == 0, ph, pl);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                accO = mfma(fv[s], ph[s], accO);
+                accO = mfma(fv[s], pl[s], accO);
+            }
+        }
+        if (qa == 1) {
+            Frag ph[2], pl[2];
+            mask_split(acc1, 1, true, ph, pl);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                accO = mfma(fv[2 + s], ph[s], accO);
+                accO = mfma(fv[2 + s], pl[s], accO);
+            }
+        }
+
+        PROF(4);
+        // ---- row factors: r_i on the outputs, r_end on the state ----
+        {
+            const float osc = a.q_scale * __builtin_amdgcn_rcpf(tabC[i_row]);
+            const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { accO[r] *= osc; accS[r] *= r_end; }
             have_state = true;
         }
 
-        // ---- hand the new S^T to the next chunk; send the output tile out ----
-        if (chunk + 1 < n_chunks) publish_state(cur ^ 1);
+        // ---- send the output tile out ----
         if (OUT_BF16) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -344,7 +375,9 @@ forward_mfma_kernel(ForwardArgs a)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
-        __syncthreads();                                  // (B) output tile complete; all tile reads finished
+        PROF(5);
+        __syncthreads();                                  // (B) output tile complete; all tile and S^T reads finished
+        PROF(6);
 
         if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
             uint16_t *go = (uint16_t *)a.o + o_base;
@@ -356,6 +389,8 @@ forward_mfma_kernel(ForwardArgs a)
                         *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
             }
         }
+        if (chunk + 1 < n_chunks) publish_state();        // read after the next barrier (A)
+        PROF(7);
     }
 
     if (a.state_out) {
@@ -376,5 +411,12 @@ hipError_t launch_forward_mfma(const ForwardArgs &a, hipStream_t s)
     else hipLaunchKernelGGL(forward_mfma_kernel<0>, grid, block, 0, s, a);
     return hipGetLastError();
 }
+
+#ifdef LASAD_PROFILE
+extern "C" int lasad_debug_read_profile(long long *host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof), sizeof(long long) * n);
+}
+#endif
 
 }  // namespace lasad
