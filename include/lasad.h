@@ -82,7 +82,9 @@ int lasad_decay_factors(const float *gamma, int n_heads, int grid_h, int grid_w,
                         int start_pos, int n_tokens, int boundary_mode,
                         float *lambda_out, int32_t *cum_exp_out, void *hip_stream);
 
-/* Bytes of device workspace lasad_forward_chunked needs for these sizes (may be 0). */
+/* Bytes of device workspace lasad_forward_chunked can use for these sizes (may be 0).  With
+ * few, long sequences the bf16 d = 64 kernel cuts every sequence into segments that are
+ * processed by different workgroups; the per-segment partial states live here. */
 size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype);
 
 /*
@@ -101,8 +103,11 @@ size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, in
  *   state_in  [B, n_heads, d, d] fp32, S[i][j] = sum_t (decay) k_t[i] v_t[j] (dv
  *             contiguous), the state after position start_pos; NULL means zeros.
  *   state_out [B, n_heads, d, d] fp32 or NULL; may equal state_in.
- *   workspace device scratch of at least lasad_forward_workspace_bytes(...) bytes;
- *             may be NULL when that is 0.
+ *   workspace device scratch of at least lasad_forward_workspace_bytes(...) bytes, 16-byte
+ *             aligned, contents irrelevant on entry and undefined on return; a smaller
+ *             non-NULL workspace is LASAD_ERR_WORKSPACE.  NULL is allowed: the call then
+ *             walks every sequence with one workgroup (same results up to rounding,
+ *             slower when there are fewer sequences than the GPU has compute units).
  * Pointers must be aligned to 16 bytes and strides multiples of 8 elements for the
  * bf16 kernels (4 for fp32).  n_tokens may be 0 (then state_out = state_in).
  */

@@ -121,9 +121,12 @@ def lasad_forward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gam
                           boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
                           state_in: torch.Tensor | None = None, state_out: torch.Tensor | None = None,
                           out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
-                          workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+                          workspace: torch.Tensor | None = None, use_workspace: bool = True,
+                          stream=None) -> torch.Tensor:
     """Chunked forward over positions start_pos+1 .. start_pos+n.  q, k, v: logical [B, n, Hh, d]
-    views sharing one set of strides; returns o (allocated like q unless `out` is given)."""
+    views sharing one set of strides; returns o (allocated like q unless `out` is given).
+    `workspace`: a device buffer of lasad_forward_workspace_bytes(...) bytes; when None one is
+    taken from torch's caching allocator (use_workspace=False passes NULL: single-pass kernel)."""
     B, n, Hh, d = q.shape
     if k.shape != q.shape or v.shape != q.shape or k.stride() != q.stride() or v.stride() != q.stride():
         raise ValueError("q, k, v must share shape and strides")
@@ -138,6 +141,10 @@ def lasad_forward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gam
             raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
     assert gamma.dtype == torch.float32 and gamma.is_contiguous() and tuple(gamma.shape) == (Hh,)
     lq, lo = _layout(q), _layout(out)
+    if workspace is None and use_workspace and n > 0:
+        need = lasad_forward_workspace_bytes(B, Hh, n, d, _dtype_code(q))
+        if need:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().lasad_forward_chunked(
         _ptr(q), _ptr(k), _ptr(v), _ptr(out), ctypes.byref(lq), ctypes.byref(lo),

@@ -71,8 +71,10 @@ int lasad_decay_factors(const float *gamma, int n_heads, int grid_h, int grid_w,
 
 size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype)
 {
-    (void)B; (void)n_heads; (void)n_tokens; (void)d; (void)io_dtype;
-    return 0;   // every kernel keeps its intermediates in registers and LDS
+    if (B < 1 || n_heads < 1 || n_tokens < 1) return 0;
+    if (io_dtype == LASAD_BF16 && d == 64 && !force_generic())
+        return lasad::forward_mfma_workspace_bytes((int64_t)B * n_heads, n_tokens);
+    return 0;   // the fp32 kernel keeps everything in registers and LDS
 }
 
 int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
@@ -84,7 +86,6 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
                           const float *state_in, float *state_out,
                           void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    (void)workspace; (void)workspace_bytes;
     if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
     if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
     if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
@@ -121,6 +122,14 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
     a.start_pos = start_pos; a.n_tokens = n_tokens;
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state_in = state_in; a.state_out = state_out;
+    a.seg_states = nullptr; a.n_segments = 1; a.seg_chunks = 0;
+    if (workspace) {
+        const size_t need = lasad_forward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype);
+        if (workspace_bytes < need)
+            return fail(LASAD_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", workspace_bytes, need);
+        if (!aligned(workspace, 16)) return fail(LASAD_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+        if (need > 0) a.seg_states = (float *)workspace;
+    }
 
     if (n_tokens == 0 && (!state_out || state_out == state_in)) return LASAD_OK;   // nothing to do
 

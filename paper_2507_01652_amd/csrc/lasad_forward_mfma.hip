@@ -40,6 +40,16 @@
 // all elementwise work is done once per element (the decayed keys at staging
 // time by the thread that loaded them) and the extra MFMAs are cheap.
 //
+// Few, long sequences.  When there are fewer sequences than the chip has room
+// for workgroups, each sequence is cut into segments of whole chunks and the work
+// is done in two launches: a state pass in which every segment but the last
+// builds, from a zero state, its own contribution U_g to the state (K, V only, no
+// scores, no output), written to a workspace; then the full pass, in which the
+// workgroup of segment g folds U_0..U_{g-1} (and the caller's initial state) into
+// its incoming state, S <- gamma^{E(end_g') - E(begin_g')} S + U_g', and walks its
+// own chunks.  The serial chain per sequence shrinks from all chunks to one
+// segment's chunks plus a few 16 KB folds.
+//
 // Decay.  Powers of gamma are only formed for in-chunk exponents (0..64), from
 // each token's (row, column) position.  The separable form needs c_j <= 2^64,
 // i.e. gamma > 0.5; a head with a smaller gamma is walked with the fp32
@@ -101,7 +111,7 @@ __device__ inline void split2(float x0, float x1, uint32_t &hi, uint32_t &lo)
     lo = pack2(x0 - h0, x1 - h1);
 }
 
-// number of boundary positions among the x small offsets: floor(x / W), 0 <= x < W + 128
+// number of boundary positions among x small offsets: floor(x / W), 0 <= x < W + 128
 __device__ inline int small_div(int x, int W, float rcpW)
 {
     if (W > 128) return x >= W ? 1 : 0;
@@ -112,6 +122,177 @@ __device__ inline int small_div(int x, int W, float rcpW)
     return q;
 }
 
+// Per-chunk position bookkeeping.  col0 = (tokens before the chunk) mod W.  The number of
+// boundary positions among the first j+1 tokens of the chunk is floor((j + xoff) / W) with a
+// small per-chunk offset xoff, so e_j = j + 1 - floor((j + xoff) / W).
+struct ChunkPos {
+    int W, mode, col0;
+    float rcpW;
+    __device__ void init(int start, int grid_w, int boundary_mode)
+    {
+        W = grid_w; mode = boundary_mode; col0 = start % grid_w; rcpW = 1.0f / (float)grid_w;
+    }
+    __device__ int xoff() const
+    {
+        if (mode == LASAD_RESET_LAST_COL) return col0 + 1;
+        if (mode == LASAD_RESET_FIRST_COL) return col0 ? col0 : W;
+        return 0;
+    }
+    __device__ int e_of(int j, int xo) const     // e_j of chunk-local token j
+    {
+        return j + 1 - (mode == LASAD_RESET_NONE ? 0 : small_div(j + xo, W, rcpW));
+    }
+    __device__ void advance()                    // to the next chunk
+    {
+        col0 += C;
+        if (W > 128) col0 -= col0 >= W ? W : 0;
+        else col0 -= W * small_div(col0, W, rcpW);
+    }
+};
+
+// Stage one chunk's K, V (as loaded) and the decayed keys c_j K[j][:] (bf16 hi + lo) into LDS;
+// every thread handles the two 16-byte pieces it loaded (rows tid/8 and tid/8 + 32).
+template <bool RAW_K>
+__device__ inline void stage_chunk(uint16_t *sK, uint16_t *sV, uint16_t *sKh, uint16_t *sKl, float *tabC,
+                                   uint4 (&rk)[2], uint4 (&rv)[2], int tid, int nt,
+                                   const ChunkPos &pos, float lg)
+{
+    const int xo = pos.xoff();
+    if (nt < C) {                                   // tail chunk: rows past the end are zero
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+            if ((tid >> 3) + 32 * it >= nt) rk[it] = rv[it] = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int row = (tid >> 3) + 32 * it;
+        const int col = (tid & 7) * 8;
+        const float cj = __builtin_amdgcn_exp2f(-(float)pos.e_of(row, xo) * lg);   // gamma^{-e_j}
+        if ((tid & 7) == 0) tabC[row] = cj;
+        const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2)
+            split2(__uint_as_float(kw[w2] << 16) * cj, __uint_as_float(kw[w2] & 0xffff0000u) * cj,
+                   hi[w2], lo[w2]);
+        if (RAW_K) *(uint4 *)&sK[row * RS + col] = rk[it];
+        *(uint4 *)&sV[row * VS + col] = rv[it];
+        *(uint4 *)&sKh[row * VS + col] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        *(uint4 *)&sKl[row * VS + col] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
+}
+
+// V fragments of value-channel half wc: channel n = wc*32 + l32, tokens 16*s + 4*g + {0..3}, + 8
+__device__ inline void load_v_frags(Frag (&fv)[4], const uint16_t *sV, int wc, int lane)
+{
+    const int l32 = lane & 31, g = lane >> 5;
+    const int trow = (lane & 15) >> 2;               // row inside the 4-row group this lane points at
+    const int tcol = wc * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        fv[s].h[0] = tr_read(&sV[(16 * s + 4 * g + trow) * VS + tcol]);
+        fv[s].h[1] = tr_read(&sV[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+    }
+}
+
+// S[dk][dv] += sum_j (c_j K[j][dk]) V[j][dv] for the wave's 32 x 32 tile (dk half wa)
+__device__ inline void state_update(f32x16 &accS, const uint16_t *sKh, const uint16_t *sKl,
+                                    const Frag (&fv)[4], int wa, int lane)
+{
+    const int l32 = lane & 31, g = lane >> 5;
+    const int trow = (lane & 15) >> 2;
+    const int tcol = wa * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        Frag fkt;
+        fkt.h[0] = tr_read(&sKh[(16 * s + 4 * g + trow) * VS + tcol]);
+        fkt.h[1] = tr_read(&sKh[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+        accS = mfma(fkt, fv[s], accS);
+        fkt.h[0] = tr_read(&sKl[(16 * s + 4 * g + trow) * VS + tcol]);
+        fkt.h[1] = tr_read(&sKl[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+        accS = mfma(fkt, fv[s], accS);
+    }
+}
+
+// K/V staging loads of one chunk of a token range [0, n): unconditional, index clamped.
+__device__ inline void load_kv(uint4 (&rk)[2], uint4 (&rv)[2], const uint16_t *gk, const uint16_t *gv,
+                               int t0, int n, int64_t stride_n, int tid)
+{
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int tok = min(t0 + (tid >> 3) + 32 * it, n - 1);
+        const int64_t off = (int64_t)tok * stride_n + (tid & 7) * 8;
+        rk[it] = *(const uint4 *)(gk + off);
+        rv[it] = *(const uint4 *)(gv + off);
+    }
+}
+
+// exponent E(end) - E(begin) of a token range, begin/end = tokens consumed before / after it
+__device__ inline int range_exponent(int begin, int end, int W, int mode)
+{
+    return cum_exp(end, W, mode) - cum_exp(begin, W, mode);
+}
+
+// ------------------------------------------------------------------------------------------
+// State pass: segment g < G-1 of every sequence builds U_g = sum_j gamma^{E(end) - E(j)} k_j v_j^T
+// from a zero state and writes it (fp32 [dk][dv]) to seg_states[(bh * (G-1) + g)].
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads, 2)
+segment_state_kernel(ForwardArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t sV[C * VS], sKh[C * VS], sKl[C * VS];
+    __shared__ __attribute__((aligned(16))) float tabC[C];
+
+    const int G1 = a.n_segments - 1;
+    const int bh = blockIdx.x / G1, seg = blockIdx.x - bh * G1;
+    const int b = bh / a.Hh, h = bh - b * a.Hh;
+    const float lg = log2f(a.gamma[h]);
+    if (!(lg * (float)C > -64.0f)) return;        // this head is walked by the fp32 recurrence
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wa = wave >> 1, wc = wave & 1;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int seg_t0 = seg * a.seg_chunks * C;                 // first token of the segment
+    const int n = min(a.seg_chunks * C, a.n_tokens - seg_t0);   // its length (a full segment here)
+    const int64_t base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + (int64_t)seg_t0 * a.in.stride_n;
+    const uint16_t *gk = (const uint16_t *)a.k + base;
+    const uint16_t *gv = (const uint16_t *)a.v + base;
+
+    ChunkPos pos;
+    pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
+
+    f32x16 accS;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accS[r] = 0.f;
+
+    uint4 rk[2], rv[2];
+    load_kv(rk, rv, gk, gv, 0, n, a.in.stride_n, tid);
+    const int n_chunks = (n + C - 1) / C;
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        const int nt = min(C, n - chunk * C);
+        stage_chunk<false>(nullptr, sV, sKh, sKl, tabC, rk, rv, tid, nt, pos, lg);
+        pos.advance();
+        __syncthreads();
+        if (chunk + 1 < n_chunks) load_kv(rk, rv, gk, gv, (chunk + 1) * C, n, a.in.stride_n, tid);
+        Frag fv[4];
+        load_v_frags(fv, sV, wc, lane);
+        state_update(accS, sKh, sKl, fv, wa, lane);
+        const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accS[r] *= r_end;
+        __syncthreads();                                   // tiles free for the next chunk
+    }
+    float *u = a.seg_states + ((int64_t)bh * G1 + seg) * D * D;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        u[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32] = accS[r];
+}
+
+// ------------------------------------------------------------------------------------------
+// Full pass: workgroup (bh, seg) walks the chunks of its segment.
+// ------------------------------------------------------------------------------------------
 template <int OUT_BF16>
 __global__ void __launch_bounds__(kThreads, 2)
 forward_mfma_kernel(ForwardArgs a)
@@ -130,12 +311,13 @@ forward_mfma_kernel(ForwardArgs a)
     uint16_t *sSl = sSh + D * RS;      // S^T lo
     uint16_t *sO = sSl + D * RS;       // output tile [token][dv] bf16
 
-    const int bh = blockIdx.x;
+    const int G = a.n_segments;
+    const int bh = blockIdx.x / G, seg = blockIdx.x - bh * G;
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const float gamma = a.gamma[h];
     const float lg = log2f(gamma);
     if (!(lg * (float)C > -64.0f)) {   // gamma <= 0.5 (or 0): separable factors could overflow
-        recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);
+        if (seg == 0) recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);   // whole sequence
         return;
     }
 
@@ -143,15 +325,29 @@ forward_mfma_kernel(ForwardArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int wa = wave >> 1, wc = wave & 1;     // key-channel half, value-channel half
     const int l32 = lane & 31, g = lane >> 5;    // column inside the 32-wide tile, k-group
-    const int W = a.grid_w;
-    const float rcpW = 1.0f / (float)W;
 
-    const uint16_t *gq = (const uint16_t *)a.q + (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
-    const uint16_t *gk = (const uint16_t *)a.k + (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
-    const uint16_t *gv = (const uint16_t *)a.v + (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
-    const int64_t o_base = (int64_t)b * a.out.stride_b + (int64_t)h * a.out.stride_h;
+    const int seg_t0 = seg * a.seg_chunks * C;                 // first token of this segment
+    const int n = min(a.seg_chunks * C, a.n_tokens - seg_t0);   // tokens in this segment
+    const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + (int64_t)seg_t0 * a.in.stride_n;
+    const uint16_t *gq = (const uint16_t *)a.q + in_base;
+    const uint16_t *gk = (const uint16_t *)a.k + in_base;
+    const uint16_t *gv = (const uint16_t *)a.v + in_base;
+    const int64_t o_base = (int64_t)b * a.out.stride_b + (int64_t)h * a.out.stride_h + (int64_t)seg_t0 * a.out.stride_n;
+
+    // first loads go out before the incoming state is assembled
+    uint4 rk[2], rv[2];
+    Frag fqn[4];
+    auto prefetch = [&](int chunk) {
+        load_kv(rk, rv, gk, gv, chunk * C, n, a.in.stride_n, tid);
+        const int qtok = min(chunk * C + (wa ^ (chunk & 1)) * 32 + l32, n - 1);
+        const uint16_t *p = gq + (int64_t)qtok * a.in.stride_n + 8 * g;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);
+    };
+    prefetch(0);
 
     // --- state accumulators: S[dk = wa*32 + 8*(r/4) + 4*g + r%4][dv = wc*32 + l32] ---
+    // incoming state = caller's state folded through the segments before this one
     f32x16 accS;
     bool have_state = a.state_in != nullptr;
     if (have_state) {
@@ -162,6 +358,18 @@ forward_mfma_kernel(ForwardArgs a)
     } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) accS[r] = 0.f;
+    }
+    for (int sp = 0; sp < seg; ++sp) {
+        const int begin = a.start_pos + sp * a.seg_chunks * C;
+        const int de = range_exponent(begin, begin + a.seg_chunks * C, a.grid_w, a.mode);
+        const float dec = de == 0 ? 1.0f : __builtin_amdgcn_exp2f((float)de * lg);
+        const float *u = a.seg_states + ((int64_t)bh * (G - 1) + sp) * D * D;
+        float ur[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ur[r] = u[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accS[r] = fmaf(dec, accS[r], ur[r]);
+        have_state = true;
     }
     // bf16 hi/lo copy of S^T for the Q S product of the next chunk
     auto publish_state = [&]() {
@@ -177,77 +385,31 @@ forward_mfma_kernel(ForwardArgs a)
     };
     if (have_state) publish_state();
 
-    const int n_chunks = (a.n_tokens + C - 1) / C;
+    ChunkPos pos;
+    pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
 
-    // Position bookkeeping: col0 = (tokens before the chunk) mod W.  The number of boundary
-    // positions among the first j+1 tokens of the chunk is floor((j + xoff) / W) with a small
-    // per-chunk offset xoff, so e_j = j + 1 - floor((j + xoff) / W).
-    int col0 = a.start_pos % W;
-
-    // global -> register staging of K and V: 16 B pieces (row = tid/8 + 32*it, piece = tid%8);
-    // Q: this lane's operand fragments of query row l32 of the wave's query half.
-    uint4 rk[2], rv[2];
-    Frag fqn[4];
-    // Loads are unconditional (the token index is clamped into the sequence): nothing
-    // touches the loaded registers until the next chunk is staged, so the loads stay in
-    // flight behind this chunk's arithmetic.  Rows past the end are zeroed at staging.
-    auto prefetch = [&](int chunk) {
-        const int t0 = chunk * C;
-        const int last = a.n_tokens - 1;
+    // causal mask of a diagonal 32 x 32 score block in block-local coordinates (loop invariant):
+    // bit 4*qd + e is set when key 8*qd + 4*g + e is at or before query l32
+    uint32_t causal_bits = 0;
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int tok = t0 + (tid >> 3) + 32 * it;
-            const int64_t off = (int64_t)min(tok, last) * a.in.stride_n + (tid & 7) * 8;
-            rk[it] = *(const uint4 *)(gk + off);
-            rv[it] = *(const uint4 *)(gv + off);
-        }
-        const int qtok = t0 + (wa ^ (chunk & 1)) * 32 + l32;
-        const uint16_t *p = gq + (int64_t)min(qtok, last) * a.in.stride_n + 8 * g;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);
-    };
-    prefetch(0);
+    for (int r = 0; r < 16; ++r) causal_bits |= (8 * (r / 4) + 4 * g + (r % 4) <= l32 ? 1u : 0u) << r;
 
+    const int n_chunks = (n + C - 1) / C;
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
-        const int nt = min(C, a.n_tokens - t0);
+        const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
 
         PROF(0);
-        // ---- stage K, V and the decayed keys c_j K (hi + lo) into LDS ----
-        int xoff = 0;
-        if (a.mode == LASAD_RESET_LAST_COL) xoff = col0 + 1;
-        else if (a.mode == LASAD_RESET_FIRST_COL) xoff = col0 ? col0 : W;
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int row = (tid >> 3) + 32 * it;
-            const int col = (tid & 7) * 8;
-            if (row >= nt) rk[it] = rv[it] = make_uint4(0, 0, 0, 0);   // tail chunk only
-            const int nb = a.mode == LASAD_RESET_NONE ? 0 : small_div(row + xoff, W, rcpW);
-            const float cj = __builtin_amdgcn_exp2f(-(float)(row + 1 - nb) * lg);   // gamma^{-e_j}
-            if ((tid & 7) == 0) tabC[row] = cj;
-            const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2)
-                split2(__uint_as_float(kw[w2] << 16) * cj, __uint_as_float(kw[w2] & 0xffff0000u) * cj,
-                       hi[w2], lo[w2]);
-            *(uint4 *)&sK[row * RS + col] = rk[it];
-            *(uint4 *)&sV[row * VS + col] = rv[it];
-            *(uint4 *)&sKh[row * VS + col] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-            *(uint4 *)&sKl[row * VS + col] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-        }
+        stage_chunk<true>(sK, sV, sKh, sKl, tabC, rk, rv, tid, nt, pos, lg);
+        pos.advance();
         Frag fq[4];
-        {
-            const uint32_t keep = (qa * 32 + l32) < nt ? 0xffffffffu : 0u;   // query rows past the end
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                fq[s].u = make_uint4(fqn[s].u.x & keep, fqn[s].u.y & keep, fqn[s].u.z & keep, fqn[s].u.w & keep);
+        for (int s = 0; s < 4; ++s) fq[s].u = fqn[s].u;
+        if (nt < C && qa * 32 + l32 >= nt) {              // tail chunk: query rows past the end
+#pragma unroll
+            for (int s = 0; s < 4; ++s) fq[s].u = make_uint4(0, 0, 0, 0);
         }
-        // next chunk's col0
-        col0 += C;
-        if (W > 128) col0 -= col0 >= W ? W : 0;
-        else col0 -= W * small_div(col0, W, rcpW);
 
         PROF(1);
         __syncthreads();                                  // (A) tiles, c_j table and S^T visible
@@ -255,13 +417,11 @@ forward_mfma_kernel(ForwardArgs a)
         if (chunk + 1 < n_chunks) prefetch(chunk + 1);
 
         const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
-        const int trow = (lane & 15) >> 2;                // transpose reads: row inside the 4-row group
-        const int tsub = 16 * (l32 >> 4) + 4 * (lane & 3);
 
         // ---- scores of key block 0, P^T[j][i] = sum_d K[j][d] Q[i][d] ----
         f32x16 acc0, acc1, accO;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = accO[r] = 0.f;
+        for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; accO[r] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             Frag fk;
@@ -288,24 +448,10 @@ forward_mfma_kernel(ForwardArgs a)
                 acc1 = mfma(fk, fq[s], acc1);
             }
         }
-        // ---- V fragments: value channel n = wc*32 + l32, token rows 16*s + 4*g + {0..3} and + 8 ----
+        // ---- state update (independent of the scores) ----
         Frag fv[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            fv[s].h[0] = tr_read(&sV[(16 * s + 4 * g + trow) * VS + wc * 32 + tsub]);
-            fv[s].h[1] = tr_read(&sV[(16 * s + 8 + 4 * g + trow) * VS + wc * 32 + tsub]);
-        }
-        // ---- state: S[dk][dv] += sum_j (c_j K[j][dk]) V[j][dv]  (independent of the scores) ----
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            Frag fkt;
-            fkt.h[0] = tr_read(&sKh[(16 * s + 4 * g + trow) * VS + wa * 32 + tsub]);
-            fkt.h[1] = tr_read(&sKh[(16 * s + 8 + 4 * g + trow) * VS + wa * 32 + tsub]);
-            accS = mfma(fkt, fv[s], accS);
-            fkt.h[0] = tr_read(&sKl[(16 * s + 4 * g + trow) * VS + wa * 32 + tsub]);
-            fkt.h[1] = tr_read(&sKl[(16 * s + 8 + 4 * g + trow) * VS + wa * 32 + tsub]);
-            accS = mfma(fkt, fv[s], accS);
-        }
+        load_v_frags(fv, sV, wc, lane);
+        state_update(accS, sKh, sKl, fv, wa, lane);
 
         PROF(3);
         // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
@@ -314,13 +460,14 @@ forward_mfma_kernel(ForwardArgs a)
         auto mask_split = [&](const f32x16 &acc, int jb, bool diagonal, Frag *ph, Frag *pl) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                const int j0 = jb * 32 + 8 * qd + 4 * g;
-                const float4 c4 = *(const float4 *)&tabC[j0];
+                const float4 c4 = *(const float4 *)&tabC[jb * 32 + 8 * qd + 4 * g];
                 float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
                 float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
                 if (diagonal) {
-                    p0 = (j0 + 0 <= i_row) ? p0 : 0.f; p1 = (j0 + 1 <= i_row) ? p1 : 0.f;
-                    p2 = (j0 + 2 <= i_row) ? p2 : 0.f; p3 = (j0 + 3 <= i_row) ? p3 : 0.f;
+                    p0 = (causal_bits >> (4 * qd + 0)) & 1 ? p0 : 0.f;
+                    p1 = (causal_bits >> (4 * qd + 1)) & 1 ? p1 : 0.f;
+                    p2 = (causal_bits >> (4 * qd + 2)) & 1 ? p2 : 0.f;
+                    p3 = (causal_bits >> (4 * qd + 3)) & 1 ? p3 : 0.f;
                 }
                 uint2 hi, lo;
                 split2(p0, p1, hi.x, lo.x);
@@ -393,7 +540,7 @@ forward_mfma_kernel(ForwardArgs a)
         PROF(7);
     }
 
-    if (a.state_out) {
+    if (a.state_out && seg == G - 1) {
         float *s1 = a.state_out + (int64_t)bh * D * D;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -403,10 +550,47 @@ forward_mfma_kernel(ForwardArgs a)
 
 }  // namespace
 
-hipError_t launch_forward_mfma(const ForwardArgs &a, hipStream_t s)
+// Segments per sequence for `n_seq` sequences of `n_chunks` chunks: enough workgroups to fill
+// the chip's resident slots (2 per compute unit) once.  Short sequences stay whole (two
+// launches cost more than their few chunks), and a workgroup folds at most kMaxSegments - 1
+// partial states.
+constexpr int kMaxSegments = 8;
+constexpr int kMinChunksToSplit = 8;
+void plan_segments(int64_t n_seq, int n_chunks, int *n_segments, int *seg_chunks)
 {
-    if (a.d != D || a.io_dtype != LASAD_BF16) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(a.B * a.Hh)), block(kThreads);
+    const int64_t slots = 512;
+    int G = (int)(slots / (n_seq > 0 ? n_seq : 1));
+    if (n_chunks < kMinChunksToSplit) G = 1;
+    if (G > kMaxSegments) G = kMaxSegments;
+    if (G > n_chunks / 2) G = n_chunks / 2;          // at least two chunks per segment
+    if (G < 1) G = 1;
+    const int L = (n_chunks + G - 1) / G;
+    *seg_chunks = L > 0 ? L : 1;
+    *n_segments = L > 0 ? (n_chunks + L - 1) / L : 1;
+}
+
+size_t forward_mfma_workspace_bytes(int64_t n_seq, int n_tokens)
+{
+    int G, L;
+    plan_segments(n_seq, (n_tokens + C - 1) / C, &G, &L);
+    return G > 1 ? (size_t)n_seq * (G - 1) * D * D * sizeof(float) : 0;
+}
+
+hipError_t launch_forward_mfma(const ForwardArgs &a_in, hipStream_t s)
+{
+    if (a_in.d != D || a_in.io_dtype != LASAD_BF16 || a_in.n_tokens < 1) return hipErrorInvalidValue;
+    ForwardArgs a = a_in;
+    const int64_t n_seq = (int64_t)a.B * a.Hh;
+    if (a.seg_states) plan_segments(n_seq, (a.n_tokens + C - 1) / C, &a.n_segments, &a.seg_chunks);
+    else { a.n_segments = 1; a.seg_chunks = (a.n_tokens + C - 1) / C; }
+    if (n_seq * a.n_segments > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 block(kThreads);
+    if (a.n_segments > 1) {
+        hipLaunchKernelGGL(segment_state_kernel, dim3((unsigned)(n_seq * (a.n_segments - 1))), block, 0, s, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const dim3 grid((unsigned)(n_seq * a.n_segments));
     if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_kernel<1>, grid, block, 0, s, a);
     else hipLaunchKernelGGL(forward_mfma_kernel<0>, grid, block, 0, s, a);
     return hipGetLastError();

@@ -24,6 +24,9 @@ struct ForwardArgs {
     float q_scale;
     const float *state_in;
     float *state_out;
+    // segment-parallel plan of the MFMA kernel (filled by its launcher)
+    float *seg_states;           // workspace: [B*Hh][n_segments-1][d][d] fp32, or NULL
+    int n_segments, seg_chunks;
 };
 
 struct DecodeArgs {
@@ -43,6 +46,8 @@ hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int star
 hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s);
 // bf16 in, d == 64: MFMA chunked kernel.
 hipError_t launch_forward_mfma(const ForwardArgs &a, hipStream_t s);
+// device workspace the MFMA kernel wants for n_seq sequences of n_tokens tokens (0 = none)
+size_t forward_mfma_workspace_bytes(int64_t n_seq, int n_tokens);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 
 // ---- device helpers -----------------------------------------------------------

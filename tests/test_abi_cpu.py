@@ -45,7 +45,12 @@ def test_binding_names_match_header():
 
 def test_version_and_workspace(lib):
     assert b"gfx950" in lib.lasad_version()
-    assert lib.lasad_forward_workspace_bytes(8, 12, 256, 64, 1) == 0
+    # high-res stress: 96 sequences of 64 chunks -> 5 segments, 4 partial 64x64 fp32 states each
+    assert lib.lasad_forward_workspace_bytes(4, 24, 4096, 64, 1) == 96 * 4 * 64 * 64 * 4
+    assert lib.lasad_forward_workspace_bytes(8, 12, 256, 64, 1) == 0       # 4 chunks: not worth two launches
+    assert lib.lasad_forward_workspace_bytes(32, 16, 576, 64, 1) == 0      # 512 sequences fill the chip
+    assert lib.lasad_forward_workspace_bytes(4, 24, 4096, 64, 0) == 0      # fp32 kernel needs none
+    assert lib.lasad_forward_workspace_bytes(4, 24, 4096, 32, 1) == 0
 
 
 class Layout(ctypes.Structure):
@@ -62,7 +67,8 @@ def _forward(lib, **kw):
                                      ctypes.byref(a["lq"]), ctypes.byref(a["lo"]), a["io"], a["out"],
                                      a["B"], a["Hh"], a["d"], a["gh"], a["gw"], a["sp"], a["n"],
                                      vp(a["gamma"]), a["mode"], ctypes.c_float(a["qs"]),
-                                     vp(a["s_in"]), vp(a["s_out"]), None, ctypes.c_size_t(0), None)
+                                     vp(a["s_in"]), vp(a["s_out"]), vp(a.get("ws")),
+                                     ctypes.c_size_t(a.get("ws_bytes", 0)), None)
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -70,6 +76,8 @@ def _forward(lib, **kw):
     (dict(sp=2, n=3), 1), (dict(sp=-1), 1), (dict(n=-1), 1), (dict(io=2), 1), (dict(io=0, out=1), 2),
     (dict(q=None), 1), (dict(gamma=None), 1), (dict(q=0x1004), 1), (dict(o=0x1000), 1),
     (dict(lq=Layout(512, 127, 64)), 1), (dict(lq=Layout(512, 32, 64)), 1), (dict(s_in=0x6008), 1),
+    (dict(B=4, Hh=24, gh=64, gw=64, n=4096, lq=Layout(4096 * 1536, 1536, 64), lo=Layout(4096 * 1536, 1536, 64),
+          ws=0x7000, ws_bytes=1024), 3),
 ])
 def test_forward_rejects_bad_arguments_before_launch(lib, kw, code):
     """Every call here fails validation, so no kernel is launched (the pointers are fake)."""

@@ -34,7 +34,7 @@ def _odt(name):
 
 
 def _gpu_forward(lasad, w, q, k, v, g, *, start_pos=0, n=None, mode=0, q_scale=1.0, s0=None,
-                 want_state=False, out_dtype=None):
+                 want_state=False, out_dtype=None, use_workspace=True):
     torch = _torch()
     n = q.shape[1] if n is None else n
     tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
@@ -43,7 +43,7 @@ def _gpu_forward(lasad, w, q, k, v, g, *, start_pos=0, n=None, mode=0, q_scale=1
     ts1 = torch.empty((q.shape[0], q.shape[2], w.d, w.d), dtype=torch.float32, device="cuda") if want_state else None
     o = lasad.lasad_forward_chunked(tq, tk, tv, tg, w.grid_h, w.grid_w, start_pos=start_pos,
                                     boundary_mode=mode, q_scale=q_scale, state_in=ts0, state_out=ts1,
-                                    out_dtype=out_dtype)
+                                    out_dtype=out_dtype, use_workspace=use_workspace)
     torch.cuda.synchronize()
     o = o.float().cpu().numpy()
     return (o, ts1.cpu().numpy()) if want_state else o
@@ -78,13 +78,15 @@ def test_forward_tiny_fp32(lasad, oracle):
     assert rel_err(s_got, s_ref) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("segmented", [True, False], ids=["segments", "single_pass"])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
-def test_forward_base_prefill_full(lasad, oracle, out):
+def test_forward_base_prefill_full(lasad, oracle, out, segmented):
     w = wl.BASE_PREFILL
     q, k, v, g = wl.prefill_inputs(w)
     lam, _ = oracle.decay_factors(g, w.grid_h, w.grid_w, 0, w.N)
     ref, s_ref = oracle.forward_fullmask(q, k, v, lam, want_state=True)
-    got, s_got = _gpu_forward(lasad, w, q, k, v, g, want_state=True, out_dtype=_odt(out))
+    got, s_got = _gpu_forward(lasad, w, q, k, v, g, want_state=True, out_dtype=_odt(out),
+                              use_workspace=segmented)
     assert parity_err(got, ref, out == "bf16") <= TOL["bf16"]
     assert rel_err(s_got, s_ref) <= TOL["bf16"]
 
@@ -154,6 +156,27 @@ def test_forward_carried_state_mid_row(lasad, oracle, dtype, start, n):
     if n > 0:
         assert parity_err(got, ref, dtype == "bf16") <= TOL[dtype]
     assert rel_err(s_got, s_ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("name,B,Hh,H,W", [("seg_ragged", 1, 3, 33, 19), ("seg_two", 2, 2, 32, 16), ("seg_long", 1, 1, 40, 33), ("seg_many", 70, 1, 24, 24)])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_forward_segmented_vs_oracle(lasad, oracle, name, B, Hh, H, W, mode):
+    """Few sequences of several chunks: the segment-parallel plan (state pass + full pass), with a
+    carried-in state, a ragged last chunk, and one head whose small gamma takes the fp32 recurrence."""
+    torch = _torch()
+    w = wl.Workload(name, B, Hh, 64, H, W, "bf16", 0.6, 0.999, seed=zlib.crc32(name.encode()) % 1000 + mode)
+    q, k, v, g = wl.prefill_inputs(w)
+    if Hh >= 3:
+        g[1] = 0.3
+    assert lasad.lasad_forward_workspace_bytes(B, Hh, w.N, 64, lasad.BF16) > 0
+    s0 = wl.random_state(w, seed=11)
+    lam, _ = oracle.decay_factors(g, H, W, 0, w.N, mode)
+    ref, s_ref = oracle.forward_fullmask(q, k, v, lam, s0=s0.astype(np.float64), want_state=True)
+    for segmented in (True, False):
+        got, s_got = _gpu_forward(lasad, w, q, k, v, g, mode=mode, s0=s0, want_state=True,
+                                  out_dtype=torch.float32, use_workspace=segmented)
+        assert rel_err(got, ref) <= TOL["bf16"], segmented
+        assert rel_err(s_got, s_ref) <= TOL["bf16"], segmented
 
 
 def test_forward_split_equals_single_call_on_gpu(lasad, oracle):
