@@ -32,13 +32,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/);
-# None until a counter run for that workload has been recorded.
+# HBM bytes per step (read + write, all kernels of the step) measured with two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a 256 MiB device copy; the
+# summaries are profiles/*_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "base_prefill_16x16": None,
-    "large_prefill_24x24": None,
-    "highres_64x64": None,
-    "ar_decode_16x16": None,
+    "base_prefill_16x16": 12826733,      # algorithmic 12582912
+    "large_prefill_24x24": 151222649,    # algorithmic 150994944
+    "highres_64x64": 305424902,          # algorithmic 201326592; the segment plan re-reads K, V once
+    "ar_decode_16x16": 170448108,        # algorithmic 170393600
 }
 
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
@@ -55,6 +56,9 @@ def parse():
     p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run three plain 256 MiB device copies (reference dispatches of known "
+                        "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return p.parse_args()
 
 
@@ -223,6 +227,14 @@ def main():
     from paper_2507_01652_amd import binding as lasad, workloads as wl
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     lasad.load()
+
+    if args.calibrate_copy:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     pre = bench_prefill(args, torch, lasad, wl)
     w = pre["workload"]
