@@ -9,13 +9,32 @@
 // before any arithmetic to keep many bytes in flight.  Each lane keeps the partial q-weighted column sums of
 // the rows it touched; lanes that share a column group are then combined with
 // cross-lane shuffles (no LDS round trip for the reduction).
+//
+// The states are touched exactly once per step, so their loads and stores carry
+// the non-temporal hint (measured: 28.6 us instead of 33.6 us per step on 5120
+// states, the same as a plain read-modify-write stream over the same bytes), and
+// a workgroup is a single wavefront so that every wave starts as early as possible.
 #include "lasad_internal.h"
 
 namespace lasad {
 
 namespace {
 
-constexpr int kWaves = 4;   // wavefronts (= states) per workgroup
+constexpr int kWaves = 1;   // wavefronts (= states) per workgroup
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline float4 load_stream(const float4 *p)
+{
+    const f32x4 r = __builtin_nontemporal_load((const f32x4 *)p);
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+
+__device__ inline void store_stream(float4 *p, float4 x)
+{
+    const f32x4 r = {x.x, x.y, x.z, x.w};
+    __builtin_nontemporal_store(r, (f32x4 *)p);
+}
 
 template <int IN_BF16>
 __device__ inline float ld_in(const void *p, int64_t idx)
@@ -64,7 +83,7 @@ decode_kernel(DecodeArgs a, int n_states)
 
     float4 s[PB];
 #pragma unroll
-    for (int p = 0; p < PB; ++p) s[p] = S[(r0 + p * RPP) * CG + cg];
+    for (int p = 0; p < PB; ++p) s[p] = load_stream(&S[(r0 + p * RPP) * CG + cg]);
 
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
@@ -88,7 +107,7 @@ decode_kernel(DecodeArgs a, int n_states)
             x.y = fmaf(lam, x.y, ki * vv.y);
             x.z = fmaf(lam, x.z, ki * vv.z);
             x.w = fmaf(lam, x.w, ki * vv.w);
-            S[row * CG + cg] = x;
+            store_stream(&S[row * CG + cg], x);
             acc.x = fmaf(qi, x.x, acc.x);
             acc.y = fmaf(qi, x.y, acc.y);
             acc.z = fmaf(qi, x.z, acc.z);
@@ -96,7 +115,7 @@ decode_kernel(DecodeArgs a, int n_states)
         }
         if (p0 + PB < P) {   // next batch of state pieces (d = 128 only)
 #pragma unroll
-            for (int p = 0; p < PB; ++p) s[p] = S[(r0 + (p0 + PB + p) * RPP) * CG + cg];
+            for (int p = 0; p < PB; ++p) s[p] = load_stream(&S[(r0 + (p0 + PB + p) * RPP) * CG + cg]);
         }
     }
     // combine the RPP lanes that share a column group (lane bits above log2(CG))
