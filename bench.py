@@ -56,6 +56,8 @@ def parse():
     p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    p.add_argument("--buffer-sets", type=int, default=0,
+                   help="prefill buffer sets in rotation (0 = enough for > 1 GB; 1 = warm caches)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run three plain 256 MiB device copies (reference dispatches of known "
                         "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -90,7 +92,7 @@ def bench_prefill(args, torch, lasad, wl):
     tg = torch.from_numpy(gam).cuda()
     token_heads = w.B * w.N * w.Hh
     bytes_per_launch = token_heads * 4 * w.d * 2            # q, k, v read + o written, bf16
-    sets = max(4, min(96, -(-(1 << 30) // bytes_per_launch)))
+    sets = args.buffer_sets if args.buffer_sets > 0 else max(4, min(96, -(-(1 << 30) // bytes_per_launch)))
     bufs = [(tq, tk, tv, torch.empty_like(tq))]
     for _ in range(sets - 1):
         bufs.append((tq.clone(), tk.clone(), tv.clone(), torch.empty_like(tq)))

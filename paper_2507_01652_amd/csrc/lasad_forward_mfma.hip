@@ -76,6 +76,17 @@ __device__ long long g_prof[16 * 64];
 #define PROF(slot) do { } while (0)
 #endif
 
+// Schedule switches of the full-pass kernel (chosen by measurement on the large-prefill shape).
+#ifndef OPT_DIRECT_O
+#define OPT_DIRECT_O 0        // 1: store the output tile from registers; 0: through LDS, 16-byte rows
+#endif
+#ifndef OPT_EARLY_PUBLISH
+#define OPT_EARLY_PUBLISH 0   // 1: publish S^T mid-chunk into a second LDS buffer; 0: after barrier B
+#endif
+#ifndef OPT_EARLY_PREP
+#define OPT_EARLY_PREP 1      // 1: scale/split the next chunk's keys before barrier B; 0: after it
+#endif
+
 constexpr int C = 64;      // chunk length (tokens)
 constexpr int D = 64;      // head dim
 constexpr int kThreads = 256;
@@ -103,12 +114,29 @@ __device__ inline f32x16 mfma(const Frag &a, const Frag &b, f32x16 acc)
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc, 0, 0, 0);
 }
 
-// split a pair of fp32 values into packed bf16 hi (round to nearest) and lo (residual)
-__device__ inline void split2(float x0, float x1, uint32_t &hi, uint32_t &lo)
+// Constants of the hi/lo split: the packed bf16 pairs (-1, 0) and (0, -1).  They are kept
+// opaque to the compiler (in VGPRs) because, folded into an inline constant of
+// v_dot2c_f32_bf16, -1.0 is encoded in the fp16 format and the product comes out wrong.
+struct SplitConst {
+    bf16x2 m10, m01;
+    __device__ void init()
+    {
+        uint32_t a = 0x0000BF80u, b = 0xBF800000u;
+        asm volatile("" : "+v"(a), "+v"(b));
+        m10 = __builtin_bit_cast(bf16x2, a);
+        m01 = __builtin_bit_cast(bf16x2, b);
+    }
+};
+
+// split a pair of fp32 values into packed bf16 hi (round to nearest) and lo (the residual
+// x - hi, exact in fp32, formed as x + (-1) * hi by one bf16 dot-product instruction each)
+__device__ inline void split2(float x0, float x1, uint32_t &hi, uint32_t &lo, const SplitConst &sc)
 {
     hi = pack2(x0, x1);
-    const float h0 = __uint_as_float(hi << 16), h1 = __uint_as_float(hi & 0xffff0000u);
-    lo = pack2(x0 - h0, x1 - h1);
+    const bf16x2 hv = __builtin_bit_cast(bf16x2, hi);
+    const float l0 = __builtin_amdgcn_fdot2_f32_bf16(hv, sc.m10, x0, false);
+    const float l1 = __builtin_amdgcn_fdot2_f32_bf16(hv, sc.m01, x1, false);
+    lo = pack2(l0, l1);
 }
 
 // number of boundary positions among x small offsets: floor(x / W), 0 <= x < W + 128
@@ -150,12 +178,15 @@ struct ChunkPos {
     }
 };
 
-// Stage one chunk's K, V (as loaded) and the decayed keys c_j K[j][:] (bf16 hi + lo) into LDS;
-// every thread handles the two 16-byte pieces it loaded (rows tid/8 and tid/8 + 32).
-template <bool RAW_K>
-__device__ inline void stage_chunk(uint16_t *sK, uint16_t *sV, uint16_t *sKh, uint16_t *sKl, float *tabC,
-                                   uint4 (&rk)[2], uint4 (&rv)[2], int tid, int nt,
-                                   const ChunkPos &pos, float lg)
+// Decayed keys of one chunk, in registers: every thread scales the two 16-byte pieces of K it
+// loaded (rows tid/8 and tid/8 + 32) by c_j = gamma^{-e_j} and splits them into bf16 hi + lo.
+struct StagedKeys {
+    uint4 hi[2], lo[2];
+    float cj[2];
+};
+
+__device__ inline void prepare_keys(StagedKeys &st, uint4 (&rk)[2], uint4 (&rv)[2], int tid, int nt,
+                                    const ChunkPos &pos, float lg, const SplitConst &sc)
 {
     const int xo = pos.xoff();
     if (nt < C) {                                   // tail chunk: rows past the end are zero
@@ -166,19 +197,33 @@ __device__ inline void stage_chunk(uint16_t *sK, uint16_t *sV, uint16_t *sKh, ui
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int row = (tid >> 3) + 32 * it;
-        const int col = (tid & 7) * 8;
         const float cj = __builtin_amdgcn_exp2f(-(float)pos.e_of(row, xo) * lg);   // gamma^{-e_j}
-        if ((tid & 7) == 0) tabC[row] = cj;
+        st.cj[it] = cj;
         const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int w2 = 0; w2 < 4; ++w2)
             split2(__uint_as_float(kw[w2] << 16) * cj, __uint_as_float(kw[w2] & 0xffff0000u) * cj,
-                   hi[w2], lo[w2]);
+                   hi[w2], lo[w2], sc);
+        st.hi[it] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        st.lo[it] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
+}
+
+// Write one chunk's K, V (as loaded), decayed keys (hi, lo) and the table of c_j to LDS.
+template <bool RAW_K>
+__device__ inline void write_tiles(uint16_t *sK, uint16_t *sV, uint16_t *sKh, uint16_t *sKl, float *tabC,
+                                   const uint4 (&rk)[2], const uint4 (&rv)[2], const StagedKeys &st, int tid)
+{
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int row = (tid >> 3) + 32 * it;
+        const int col = (tid & 7) * 8;
+        if ((tid & 7) == 0) tabC[row] = st.cj[it];
         if (RAW_K) *(uint4 *)&sK[row * RS + col] = rk[it];
         *(uint4 *)&sV[row * VS + col] = rv[it];
-        *(uint4 *)&sKh[row * VS + col] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-        *(uint4 *)&sKl[row * VS + col] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        *(uint4 *)&sKh[row * VS + col] = st.hi[it];
+        *(uint4 *)&sKl[row * VS + col] = st.lo[it];
     }
 }
 
@@ -262,6 +307,8 @@ segment_state_kernel(ForwardArgs a)
 
     ChunkPos pos;
     pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
+    SplitConst sc;
+    sc.init();
 
     f32x16 accS;
 #pragma unroll
@@ -272,7 +319,9 @@ segment_state_kernel(ForwardArgs a)
     const int n_chunks = (n + C - 1) / C;
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int nt = min(C, n - chunk * C);
-        stage_chunk<false>(nullptr, sV, sKh, sKl, tabC, rk, rv, tid, nt, pos, lg);
+        StagedKeys st;
+        prepare_keys(st, rk, rv, tid, nt, pos, lg, sc);
+        write_tiles<false>(nullptr, sV, sKh, sKl, tabC, rk, rv, st, tid);
         pos.advance();
         __syncthreads();
         if (chunk + 1 < n_chunks) load_kv(rk, rv, gk, gv, (chunk + 1) * C, n, a.in.stride_n, tid);
@@ -292,14 +341,22 @@ segment_state_kernel(ForwardArgs a)
 
 // ------------------------------------------------------------------------------------------
 // Full pass: workgroup (bh, seg) walks the chunks of its segment.
+//
+// Schedule of one chunk (two barriers):
+//   write the staged tiles (prepared during the previous chunk) to LDS          | barrier A
+//   issue the global loads of the next chunk (K, V pieces, Q fragments)
+//   scores K Q^T, Q S, state update K~^T V        (MFMA chains, operands from LDS)
+//   decay + causal mask, hi/lo split, P V          (VALU, then MFMA)
+//   scale and publish the new S^T (other LDS buffer), scale and store O straight from registers
+//   scale/split the next chunk's keys in registers (its loads have landed by now)  | barrier B
 // ------------------------------------------------------------------------------------------
 template <int OUT_BF16>
 __global__ void __launch_bounds__(kThreads, 2)
 forward_mfma_kernel(ForwardArgs a)
 {
-    // LDS: K tile (16-byte reads), V and decayed-K hi/lo tiles (transpose reads), S^T hi/lo,
-    // the bf16 output tile, the table of c_j.  The fp32-recurrence fallback reuses the block.
-    constexpr int kLdsHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;
+    // LDS: K tile (16-byte reads), V and decayed-K hi/lo tiles (transpose reads), two buffers of
+    // S^T hi/lo, the table of c_j.  The fp32-recurrence fallback reuses the block.
+    constexpr int kLdsHalfs = C * RS + 3 * C * VS + (OPT_EARLY_PUBLISH ? 4 : 2) * D * RS + (OPT_DIRECT_O ? 0 : C * RS);
     __shared__ __attribute__((aligned(16))) uint16_t smem[kLdsHalfs];
     __shared__ __attribute__((aligned(16))) float tabC[C];
     static_assert(kLdsHalfs * 2 >= recurrence_lds_floats<D>() * 4, "fallback needs the LDS block");
@@ -307,9 +364,10 @@ forward_mfma_kernel(ForwardArgs a)
     uint16_t *sV = sK + C * RS;
     uint16_t *sKh = sV + C * VS;
     uint16_t *sKl = sKh + C * VS;
-    uint16_t *sSh = sKl + C * VS;      // S^T hi [dv][dk]
-    uint16_t *sSl = sSh + D * RS;      // S^T lo
-    uint16_t *sO = sSl + D * RS;       // output tile [token][dv] bf16
+    uint16_t *sS = sKl + C * VS;       // S^T [buffer][hi, lo][dv][dk]
+#if !OPT_DIRECT_O
+    uint16_t *sO = sS + (OPT_EARLY_PUBLISH ? 4 : 2) * D * RS;   // bf16 output tile [token][dv]
+#endif
 
     const int G = a.n_segments;
     const int bh = blockIdx.x / G, seg = blockIdx.x - bh * G;
@@ -333,6 +391,9 @@ forward_mfma_kernel(ForwardArgs a)
     const uint16_t *gk = (const uint16_t *)a.k + in_base;
     const uint16_t *gv = (const uint16_t *)a.v + in_base;
     const int64_t o_base = (int64_t)b * a.out.stride_b + (int64_t)h * a.out.stride_h + (int64_t)seg_t0 * a.out.stride_n;
+
+    SplitConst sc;
+    sc.init();
 
     // first loads go out before the incoming state is assembled
     uint4 rk[2], rv[2];
@@ -371,48 +432,66 @@ forward_mfma_kernel(ForwardArgs a)
         for (int r = 0; r < 16; ++r) accS[r] = fmaf(dec, accS[r], ur[r]);
         have_state = true;
     }
-    // bf16 hi/lo copy of S^T for the Q S product of the next chunk
-    auto publish_state = [&]() {
+    // bf16 hi/lo copy of S^T for the Q S product of the next chunk, into buffer `buf`
+    auto publish_state = [&](int buf) {
+        uint16_t *sh = sS + buf * 2 * D * RS, *sl = sh + D * RS;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) {
             uint2 hi, lo;
-            split2(accS[4 * qd + 0], accS[4 * qd + 1], hi.x, lo.x);
-            split2(accS[4 * qd + 2], accS[4 * qd + 3], hi.y, lo.y);
+            split2(accS[4 * qd + 0], accS[4 * qd + 1], hi.x, lo.x, sc);
+            split2(accS[4 * qd + 2], accS[4 * qd + 3], hi.y, lo.y, sc);
             const int off = (wc * 32 + l32) * RS + wa * 32 + 8 * qd + 4 * g;
-            *(uint2 *)&sSh[off] = hi;
-            *(uint2 *)&sSl[off] = lo;
+            *(uint2 *)&sh[off] = hi;
+            *(uint2 *)&sl[off] = lo;
         }
     };
-    if (have_state) publish_state();
+    if (have_state) publish_state(0);
 
     ChunkPos pos;
     pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
 
     // causal mask of a diagonal 32 x 32 score block in block-local coordinates (loop invariant):
-    // bit 4*qd + e is set when key 8*qd + 4*g + e is at or before query l32
-    uint32_t causal_bits = 0;
+    // causal[4*qd + e] says whether key 8*qd + 4*g + e is at or before query l32
+    bool causal[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) causal_bits |= (8 * (r / 4) + 4 * g + (r % 4) <= l32 ? 1u : 0u) << r;
+    for (int r = 0; r < 16; ++r) causal[r] = 8 * (r / 4) + 4 * g + (r % 4) <= l32;
 
     const int n_chunks = (n + C - 1) / C;
+
+    // keys and Q fragments of chunk 0
+    StagedKeys st;
+    Frag fq[4];
+    auto take_q = [&](int chunk) {                        // prefetched Q fragments -> fq (tail rows zero)
+        const bool live = chunk * C + (wa ^ (chunk & 1)) * 32 + l32 < n;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
+    };
+#if OPT_EARLY_PREP
+    prepare_keys(st, rk, rv, tid, min(C, n), pos, lg, sc);
+    pos.advance();
+    take_q(0);
+#endif
+
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
+#if OPT_EARLY_PUBLISH
+        const int cur = chunk & 1;                        // S^T buffer read by this chunk
+#else
+        const int cur = 0;
+#endif
+        const uint16_t *sSh = sS + cur * 2 * D * RS, *sSl = sSh + D * RS;
 
         PROF(0);
-        stage_chunk<true>(sK, sV, sKh, sKl, tabC, rk, rv, tid, nt, pos, lg);
+#if !OPT_EARLY_PREP
+        prepare_keys(st, rk, rv, tid, nt, pos, lg, sc);
         pos.advance();
-        Frag fq[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) fq[s].u = fqn[s].u;
-        if (nt < C && qa * 32 + l32 >= nt) {              // tail chunk: query rows past the end
-#pragma unroll
-            for (int s = 0; s < 4; ++s) fq[s].u = make_uint4(0, 0, 0, 0);
-        }
-
+        take_q(chunk);
+#endif
+        write_tiles<true>(sK, sV, sKh, sKl, tabC, rk, rv, st, tid);
         PROF(1);
-        __syncthreads();                                  // (A) tiles, c_j table and S^T visible
+        __syncthreads();                                  // (A) tiles, c_j table and S^T[cur] visible
         PROF(2);
         if (chunk + 1 < n_chunks) prefetch(chunk + 1);
 
@@ -428,6 +507,7 @@ forward_mfma_kernel(ForwardArgs a)
             fk.u = *(const uint4 *)&sK[l32 * RS + 16 * s + 8 * g];
             acc0 = mfma(fk, fq[s], acc0);
         }
+        PROF(8);
         // ---- O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk]  (independent of the scores) ----
         if (have_state) {
 #pragma unroll
@@ -439,6 +519,7 @@ forward_mfma_kernel(ForwardArgs a)
                 accO = mfma(fs, fq[s], accO);
             }
         }
+        PROF(9);
         // ---- scores of key block 1 (all masked for the lower query half) ----
         if (qa == 1) {
 #pragma unroll
@@ -448,10 +529,21 @@ forward_mfma_kernel(ForwardArgs a)
                 acc1 = mfma(fk, fq[s], acc1);
             }
         }
+        PROF(10);
         // ---- state update (independent of the scores) ----
         Frag fv[4];
         load_v_frags(fv, sV, wc, lane);
+        PROF(11);
         state_update(accS, sKh, sKl, fv, wa, lane);
+#if OPT_EARLY_PUBLISH
+        {
+            const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accS[r] *= r_end;
+            have_state = true;
+            if (chunk + 1 < n_chunks) publish_state(cur ^ 1);   // read after the next barrier (A)
+        }
+#endif
 
         PROF(3);
         // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
@@ -464,14 +556,14 @@ forward_mfma_kernel(ForwardArgs a)
                 float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
                 float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
                 if (diagonal) {
-                    p0 = (causal_bits >> (4 * qd + 0)) & 1 ? p0 : 0.f;
-                    p1 = (causal_bits >> (4 * qd + 1)) & 1 ? p1 : 0.f;
-                    p2 = (causal_bits >> (4 * qd + 2)) & 1 ? p2 : 0.f;
-                    p3 = (causal_bits >> (4 * qd + 3)) & 1 ? p3 : 0.f;
+                    p0 = causal[4 * qd + 0] ? p0 : 0.f;
+                    p1 = causal[4 * qd + 1] ? p1 : 0.f;
+                    p2 = causal[4 * qd + 2] ? p2 : 0.f;
+                    p3 = causal[4 * qd + 3] ? p3 : 0.f;
                 }
                 uint2 hi, lo;
-                split2(p0, p1, hi.x, lo.x);
-                split2(p2, p3, hi.y, lo.y);
+                split2(p0, p1, hi.x, lo.x, sc);
+                split2(p2, p3, hi.y, lo.y, sc);
                 ph[qd / 2].h[qd % 2] = hi;
                 pl[qd / 2].h[qd % 2] = lo;
             }
@@ -479,12 +571,14 @@ forward_mfma_kernel(ForwardArgs a)
         {
             Frag ph[2], pl[2];
             mask_split(acc0, 0, qa == 0, ph, pl);
+            PROF(12);
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 accO = mfma(fv[s], ph[s], accO);
                 accO = mfma(fv[s], pl[s], accO);
             }
         }
+        PROF(13);
         if (qa == 1) {
             Frag ph[2], pl[2];
             mask_split(acc1, 1, true, ph, pl);
@@ -496,17 +590,41 @@ forward_mfma_kernel(ForwardArgs a)
         }
 
         PROF(4);
-        // ---- row factors: r_i on the outputs, r_end on the state ----
+        // ---- row factors ----
         {
             const float osc = a.q_scale * __builtin_amdgcn_rcpf(tabC[i_row]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accO[r] *= osc;
+#if !OPT_EARLY_PUBLISH
             const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { accO[r] *= osc; accS[r] *= r_end; }
+            for (int r = 0; r < 16; ++r) accS[r] *= r_end;
             have_state = true;
+#endif
         }
-
-        // ---- send the output tile out ----
-        if (OUT_BF16) {
+        // ---- the output tile: a lane owns four consecutive value channels of its query per quad ----
+#if OPT_DIRECT_O
+        if (i_row < nt) {
+            const int64_t off = o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
+            if (OUT_BF16) {
+                uint16_t *go = (uint16_t *)a.o + off;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    uint2 w2;
+                    w2.x = pack2(accO[4 * qd + 0], accO[4 * qd + 1]);
+                    w2.y = pack2(accO[4 * qd + 2], accO[4 * qd + 3]);
+                    *(uint2 *)(go + 8 * qd) = w2;
+                }
+            } else {
+                float *go = (float *)a.o + off;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
+                                                           accO[4 * qd + 2], accO[4 * qd + 3]);
+            }
+        }
+#else
+        if (OUT_BF16) {                                   // via LDS for 16-byte coalesced stores
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 uint2 w2;
@@ -515,17 +633,26 @@ forward_mfma_kernel(ForwardArgs a)
                 *(uint2 *)&sO[i_row * RS + wc * 32 + 8 * qd + 4 * g] = w2;
             }
         } else if (i_row < nt) {
-            // fp32 output: a lane owns 4 consecutive value channels of its query, 16-byte stores
             float *go = (float *)a.o + o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
+#endif
         PROF(5);
-        __syncthreads();                                  // (B) output tile complete; all tile and S^T reads finished
+#if OPT_EARLY_PREP
+        // ---- the next chunk's keys (scaled and split) and Q fragments, in registers ----
+        if (chunk + 1 < n_chunks) {
+            prepare_keys(st, rk, rv, tid, min(C, n - t0 - C), pos, lg, sc);
+            pos.advance();
+            take_q(chunk + 1);
+        }
+#endif
         PROF(6);
-
+        __syncthreads();                                  // (B) all reads of the tiles and of S^T[cur] finished
+        PROF(7);
+#if !OPT_DIRECT_O
         if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
             uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
@@ -536,8 +663,10 @@ forward_mfma_kernel(ForwardArgs a)
                         *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
             }
         }
-        if (chunk + 1 < n_chunks) publish_state();        // read after the next barrier (A)
-        PROF(7);
+#endif
+#if !OPT_EARLY_PUBLISH
+        if (chunk + 1 < n_chunks) publish_state(0);       // read after the next barrier (A)
+#endif
     }
 
     if (a.state_out && seg == G - 1) {
