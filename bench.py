@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 # runs (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a 256 MiB device copy; the
 # summaries are profiles/*_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "base_prefill_16x16": 12826733,      # algorithmic 12582912
-    "large_prefill_24x24": 151222649,    # algorithmic 150994944
-    "highres_64x64": 305424902,          # algorithmic 201326592; the segment plan re-reads K, V once
-    "ar_decode_16x16": 170448108,        # algorithmic 170393600
+    "base_prefill_16x16": 12828810,      # algorithmic 12582912
+    "large_prefill_24x24": 151224938,    # algorithmic 150994944
+    "highres_64x64": 305425015,          # algorithmic 201326592; the segment plan re-reads K, V once
+    "ar_decode_16x16": 170446445,        # algorithmic 170393600
 }
 
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
