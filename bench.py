@@ -56,6 +56,8 @@ def parse():
     p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    p.add_argument("--layout", default="bnhd", choices=["bnhd", "bhnd"],
+                   help="memory order of q, k, v, o: [B, N, Hh, d] (default) or [B, Hh, N, d]")
     p.add_argument("--buffer-sets", type=int, default=0,
                    help="prefill buffer sets in rotation (0 = enough for > 1 GB; 1 = warm caches)")
     p.add_argument("--calibrate-copy", action="store_true",
@@ -87,7 +89,7 @@ def capture(torch, fn):
 def bench_prefill(args, torch, lasad, wl):
     import numpy as np
     w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
-    q, k, v, gam = wl.prefill_inputs(w)
+    q, k, v, gam = wl.prefill_inputs(w, layout=args.layout)
     tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
     tg = torch.from_numpy(gam).cuda()
     token_heads = w.B * w.N * w.Hh
@@ -247,7 +249,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.B, "heads": w.Hh, "head_dim": w.d,
                    "grid": [w.grid_h, w.grid_w], "tokens_per_step": w.B * w.N, "chunk": 64,
-                   "io": "bf16 q,k,v in, bf16 o out, fp32 accumulation",
+                   "io": "bf16 q,k,v in, bf16 o out, fp32 accumulation", "layout": args.layout,
                    "timing": "HIP graph replay of the timed steps" if pre["graph_ms_per_step"] is not None else "eager launches",
                    "buffer_sets_in_rotation": pre["buffer_sets"]},
         "eager_ms_per_step": pre["eager_ms_per_step"],
