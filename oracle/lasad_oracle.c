@@ -260,6 +260,87 @@ int lasad_oracle_bruteforce(const double *q, const double *k, const double *v,
     return 0;
 }
 
+/* ------------------------------------------------------------------------------------------
+ * Vector, data-dependent decay: the recurrence exactly as Section 3.4 / Algorithm 1 state it.
+ * Every token carries its own decay vector lambda_t in [0,1]^d over the key channels,
+ *     s_t = diag(lambda_t^spatial) s_{t-1} + k_t v_t^T,   o_t^T = q_scale * q_t^T s_t,
+ * with lambda_t^spatial = 1 (every channel) at a row-boundary position and lambda_t elsewhere,
+ * and with the key tied to the decay, k_t = 1 - lambda_t (Section 3.4, "base decay factor"
+ * equation; Algorithm 1 sets k before the boundary override, so k_t keeps the base lambda_t
+ * also at a boundary).  When `k` is not NULL it is used instead of 1 - lambda (the gate of GLA
+ * with an independent key, Section 4.5).
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * Sequential form (the loop of Algorithm 1), state in fp64.
+ *   q, lam, k (or NULL), v, o : [B][Hh][n][d];  s0 / s_out : [B][Hh][d][d] or NULL.
+ *   Positions are start_pos+1 .. start_pos+n of a grid of width grid_w under rule `mode`.
+ */
+int lasad_oracle_gated_recurrent(const double *q, const double *lam, const double *k, const double *v,
+                                 double q_scale, const double *s0, double *o, double *s_out,
+                                 int B, int n_heads, int n, int d, int grid_w, int start_pos, int mode)
+{
+    if (!q || !lam || !v || !o || B < 1 || n_heads < 1 || n < 0 || d < 1 || grid_w < 1 || start_pos < 0) return 1;
+    if (mode < 0 || mode > 2) return 1;
+    int status = 0;
+    const int64_t n_seq = (int64_t)B * n_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < n_seq; ++bh) {
+        double *S = (double *)malloc(sizeof(double) * (size_t)d * d);
+        if (!S) {
+#pragma omp atomic write
+            status = 2;
+            continue;
+        }
+        if (s0) memcpy(S, s0 + (size_t)bh * d * d, sizeof(double) * (size_t)d * d);
+        else    memset(S, 0, sizeof(double) * (size_t)d * d);
+        for (int t = 0; t < n; ++t) {
+            const size_t off = ((size_t)bh * n + t) * d;
+            const int boundary = is_boundary((int64_t)start_pos + 1 + t, grid_w, mode);
+            for (int r = 0; r < d; ++r) {
+                const double l = lam[off + r];
+                const double kr = k ? k[off + r] : 1.0 - l;       /* key from the BASE decay */
+                const double ls = boundary ? 1.0 : l;             /* spatial-aware decay     */
+                for (int c = 0; c < d; ++c)
+                    S[(size_t)r * d + c] = ls * S[(size_t)r * d + c] + kr * v[off + c];
+            }
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < d; ++r) acc += q[off + r] * S[(size_t)r * d + c];
+                o[off + c] = q_scale * acc;
+            }
+        }
+        if (s_out) memcpy(s_out + (size_t)bh * d * d, S, sizeof(double) * (size_t)d * d);
+        free(S);
+    }
+    return status;
+}
+
+/*
+ * Brute force for tiny inputs, one sequence: unrolling the recurrence channel by channel,
+ *     o_i[c] = q_scale * sum_{j<=i} sum_r q_i[r] (prod_{s=j+1..i} lambda_s^spatial[r]) k_j[r] v_j[c],
+ * every product formed by its own loop; no state.  q, lam, k (or NULL), v, o: [n][d].
+ */
+int lasad_oracle_gated_bruteforce(const double *q, const double *lam, const double *k, const double *v,
+                                  double q_scale, double *o, int n, int d, int grid_w, int start_pos, int mode)
+{
+    if (!q || !lam || !v || !o || n < 0 || d < 1 || grid_w < 1 || mode < 0 || mode > 2) return 1;
+    for (int i = 0; i < n; ++i)
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j <= i; ++j)
+                for (int r = 0; r < d; ++r) {
+                    double decay = 1.0;
+                    for (int s = j + 1; s <= i; ++s)
+                        decay *= is_boundary((int64_t)start_pos + 1 + s, grid_w, mode) ? 1.0 : lam[(size_t)s * d + r];
+                    const double kr = k ? k[(size_t)j * d + r] : 1.0 - lam[(size_t)j * d + r];
+                    acc += q[(size_t)i * d + r] * decay * kr * v[(size_t)j * d + c];
+                }
+            o[(size_t)i * d + c] = q_scale * acc;
+        }
+    return 0;
+}
+
 /* Threads the OpenMP loops above will use (reported by the benchmark). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -56,6 +56,11 @@ def _load():
         lib.lasad_oracle_decode_step.restype = ci
         lib.lasad_oracle_bruteforce.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, ci, ci]
         lib.lasad_oracle_bruteforce.restype = ci
+        lib.lasad_oracle_gated_recurrent.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp,
+                                                     ci, ci, ci, ci, ci, ci, ci]
+        lib.lasad_oracle_gated_recurrent.restype = ci
+        lib.lasad_oracle_gated_bruteforce.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, ci, ci, ci, ci, ci]
+        lib.lasad_oracle_gated_bruteforce.restype = ci
         lib.lasad_oracle_num_threads.argtypes = []
         lib.lasad_oracle_num_threads.restype = ci
         _lib = lib
@@ -145,4 +150,41 @@ def bruteforce(q, k, v, lam, q_scale=1.0):
                                          _dptr(o), n, d)
     if rc != 0:
         raise RuntimeError(f"lasad_oracle_bruteforce failed (rc={rc})")
+    return o
+
+
+# ---- vector, data-dependent decay (Section 3.4 / Algorithm 1 as written) ----------------------
+
+def gated_recurrent(q, lam, v, grid_w, k=None, start_pos=0, mode=RESET_LAST_COL, q_scale=1.0, s0=None,
+                    want_state=False):
+    """Sequential recurrence with a decay vector per token.  q, lam, v (and k, or None for
+    k = 1 - lam): [B, n, Hh, d]; returns o [B, n, Hh, d] (and the final state [B, Hh, d, d])."""
+    q, lam, v = (np.asarray(x, dtype=np.float64) for x in (q, lam, v))
+    B, n, Hh, d = q.shape
+    assert lam.shape == q.shape and v.shape == q.shape
+    tr = lambda x: np.ascontiguousarray(x.transpose(0, 2, 1, 3))
+    qh, lh, vh = tr(q), tr(lam), tr(v)
+    kh = None if k is None else tr(np.asarray(k, dtype=np.float64))
+    oh = np.empty_like(qh)
+    s0c = None if s0 is None else _f64c(s0)
+    s_out = np.empty((B, Hh, d, d), dtype=np.float64) if want_state else None
+    rc = _load().lasad_oracle_gated_recurrent(_dptr(qh), _dptr(lh), _dptr(kh), _dptr(vh), float(q_scale),
+                                              _dptr(s0c), _dptr(oh), _dptr(s_out), B, Hh, n, d,
+                                              grid_w, start_pos, mode)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_gated_recurrent failed (rc={rc})")
+    o = np.ascontiguousarray(oh.transpose(0, 2, 1, 3))
+    return (o, s_out) if want_state else o
+
+
+def gated_bruteforce(q, lam, v, grid_w, k=None, start_pos=0, mode=RESET_LAST_COL, q_scale=1.0):
+    """Per-pair, per-channel sums for ONE sequence: q, lam, v (k) are [n, d]."""
+    q, lam, v = (_f64c(x) for x in (q, lam, v))
+    kc = None if k is None else _f64c(k)
+    n, d = q.shape
+    o = np.empty_like(q)
+    rc = _load().lasad_oracle_gated_bruteforce(_dptr(q), _dptr(lam), _dptr(kc), _dptr(v), float(q_scale),
+                                               _dptr(o), n, d, grid_w, start_pos, mode)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_gated_bruteforce failed (rc={rc})")
     return o
