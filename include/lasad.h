@@ -135,6 +135,37 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
                       const float *gamma, int boundary_mode, float q_scale,
                       float *state, void *hip_stream);
 
+/*
+ * Vector, data-dependent decay: the recurrence exactly as Section 3.4 / Algorithm 1 write it.
+ * Every token carries a decay vector lambda_t in [0, 1]^d over the key channels,
+ *     s_t = diag(lambda_t^spatial) s_{t-1} + k_t v_t^T,   o_t^T = q_scale * q_t^T s_t,
+ * lambda_t^spatial = 1 on every channel at a boundary position and lambda_t elsewhere.
+ *   lam   [B, n_tokens, n_heads, d], same strides and type as q (the post-sigmoid gate).
+ *   k     same shape, or NULL: then the key is tied to the base decay, k_t = 1 - lambda_t
+ *         (Section 3.4 "base decay factor" equation; the key keeps the base lambda_t also
+ *         at a boundary, Algorithm 1 sets it before the override).
+ * Everything else as in lasad_forward_chunked.  This first version walks each sequence with
+ * the fp32 recurrence on the vector ALUs (any supported d, fp32 or bf16 storage, fp32 state);
+ * it needs no workspace.
+ */
+int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
+                        const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
+                        int io_dtype, int out_dtype,
+                        int B, int n_heads, int d, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                        const float *state_in, float *state_out, void *hip_stream);
+
+/*
+ * Decode step of the vector-decay recurrence (Algorithm 1 loop body as written): one token for
+ * every (batch, head): row i of S is scaled by lambda[i] (1 at a boundary position), then
+ * S += k v^T with k = 1 - lambda when k is NULL, and o = q_scale * S^T q.
+ *   q, lam, k (or NULL), v  [B, n_heads, d] contiguous; state [B, n_heads, d, d] fp32 in place.
+ */
+int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
+                            int io_dtype, int out_dtype, int B, int n_heads, int d,
+                            int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                            float *state, void *hip_stream);
+
 /* Reason for the last non-OK status returned on this thread (static storage). */
 const char *lasad_last_error(void);
 

@@ -20,7 +20,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
-    "lasad_decode_step", "lasad_last_error", "lasad_version",
+    "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
+    "lasad_last_error", "lasad_version",
 )
 
 
@@ -58,6 +59,11 @@ def load() -> ctypes.CDLL:
     lib.lasad_forward_chunked.restype = ci
     lib.lasad_decode_step.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, cf, vp, vp]
     lib.lasad_decode_step.restype = ci
+    lib.lasad_forward_gated.argtypes = [vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                        ci, cf, vp, vp, vp]
+    lib.lasad_forward_gated.restype = ci
+    lib.lasad_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp]
+    lib.lasad_decode_step_gated.restype = ci
     lib.lasad_last_error.argtypes = []
     lib.lasad_last_error.restype = ctypes.c_char_p
     lib.lasad_version.argtypes = []
@@ -175,6 +181,55 @@ def lasad_decode_step(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: 
     _check(load().lasad_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _dtype_code(q), _dtype_code(out),
                                     B, Hh, d, grid_h, grid_w, pos, _ptr(gamma), boundary_mode, q_scale,
                                     _ptr(state), _stream(stream)))
+    return out
+
+
+def lasad_forward_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, grid_h: int, grid_w: int,
+                        k: torch.Tensor | None = None, start_pos: int = 0,
+                        boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                        state_in: torch.Tensor | None = None, state_out: torch.Tensor | None = None,
+                        out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                        stream=None) -> torch.Tensor:
+    """Vector-decay forward (Section 3.4 as written).  q, lam, v (and k, or None for k = 1 - lam):
+    logical [B, n, Hh, d] views sharing one set of strides; returns o."""
+    B, n, Hh, d = q.shape
+    for t in (lam, v) + (() if k is None else (k,)):
+        if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
+            raise ValueError("q, lam, k, v must share shape, strides and dtype")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape:
+        raise ValueError("out has the wrong shape")
+    for s in (state_in, state_out):
+        if s is not None and (s.dtype != torch.float32 or not s.is_contiguous() or tuple(s.shape) != (B, Hh, d, d)):
+            raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
+    lq, lo = _layout(q), _layout(out)
+    _check(load().lasad_forward_gated(
+        _ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(out), ctypes.byref(lq), ctypes.byref(lo),
+        _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, start_pos, n,
+        boundary_mode, q_scale, _ptr(state_in), _ptr(state_out), _stream(stream)))
+    return out
+
+
+def lasad_decode_step_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, state: torch.Tensor,
+                            grid_h: int, grid_w: int, pos: int, k: torch.Tensor | None = None,
+                            boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                            out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                            stream=None) -> torch.Tensor:
+    """One vector-decay decode step.  q, lam, v (k): contiguous [B, Hh, d]; state fp32 [B, Hh, d, d] in place."""
+    B, Hh, d = q.shape
+    for t in (q, lam, v) + (() if k is None else (k,)):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("q, lam, k, v must be contiguous [B, Hh, d] of one dtype")
+    if state.dtype != torch.float32 or not state.is_contiguous() or tuple(state.shape) != (B, Hh, d, d):
+        raise ValueError("state must be contiguous fp32 [B, Hh, d, d]")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hh, d]")
+    _check(load().lasad_decode_step_gated(_ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(out),
+                                          _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, pos,
+                                          boundary_mode, q_scale, _ptr(state), _stream(stream)))
     return out
 
 

@@ -114,7 +114,7 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
     if (n_tokens > 0 && (o == q || o == k || o == v)) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
 
     lasad::ForwardArgs a;
-    a.q = q; a.k = k; a.v = v; a.o = o;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lam = nullptr;
     a.in = *qkv_layout; a.out = *o_layout;
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
@@ -164,7 +164,7 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
     if (o == q || o == k || o == v) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
 
     lasad::DecodeArgs a;
-    a.q = q; a.k = k; a.v = v; a.o = o;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lam = nullptr;
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
     a.grid_w = grid_w; a.pos = pos;
@@ -172,6 +172,85 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
     a.state = state;
     hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_decode_step launch", e);
+    return LASAD_OK;
+}
+
+int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
+                        const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
+                        int io_dtype, int out_dtype,
+                        int B, int n_heads, int d, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                        const float *state_in, float *state_out, void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
+    if (start_pos < 0 || n_tokens < 0 || (int64_t)start_pos + n_tokens > (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "positions %d+1..%d+%d leave the %d x %d grid", start_pos, start_pos, n_tokens, grid_h, grid_w);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (out_dtype != LASAD_F32 && out_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "out_dtype %d", out_dtype);
+    if (io_dtype == LASAD_F32 && out_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 output");
+    if (!in_layout || !o_layout) return fail(LASAD_ERR_INVALID_ARG, "layout is NULL");
+    if (n_tokens > 0 && (!q || !lam || !v || !o)) return fail(LASAD_ERR_INVALID_ARG, "q, lam, v or o is NULL");
+    const int vec = io_dtype == LASAD_BF16 ? 8 : 4, ovec = out_dtype == LASAD_BF16 ? 8 : 4;
+    if (in_layout->stride_b % vec || in_layout->stride_n % vec || in_layout->stride_h % vec ||
+        in_layout->stride_b < 0 || in_layout->stride_n < 0 || in_layout->stride_h < 0)
+        return fail(LASAD_ERR_INVALID_ARG, "input strides must be non-negative multiples of %d elements", vec);
+    if (o_layout->stride_b % ovec || o_layout->stride_n % ovec || o_layout->stride_h % ovec ||
+        o_layout->stride_b < 0 || o_layout->stride_n < 0 || o_layout->stride_h < 0)
+        return fail(LASAD_ERR_INVALID_ARG, "o strides must be non-negative multiples of %d elements", ovec);
+    if (n_tokens > 0 && (in_layout->stride_n < d || o_layout->stride_n < d))
+        return fail(LASAD_ERR_INVALID_ARG, "token stride smaller than the head dim");
+    if (!aligned(q, 16) || !aligned(lam, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) ||
+        !aligned(state_in, 16) || !aligned(state_out, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "q, lam, k, v, o and the states must be 16-byte aligned");
+    if (n_tokens > 0 && (o == q || o == lam || o == v || (k && o == k))) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
+
+    lasad::ForwardArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lam = lam;
+    a.in = *in_layout; a.out = *o_layout;
+    a.io_dtype = io_dtype; a.out_dtype = out_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d;
+    a.grid_w = grid_w;
+    a.start_pos = start_pos; a.n_tokens = n_tokens;
+    a.gamma = nullptr; a.mode = boundary_mode; a.q_scale = q_scale;
+    a.state_in = state_in; a.state_out = state_out;
+    a.seg_states = nullptr; a.n_segments = 1; a.seg_chunks = 0;
+    if (n_tokens == 0 && (!state_out || state_out == state_in)) return LASAD_OK;
+    hipError_t e = lasad::launch_forward_generic(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_forward_gated launch", e);
+    return LASAD_OK;
+}
+
+int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
+                            int io_dtype, int out_dtype, int B, int n_heads, int d,
+                            int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                            float *state, void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
+    if (pos < 0 || (int64_t)pos >= (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "pos %d is outside the %d x %d grid", pos, grid_h, grid_w);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (out_dtype != LASAD_F32 && out_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "out_dtype %d", out_dtype);
+    if (io_dtype == LASAD_F32 && out_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 output");
+    if (!q || !lam || !v || !o || !state) return fail(LASAD_ERR_INVALID_ARG, "a required pointer is NULL");
+    if (!aligned(q, 16) || !aligned(lam, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(state, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "q, lam, k, v, o and state must be 16-byte aligned");
+    if (o == q || o == lam || o == v || (k && o == k)) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
+
+    lasad::DecodeArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lam = lam;
+    a.io_dtype = io_dtype; a.out_dtype = out_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d;
+    a.grid_w = grid_w; a.pos = pos;
+    a.gamma = nullptr; a.mode = boundary_mode; a.q_scale = q_scale;
+    a.state = state;
+    hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_decode_step_gated launch", e);
     return LASAD_OK;
 }
 

@@ -43,7 +43,10 @@ __device__ inline float ld_in(const void *p, int64_t idx)
     return ((const float *)p)[idx];
 }
 
-template <int D, int IN_BF16, int OUT_BF16>
+// GATED = 1: the decay is a vector over the key channels (row i of S is scaled by lambda[i],
+// or by 1 at a row-boundary position) and the key is 1 - lambda unless a key is given
+// (Section 3.4, Algorithm 1 as written).
+template <int D, int IN_BF16, int OUT_BF16, int GATED>
 __global__ void __launch_bounds__(kWaves * 64)
 decode_kernel(DecodeArgs a, int n_states)
 {
@@ -51,14 +54,15 @@ decode_kernel(DecodeArgs a, int n_states)
     constexpr int RPP = 64 / CG;     // rows covered by one wave-wide load
     constexpr int P = D / RPP;       // loads per lane for the whole state
     constexpr int PB = P < 16 ? P : 16;   // loads in flight per lane at a time
-    __shared__ float sqk[kWaves][2][D];
+    __shared__ float sqk[kWaves][2 + GATED][D];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int bh = blockIdx.x * kWaves + wave;
     if (bh >= n_states) return;      // whole wave leaves together; no barrier below
     const int h = bh % a.Hh;
     const int t = a.pos + 1;
-    const float lam = is_boundary(t, a.grid_w, a.mode) ? 1.0f : a.gamma[h];
+    const bool boundary = is_boundary(t, a.grid_w, a.mode);
+    const float lam = (boundary || GATED) ? 1.0f : a.gamma[h];
 
     const int cg = lane % CG, r0 = lane / CG;
     float4 *S = (float4 *)(a.state + (int64_t)bh * D * D);
@@ -68,12 +72,19 @@ decode_kernel(DecodeArgs a, int n_states)
     // wave-private region) so that every lane can read any row's q_i, k_i.
     const int64_t vec = (int64_t)bh * D;
     constexpr int NQ = (D + 63) / 64;
-    float qr[NQ], kr[NQ];
+    float qr[NQ], kr[NQ], lr[NQ];
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
         const int c = lane + 64 * i;
         qr[i] = c < D ? ld_in<IN_BF16>(a.q, vec + c) : 0.f;
-        kr[i] = c < D ? ld_in<IN_BF16>(a.k, vec + c) : 0.f;
+        if (GATED) {
+            const float l = c < D ? ld_in<IN_BF16>(a.lam, vec + c) : 1.f;
+            kr[i] = a.k ? (c < D ? ld_in<IN_BF16>(a.k, vec + c) : 0.f) : 1.0f - l;   // key from the base decay
+            lr[i] = boundary ? 1.0f : l;
+        } else {
+            kr[i] = c < D ? ld_in<IN_BF16>(a.k, vec + c) : 0.f;
+            lr[i] = 1.0f;
+        }
     }
     float4 vv;
     vv.x = ld_in<IN_BF16>(a.v, vec + cg * 4 + 0);
@@ -88,7 +99,11 @@ decode_kernel(DecodeArgs a, int n_states)
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
         const int c = lane + 64 * i;
-        if (c < D) { sqk[wave][0][c] = qr[i]; sqk[wave][1][c] = kr[i]; }
+        if (c < D) {
+            sqk[wave][0][c] = qr[i];
+            sqk[wave][1][c] = kr[i];
+            if (GATED) sqk[wave][2][c] = lr[i];
+        }
     }
     // wave-level ordering of the LDS writes above against the reads below
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -102,11 +117,12 @@ decode_kernel(DecodeArgs a, int n_states)
         for (int p = 0; p < PB; ++p) {
             const int row = r0 + (p0 + p) * RPP;
             const float qi = sqk[wave][0][row], ki = sqk[wave][1][row];
+            const float li = GATED ? sqk[wave][2][row] : lam;
             float4 x = s[p];
-            x.x = fmaf(lam, x.x, ki * vv.x);
-            x.y = fmaf(lam, x.y, ki * vv.y);
-            x.z = fmaf(lam, x.z, ki * vv.z);
-            x.w = fmaf(lam, x.w, ki * vv.w);
+            x.x = fmaf(li, x.x, ki * vv.x);
+            x.y = fmaf(li, x.y, ki * vv.y);
+            x.z = fmaf(li, x.z, ki * vv.z);
+            x.w = fmaf(li, x.w, ki * vv.w);
             store_stream(&S[row * CG + cg], x);
             acc.x = fmaf(qi, x.x, acc.x);
             acc.y = fmaf(qi, x.y, acc.y);
@@ -149,9 +165,15 @@ hipError_t launch_d(const DecodeArgs &a, hipStream_t s)
     const int n_states = a.B * a.Hh;
     const dim3 grid((unsigned)((n_states + kWaves - 1) / kWaves)), block(kWaves * 64);
     const bool in16 = a.io_dtype == LASAD_BF16, out16 = a.out_dtype == LASAD_BF16;
-    if (in16 && out16) hipLaunchKernelGGL((decode_kernel<D, 1, 1>), grid, block, 0, s, a, n_states);
-    else if (in16) hipLaunchKernelGGL((decode_kernel<D, 1, 0>), grid, block, 0, s, a, n_states);
-    else hipLaunchKernelGGL((decode_kernel<D, 0, 0>), grid, block, 0, s, a, n_states);
+    if (a.lam) {
+        if (in16 && out16) hipLaunchKernelGGL((decode_kernel<D, 1, 1, 1>), grid, block, 0, s, a, n_states);
+        else if (in16) hipLaunchKernelGGL((decode_kernel<D, 1, 0, 1>), grid, block, 0, s, a, n_states);
+        else hipLaunchKernelGGL((decode_kernel<D, 0, 0, 1>), grid, block, 0, s, a, n_states);
+    } else {
+        if (in16 && out16) hipLaunchKernelGGL((decode_kernel<D, 1, 1, 0>), grid, block, 0, s, a, n_states);
+        else if (in16) hipLaunchKernelGGL((decode_kernel<D, 1, 0, 0>), grid, block, 0, s, a, n_states);
+        else hipLaunchKernelGGL((decode_kernel<D, 0, 0, 0>), grid, block, 0, s, a, n_states);
+    }
     return hipGetLastError();
 }
 

@@ -1,20 +1,21 @@
 // Generic forward kernel: fp32 arithmetic on the vector ALUs, any supported head
 // dim (32 / 64 / 128), fp32 or bf16 storage.  It is the path for fp32 inputs (whose
 // 1e-5 tolerance rules out bf16 matrix-core operands) and for shapes the MFMA
-// kernel does not take.  One workgroup walks one (batch, head) sequence with the
-// recurrence of Section 3.4 (see lasad_recurrence.h).
+// kernel does not take, and for the vector (data-dependent) decay of Section 3.4.
+// One workgroup walks one (batch, head) sequence with the recurrence of
+// Section 3.4 (see lasad_recurrence.h).
 #include "lasad_recurrence.h"
 
 namespace lasad {
 
 namespace {
 
-template <int D, int IN_BF16, int OUT_BF16>
+template <int D, int IN_BF16, int OUT_BF16, int GATED>
 __global__ void __launch_bounds__(kRecThreads)
 forward_generic_kernel(ForwardArgs a)
 {
-    __shared__ float smem[recurrence_lds_floats<D>()];
-    recurrence_sequence<D, IN_BF16, OUT_BF16>(a, blockIdx.x, smem);
+    __shared__ float smem[recurrence_lds_floats<D, GATED>()];
+    recurrence_sequence<D, IN_BF16, OUT_BF16, GATED>(a, blockIdx.x, smem);
 }
 
 template <int D>
@@ -22,9 +23,15 @@ hipError_t launch_d(const ForwardArgs &a, hipStream_t s)
 {
     const dim3 grid((unsigned)(a.B * a.Hh)), block(kRecThreads);
     const bool in16 = a.io_dtype == LASAD_BF16, out16 = a.out_dtype == LASAD_BF16;
-    if (in16 && out16) hipLaunchKernelGGL((forward_generic_kernel<D, 1, 1>), grid, block, 0, s, a);
-    else if (in16) hipLaunchKernelGGL((forward_generic_kernel<D, 1, 0>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((forward_generic_kernel<D, 0, 0>), grid, block, 0, s, a);
+    if (a.lam) {
+        if (in16 && out16) hipLaunchKernelGGL((forward_generic_kernel<D, 1, 1, 1>), grid, block, 0, s, a);
+        else if (in16) hipLaunchKernelGGL((forward_generic_kernel<D, 1, 0, 1>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((forward_generic_kernel<D, 0, 0, 1>), grid, block, 0, s, a);
+    } else {
+        if (in16 && out16) hipLaunchKernelGGL((forward_generic_kernel<D, 1, 1, 0>), grid, block, 0, s, a);
+        else if (in16) hipLaunchKernelGGL((forward_generic_kernel<D, 1, 0, 0>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((forward_generic_kernel<D, 0, 0, 0>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 

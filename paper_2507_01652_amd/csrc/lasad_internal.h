@@ -13,6 +13,8 @@ namespace lasad {
 // Arguments of one forward call, already validated.
 struct ForwardArgs {
     const void *q, *k, *v;
+    const void *lam;             // vector decay [B, n, Hh, d] (same layout as q), or NULL: per-head gamma.
+                                 // With lam, k may be NULL: the key is then 1 - lam.
     void *o;
     lasad_layout_t in, out;      // element strides of q/k/v and of o
     int io_dtype, out_dtype;
@@ -31,6 +33,7 @@ struct ForwardArgs {
 
 struct DecodeArgs {
     const void *q, *k, *v;
+    const void *lam;             // vector decay [B, Hh, d], or NULL: per-head gamma (k NULL: key = 1 - lam)
     void *o;
     int io_dtype, out_dtype;
     int B, Hh, d;

@@ -9,6 +9,11 @@
 //
 // Used by the generic kernel (any supported d, fp32 or bf16 storage) and by the
 // MFMA kernel for heads whose decay is too small for its separable mask.
+//
+// GATED = 1 is the recurrence exactly as Section 3.4 / Algorithm 1 write it: a decay
+// vector lambda_t per token over the key channels (row r of S is scaled by lambda_t[r],
+// or by 1 at a row-boundary position), with the key tied to the base decay,
+// k_t = 1 - lambda_t, unless a key tensor is given.
 #pragma once
 
 #include "lasad_internal.h"
@@ -19,8 +24,8 @@ constexpr int kRecThreads = 256;
 constexpr int kRecT = 16;   // tokens staged per round
 
 // LDS floats the routine needs for head dim D
-template <int D>
-constexpr int recurrence_lds_floats() { return 3 * kRecT * D + kRecT * (kRecThreads / D) * D; }
+template <int D, int GATED = 0>
+constexpr int recurrence_lds_floats() { return (3 + GATED) * kRecT * D + kRecT * (kRecThreads / D) * D; }
 
 template <int IN_BF16>
 __device__ inline float rec_load(const void *p, int64_t idx)
@@ -36,7 +41,7 @@ __device__ inline void rec_store(void *p, int64_t idx, float x)
     else ((float *)p)[idx] = x;
 }
 
-template <int D, int IN_BF16, int OUT_BF16>
+template <int D, int IN_BF16, int OUT_BF16, int GATED = 0>
 __device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem)
 {
     constexpr int G = kRecThreads / D;   // row groups
@@ -44,12 +49,13 @@ __device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem)
     float (*sq)[D] = (float (*)[D])smem;
     float (*sk)[D] = (float (*)[D])(smem + kRecT * D);
     float (*sv)[D] = (float (*)[D])(smem + 2 * kRecT * D);
-    float (*red)[G][D] = (float (*)[G][D])(smem + 3 * kRecT * D);
+    float (*sl)[D] = (float (*)[D])(smem + 3 * kRecT * D);      // GATED only: decay vectors
+    float (*red)[G][D] = (float (*)[G][D])(smem + (3 + GATED) * kRecT * D);
 
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const int tid = threadIdx.x;
     const int j = tid % D, g = tid / D;
-    const float gamma = a.gamma[h];
+    const float gamma = GATED ? 1.0f : a.gamma[h];
 
     float S[R];
     if (a.state_in) {
@@ -68,14 +74,21 @@ __device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem)
         const int nt = min(kRecT, a.n_tokens - t0);
         for (int e = tid; e < kRecT * D; e += kRecThreads) {
             const int tt = e / D, c = e - tt * D;
-            float fq = 0.f, fk = 0.f, fv = 0.f;
+            float fq = 0.f, fk = 0.f, fv = 0.f, fl = 1.f;
             if (tt < nt) {
                 const int64_t idx = in_base + (int64_t)(t0 + tt) * a.in.stride_n + c;
                 fq = rec_load<IN_BF16>(a.q, idx);
-                fk = rec_load<IN_BF16>(a.k, idx);
                 fv = rec_load<IN_BF16>(a.v, idx);
+                if (GATED) {
+                    fl = rec_load<IN_BF16>(a.lam, idx);
+                    fk = a.k ? rec_load<IN_BF16>(a.k, idx) : 1.0f - fl;     // key from the base decay
+                    if (is_boundary(a.start_pos + t0 + tt + 1, a.grid_w, a.mode)) fl = 1.0f;
+                } else {
+                    fk = rec_load<IN_BF16>(a.k, idx);
+                }
             }
             sq[tt][c] = fq; sk[tt][c] = fk; sv[tt][c] = fv;
+            if (GATED) sl[tt][c] = fl;
         }
         __syncthreads();
         for (int tt = 0; tt < nt; ++tt) {
@@ -85,7 +98,8 @@ __device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem)
             float part = 0.f;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                S[r] = fmaf(lam, S[r], sk[tt][g * R + r] * vj);
+                const float lr = GATED ? sl[tt][g * R + r] : lam;
+                S[r] = fmaf(lr, S[r], sk[tt][g * R + r] * vj);
                 part = fmaf(sq[tt][g * R + r], S[r], part);
             }
             red[tt][g][j] = part;

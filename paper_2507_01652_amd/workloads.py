@@ -131,3 +131,14 @@ def random_state(w: Workload, seed: int) -> np.ndarray:
     """A float32 carried state [B, Hh, d, d] for carried-state tests."""
     rng = np.random.default_rng(seed)
     return rng.standard_normal(size=(w.B, w.Hh, w.d, w.d), dtype=np.float32) * np.float32(0.5)
+
+
+def gate_inputs(shape, dtype: str, seed: int) -> np.ndarray:
+    """A synthetic post-sigmoid gate lambda in (0, 1) of the given shape: sigmoid of N(2, 1) draws
+    (median 0.88, a long tail towards small values), rounded to the storage type.  Stands in for
+    the trained gate sigmoid(Linear(x)) of Algorithm 1, which is not available."""
+    rng = np.random.default_rng(seed)
+    z = rng.standard_normal(size=shape, dtype=np.float32) + np.float32(2.0)
+    lam = (1.0 / (1.0 + np.exp(-z.astype(np.float64)))).astype(np.float32)
+    lam = store_round(lam, dtype)
+    return np.minimum(lam, np.float32(1.0))

@@ -29,12 +29,17 @@ def gather_pairs(x, pairs):
     return np.stack([x[b, :, h, :] for b, h in pairs], axis=1)[None]
 
 
-BF16_HALF_ULP = 2.0 ** -9   # largest relative error of round-to-nearest-even storage in bf16
+def bf16_half_ulp(x):
+    """Half the spacing of bf16 values (8 significant bits) at |x|: the largest error that
+    round-to-nearest storage of a value landing on x can carry; between 2^-9 and 2^-8 of |x|."""
+    ax = np.abs(np.asarray(x, dtype=np.float64))
+    e = np.floor(np.log2(np.where(ax > 0, ax, 1.0)))
+    return np.where(ax > 0, 2.0 ** (e - 8.0), 0.0)
 
 
 def parity_err(got, ref, out_bf16):
     """max |gpu - oracle| / rms(oracle).  When the GPU result was STORED as bf16, the storage
-    rounding of that one element (at most 2^-9 of its magnitude, whatever computed it) is
+    rounding of that one element (half a bf16 spacing at its magnitude, whatever computed it) is
     taken off first: the tolerance is on the computation, and an output element 15 x the RMS
     cannot be stored in bf16 more closely than 3 % of the RMS by any implementation."""
     got = np.asarray(got, dtype=np.float64)
@@ -43,6 +48,6 @@ def parity_err(got, ref, out_bf16):
         return 0.0
     diff = np.abs(got - ref)
     if out_bf16:
-        diff = np.maximum(diff - BF16_HALF_ULP * np.abs(got), 0.0)
+        diff = np.maximum(diff - bf16_half_ulp(got), 0.0)
     rms = np.sqrt(np.mean(ref * ref))
     return float(diff.max() / rms) if rms > 0 else float(diff.max())

@@ -1,0 +1,113 @@
+"""GPU parity of the vector-decay path (Section 3.4 / Algorithm 1 as written: a decay vector per
+token, key tied to the decay) against the fp64 oracle.  Same tolerances as the scalar path."""
+import numpy as np
+import pytest
+
+from paper_2507_01652_amd import workloads as wl
+from helpers import TOL, parity_err, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lasad():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2507_01652_amd import binding
+    binding.load()
+    return binding
+
+
+def _inputs(B, n, Hh, d, dtype, seed, tied):
+    rng = np.random.default_rng(seed)
+    sc = np.float32(1.0 / np.sqrt(d))
+    q = wl.store_round(rng.standard_normal((B, n, Hh, d), dtype=np.float32) * sc, dtype)
+    v = wl.store_round(rng.standard_normal((B, n, Hh, d), dtype=np.float32) * sc, dtype)
+    k = None if tied else wl.store_round(rng.standard_normal((B, n, Hh, d), dtype=np.float32) * sc, dtype)
+    lam = wl.gate_inputs((B, n, Hh, d), dtype, seed + 1)
+    return q, lam, k, v
+
+
+@pytest.mark.parametrize("d,dtype,H,W,B,Hh", [(64, "bf16", 16, 16, 2, 3), (64, "f32", 8, 8, 1, 2),
+                                             (32, "bf16", 5, 7, 2, 2), (128, "bf16", 3, 5, 1, 2),
+                                             (64, "bf16", 1, 37, 1, 1)])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("tied", [True, False], ids=["k=1-lam", "own_k"])
+def test_forward_gated(lasad, oracle, d, dtype, H, W, B, Hh, mode, tied):
+    import torch
+    n = H * W
+    q, lam, k, v = _inputs(B, n, Hh, d, dtype, 300 + d + mode, tied)
+    s0 = (np.random.default_rng(5).standard_normal((B, Hh, d, d)) * 0.5).astype(np.float32)
+    ref, s_ref = oracle.gated_recurrent(q, lam, v, W, k=k, mode=mode, q_scale=0.8,
+                                        s0=s0.astype(np.float64), want_state=True)
+    dev = lambda x: None if x is None else lasad.to_device(x, dtype)
+    s1 = torch.empty((B, Hh, d, d), dtype=torch.float32, device="cuda")
+    o = lasad.lasad_forward_gated(dev(q), dev(lam), dev(v), H, W, k=dev(k), boundary_mode=mode, q_scale=0.8,
+                                  state_in=torch.from_numpy(s0).cuda(), state_out=s1)
+    torch.cuda.synchronize()
+    assert parity_err(o.float().cpu().numpy(), ref, dtype == "bf16") <= TOL[dtype]
+    assert rel_err(s1.cpu().numpy(), s_ref) <= TOL[dtype]
+
+
+def test_forward_gated_split_and_layout(lasad, oracle):
+    """[B, Hh, N, d] memory order and a call that starts mid-row from a carried state."""
+    import torch
+    H, W, B, Hh, d = 6, 10, 2, 2, 64
+    n = H * W
+    q, lam, k, v = _inputs(B, n, Hh, d, "bf16", 77, True)
+    ref, s_ref = oracle.gated_recurrent(q, lam, v, W, want_state=True)
+    perm = lambda x: lasad.to_device(np.ascontiguousarray(x.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3), "bf16")
+    p = 23
+    s1 = torch.empty((B, Hh, d, d), dtype=torch.float32, device="cuda")
+    s2 = torch.empty_like(s1)
+    o1 = lasad.lasad_forward_gated(perm(q[:, :p]), perm(lam[:, :p]), perm(v[:, :p]), H, W, state_out=s1,
+                                   out_dtype=torch.float32)
+    o2 = lasad.lasad_forward_gated(perm(q[:, p:]), perm(lam[:, p:]), perm(v[:, p:]), H, W, start_pos=p,
+                                   state_in=s1, state_out=s2, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    got = np.concatenate([o1.cpu().numpy(), o2.cpu().numpy()], axis=1)
+    assert rel_err(got, ref) <= TOL["bf16"]
+    assert rel_err(s2.cpu().numpy(), s_ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("d,dtype,H,W,B,Hh", [(64, "bf16", 16, 16, 3, 5), (32, "f32", 4, 6, 2, 3), (128, "bf16", 3, 5, 1, 2)])
+@pytest.mark.parametrize("tied", [True, False], ids=["k=1-lam", "own_k"])
+def test_decode_gated_walk(lasad, oracle, d, dtype, H, W, B, Hh, tied):
+    """Raster walk of decode steps against the oracle's sequential recurrence, every step's output."""
+    import torch
+    n = H * W
+    q, lam, k, v = _inputs(B, n, Hh, d, dtype, 500 + d, tied)
+    ref, s_ref = oracle.gated_recurrent(q, lam, v, W, k=k, q_scale=1.1, want_state=True)
+    dev = lambda x: None if x is None else lasad.to_device(np.ascontiguousarray(x.transpose(1, 0, 2, 3)), dtype)
+    tq, tl, tk, tv = dev(q), dev(lam), dev(k), dev(v)
+    state = torch.zeros((B, Hh, d, d), dtype=torch.float32, device="cuda")
+    outs = []
+    for t in range(n):
+        outs.append(lasad.lasad_decode_step_gated(tq[t], tl[t], tv[t], state, H, W, t,
+                                                  k=None if tk is None else tk[t], q_scale=1.1))
+    torch.cuda.synchronize()
+    got = torch.stack(outs).float().cpu().numpy().transpose(1, 0, 2, 3)
+    for t in range(n):
+        assert parity_err(got[:, t], ref[:, t], dtype == "bf16") <= TOL[dtype], f"step {t}"
+    assert rel_err(state.cpu().numpy(), s_ref) <= TOL[dtype]
+
+
+def test_decode_gated_full_batch_sampled_rows(lasad, oracle):
+    """AR-decode shape (256 x 20 states) with the vector decay; oracle on sampled batch rows."""
+    import torch
+    w = wl.AR_DECODE
+    steps = 64
+    q, lam, k, v = _inputs(w.B, steps, w.Hh, w.d, "bf16", 900, True)
+    rows = [0, 130, 255]
+    ref, s_ref = oracle.gated_recurrent(q[rows], lam[rows], v[rows], w.grid_w, want_state=True)
+    dev = lambda x: lasad.to_device(np.ascontiguousarray(x.transpose(1, 0, 2, 3)), "bf16")
+    tq, tl, tv = dev(q), dev(lam), dev(v)
+    state = torch.zeros((w.B, w.Hh, w.d, w.d), dtype=torch.float32, device="cuda")
+    outs = []
+    for t in range(steps):
+        outs.append(lasad.lasad_decode_step_gated(tq[t], tl[t], tv[t], state, w.grid_h, w.grid_w, t,
+                                                  out_dtype=torch.float32)[rows])
+    torch.cuda.synchronize()
+    got = torch.stack(outs).cpu().numpy().transpose(1, 0, 2, 3)
+    assert rel_err(got, ref) <= TOL["bf16"]
+    assert rel_err(state[rows].cpu().numpy(), s_ref) <= TOL["bf16"]

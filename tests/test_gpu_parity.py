@@ -1,7 +1,7 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
 on the same seeded inputs.  Tolerances: max |gpu - oracle| / rms(oracle) <= 1e-5 for fp32 inputs,
 2e-2 for bf16 inputs; the decay table is compared bit for bit.  Outputs the GPU STORES as bf16
-are given that one storage rounding (2^-9 of the element) on top -- see helpers.parity_err; the
+are given that one storage rounding (half a bf16 spacing at the element) on top -- see helpers.parity_err; the
 benchmark configurations are also run with fp32 output, where the bare tolerance applies."""
 import zlib
 
