@@ -55,6 +55,8 @@ def parse():
     p.add_argument("--decode-walks", type=int, default=4, help="timed raster walks of 256 decode steps (0 = skip)")
     p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-gated", action="store_true",
+                   help="skip the vector-decay (per-channel gate) forward and decode legs")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
     p.add_argument("--layout", default="bnhd", choices=["bnhd", "bhnd"],
                    help="memory order of q, k, v, o: [B, N, Hh, d] (default) or [B, Hh, N, d]")
@@ -221,6 +223,95 @@ def bench_decode(args, torch, lasad, wl):
     return res
 
 
+def bench_gated(args, torch, lasad, wl):
+    """Vector-decay legs (Section 3.4 as written, key tied to the gate): the forward over the prefill
+    workload's shape and the decode step over the AR-decode shape, timed like the scalar legs."""
+    import numpy as np
+    w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
+    q, _, v, _ = wl.prefill_inputs(w, layout=args.layout)
+    lam = wl.gate_inputs(q.shape, w.dtype, w.seed + 7)
+    if args.layout == "bhnd":
+        lam = np.ascontiguousarray(lam.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    tq, tl, tv = (lasad.to_device(x, w.dtype) for x in (q, lam, v))
+    token_heads = w.B * w.N * w.Hh
+    bytes_fwd = token_heads * 4 * w.d * 2               # q, lambda, v read + o written, bf16
+    sets = max(4, min(96, -(-(1 << 30) // bytes_fwd)))
+    bufs = [(tq, tl, tv, torch.empty_like(tq))]
+    for _ in range(sets - 1):
+        bufs.append((tq.clone(), tl.clone(), tv.clone(), torch.empty_like(tq)))
+    steps = max(1, min(args.steps, 50))
+
+    def run(nsteps, first=0):
+        for i in range(nsteps):
+            a, b, c, o = bufs[(first + i) % sets]
+            lasad.lasad_forward_gated(a, b, c, w.grid_h, w.grid_w, out=o)
+
+    run(min(args.warmup, 5))
+    eager_ms = time_region(torch, lambda: run(steps, 5))
+    graph_ms = None
+    if not args.no_graph:
+        g = capture(torch, lambda: run(steps, 5))
+        g.replay()
+        graph_ms = time_region(torch, g.replay)
+    dur_s = (graph_ms if graph_ms is not None else eager_ms) / steps * 1e-3
+    res = {"forward": {
+        "workload": w.name + " (q, gate, v; k = 1 - gate)", "value": w.B * w.N / dur_s, "unit": "tokens/s",
+        "ms_per_step": dur_s * 1e3, "steps_timed": steps, "eager_ms_per_step": eager_ms / steps,
+        "roofline": {"bound": "hbm", "kernel": "lasad_forward_gated", "achieved": bytes_fwd / dur_s / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_fwd / dur_s / 1e9 / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_launch": bytes_fwd,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get("gated:" + w.name)}}}
+    if not args.no_cpu_baseline:
+        from oracle import lasad_oracle as oracle
+        n_seq = min(w.B * w.Hh, 4 * oracle.num_threads())
+        pairs = [(i // w.Hh, i % w.Hh) for i in np.linspace(0, w.B * w.Hh - 1, n_seq).astype(int)]
+        gq, gl, gv = (np.stack([x[b, :, h, :] for b, h in pairs], axis=1)[None] for x in (q, lam, v))
+        passes, t0 = 0, time.perf_counter()
+        while True:
+            oracle.gated_recurrent(gq, gl, gv, w.grid_w)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt > 3.0 or passes >= 200:
+                break
+        res["forward"]["cpu_baseline"] = {
+            "value": passes * n_seq * w.N / w.Hh / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n_seq} of {w.B * w.Hh} (batch, head) sequences, fp64 recurrence, {passes} pass(es), {dt:.2f} s wall"}
+    del bufs
+
+    if args.decode_walks > 0:
+        wd = wl.AR_DECODE
+        dq, _, dv, _ = wl.decode_inputs(wd)
+        dl = wl.gate_inputs(dq.shape, wd.dtype, wd.seed + 7)
+        tq, tl, tv = (lasad.to_device(x, wd.dtype) for x in (dq, dl, dv))
+        L = args.decode_layers
+        states = [torch.zeros((wd.B, wd.Hh, wd.d, wd.d), dtype=torch.float32, device="cuda") for _ in range(L)]
+        outs = [torch.empty((wd.B, wd.Hh, wd.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+        n_steps = args.decode_walks * wd.steps
+
+        def drun(nsteps):
+            for i in range(nsteps):
+                t = i % wd.steps
+                lasad.lasad_decode_step_gated(tq[t], tl[t], tv[t], states[i % L], wd.grid_h, wd.grid_w, t, out=outs[i % L])
+
+        drun(wd.steps)
+        eager_ms = time_region(torch, lambda: drun(n_steps))
+        graph_ms = None
+        if not args.no_graph:
+            g = capture(torch, lambda: drun(n_steps))
+            g.replay()
+            graph_ms = time_region(torch, g.replay)
+        dur_s = (graph_ms if graph_ms is not None else eager_ms) / n_steps * 1e-3
+        bytes_dec = wd.B * wd.Hh * (2 * wd.d * wd.d * 4 + 4 * wd.d * 2)
+        res["decode"] = {
+            "workload": wd.name + " (q, gate, v; k = 1 - gate)", "value": 1.0 / dur_s, "unit": "steps/s",
+            "ms_per_step": dur_s * 1e3, "steps_timed": n_steps, "eager_ms_per_step": eager_ms / n_steps,
+            "roofline": {"bound": "hbm", "kernel": "lasad_decode_step_gated", "achieved": bytes_dec / dur_s / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_dec / dur_s / 1e9 / HBM_PEAK_GBS,
+                         "algorithmic_bytes_per_launch": bytes_dec,
+                         "traffic": MEASURED_TRAFFIC_BYTES.get("gated:" + wd.name)}}
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -259,6 +350,8 @@ def main():
         line["cpu_baseline"] = cpu_baseline_prefill(pre)
     if args.decode_walks > 0:
         line["decode"] = bench_decode(args, torch, lasad, wl)
+    if not args.no_gated:
+        line["gated"] = bench_gated(args, torch, lasad, wl)
     print(json.dumps(line), flush=True)
 
 

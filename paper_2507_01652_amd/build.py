@@ -17,6 +17,7 @@ SOURCES = [
     "lasad_api.hip",
     "lasad_decay.hip",
     "lasad_forward_generic.hip",
+    "lasad_forward_scan.hip",
     "lasad_forward_mfma.hip",
     "lasad_decode.hip",
 ]

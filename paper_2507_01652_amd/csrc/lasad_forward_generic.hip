@@ -3,7 +3,10 @@
 // 1e-5 tolerance rules out bf16 matrix-core operands) and for shapes the MFMA
 // kernel does not take, and for the vector (data-dependent) decay of Section 3.4.
 // One workgroup walks one (batch, head) sequence with the recurrence of
-// Section 3.4 (see lasad_recurrence.h).
+// Section 3.4 (see lasad_recurrence.h).  Head dim 64 goes to the faster scan kernel
+// (lasad_forward_scan.hip) unless the environment sets LASAD_SCAN=0.
+#include <stdlib.h>
+
 #include "lasad_recurrence.h"
 
 namespace lasad {
@@ -39,6 +42,8 @@ hipError_t launch_d(const ForwardArgs &a, hipStream_t s)
 
 hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s)
 {
+    static const bool scan = [] { const char *e = getenv("LASAD_SCAN"); return !(e && e[0] == '0'); }();
+    if (a.d == 64 && scan) return launch_forward_scan(a, s);
     switch (a.d) {
         case 32: return launch_d<32>(a, s);
         case 64: return launch_d<64>(a, s);

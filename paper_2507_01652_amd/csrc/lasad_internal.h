@@ -47,6 +47,8 @@ struct DecodeArgs {
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,
                                 int mode, float *lambda_out, int32_t *cum_out, hipStream_t s);
 hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s);
+// d == 64, any storage type, scalar or vector decay: token-serial fp32 scan kernel.
+hipError_t launch_forward_scan(const ForwardArgs &a, hipStream_t s);
 // bf16 in, d == 64: MFMA chunked kernel.
 hipError_t launch_forward_mfma(const ForwardArgs &a, hipStream_t s);
 // device workspace the MFMA kernel wants for n_seq sequences of n_tokens tokens (0 = none)

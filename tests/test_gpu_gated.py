@@ -30,7 +30,9 @@ def _inputs(B, n, Hh, d, dtype, seed, tied):
 
 @pytest.mark.parametrize("d,dtype,H,W,B,Hh", [(64, "bf16", 16, 16, 2, 3), (64, "f32", 8, 8, 1, 2),
                                              (32, "bf16", 5, 7, 2, 2), (128, "bf16", 3, 5, 1, 2),
-                                             (64, "bf16", 1, 37, 1, 1)])
+                                             (64, "bf16", 1, 37, 1, 1),
+                                             # more than 256 sequences: one workgroup per head, ragged tail
+                                             (64, "bf16", 5, 7, 9, 32), (64, "f32", 3, 11, 5, 53)])
 @pytest.mark.parametrize("mode", [0, 1, 2])
 @pytest.mark.parametrize("tied", [True, False], ids=["k=1-lam", "own_k"])
 def test_forward_gated(lasad, oracle, d, dtype, H, W, B, Hh, mode, tied):

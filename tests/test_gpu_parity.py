@@ -124,6 +124,7 @@ CASES = [
     ("d128_bf16", 1, 2, 128, 6, 9, "bf16"),
     ("d64_f32", 2, 2, 64, 10, 10, "f32"),
     ("d128_f32", 1, 1, 128, 5, 5, "f32"),
+    ("d64_f32_many_seqs", 6, 50, 64, 3, 13, "f32"),    # > 256 sequences: one workgroup per head in the fp32 kernel
 ]
 
 
