@@ -218,7 +218,11 @@ int lasad_forward_gated(const void *q, const void *lam, const void *k, const voi
     a.state_in = state_in; a.state_out = state_out;
     a.seg_states = nullptr; a.n_segments = 1; a.seg_chunks = 0;
     if (n_tokens == 0 && (!state_out || state_out == state_in)) return LASAD_OK;
-    hipError_t e = lasad::launch_forward_generic(a, (hipStream_t)hip_stream);
+    hipError_t e;
+    if (io_dtype == LASAD_BF16 && d == 64 && n_tokens > 0 && !force_generic())
+        e = lasad::launch_forward_gated_mfma(a, (hipStream_t)hip_stream);
+    else
+        e = lasad::launch_forward_generic(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_forward_gated launch", e);
     return LASAD_OK;
 }

@@ -55,18 +55,12 @@
 // i.e. gamma > 0.5; a head with a smaller gamma is walked with the fp32
 // recurrence instead (lasad_recurrence.h), where its decay is applied step by
 // step.
+#include "lasad_mfma_util.h"
 #include "lasad_recurrence.h"
 
 namespace lasad {
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((__vector_size__(4 * sizeof(short))));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 #ifdef LASAD_PROFILE
 // Development aid: cycle stamps of workgroup 0 / wave 0 at phase boundaries of each chunk.
@@ -92,52 +86,6 @@ constexpr int D = 64;      // head dim
 constexpr int kThreads = 256;
 constexpr int RS = 72;     // LDS row stride (elements) of tiles read 16 bytes at a time: 144 B
 constexpr int VS = 80;     // LDS row stride of the V tile (transpose reads only): 160 B
-
-struct Frag {              // 8 bf16 = one lane's share of a 32x16 MFMA operand
-    union { bf16x8 v; uint4 u; uint2 h[2]; };
-};
-
-__device__ inline uint32_t pack2(float lo, float hi)
-{
-    f32x2 x = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-}
-
-__device__ inline uint2 tr_read(const uint16_t *p)
-{
-    s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-    return __builtin_bit_cast(uint2, r);
-}
-
-__device__ inline f32x16 mfma(const Frag &a, const Frag &b, f32x16 acc)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc, 0, 0, 0);
-}
-
-// Constants of the hi/lo split: the packed bf16 pairs (-1, 0) and (0, -1).  They are kept
-// opaque to the compiler (in VGPRs) because, folded into an inline constant of
-// v_dot2c_f32_bf16, -1.0 is encoded in the fp16 format and the product comes out wrong.
-struct SplitConst {
-    bf16x2 m10, m01;
-    __device__ void init()
-    {
-        uint32_t a = 0x0000BF80u, b = 0xBF800000u;
-        asm volatile("" : "+v"(a), "+v"(b));
-        m10 = __builtin_bit_cast(bf16x2, a);
-        m01 = __builtin_bit_cast(bf16x2, b);
-    }
-};
-
-// split a pair of fp32 values into packed bf16 hi (round to nearest) and lo (the residual
-// x - hi, exact in fp32, formed as x + (-1) * hi by one bf16 dot-product instruction each)
-__device__ inline void split2(float x0, float x1, uint32_t &hi, uint32_t &lo, const SplitConst &sc)
-{
-    hi = pack2(x0, x1);
-    const bf16x2 hv = __builtin_bit_cast(bf16x2, hi);
-    const float l0 = __builtin_amdgcn_fdot2_f32_bf16(hv, sc.m10, x0, false);
-    const float l1 = __builtin_amdgcn_fdot2_f32_bf16(hv, sc.m01, x1, false);
-    lo = pack2(l0, l1);
-}
 
 // number of boundary positions among x small offsets: floor(x / W), 0 <= x < W + 128
 __device__ inline int small_div(int x, int W, float rcpW)

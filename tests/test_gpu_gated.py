@@ -113,3 +113,89 @@ def test_decode_gated_full_batch_sampled_rows(lasad, oracle):
     got = torch.stack(outs).cpu().numpy().transpose(1, 0, 2, 3)
     assert rel_err(got, ref) <= TOL["bf16"]
     assert rel_err(state[rows].cpu().numpy(), s_ref) <= TOL["bf16"]
+
+
+def _sampled_check(lasad, oracle, w, lam_fn, tied, n_pairs, out_dtype_name):
+    """Full-size forward on the GPU, oracle on sampled (batch, head) sequences."""
+    import torch
+    from helpers import sample_pairs, gather_pairs
+    q, k, v, _ = wl.prefill_inputs(w)
+    lam = lam_fn((w.B, w.N, w.Hh, w.d))
+    if tied:
+        k = None
+    dev = lambda x: None if x is None else lasad.to_device(x, w.dtype)
+    out_dtype = {"bf16": torch.bfloat16, "f32": torch.float32}[out_dtype_name]
+    s1 = torch.empty((w.B, w.Hh, w.d, w.d), dtype=torch.float32, device="cuda")
+    o = lasad.lasad_forward_gated(dev(q), dev(lam), dev(v), w.grid_h, w.grid_w, k=dev(k), state_out=s1,
+                                  out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    pairs = sample_pairs(w.B, w.Hh, n_pairs, seed=w.seed)
+    ref, s_ref = oracle.gated_recurrent(gather_pairs(q, pairs), gather_pairs(lam, pairs), gather_pairs(v, pairs),
+                                        w.grid_w, k=None if k is None else gather_pairs(k, pairs), want_state=True)
+    got = gather_pairs(o.float().cpu().numpy(), pairs)
+    s_got = np.stack([s1.cpu().numpy()[b, h] for b, h in pairs])[None]
+    assert parity_err(got, ref, out_dtype_name == "bf16") <= TOL["bf16"]
+    assert rel_err(s_got, s_ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("name", ["base_prefill_16x16", "large_prefill_24x24"])
+@pytest.mark.parametrize("tied", [True, False], ids=["k=1-lam", "own_k"])
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_forward_gated_bench_shapes(lasad, oracle, name, tied, out):
+    """The shapes bench.py times, in the launch configuration it uses; fp32 output meets the bare tolerance."""
+    w = wl.CONFIGS[name]
+    _sampled_check(lasad, oracle, w, lambda shape: wl.gate_inputs(shape, w.dtype, w.seed + 7), tied, 24, out)
+
+
+GATE_EXTREMES = {
+    # every chunk's total decay is far below what the chunked factorisation takes: token-serial redo
+    "strong_decay": lambda rng, shape: rng.uniform(0.0, 0.3, size=shape),
+    # exact zeros and ones mixed into ordinary gates
+    "zeros_and_ones": lambda rng, shape: np.where(rng.random(shape) < 0.02, 0.0,
+                                                  np.where(rng.random(shape) < 0.3, 1.0, rng.uniform(0.5, 1.0, size=shape))),
+    # never decays: plain linear attention
+    "all_ones": lambda rng, shape: np.ones(shape),
+    # decay strong enough for some sequences only (head 0 weak, others strong)
+    "mixed_heads": lambda rng, shape: np.concatenate([rng.uniform(0.9, 1.0, size=shape[:2] + (1,) + shape[3:]),
+                                                      rng.uniform(0.2, 0.6, size=shape[:2] + (shape[2] - 1,) + shape[3:])], axis=2),
+    # a chunk total of about 2^-50, just inside what the chunked factorisation takes
+    "near_limit": lambda rng, shape: 0.57 * np.ones(shape),
+    # one channel just outside it (about 2^-65 per chunk), all others mild
+    "one_channel_below_limit": lambda rng, shape: np.where(np.arange(shape[3]) == 5, 0.48, 0.95) * np.ones(shape),
+}
+
+
+@pytest.mark.parametrize("kind", sorted(GATE_EXTREMES))
+@pytest.mark.parametrize("tied", [True, False], ids=["k=1-lam", "own_k"])
+def test_forward_gated_extreme_gates(lasad, oracle, kind, tied):
+    import torch
+    B, Hh, d, H, W = 2, 3, 64, 9, 17          # 153 tokens: two full chunks and a tail
+    n = H * W
+    q, _, k, v = _inputs(B, n, Hh, d, "bf16", 900, tied)
+    rng = np.random.default_rng(zlib_seed(kind))
+    lam = wl.store_round(GATE_EXTREMES[kind](rng, (B, n, Hh, d)).astype(np.float32), "bf16")
+    ref, s_ref = oracle.gated_recurrent(q, lam, v, W, k=k, want_state=True)
+    dev = lambda x: None if x is None else lasad.to_device(x, "bf16")
+    s1 = torch.empty((B, Hh, d, d), dtype=torch.float32, device="cuda")
+    o = lasad.lasad_forward_gated(dev(q), dev(lam), dev(v), H, W, k=dev(k), state_out=s1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.isfinite(o.cpu().numpy()).all()
+    assert rel_err(o.cpu().numpy(), ref) <= TOL["bf16"]
+    assert rel_err(s1.cpu().numpy(), s_ref) <= TOL["bf16"]
+
+
+def zlib_seed(name):
+    import zlib
+    return zlib.crc32(name.encode()) % 100000
+
+
+def test_forward_gated_deterministic(lasad):
+    import torch
+    w = wl.scaled(wl.BASE_PREFILL, B=2)
+    q, _, v, _ = wl.prefill_inputs(w)
+    lam = wl.gate_inputs(q.shape, w.dtype, 3)
+    tq, tl, tv = (lasad.to_device(x, w.dtype) for x in (q, lam, v))
+    o1 = lasad.lasad_forward_gated(tq, tl, tv, w.grid_h, w.grid_w)
+    o2 = lasad.lasad_forward_gated(tq, tl, tv, w.grid_h, w.grid_w)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
