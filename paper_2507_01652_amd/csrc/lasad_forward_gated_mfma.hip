@@ -50,6 +50,12 @@ constexpr float kMinChunkDecay = 8.6736174e-19f;   // 2^-60
 // into different banks; 8- and 4-element runs stay contiguous.
 __device__ inline int tix(int row, int col) { return row * TS + ((col + (row & 48)) & 63); }
 
+// x where keep, else every 32-bit word = fill (component-wise, so the values stay in registers)
+__device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
+{
+    return make_uint4(keep ? x.x : fill, keep ? x.y : fill, keep ? x.z : fill, keep ? x.w : fill);
+}
+
 template <int OUT_BF16, int OWNKEY>
 __global__ void __launch_bounds__(kThreads, 2)
 forward_gated_mfma_kernel(ForwardArgs a)
@@ -146,12 +152,10 @@ forward_gated_mfma_kernel(ForwardArgs a)
         for (int it = 0; it < 2; ++it) {
             const int row = (tid >> 3) + 32 * it, col = (tid & 7) * 8;
             const bool live = row < nt;
-            const uint4 zero = make_uint4(0, 0, 0, 0);
-            const uint4 ones = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
-            *(uint4 *)&sQh[tix(row, col)] = live ? rq[it] : zero;
-            *(uint4 *)&sKh[tix(row, col)] = live ? rl[it] : ones;
-            if (OWNKEY) *(uint4 *)&sKl[tix(row, col)] = live ? rk[it] : zero;
-            *(uint4 *)&sV[row * TS + col] = live ? rv[it] : zero;
+            *(uint4 *)&sQh[tix(row, col)] = keep_or(live, rq[it], 0u);
+            *(uint4 *)&sKh[tix(row, col)] = keep_or(live, rl[it], 0x3f803f80u);     // lambda = 1
+            if (OWNKEY) *(uint4 *)&sKl[tix(row, col)] = keep_or(live, rk[it], 0u);
+            *(uint4 *)&sV[row * TS + col] = keep_or(live, rv[it], 0u);
         }
         // which of the chunk's 64 tokens sit on a row boundary (bit t), same in every wavefront
         const unsigned long long bmask =
