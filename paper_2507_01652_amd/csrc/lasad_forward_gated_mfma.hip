@@ -133,10 +133,9 @@ forward_gated_mfma_kernel(ForwardArgs a)
     };
     if (have_state) publish_state();
 
-    // causal mask of a diagonal 32 x 32 score block: is key 8*qd + 4*g + e at or before query l32
-    bool causal[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) causal[r] = 8 * (r / 4) + 4 * g + (r % 4) <= l32;
+    // causal mask of a diagonal 32 x 32 score block: key 8*qd + 4*g + e is at or before query l32
+    // iff 8*qd + e <= cq
+    const int cq = l32 - 4 * g;
 
     // column-wise preparation: this thread's key channel and token quarter
     const int pc = 16 * wave + (lane & 15), pu = lane >> 4;
@@ -166,20 +165,17 @@ forward_gated_mfma_kernel(ForwardArgs a)
         // ---- column-wise: running decay, K~ = k / A, Q~ = q_scale q A, split, in place ----
         bool trip;
         {
-            float lam[16], kk[16], qq[16];
+            float A[16], kk[16];
             const uint32_t bits = (uint32_t)(bmask >> (16 * pu)) & 0xffffu;
 #pragma unroll
             for (int m = 0; m < 16; ++m) {
                 const int idx = tix(16 * pu + m, pc);
                 const float lraw = __uint_as_float((uint32_t)sKh[idx] << 16);
-                qq[m] = __uint_as_float((uint32_t)sQh[idx] << 16);
                 kk[m] = OWNKEY ? __uint_as_float((uint32_t)sKl[idx] << 16) : 1.0f - lraw;
-                lam[m] = ((bits >> m) & 1u) ? 1.0f : lraw;
+                A[m] = ((bits >> m) & 1u) ? 1.0f : lraw;
             }
-            float A[16];
-            A[0] = lam[0];
 #pragma unroll
-            for (int m = 1; m < 16; ++m) A[m] = A[m - 1] * lam[m];
+            for (int m = 1; m < 16; ++m) A[m] *= A[m - 1];
             // totals of the four quarters of this channel (lanes pc%16 + 16*u of this wavefront)
             const float T = A[15];
             const float T0 = __shfl(T, lane & 15), T1 = __shfl(T, (lane & 15) + 16);
@@ -191,13 +187,14 @@ forward_gated_mfma_kernel(ForwardArgs a)
             const float pq = pre * a.q_scale;
 #pragma unroll
             for (int m = 0; m < 16; m += 2) {
+                const int i0 = tix(16 * pu + m, pc), i1 = tix(16 * pu + m + 1, pc);
+                const float q0 = __uint_as_float((uint32_t)sQh[i0] << 16), q1 = __uint_as_float((uint32_t)sQh[i1] << 16);
                 const float a0 = A[m] * pre, a1 = A[m + 1] * pre;
                 uint32_t hi, lo;
                 split2(kk[m] * __builtin_amdgcn_rcpf(a0), kk[m + 1] * __builtin_amdgcn_rcpf(a1), hi, lo, sc);
-                const int i0 = tix(16 * pu + m, pc), i1 = tix(16 * pu + m + 1, pc);
                 sKh[i0] = (uint16_t)hi; sKh[i1] = (uint16_t)(hi >> 16);
                 sKl[i0] = (uint16_t)lo; sKl[i1] = (uint16_t)(lo >> 16);
-                split2(qq[m] * (A[m] * pq), qq[m + 1] * (A[m + 1] * pq), hi, lo, sc);
+                split2(q0 * (A[m] * pq), q1 * (A[m + 1] * pq), hi, lo, sc);
                 sQh[i0] = (uint16_t)hi; sQh[i1] = (uint16_t)(hi >> 16);
                 sQl[i0] = (uint16_t)lo; sQl[i1] = (uint16_t)(lo >> 16);
             }
@@ -280,10 +277,10 @@ forward_gated_mfma_kernel(ForwardArgs a)
             for (int qd = 0; qd < 4; ++qd) {
                 float p0 = acc[4 * qd + 0], p1 = acc[4 * qd + 1], p2 = acc[4 * qd + 2], p3 = acc[4 * qd + 3];
                 if (diagonal) {
-                    p0 = causal[4 * qd + 0] ? p0 : 0.f;
-                    p1 = causal[4 * qd + 1] ? p1 : 0.f;
-                    p2 = causal[4 * qd + 2] ? p2 : 0.f;
-                    p3 = causal[4 * qd + 3] ? p3 : 0.f;
+                    p0 = 8 * qd + 0 <= cq ? p0 : 0.f;
+                    p1 = 8 * qd + 1 <= cq ? p1 : 0.f;
+                    p2 = 8 * qd + 2 <= cq ? p2 : 0.f;
+                    p3 = 8 * qd + 3 <= cq ? p3 : 0.f;
                 }
                 uint2 hi, lo;
                 split2(p0, p1, hi.x, lo.x, sc);
