@@ -16,13 +16,14 @@
 // value-channel half c of the fp32 state (kept in accumulators), P^T = K~ Q~^T and
 // O^T = V^T P^T + S^T Q~^T so that accumulators feed the next MFMA without shuffles.
 //
-// Chunk preparation.  The 16-byte pieces of q, lambda, (k,) v fetched during the previous chunk
-// are written raw (bf16) into the LDS tiles; after a barrier the workgroup re-reads them
-// column-wise: thread (channel c, quarter u) owns tokens 16u .. 16u+15 of channel c, forms the
-// running product of lambda in fp32, exchanges the quarter totals with the three other lanes
-// of its channel (same wavefront, no barrier), and overwrites the tiles in place with the bf16
-// hi + lo pairs of K~ and Q~.  The tied key k = 1 - lambda uses lambda before the boundary
-// override, as Algorithm 1 does.
+// Chunk preparation, in registers.  Wave w fetches key channels 16w .. 16w+15 of all 64 tokens
+// of the chunk: lane (r, p) holds tokens 2r, 2r+1 and channels 16w + 8p .. +7 of q, lambda, (k,)
+// v as 16-byte pieces.  The running product of lambda along the tokens is a scan across the 32
+// lanes of each half wavefront (DPP row shifts and the row-15 broadcast; no LDS, no barrier);
+// the lane then forms K~ and Q~ for its two token rows, splits them into bf16 hi + lo and keeps
+// them in registers until the tiles of the previous chunk are free.  This happens one chunk
+// ahead, overlapped with the other wavefronts' MFMA work.  The tied key k = 1 - lambda uses
+// lambda before the boundary override, as Algorithm 1 does.
 //
 // Precision: Q~, K~, P and S are computed operands and are each split into bf16 hi + lo (three
 // MFMAs for a product of two split operands, two when one side is exact); v is exact bf16.
@@ -41,14 +42,46 @@ namespace {
 constexpr int C = 64;      // chunk length (tokens)
 constexpr int D = 64;      // head dim
 constexpr int kThreads = 256;
-constexpr int TS = 80;     // LDS row stride (bf16 elements) of the operand tiles: 160 B
-constexpr int RS = 72;     // LDS row stride of the S^T and output tiles: 144 B
+#ifndef LASAD_GATED_KS
+#define LASAD_GATED_KS 80
+#endif
+constexpr int TS = 80;     // LDS row stride (bf16 elements) of the V tile (transpose reads): 160 B
+constexpr int KS = LASAD_GATED_KS;   // of the K~ tiles (16-byte row reads and transpose reads)
+constexpr int RS = 72;     // of the Q~, S^T and output tiles (16-byte row reads): 144 B
 constexpr float kMinChunkDecay = 8.6736174e-19f;   // 2^-60
 
-// Element (row, col) of a 64 x 64 operand tile.  Rows are rotated by 16 channels per 16-row
-// band so that the column-wise 2-byte accesses of the four token quarters of a wavefront fall
-// into different banks; 8- and 4-element runs stay contiguous.
-__device__ inline int tix(int row, int col) { return row * TS + ((col + (row & 48)) & 63); }
+// Running products of eight values along the 32 lanes of each half wavefront: on return x[c]
+// of lane l holds the product over lanes 0..l of its half (inclusive) and e[c] the product over
+// lanes 0..l-1 (1 in lane 0 of a half).  Each DPP step multiplies by the value 1, 2, 4, 8 lanes
+// down the 16-lane row (lanes without a source keep their value), the last one by lane 15 of
+// the row below (rows 1 and 3 only).  The eight chains are interleaved, so every DPP source
+// was written eight instructions earlier; the s_nop covers what preceded the block.
+#define SCAN_STEP(ctrl)                                                                           \
+    "v_mul_f32_dpp %0, %0, %0 " ctrl "\n v_mul_f32_dpp %1, %1, %1 " ctrl "\n"                     \
+    "v_mul_f32_dpp %2, %2, %2 " ctrl "\n v_mul_f32_dpp %3, %3, %3 " ctrl "\n"                     \
+    "v_mul_f32_dpp %4, %4, %4 " ctrl "\n v_mul_f32_dpp %5, %5, %5 " ctrl "\n"                     \
+    "v_mul_f32_dpp %6, %6, %6 " ctrl "\n v_mul_f32_dpp %7, %7, %7 " ctrl "\n"
+__device__ inline void scan_mul32x8(float (&x)[8], float (&e)[8], bool half_start)
+{
+    asm("s_nop 1\n"
+        SCAN_STEP("row_shr:1 row_mask:0xf bank_mask:0xf")
+        SCAN_STEP("row_shr:2 row_mask:0xf bank_mask:0xf")
+        SCAN_STEP("row_shr:4 row_mask:0xf bank_mask:0xf")
+        SCAN_STEP("row_shr:8 row_mask:0xf bank_mask:0xf")
+        SCAN_STEP("row_bcast:15 row_mask:0xa bank_mask:0xf")
+        : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]));
+#pragma unroll
+    for (int c = 0; c < 8; ++c) e[c] = 1.0f;
+    asm("s_nop 1\n"
+        "v_mov_b32_dpp %0, %8 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %1, %9 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
+        "v_mov_b32_dpp %2, %10 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %3, %11 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
+        "v_mov_b32_dpp %4, %12 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %5, %13 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
+        "v_mov_b32_dpp %6, %14 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %7, %15 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
+        : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]), "+v"(e[4]), "+v"(e[5]), "+v"(e[6]), "+v"(e[7])
+        : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "v"(x[4]), "v"(x[5]), "v"(x[6]), "v"(x[7]));
+#pragma unroll
+    for (int c = 0; c < 8; ++c) e[c] = half_start ? 1.0f : e[c];
+}
 
 // x where keep, else every 32-bit word = fill (component-wise, so the values stay in registers)
 __device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
@@ -61,16 +94,16 @@ __global__ void __launch_bounds__(kThreads, 2)
 forward_gated_mfma_kernel(ForwardArgs a)
 {
     // tiles: Q~ hi, Q~ lo, K~ hi, K~ lo, V (stride TS); S^T hi, lo and the bf16 output tile (stride RS)
-    constexpr int kTileHalfs = 5 * C * TS + 3 * D * RS;
+    constexpr int kTileHalfs = C * TS + 2 * C * KS + 2 * C * RS + 3 * D * RS;
     constexpr int kScanFloats = scan::lds_floats<OWNKEY ? scan::OWNKEY : scan::TIED>();
     constexpr int kLdsBytes = kTileHalfs * 2 > kScanFloats * 4 ? kTileHalfs * 2 : kScanFloats * 4;
     __shared__ __attribute__((aligned(16))) unsigned char smem_raw[kLdsBytes];
-    __shared__ __attribute__((aligned(16))) float sTot[D];     // A_end per key channel
+    __shared__ __attribute__((aligned(16))) float sTot[2][D];  // A_end per key channel, by chunk parity
     uint16_t *sQh = (uint16_t *)smem_raw;
-    uint16_t *sQl = sQh + C * TS;
-    uint16_t *sKh = sQl + C * TS;
-    uint16_t *sKl = sKh + C * TS;
-    uint16_t *sV = sKl + C * TS;
+    uint16_t *sQl = sQh + C * RS;
+    uint16_t *sKh = sQl + C * RS;
+    uint16_t *sKl = sKh + C * KS;
+    uint16_t *sV = sKl + C * KS;
     uint16_t *sSh = sV + C * TS;        // S^T [dv][dk]
     uint16_t *sSl = sSh + D * RS;
     uint16_t *sO = sSl + D * RS;        // [token][dv]
@@ -93,13 +126,14 @@ forward_gated_mfma_kernel(ForwardArgs a)
     SplitConst sc;
     sc.init();
 
-    // staging loads: rows tid/8 and tid/8 + 32 of the chunk, channels (tid%8)*8 .. +7; unconditional, clamped
+    // staging loads: token rows 2*l32, 2*l32 + 1 of the chunk, channels 16*wave + 8*g .. +7; unconditional, clamped
+    const int pcol = 16 * wave + 8 * g;
     uint4 rq[2], rl[2], rk[2], rv[2];
     auto prefetch = [&](int chunk) {
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const int tok = min(chunk * C + (tid >> 3) + 32 * it, n - 1);
-            const int64_t off = (int64_t)tok * a.in.stride_n + (tid & 7) * 8;
+            const int tok = min(chunk * C + 2 * l32 + it, n - 1);
+            const int64_t off = (int64_t)tok * a.in.stride_n + pcol;
             rq[it] = *(const uint4 *)(gq + off);
             rl[it] = *(const uint4 *)(gl + off);
             if (OWNKEY) rk[it] = *(const uint4 *)(gk + off);
@@ -137,92 +171,124 @@ forward_gated_mfma_kernel(ForwardArgs a)
     // iff 8*qd + e <= cq
     const int cq = l32 - 4 * g;
 
-    // column-wise preparation: this thread's key channel and token quarter
-    const int pc = 16 * wave + (lane & 15), pu = lane >> 4;
+    // Operands of one chunk, prepared in registers from the staged pieces: bf16 hi + lo of
+    // K~ = k / A and Q~ = q_scale q A for this lane's two token rows and eight channels.
+    uint4 pkh[2], pkl[2], pqh[2], pql[2], pv[2];
+    bool trip = false;
+    auto prepare = [&](int chunk) {
+        const int t0 = chunk * C, nt = min(C, n - t0);
+        // which of the chunk's 64 tokens sit on a row boundary (bit t), same in every wavefront
+        const unsigned long long bmask = __ballot(is_boundary(a.start_pos + t0 + lane + 1, a.grid_w, a.mode));
+        float *sTotN = sTot[chunk & 1];
+        float lam[2][8], kk[2][8];
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int row = 2 * l32 + it;
+            const bool bnd = (bmask >> row) & 1ull;
+            const uint32_t lw[4] = {rl[it].x, rl[it].y, rl[it].z, rl[it].w};
+            const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float l0 = __uint_as_float(lw[e] << 16), l1 = __uint_as_float(lw[e] & 0xffff0000u);
+                const float k0 = OWNKEY ? __uint_as_float(kw[e] << 16) : 1.0f - l0;
+                const float k1 = OWNKEY ? __uint_as_float(kw[e] & 0xffff0000u) : 1.0f - l1;
+                kk[it][2 * e] = k0;
+                kk[it][2 * e + 1] = k1;
+                lam[it][2 * e] = bnd ? 1.0f : l0;
+                lam[it][2 * e + 1] = bnd ? 1.0f : l1;
+            }
+            pv[it] = rv[it];
+        }
+        if (nt < C) {                                      // tail chunk: rows past the end get lambda 1, q = k = v = 0
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const bool live = 2 * l32 + it < nt;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    kk[it][c] = live ? kk[it][c] : 0.f;
+                    lam[it][c] = live ? lam[it][c] : 1.0f;
+                }
+                pv[it] = keep_or(live, pv[it], 0u);
+                rq[it] = keep_or(live, rq[it], 0u);
+            }
+        }
+        // product over the token pairs of lanes 0..l32 (tot) and 0..l32-1 (exc), per channel
+        float tot[8], exc[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) tot[c] = lam[0][c] * lam[1][c];
+        scan_mul32x8(tot, exc, l32 == 0);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            lam[0][c] *= exc[c];                                // A of token 2*l32
+            lam[1][c] *= lam[0][c];                             // A of token 2*l32 + 1
+        }
+        if (l32 == 31) {                                        // chunk totals A_end of this half's channels
+            *(float4 *)&sTotN[pcol] = make_float4(tot[0], tot[1], tot[2], tot[3]);
+            *(float4 *)&sTotN[pcol + 4] = make_float4(tot[4], tot[5], tot[6], tot[7]);
+        }
+        // A decreases along the tokens: the smallest value of each channel sits in lane 31
+        float amin = lam[1][0];
+#pragma unroll
+        for (int c = 1; c < 8; ++c) amin = fminf(amin, lam[1][c]);
+        trip = !(amin >= kMinChunkDecay);
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const uint32_t qw[4] = {rq[it].x, rq[it].y, rq[it].z, rq[it].w};
+            uint32_t kh[4], kl[4], qh[4], ql[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a0 = lam[it][2 * e], a1 = lam[it][2 * e + 1];
+                split2(kk[it][2 * e] * __builtin_amdgcn_rcpf(a0), kk[it][2 * e + 1] * __builtin_amdgcn_rcpf(a1), kh[e], kl[e], sc);
+                split2(__uint_as_float(qw[e] << 16) * (a0 * a.q_scale), __uint_as_float(qw[e] & 0xffff0000u) * (a1 * a.q_scale),
+                       qh[e], ql[e], sc);
+            }
+            pkh[it] = make_uint4(kh[0], kh[1], kh[2], kh[3]); pkl[it] = make_uint4(kl[0], kl[1], kl[2], kl[3]);
+            pqh[it] = make_uint4(qh[0], qh[1], qh[2], qh[3]); pql[it] = make_uint4(ql[0], ql[1], ql[2], ql[3]);
+        }
+    };
 
     const int n_chunks = (n + C - 1) / C;
+    prepare(0);
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
 
-        // ---- raw tiles: q -> Q~hi, lambda -> K~hi, own key -> K~lo, v -> V; rows past the end neutral ----
+        // ---- write the prepared tiles (free since barrier B of the previous chunk) ----
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const int row = (tid >> 3) + 32 * it, col = (tid & 7) * 8;
-            const bool live = row < nt;
-            *(uint4 *)&sQh[tix(row, col)] = keep_or(live, rq[it], 0u);
-            *(uint4 *)&sKh[tix(row, col)] = keep_or(live, rl[it], 0x3f803f80u);     // lambda = 1
-            if (OWNKEY) *(uint4 *)&sKl[tix(row, col)] = keep_or(live, rk[it], 0u);
-            *(uint4 *)&sV[row * TS + col] = keep_or(live, rv[it], 0u);
+            const int row = 2 * l32 + it;
+            *(uint4 *)&sKh[(row) * KS + pcol] = pkh[it];
+            *(uint4 *)&sKl[(row) * KS + pcol] = pkl[it];
+            *(uint4 *)&sQh[(row) * RS + pcol] = pqh[it];
+            *(uint4 *)&sQl[(row) * RS + pcol] = pql[it];
+            *(uint4 *)&sV[row * TS + pcol] = pv[it];
         }
-        // which of the chunk's 64 tokens sit on a row boundary (bit t), same in every wavefront
-        const unsigned long long bmask =
-            __ballot(is_boundary(a.start_pos + t0 + lane + 1, a.grid_w, a.mode));
-        __syncthreads();                                  // (P) raw tiles visible
-        if (chunk + 1 < n_chunks) prefetch(chunk + 1);
-
-        // ---- column-wise: running decay, K~ = k / A, Q~ = q_scale q A, split, in place ----
-        bool trip;
-        {
-            float A[16], kk[16];
-            const uint32_t bits = (uint32_t)(bmask >> (16 * pu)) & 0xffffu;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) {
-                const int idx = tix(16 * pu + m, pc);
-                const float lraw = __uint_as_float((uint32_t)sKh[idx] << 16);
-                kk[m] = OWNKEY ? __uint_as_float((uint32_t)sKl[idx] << 16) : 1.0f - lraw;
-                A[m] = ((bits >> m) & 1u) ? 1.0f : lraw;
-            }
-#pragma unroll
-            for (int m = 1; m < 16; ++m) A[m] *= A[m - 1];
-            // totals of the four quarters of this channel (lanes pc%16 + 16*u of this wavefront)
-            const float T = A[15];
-            const float T0 = __shfl(T, lane & 15), T1 = __shfl(T, (lane & 15) + 16);
-            const float T2 = __shfl(T, (lane & 15) + 32), T3 = __shfl(T, (lane & 15) + 48);
-            const float pre = pu == 0 ? 1.0f : pu == 1 ? T0 : pu == 2 ? T0 * T1 : (T0 * T1) * T2;
-            const float tot = ((T0 * T1) * T2) * T3;
-            trip = !(tot >= kMinChunkDecay);
-            if (pu == 0) sTot[pc] = tot;
-            const float pq = pre * a.q_scale;
-#pragma unroll
-            for (int m = 0; m < 16; m += 2) {
-                const int i0 = tix(16 * pu + m, pc), i1 = tix(16 * pu + m + 1, pc);
-                const float q0 = __uint_as_float((uint32_t)sQh[i0] << 16), q1 = __uint_as_float((uint32_t)sQh[i1] << 16);
-                const float a0 = A[m] * pre, a1 = A[m + 1] * pre;
-                uint32_t hi, lo;
-                split2(kk[m] * __builtin_amdgcn_rcpf(a0), kk[m + 1] * __builtin_amdgcn_rcpf(a1), hi, lo, sc);
-                sKh[i0] = (uint16_t)hi; sKh[i1] = (uint16_t)(hi >> 16);
-                sKl[i0] = (uint16_t)lo; sKl[i1] = (uint16_t)(lo >> 16);
-                split2(q0 * (A[m] * pq), q1 * (A[m + 1] * pq), hi, lo, sc);
-                sQh[i0] = (uint16_t)hi; sQh[i1] = (uint16_t)(hi >> 16);
-                sQl[i0] = (uint16_t)lo; sQl[i1] = (uint16_t)(lo >> 16);
-            }
-        }
-        if (__syncthreads_or(trip)) {                     // (A) operand tiles visible, or give up
+        if (__syncthreads_or(trip)) {                     // (A) operand tiles and A_end visible, or give up
             // every thread has left the tiles; redo the whole sequence step by step
             scan::scan_sequence<1, OUT_BF16, OWNKEY ? scan::OWNKEY : scan::TIED, 64>(a, bh, 0, (float *)smem_raw);
             return;
         }
+        if (chunk + 1 < n_chunks) prefetch(chunk + 1);
 
         const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
         Frag fqh[4], fql[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            fqh[s].u = *(const uint4 *)&sQh[tix(i_row, 16 * s + 8 * g)];
-            fql[s].u = *(const uint4 *)&sQl[tix(i_row, 16 * s + 8 * g)];
+            fqh[s].u = *(const uint4 *)&sQh[(i_row) * RS + 16 * s + 8 * g];
+            fql[s].u = *(const uint4 *)&sQl[(i_row) * RS + 16 * s + 8 * g];
         }
 
-        f32x16 acc0, acc1, accO;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; accO[r] = 0.f; }
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 acc0, acc1 = zero16, accO = zero16;
         // ---- scores P^T[j][i] = sum_c K~[j][c] Q~[i][c], key block 0 (and 1 for the upper query half) ----
         auto scores = [&](f32x16 &acc, int jb) {
+            acc = zero16;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 Frag kh, kl;
-                kh.u = *(const uint4 *)&sKh[tix(jb * 32 + l32, 16 * s + 8 * g)];
-                kl.u = *(const uint4 *)&sKl[tix(jb * 32 + l32, 16 * s + 8 * g)];
+                kh.u = *(const uint4 *)&sKh[(jb * 32 + l32) * KS + 16 * s + 8 * g];
+                kl.u = *(const uint4 *)&sKl[(jb * 32 + l32) * KS + 16 * s + 8 * g];
                 acc = mfma(kh, fqh[s], acc);
                 acc = mfma(kl, fqh[s], acc);
                 acc = mfma(kh, fql[s], acc);
@@ -255,16 +321,16 @@ forward_gated_mfma_kernel(ForwardArgs a)
                 fv[s].h[0] = tr_read(&sV[r0 * TS + vcol]);
                 fv[s].h[1] = tr_read(&sV[r1 * TS + vcol]);
                 Frag fk;
-                fk.h[0] = tr_read(&sKh[tix(r0, kcol)]);
-                fk.h[1] = tr_read(&sKh[tix(r1, kcol)]);
+                fk.h[0] = tr_read(&sKh[(r0) * KS + kcol]);
+                fk.h[1] = tr_read(&sKh[(r1) * KS + kcol]);
                 accS = mfma(fk, fv[s], accS);
-                fk.h[0] = tr_read(&sKl[tix(r0, kcol)]);
-                fk.h[1] = tr_read(&sKl[tix(r1, kcol)]);
+                fk.h[0] = tr_read(&sKl[(r0) * KS + kcol]);
+                fk.h[1] = tr_read(&sKl[(r1) * KS + kcol]);
                 accS = mfma(fk, fv[s], accS);
             }
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                const float4 t4 = *(const float4 *)&sTot[wa * 32 + 8 * qd + 4 * g];
+                const float4 t4 = *(const float4 *)&sTot[chunk & 1][wa * 32 + 8 * qd + 4 * g];
                 accS[4 * qd + 0] *= t4.x; accS[4 * qd + 1] *= t4.y;
                 accS[4 * qd + 2] *= t4.z; accS[4 * qd + 3] *= t4.w;
             }
@@ -324,6 +390,7 @@ forward_gated_mfma_kernel(ForwardArgs a)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
+        if (chunk + 1 < n_chunks) prepare(chunk + 1);     // its loads have landed by now
         __syncthreads();                                  // (B) all reads of the tiles and of S^T finished
         if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
             uint16_t *go = (uint16_t *)a.o + o_base;
