@@ -40,6 +40,11 @@ MEASURED_TRAFFIC_BYTES = {
     "large_prefill_24x24": 151224938,    # algorithmic 150994944
     "highres_64x64": 305425015,          # algorithmic 201326592; the segment plan re-reads K, V once
     "ar_decode_16x16": 170446445,        # algorithmic 170393600
+    # vector-decay kernels (key tied to the gate): same algorithmic bytes as the scalar ones
+    "gated:base_prefill_16x16": 14512690,    # algorithmic 12582912 (+ register spill traffic)
+    "gated:large_prefill_24x24": 160648201,  # algorithmic 150994944
+    "gated:highres_64x64": 203259595,        # algorithmic 201326592 (single launch, no segment plan)
+    "gated:ar_decode_16x16": 170447168,      # algorithmic 170393600
 }
 
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
