@@ -20,6 +20,9 @@
  * All tensors here are dense, fp64, in [B][Hh][n][d] order ("head-major");
  * states are [B][Hh][dk][dv] with dv contiguous: S[i][j] = sum_t k_t[i] v_t[j].
  *
+ * Gradients (lasad_oracle_backward, lasad_oracle_dgamma) differentiate the same recurrence
+ * step by step in reverse.
+ *
  * Every function below is pinned by the CPU test-suite against values fixed by
  * the paper's equations (hand-worked recurrences, geometric-series closed
  * forms, the gamma = 1 reduction to plain causal linear attention of
@@ -342,6 +345,107 @@ int lasad_oracle_gated_bruteforce(const double *q, const double *lam, const doub
 }
 
 /* Threads the OpenMP loops above will use (reported by the benchmark). */
+/*
+ * Gradients of the sequential form (Section 3.4 recurrence from a zero state) by differentiating
+ * it step by step in reverse.  Given d_o[t] = dL/do_t, with
+ *     s_t = lambda_t s_{t-1} + k_t v_t^T,        o_t = q_scale * s_t^T q_t,
+ * the state gradient g_t = dL/ds_t obeys g_t = q_scale q_t d_o_t^T + lambda_{t+1} g_{t+1}, and
+ *     dq_t = q_scale * s_t d_o_t,   dk_t = g_t v_t,   dv_t = g_t^T k_t,   dlambda_t = <g_t, s_{t-1}>.
+ * The forward states s_0 .. s_n are kept (n+1 matrices per sequence).  lam is [Hh][n]; dq, dk, dv
+ * are [B][Hh][n][d]; dlam is [B][Hh][n], the gradient with respect to the decay applied at each
+ * token of each sequence (the caller sums it over whatever positions share a parameter).
+ */
+int lasad_oracle_backward(const double *q, const double *k, const double *v,
+                          const double *lam, double q_scale, const double *d_o,
+                          double *dq, double *dk, double *dv, double *dlam,
+                          int B, int n_heads, int n, int d)
+{
+    if (!q || !k || !v || !lam || !d_o || !dq || !dk || !dv || !dlam || B < 1 || n_heads < 1 || n < 0 || d < 1)
+        return 1;
+    int status = 0;
+    const int64_t n_seq = (int64_t)B * n_heads;
+    const size_t dd = (size_t)d * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < n_seq; ++bh) {
+        const int h = (int)(bh % n_heads);
+        double *S = (double *)calloc((size_t)(n + 1) * dd, sizeof(double));   /* s_0 .. s_n */
+        double *G = (double *)calloc(dd, sizeof(double));
+        if (!S || !G) {
+#pragma omp atomic write
+            status = 2;
+            free(S); free(G);
+            continue;
+        }
+        for (int t = 0; t < n; ++t) {
+            const double l = lam[(size_t)h * n + t];
+            const double *kt = k + ((size_t)bh * n + t) * d;
+            const double *vt = v + ((size_t)bh * n + t) * d;
+            const double *Sp = S + (size_t)t * dd;
+            double *Sn = S + (size_t)(t + 1) * dd;
+            for (int r = 0; r < d; ++r)
+                for (int c = 0; c < d; ++c)
+                    Sn[(size_t)r * d + c] = l * Sp[(size_t)r * d + c] + kt[r] * vt[c];
+        }
+        for (int t = n - 1; t >= 0; --t) {
+            const double l = lam[(size_t)h * n + t];
+            const double *qt = q + ((size_t)bh * n + t) * d;
+            const double *kt = k + ((size_t)bh * n + t) * d;
+            const double *vt = v + ((size_t)bh * n + t) * d;
+            const double *gt = d_o + ((size_t)bh * n + t) * d;
+            const double *St = S + (size_t)(t + 1) * dd;      /* s_t (contains token t) */
+            const double *Sp = S + (size_t)t * dd;            /* s_{t-1} */
+            double *dqt = dq + ((size_t)bh * n + t) * d;
+            double *dkt = dk + ((size_t)bh * n + t) * d;
+            double *dvt = dv + ((size_t)bh * n + t) * d;
+            for (int r = 0; r < d; ++r) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += St[(size_t)r * d + c] * gt[c];
+                dqt[r] = q_scale * acc;
+            }
+            for (int r = 0; r < d; ++r)
+                for (int c = 0; c < d; ++c)
+                    G[(size_t)r * d + c] += q_scale * qt[r] * gt[c];
+            for (int r = 0; r < d; ++r) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += G[(size_t)r * d + c] * vt[c];
+                dkt[r] = acc;
+            }
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < d; ++r) acc += G[(size_t)r * d + c] * kt[r];
+                dvt[c] = acc;
+            }
+            double dl = 0.0;
+            for (size_t e = 0; e < dd; ++e) dl += G[e] * Sp[e];
+            dlam[(size_t)bh * n + t] = dl;
+            for (size_t e = 0; e < dd; ++e) G[e] *= l;
+        }
+        free(S); free(G);
+    }
+    return status;
+}
+
+/*
+ * Gradient of the per-head base decay: gamma_h is the decay of every non-boundary position of
+ * every sequence of head h (Section 3.4 second equation), so
+ *     dgamma[h] = sum_b sum_{t not a boundary} dlam[b][h][t].
+ * Positions are start_pos+1 .. start_pos+n (1-indexed raster positions).
+ */
+int lasad_oracle_dgamma(const double *dlam, int B, int n_heads, int n,
+                        int grid_w, int start_pos, int mode, double *dgamma)
+{
+    if (!dlam || !dgamma || B < 1 || n_heads < 1 || n < 0 || grid_w < 1) return 1;
+    for (int h = 0; h < n_heads; ++h) {
+        double acc = 0.0;
+        for (int b = 0; b < B; ++b)
+            for (int t = 0; t < n; ++t)
+                if (!is_boundary((int64_t)start_pos + t + 1, grid_w, mode))
+                    acc += dlam[((size_t)b * n_heads + h) * n + t];
+        dgamma[h] = acc;
+    }
+    return 0;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int lasad_oracle_num_threads(void) { return omp_get_max_threads(); }

@@ -61,6 +61,10 @@ def _load():
         lib.lasad_oracle_gated_recurrent.restype = ci
         lib.lasad_oracle_gated_bruteforce.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, ci, ci, ci, ci, ci]
         lib.lasad_oracle_gated_bruteforce.restype = ci
+        lib.lasad_oracle_backward.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp, dp, dp, ci, ci, ci, ci]
+        lib.lasad_oracle_backward.restype = ci
+        lib.lasad_oracle_dgamma.argtypes = [dp, ci, ci, ci, ci, ci, ci, dp]
+        lib.lasad_oracle_dgamma.restype = ci
         lib.lasad_oracle_num_threads.argtypes = []
         lib.lasad_oracle_num_threads.restype = ci
         _lib = lib
@@ -151,6 +155,38 @@ def bruteforce(q, k, v, lam, q_scale=1.0):
     if rc != 0:
         raise RuntimeError(f"lasad_oracle_bruteforce failed (rc={rc})")
     return o
+
+
+# ---- gradients of the scalar-decay path --------------------------------------------------------
+
+def backward(q, k, v, lam, d_o, q_scale=1.0):
+    """Gradients of the recurrence from a zero state.  q, k, v, d_o: [B, n, Hh, d]; lam [Hh, n].
+    Returns dq, dk, dv [B, n, Hh, d] and dlam [B, Hh, n] (per sequence and token)."""
+    q, k, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, k, v, d_o))
+    B, n, Hh, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and d_o.shape == q.shape
+    lam = _f64c(lam)
+    assert lam.shape == (Hh, n)
+    qh, kh, vh, gh = (np.ascontiguousarray(x.transpose(0, 2, 1, 3)) for x in (q, k, v, d_o))
+    dqh, dkh, dvh = np.empty_like(qh), np.empty_like(qh), np.empty_like(qh)
+    dlam = np.empty((B, Hh, n), dtype=np.float64)
+    rc = _load().lasad_oracle_backward(_dptr(qh), _dptr(kh), _dptr(vh), _dptr(lam), float(q_scale), _dptr(gh),
+                                       _dptr(dqh), _dptr(dkh), _dptr(dvh), _dptr(dlam), B, Hh, n, d)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_backward failed (rc={rc})")
+    dq, dk, dv = (np.ascontiguousarray(x.transpose(0, 2, 1, 3)) for x in (dqh, dkh, dvh))
+    return dq, dk, dv, dlam
+
+
+def dgamma(dlam, grid_w, start_pos=0, mode=RESET_LAST_COL):
+    """Sum of the per-token decay gradients over the non-boundary positions and the batch: [Hh]."""
+    dlam = _f64c(dlam)
+    B, Hh, n = dlam.shape
+    out = np.empty((Hh,), dtype=np.float64)
+    rc = _load().lasad_oracle_dgamma(_dptr(dlam), B, Hh, n, int(grid_w), int(start_pos), int(mode), _dptr(out))
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_dgamma failed (rc={rc})")
+    return out
 
 
 # ---- vector, data-dependent decay (Section 3.4 / Algorithm 1 as written) ----------------------
