@@ -144,9 +144,9 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
  *   k     same shape, or NULL: then the key is tied to the base decay, k_t = 1 - lambda_t
  *         (Section 3.4 "base decay factor" equation; the key keeps the base lambda_t also
  *         at a boundary, Algorithm 1 sets it before the override).
- * Everything else as in lasad_forward_chunked.  This first version walks each sequence with
- * the fp32 recurrence on the vector ALUs (any supported d, fp32 or bf16 storage, fp32 state);
- * it needs no workspace.
+ * Everything else as in lasad_forward_chunked.  bf16 storage with d = 64 runs a chunked
+ * matrix-core kernel; fp32 storage and other head dims walk each sequence with the fp32
+ * recurrence on the vector ALUs (fp32 state).  No workspace is needed.
  */
 int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
                         const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
@@ -165,6 +165,36 @@ int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const
                             int io_dtype, int out_dtype, int B, int n_heads, int d,
                             int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
                             float *state, void *hip_stream);
+
+/*
+ * Backward pass of lasad_forward_chunked for a call that starts from a zero state and whose
+ * final state is not used (a whole teacher-forced sequence, the training setting of Section 4.1):
+ * given d_o = dL/do, the gradients of the Section 3.4 recurrence
+ *     dq_i = q_scale sum_{j<=i} M[i][j] (d_o_i . v_j) k_j
+ *     dk_j = q_scale sum_{i>=j} M[i][j] (d_o_i . v_j) q_i
+ *     dv_j = q_scale sum_{i>=j} M[i][j] (q_i . k_j) d_o_i,      M[i][j] = prod_{s=j+1..i} lambda_s
+ * and dgamma[h] = dL/dgamma_h, gamma_h being the decay of every non-boundary position of head h
+ * (second equation of Section 3.4), summed over the batch.
+ *   q, k, v, d_o   [B, n_tokens, n_heads, d] views sharing in_layout and io_dtype (device).
+ *   dq, dk, dv     same logical shape, grad_layout, grad_dtype (fp32, or bf16 with bf16 inputs);
+ *                  overwritten; must not alias the inputs or each other.
+ *   dgamma         [n_heads] fp32, overwritten.  Needs gamma > 0 (it is formed from d/dlog gamma);
+ *                  for gamma = 0 the entry is inf or NaN.
+ *   workspace      device memory of at least lasad_backward_workspace_bytes(...) bytes, 256-byte
+ *                  aligned, owned by the caller, free for reuse when the call's work on the stream
+ *                  has finished.  Required (LASAD_ERR_WORKSPACE if NULL or too small).
+ * Asynchronous on hip_stream; no allocation, no synchronisation.  Results are deterministic
+ * (fixed summation order).
+ */
+size_t lasad_backward_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype);
+int lasad_backward_chunked(const void *q, const void *k, const void *v, const void *d_o,
+                           void *dq, void *dk, void *dv, float *dgamma,
+                           const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                           int io_dtype, int grad_dtype,
+                           int B, int n_heads, int d, int grid_h, int grid_w,
+                           int start_pos, int n_tokens,
+                           const float *gamma, int boundary_mode, float q_scale,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Reason for the last non-OK status returned on this thread (static storage). */
 const char *lasad_last_error(void);

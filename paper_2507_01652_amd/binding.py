@@ -21,6 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 EXPORTS = (
     "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
+    "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_last_error", "lasad_version",
 )
 
@@ -64,6 +65,11 @@ def load() -> ctypes.CDLL:
     lib.lasad_forward_gated.restype = ci
     lib.lasad_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp]
     lib.lasad_decode_step_gated.restype = ci
+    lib.lasad_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.lasad_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                           vp, ci, cf, vp, ctypes.c_size_t, vp]
+    lib.lasad_backward_chunked.restype = ci
     lib.lasad_last_error.argtypes = []
     lib.lasad_last_error.restype = ctypes.c_char_p
     lib.lasad_version.argtypes = []
@@ -231,6 +237,47 @@ def lasad_decode_step_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor,
                                           _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, pos,
                                           boundary_mode, q_scale, _ptr(state), _stream(stream)))
     return out
+
+
+def lasad_backward_workspace_bytes(B: int, n_heads: int, n_tokens: int, d: int, io_dtype: int) -> int:
+    return int(load().lasad_backward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype))
+
+
+def lasad_backward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
+                           gamma: torch.Tensor, grid_h: int, grid_w: int, start_pos: int = 0,
+                           boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                           grads: tuple | None = None, grad_dtype: torch.dtype | None = None,
+                           dgamma: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                           stream=None):
+    """Gradients of lasad_forward_chunked (zero initial state).  q, k, v, d_o: logical [B, n, Hh, d]
+    views sharing strides and dtype.  Returns (dq, dk, dv, dgamma); `grads` may give the three
+    output tensors (sharing one set of strides), `workspace` a uint8 device tensor."""
+    B, n, Hh, d = q.shape
+    for t in (k, v, d_o):
+        if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
+            raise ValueError("q, k, v, d_o must share shape, strides and dtype")
+    if grads is None:
+        grads = tuple(torch.empty_like(q, dtype=grad_dtype or q.dtype) for _ in range(3))
+    dq, dk, dv = grads
+    for t in (dk, dv):
+        if t.shape != q.shape or t.stride() != dq.stride() or t.dtype != dq.dtype:
+            raise ValueError("dq, dk, dv must share shape, strides and dtype")
+    if dq.shape != q.shape:
+        raise ValueError("gradient tensors have the wrong shape")
+    if gamma.dtype != torch.float32 or gamma.numel() != Hh or not gamma.is_contiguous():
+        raise ValueError("gamma must be contiguous fp32 [Hh]")
+    if dgamma is None:
+        dgamma = torch.empty((Hh,), dtype=torch.float32, device=q.device)
+    need = lasad_backward_workspace_bytes(B, Hh, n, d, _dtype_code(q))
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    li, lg = _layout(q), _layout(dq)
+    _check(load().lasad_backward_chunked(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgamma),
+        ctypes.byref(li), ctypes.byref(lg), _dtype_code(q), _dtype_code(dq),
+        B, Hh, d, grid_h, grid_w, start_pos, n, _ptr(gamma), boundary_mode, q_scale,
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+    return dq, dk, dv, dgamma
 
 
 # ---- host <-> device helpers for seeded numpy inputs (no arithmetic) ---------

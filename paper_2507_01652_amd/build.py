@@ -21,6 +21,7 @@ SOURCES = [
     "lasad_forward_mfma.hip",
     "lasad_forward_gated_mfma.hip",
     "lasad_decode.hip",
+    "lasad_backward.hip",
 ]
 
 # Packed-fp32 instruction selection is switched off for every HIP translation unit.

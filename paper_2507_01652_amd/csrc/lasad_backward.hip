@@ -1,0 +1,202 @@
+// Backward pass of the scalar-decay forward (gradients of the Section 3.4 recurrence from a zero
+// state): dq, dk, dv and the gradient of the per-head base decay.
+//
+// With M[i][j] = prod_{s=j+1..i} lambda_s (j <= i) and g_i = dL/do_i, the forward
+// o_i = q_scale sum_{j<=i} M[i][j] (q_i . k_j) v_j gives
+//
+//   dq_i = q_scale sum_{j<=i} M[i][j] (g_i . v_j) k_j      -- the forward itself with (q, k, v) := (g, v, k)
+//   dv_j = q_scale sum_{i>=j} M[i][j] (q_i . k_j) g_i      -- the forward over the REVERSED sequence, (k, q, g)
+//   dk_j = q_scale sum_{i>=j} M[i][j] (g_i . v_j) q_i      -- the forward over the reversed sequence, (v, g, q)
+//
+// In reversed token order m = n-1-t the decay between two tokens is still a product of the
+// lambdas of the steps between them, with the decay of original token s now applied at
+// reversed step n-s: the boundary pattern is the original one mirrored and shifted by one, which
+// for a raster grid is again "every W-th position" and is obtained by giving the forward
+// kernels a different start column.  Reversal itself costs nothing: the kernels address tokens
+// as base + token * stride, so the reversed passes get a base pointer at the last token and a
+// negative token stride.  The three passes therefore run the forward kernels unchanged (bf16
+// matrix-core kernel, fp32 scan kernel or generic kernel, as the forward would choose).
+//
+// Decay gradient.  Write the decay applied at token t as exp(a_t) and G_i = a_1 + .. + a_i; L
+// depends on the a's only through G_i - G_j, and dL/dG_i = q_i . dq_i - k_i . dk_i.  Every
+// non-boundary token has a_t = log gamma_h, so with E_i = number of non-boundary tokens among the
+// first i tokens of the call
+//
+//   dL/dgamma_h = (1 / gamma_h) sum_b sum_i E_i (q_i . dq_i - k_i . dk_i).
+//
+// dq and dk are produced in fp32 into the workspace; one finishing kernel per sequence forms the
+// sum above (fp32, fixed order) and stores dq, dk in the caller's type and layout, and a last
+// small kernel adds the per-sequence sums over the batch in a fixed order (no atomics).
+#include "lasad_internal.h"
+
+namespace lasad {
+
+namespace {
+
+constexpr int kFinThreads = 256;
+
+template <int IN_BF16, int OUT_BF16>
+__global__ void __launch_bounds__(kFinThreads)
+backward_finish_kernel(BackwardArgs a)
+{
+    __shared__ float red[kFinThreads / 64];
+    const int bh = blockIdx.x;
+    const int b = bh / a.Hh, h = bh - b * a.Hh;
+    const int d = a.d, n = a.n_tokens;
+    const int vec_per_tok = d / 4;                       // 4 channels per thread and step
+    const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
+    const int64_t g_base = (int64_t)b * a.grad.stride_b + (int64_t)h * a.grad.stride_h;
+    const int64_t w_base = ((int64_t)b * n * a.Hh + h) * d;      // workspace: [B][n][Hh][d] fp32
+    const int64_t w_stride_n = (int64_t)a.Hh * d;
+    const int e0 = cum_exp(a.start_pos, a.grid_w, a.mode);
+
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < n * vec_per_tok; i += kFinThreads) {
+        const int t = i / vec_per_tok, c = (i - t * vec_per_tok) * 4;
+        const float4 dq4 = *(const float4 *)(a.dq32 + w_base + t * w_stride_n + c);
+        const float4 dk4 = *(const float4 *)(a.dk32 + w_base + t * w_stride_n + c);
+        const int64_t ii = in_base + (int64_t)t * a.in.stride_n + c;
+        float q4[4], k4[4];
+        if (IN_BF16) {
+            const uint2 qr = *(const uint2 *)((const uint16_t *)a.q + ii);
+            const uint2 kr = *(const uint2 *)((const uint16_t *)a.k + ii);
+            q4[0] = __uint_as_float(qr.x << 16); q4[1] = __uint_as_float(qr.x & 0xffff0000u);
+            q4[2] = __uint_as_float(qr.y << 16); q4[3] = __uint_as_float(qr.y & 0xffff0000u);
+            k4[0] = __uint_as_float(kr.x << 16); k4[1] = __uint_as_float(kr.x & 0xffff0000u);
+            k4[2] = __uint_as_float(kr.y << 16); k4[3] = __uint_as_float(kr.y & 0xffff0000u);
+        } else {
+            const float4 qr = *(const float4 *)((const float *)a.q + ii);
+            const float4 kr = *(const float4 *)((const float *)a.k + ii);
+            q4[0] = qr.x; q4[1] = qr.y; q4[2] = qr.z; q4[3] = qr.w;
+            k4[0] = kr.x; k4[1] = kr.y; k4[2] = kr.z; k4[3] = kr.w;
+        }
+        const float dot = (q4[0] * dq4.x - k4[0] * dk4.x) + (q4[1] * dq4.y - k4[1] * dk4.y) +
+                          (q4[2] * dq4.z - k4[2] * dk4.z) + (q4[3] * dq4.w - k4[3] * dk4.w);
+        const int e = cum_exp(a.start_pos + t + 1, a.grid_w, a.mode) - e0;
+        acc = fmaf((float)e, dot, acc);
+        const int64_t gi = g_base + (int64_t)t * a.grad.stride_n + c;
+        if (OUT_BF16) {
+            uint2 w;
+            w.x = (uint32_t)float_to_bf16_bits(dq4.x) | ((uint32_t)float_to_bf16_bits(dq4.y) << 16);
+            w.y = (uint32_t)float_to_bf16_bits(dq4.z) | ((uint32_t)float_to_bf16_bits(dq4.w) << 16);
+            *(uint2 *)((uint16_t *)a.dq + gi) = w;
+            w.x = (uint32_t)float_to_bf16_bits(dk4.x) | ((uint32_t)float_to_bf16_bits(dk4.y) << 16);
+            w.y = (uint32_t)float_to_bf16_bits(dk4.z) | ((uint32_t)float_to_bf16_bits(dk4.w) << 16);
+            *(uint2 *)((uint16_t *)a.dk + gi) = w;
+        } else {
+            *(float4 *)((float *)a.dq + gi) = dq4;
+            *(float4 *)((float *)a.dk + gi) = dk4;
+        }
+    }
+    // fixed-order reduction: lanes of a wave (xor butterflies), then the four waves
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) a.seq_sums[bh] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// dgamma[h] = (1 / gamma[h]) * sum_b seq_sums[b][h], added in batch order
+__global__ void backward_dgamma_kernel(const float *seq_sums, const float *gamma, float *dgamma, int B, int Hh)
+{
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= Hh) return;
+    float acc = 0.f;
+    for (int b = 0; b < B; ++b) acc += seq_sums[b * Hh + h];
+    dgamma[h] = acc / gamma[h];      // gamma = 0: the formula does not apply (inf or NaN is returned)
+}
+
+// start column of the reversed passes: with it, reversed step m >= 1 carries the decay of
+// original token n - m
+int reversed_start(int start_pos, int n, int grid_w, int mode)
+{
+    const int64_t W = grid_w;
+    int64_t s = 0;
+    if (mode == LASAD_RESET_LAST_COL) s = -((int64_t)start_pos + n + 2);
+    else if (mode == LASAD_RESET_FIRST_COL) s = -((int64_t)start_pos + n);
+    s %= W;
+    if (s < 0) s += W;
+    return (int)s;
+}
+
+const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
+{
+    return (const char *)p + (int64_t)(n - 1) * l.stride_n * elt;
+}
+
+}  // namespace
+
+size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype)
+{
+    const size_t grads = 2 * (size_t)n_seq * n_tokens * d * sizeof(float);
+    const size_t sums = ((size_t)n_seq * sizeof(float) + 255) / 256 * 256;
+    const size_t fwd = (io_dtype == LASAD_BF16 && d == 64) ? forward_mfma_workspace_bytes(n_seq, n_tokens) : 0;
+    return grads + sums + fwd;
+}
+
+hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t s)
+{
+    BackwardArgs b = b_in;
+    const int64_t n_seq = (int64_t)b.B * b.Hh;
+    const int n = b.n_tokens;
+    const int elt = b.io_dtype == LASAD_BF16 ? 2 : 4;
+    const int gelt = b.grad_dtype == LASAD_BF16 ? 2 : 4;
+    // workspace: dq32, dk32 ([B][n][Hh][d] fp32), per-sequence sums, forward-kernel workspace
+    char *ws = (char *)b.workspace;
+    const size_t one = (size_t)n_seq * n * b.d * sizeof(float);
+    b.dq32 = (float *)ws;
+    b.dk32 = (float *)(ws + one);
+    b.seq_sums = (float *)(ws + 2 * one);
+    float *fwd_ws = (float *)(ws + 2 * one + ((size_t)n_seq * sizeof(float) + 255) / 256 * 256);
+    const bool has_fwd_ws = use_mfma && forward_mfma_workspace_bytes(n_seq, n) > 0;
+
+    lasad_layout_t wl;                                   // layout of dq32 / dk32
+    wl.stride_b = (int64_t)n * b.Hh * b.d; wl.stride_n = (int64_t)b.Hh * b.d; wl.stride_h = b.d;
+    lasad_layout_t in_rev = b.in, grad_rev = b.grad, wl_rev = wl;
+    in_rev.stride_n = -b.in.stride_n; grad_rev.stride_n = -b.grad.stride_n; wl_rev.stride_n = -wl.stride_n;
+
+    ForwardArgs f;
+    f.lam = nullptr;
+    f.io_dtype = b.io_dtype;
+    f.B = b.B; f.Hh = b.Hh; f.d = b.d;
+    f.grid_w = b.grid_w; f.n_tokens = n;
+    f.gamma = b.gamma; f.mode = b.mode; f.q_scale = b.q_scale;
+    f.state_in = nullptr; f.state_out = nullptr;
+    f.seg_states = has_fwd_ws ? fwd_ws : nullptr; f.n_segments = 1; f.seg_chunks = 0;
+    auto run = [&](const ForwardArgs &fa) { return use_mfma ? launch_forward_mfma(fa, s) : launch_forward_generic(fa, s); };
+
+    // dq (fp32, workspace): forward order, (q, k, v) := (d_o, v, k)
+    f.q = b.d_o; f.k = b.v; f.v = b.k; f.o = b.dq32;
+    f.in = b.in; f.out = wl; f.out_dtype = LASAD_F32; f.start_pos = b.start_pos;
+    hipError_t e = run(f);
+    if (e != hipSuccess) return e;
+
+    // dv (caller's buffer): reversed order, (q, k, v) := (k, q, d_o)
+    f.q = last_token(b.k, b.in, n, elt); f.k = last_token(b.q, b.in, n, elt); f.v = last_token(b.d_o, b.in, n, elt);
+    f.o = (void *)last_token(b.dv, b.grad, n, gelt);
+    f.in = in_rev; f.out = grad_rev; f.out_dtype = b.grad_dtype;
+    f.start_pos = reversed_start(b.start_pos, n, b.grid_w, b.mode);
+    e = run(f);
+    if (e != hipSuccess) return e;
+
+    // dk (fp32, workspace): reversed order, (q, k, v) := (v, d_o, q)
+    f.q = last_token(b.v, b.in, n, elt); f.k = last_token(b.d_o, b.in, n, elt); f.v = last_token(b.q, b.in, n, elt);
+    f.o = (void *)last_token(b.dk32, wl, n, 4);
+    f.out = wl_rev; f.out_dtype = LASAD_F32;
+    e = run(f);
+    if (e != hipSuccess) return e;
+
+    const dim3 grid((unsigned)n_seq), block(kFinThreads);
+    const bool in16 = b.io_dtype == LASAD_BF16, out16 = b.grad_dtype == LASAD_BF16;
+    if (in16 && out16) hipLaunchKernelGGL((backward_finish_kernel<1, 1>), grid, block, 0, s, b);
+    else if (in16) hipLaunchKernelGGL((backward_finish_kernel<1, 0>), grid, block, 0, s, b);
+    else if (out16) hipLaunchKernelGGL((backward_finish_kernel<0, 1>), grid, block, 0, s, b);
+    else hipLaunchKernelGGL((backward_finish_kernel<0, 0>), grid, block, 0, s, b);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(backward_dgamma_kernel, dim3((unsigned)((b.Hh + 63) / 64)), dim3(64), 0, s,
+                       b.seq_sums, b.gamma, b.dgamma, b.B, b.Hh);
+    return hipGetLastError();
+}
+
+}  // namespace lasad

@@ -44,6 +44,24 @@ struct DecodeArgs {
     float *state;
 };
 
+// Arguments of one backward call, already validated.
+struct BackwardArgs {
+    const void *q, *k, *v, *d_o;   // [B, n, Hh, d] views sharing one layout and storage type
+    void *dq, *dk, *dv;            // same logical shape, layout `grad`, type grad_dtype
+    float *dgamma;                 // [Hh]
+    lasad_layout_t in, grad;
+    int io_dtype, grad_dtype;
+    int B, Hh, d;
+    int grid_w;
+    int start_pos, n_tokens;
+    const float *gamma;
+    int mode;
+    float q_scale;
+    void *workspace;
+    // carved out of the workspace by the launcher
+    float *dq32, *dk32, *seq_sums;
+};
+
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,
                                 int mode, float *lambda_out, int32_t *cum_out, hipStream_t s);
 hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s);
@@ -56,6 +74,10 @@ hipError_t launch_forward_gated_mfma(const ForwardArgs &a, hipStream_t s);
 // device workspace the MFMA kernel wants for n_seq sequences of n_tokens tokens (0 = none)
 size_t forward_mfma_workspace_bytes(int64_t n_seq, int n_tokens);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+// Backward of the scalar-decay forward: three runs of the forward kernels (MFMA kernel if
+// use_mfma, else the generic / scan kernels) plus two small finishing kernels.
+hipError_t launch_backward(const BackwardArgs &a, bool use_mfma, hipStream_t s);
+size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype);
 
 // ---- device helpers -----------------------------------------------------------
 
