@@ -60,6 +60,7 @@ def parse():
     p.add_argument("--decode-walks", type=int, default=4, help="timed raster walks of 256 decode steps (0 = skip)")
     p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-backward", action="store_true", help="skip the backward-pass leg")
     p.add_argument("--no-gated", action="store_true",
                    help="skip the vector-decay (per-channel gate) forward and decode legs")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
@@ -228,6 +229,70 @@ def bench_decode(args, torch, lasad, wl):
     return res
 
 
+def bench_backward(args, torch, lasad, wl):
+    """Backward leg: one lasad_backward_chunked call (dq, dk, dv, dgamma from q, k, v, d_o) per step over the
+    prefill workload's shape, timed like the forward."""
+    import numpy as np
+    w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
+    q, k, v, gam = wl.prefill_inputs(w, layout=args.layout)
+    rng = np.random.default_rng(w.seed + 101)
+    g = wl.store_round(rng.standard_normal(q.shape, dtype=np.float32) / np.float32(np.sqrt(w.d)), w.dtype)
+    if args.layout == "bhnd":
+        g = np.ascontiguousarray(g.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3)
+    tq, tk, tv, td = (lasad.to_device(x, w.dtype) for x in (q, k, v, g))
+    tg = torch.from_numpy(gam).cuda()
+    token_heads = w.B * w.N * w.Hh
+    bytes_bwd = token_heads * 7 * w.d * 2             # q, k, v, d_o read + dq, dk, dv written, bf16
+    sets = max(4, min(64, -(-(1 << 30) // bytes_bwd)))
+    bufs = []
+    for i in range(sets):
+        ins = (tq, tk, tv, td) if i == 0 else tuple(x.clone() for x in (tq, tk, tv, td))
+        bufs.append(ins + (tuple(torch.empty_like(tq) for _ in range(3)),))
+    dgam = torch.empty((w.Hh,), dtype=torch.float32, device="cuda")
+    ws_bytes = lasad.lasad_backward_workspace_bytes(w.B, w.Hh, w.N, w.d, lasad.BF16)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda")
+    steps = max(1, min(args.steps, 50))
+
+    def run(nsteps, first=0):
+        for i in range(nsteps):
+            a, b, c, d_o, grads = bufs[(first + i) % sets]
+            lasad.lasad_backward_chunked(a, b, c, d_o, tg, w.grid_h, w.grid_w, grads=grads, dgamma=dgam, workspace=ws)
+
+    run(min(args.warmup, 5))
+    eager_ms = time_region(torch, lambda: run(steps, 5))
+    graph_ms = None
+    if not args.no_graph:
+        g_ = capture(torch, lambda: run(steps, 5))
+        g_.replay()
+        graph_ms = time_region(torch, g_.replay)
+    dur_s = (graph_ms if graph_ms is not None else eager_ms) / steps * 1e-3
+    res = {"workload": w.name, "value": w.B * w.N / dur_s, "unit": "tokens/s", "ms_per_step": dur_s * 1e3,
+           "steps_timed": steps, "eager_ms_per_step": eager_ms / steps, "workspace_bytes": ws_bytes,
+           "launches_per_step": "3 forward-kernel passes (+ their state passes when segmented) + 2 finishing kernels",
+           "roofline": {"bound": "hbm", "kernel": "lasad_backward_chunked (all launches of one call)",
+                        "achieved": bytes_bwd / dur_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": bytes_bwd / dur_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_bwd,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get("backward:" + w.name)}}
+    if not args.no_cpu_baseline:
+        from oracle import lasad_oracle as oracle
+        n_seq = min(w.B * w.Hh, 2 * oracle.num_threads())
+        pairs = [(i // w.Hh, i % w.Hh) for i in np.linspace(0, w.B * w.Hh - 1, n_seq).astype(int)]
+        gq, gk, gv, gg = (np.stack([x[b, :, h, :] for b, h in pairs], axis=1)[None] for x in (q, k, v, g))
+        lam, _ = oracle.decay_factors(gam[[h for _, h in pairs]], w.grid_h, w.grid_w, 0, w.N)
+        passes, t0 = 0, time.perf_counter()
+        while True:
+            oracle.backward(gq, gk, gv, lam, gg)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt > 3.0 or passes >= 100:
+                break
+        res["cpu_baseline"] = {"value": passes * n_seq * w.N / w.Hh / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{n_seq} of {w.B * w.Hh} (batch, head) sequences, fp64 reverse-mode recurrence, "
+                                         f"{passes} pass(es), {dt:.2f} s wall"}
+    return res
+
+
 def bench_gated(args, torch, lasad, wl):
     """Vector-decay legs (Section 3.4 as written, key tied to the gate): the forward over the prefill
     workload's shape and the decode step over the AR-decode shape, timed like the scalar legs."""
@@ -355,6 +420,8 @@ def main():
         line["cpu_baseline"] = cpu_baseline_prefill(pre)
     if args.decode_walks > 0:
         line["decode"] = bench_decode(args, torch, lasad, wl)
+    if not args.no_backward:
+        line["backward"] = bench_backward(args, torch, lasad, wl)
     if not args.no_gated:
         line["gated"] = bench_gated(args, torch, lasad, wl)
     print(json.dumps(line), flush=True)

@@ -24,9 +24,10 @@
 //
 //   dL/dgamma_h = (1 / gamma_h) sum_b sum_i E_i (q_i . dq_i - k_i . dk_i).
 //
-// dq and dk are produced in fp32 into the workspace; one finishing kernel per sequence forms the
-// sum above (fp32, fixed order) and stores dq, dk in the caller's type and layout, and a last
-// small kernel adds the per-sequence sums over the batch in a fixed order (no atomics).
+// dq and dk are produced in fp32 into the workspace; a finishing kernel (one workgroup per 64
+// tokens of a sequence) forms its part of the sum above (fp32, fixed order) and stores dq, dk in
+// the caller's type and layout, and a last small kernel (one wave per head) adds the partial
+// sums in a fixed order (no atomics).
 #include "lasad_internal.h"
 
 namespace lasad {
@@ -34,25 +35,28 @@ namespace lasad {
 namespace {
 
 constexpr int kFinThreads = 256;
+constexpr int kFinTokens = 64;       // tokens per workgroup of the finishing kernel
 
 template <int IN_BF16, int OUT_BF16>
 __global__ void __launch_bounds__(kFinThreads)
 backward_finish_kernel(BackwardArgs a)
 {
     __shared__ float red[kFinThreads / 64];
-    const int bh = blockIdx.x;
+    const int nblk = (a.n_tokens + kFinTokens - 1) / kFinTokens;
+    const int bh = blockIdx.x / nblk, blk = blockIdx.x - bh * nblk;
     const int b = bh / a.Hh, h = bh - b * a.Hh;
-    const int d = a.d, n = a.n_tokens;
+    const int d = a.d;
+    const int tb = blk * kFinTokens, n = min(kFinTokens, a.n_tokens - tb);   // this workgroup's tokens
     const int vec_per_tok = d / 4;                       // 4 channels per thread and step
     const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
     const int64_t g_base = (int64_t)b * a.grad.stride_b + (int64_t)h * a.grad.stride_h;
-    const int64_t w_base = ((int64_t)b * n * a.Hh + h) * d;      // workspace: [B][n][Hh][d] fp32
+    const int64_t w_base = ((int64_t)b * a.n_tokens * a.Hh + h) * d;      // workspace: [B][n][Hh][d] fp32
     const int64_t w_stride_n = (int64_t)a.Hh * d;
     const int e0 = cum_exp(a.start_pos, a.grid_w, a.mode);
 
     float acc = 0.f;
     for (int i = threadIdx.x; i < n * vec_per_tok; i += kFinThreads) {
-        const int t = i / vec_per_tok, c = (i - t * vec_per_tok) * 4;
+        const int t = tb + i / vec_per_tok, c = (i % vec_per_tok) * 4;
         const float4 dq4 = *(const float4 *)(a.dq32 + w_base + t * w_stride_n + c);
         const float4 dk4 = *(const float4 *)(a.dk32 + w_base + t * w_stride_n + c);
         const int64_t ii = in_base + (int64_t)t * a.in.stride_n + c;
@@ -93,17 +97,23 @@ backward_finish_kernel(BackwardArgs a)
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
     __syncthreads();
-    if (threadIdx.x == 0) a.seq_sums[bh] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0) a.seq_sums[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// dgamma[h] = (1 / gamma[h]) * sum_b seq_sums[b][h], added in batch order
-__global__ void backward_dgamma_kernel(const float *seq_sums, const float *gamma, float *dgamma, int B, int Hh)
+// dgamma[h] = (1 / gamma[h]) * sum over the batch and the token blocks of the partial sums of head h.
+// One wave per head: lane l adds entries l, l + 64, ... in order, then a butterfly over the lanes.
+__global__ void __launch_bounds__(64)
+backward_dgamma_kernel(const float *sums, const float *gamma, float *dgamma, int B, int Hh, int nblk)
 {
-    const int h = blockIdx.x * blockDim.x + threadIdx.x;
-    if (h >= Hh) return;
+    const int h = blockIdx.x;
     float acc = 0.f;
-    for (int b = 0; b < B; ++b) acc += seq_sums[b * Hh + h];
-    dgamma[h] = acc / gamma[h];      // gamma = 0: the formula does not apply (inf or NaN is returned)
+    for (int i = threadIdx.x; i < B * nblk; i += 64) {
+        const int b = i / nblk, blk = i - b * nblk;
+        acc += sums[((int64_t)b * Hh + h) * nblk + blk];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if (threadIdx.x == 0) dgamma[h] = acc / gamma[h];     // gamma = 0: the formula does not apply (inf or NaN)
 }
 
 // start column of the reversed passes: with it, reversed step m >= 1 carries the decay of
@@ -126,10 +136,16 @@ const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
 
 }  // namespace
 
+static size_t sums_bytes(int64_t n_seq, int n_tokens)
+{
+    const size_t nblk = (size_t)(n_tokens + kFinTokens - 1) / kFinTokens;
+    return ((size_t)n_seq * nblk * sizeof(float) + 255) / 256 * 256;
+}
+
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype)
 {
     const size_t grads = 2 * (size_t)n_seq * n_tokens * d * sizeof(float);
-    const size_t sums = ((size_t)n_seq * sizeof(float) + 255) / 256 * 256;
+    const size_t sums = sums_bytes(n_seq, n_tokens);
     const size_t fwd = (io_dtype == LASAD_BF16 && d == 64) ? forward_mfma_workspace_bytes(n_seq, n_tokens) : 0;
     return grads + sums + fwd;
 }
@@ -147,7 +163,7 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     b.dq32 = (float *)ws;
     b.dk32 = (float *)(ws + one);
     b.seq_sums = (float *)(ws + 2 * one);
-    float *fwd_ws = (float *)(ws + 2 * one + ((size_t)n_seq * sizeof(float) + 255) / 256 * 256);
+    float *fwd_ws = (float *)(ws + 2 * one + sums_bytes(n_seq, n));
     const bool has_fwd_ws = use_mfma && forward_mfma_workspace_bytes(n_seq, n) > 0;
 
     lasad_layout_t wl;                                   // layout of dq32 / dk32
@@ -186,7 +202,9 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     e = run(f);
     if (e != hipSuccess) return e;
 
-    const dim3 grid((unsigned)n_seq), block(kFinThreads);
+    const int nblk = (n + kFinTokens - 1) / kFinTokens;
+    if (n_seq * nblk > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(n_seq * nblk)), block(kFinThreads);
     const bool in16 = b.io_dtype == LASAD_BF16, out16 = b.grad_dtype == LASAD_BF16;
     if (in16 && out16) hipLaunchKernelGGL((backward_finish_kernel<1, 1>), grid, block, 0, s, b);
     else if (in16) hipLaunchKernelGGL((backward_finish_kernel<1, 0>), grid, block, 0, s, b);
@@ -194,8 +212,8 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     else hipLaunchKernelGGL((backward_finish_kernel<0, 0>), grid, block, 0, s, b);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(backward_dgamma_kernel, dim3((unsigned)((b.Hh + 63) / 64)), dim3(64), 0, s,
-                       b.seq_sums, b.gamma, b.dgamma, b.B, b.Hh);
+    hipLaunchKernelGGL(backward_dgamma_kernel, dim3((unsigned)b.Hh), dim3(64), 0, s,
+                       b.seq_sums, b.gamma, b.dgamma, b.B, b.Hh, nblk);
     return hipGetLastError();
 }
 
