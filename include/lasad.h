@@ -167,6 +167,23 @@ int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const
                             float *state, void *hip_stream);
 
 /*
+ * Decode step with one raster position per batch row (continuous batching: the sequences of a
+ * batch are at different points of their images, Section 3.1 raster order; each row's decay is
+ * switched off by the boundary rule of Section 3.4 at ITS position).
+ *   pos_rows  [B] int32 (device): 0-indexed raster position of the token each row consumes.  A
+ *             row whose entry is outside 0 .. grid_h*grid_w-1 (say -1) is inactive: its states are
+ *             left untouched and its output rows are zero.
+ *   lam       vector decay [B, n_heads, d] (then gamma must be NULL, k may be NULL for the tied
+ *             key), or NULL for the per-head scalar decay (then gamma [n_heads] and k are needed).
+ * Everything else as in lasad_decode_step / lasad_decode_step_gated.
+ */
+int lasad_decode_step_rows(const void *q, const void *lam, const void *k, const void *v, void *o,
+                           int io_dtype, int out_dtype, int B, int n_heads, int d,
+                           int grid_h, int grid_w, const int32_t *pos_rows,
+                           const float *gamma, int boundary_mode, float q_scale,
+                           float *state, void *hip_stream);
+
+/*
  * Backward pass of lasad_forward_chunked for a call that starts from a zero state and whose
  * final state is not used (a whole teacher-forced sequence, the training setting of Section 4.1):
  * given d_o = dL/do, the gradients of the Section 3.4 recurrence

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 EXPORTS = (
     "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
-    "lasad_backward_workspace_bytes", "lasad_backward_chunked",
+    "lasad_decode_step_rows", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_last_error", "lasad_version",
 )
 
@@ -65,6 +65,8 @@ def load() -> ctypes.CDLL:
     lib.lasad_forward_gated.restype = ci
     lib.lasad_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp]
     lib.lasad_decode_step_gated.restype = ci
+    lib.lasad_decode_step_rows.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, ci, cf, vp, vp]
+    lib.lasad_decode_step_rows.restype = ci
     lib.lasad_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.lasad_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.lasad_backward_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
@@ -236,6 +238,33 @@ def lasad_decode_step_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor,
     _check(load().lasad_decode_step_gated(_ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(out),
                                           _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, pos,
                                           boundary_mode, q_scale, _ptr(state), _stream(stream)))
+    return out
+
+
+def lasad_decode_step_rows(q: torch.Tensor, v: torch.Tensor, state: torch.Tensor, pos_rows: torch.Tensor,
+                           grid_h: int, grid_w: int, k: torch.Tensor | None = None,
+                           lam: torch.Tensor | None = None, gamma: torch.Tensor | None = None,
+                           boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                           out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                           stream=None) -> torch.Tensor:
+    """One decode step with a raster position per batch row (pos_rows: int32 [B] on the device; entries
+    outside the grid mark inactive rows).  Scalar decay: give gamma and k; vector decay: give lam (k optional)."""
+    B, Hh, d = q.shape
+    for t in (q, v) + tuple(x for x in (k, lam) if x is not None):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("q, lam, k, v must be contiguous [B, Hh, d] of one dtype")
+    if state.dtype != torch.float32 or not state.is_contiguous() or tuple(state.shape) != (B, Hh, d, d):
+        raise ValueError("state must be contiguous fp32 [B, Hh, d, d]")
+    if pos_rows.dtype != torch.int32 or pos_rows.numel() != B or not pos_rows.is_contiguous():
+        raise ValueError("pos_rows must be contiguous int32 [B]")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hh, d]")
+    _check(load().lasad_decode_step_rows(_ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(out),
+                                         _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w,
+                                         _ptr(pos_rows), _ptr(gamma), boundary_mode, q_scale, _ptr(state),
+                                         _stream(stream)))
     return out
 
 

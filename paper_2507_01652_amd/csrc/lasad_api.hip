@@ -167,7 +167,7 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
     a.q = q; a.k = k; a.v = v; a.o = o; a.lam = nullptr;
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
-    a.grid_w = grid_w; a.pos = pos;
+    a.grid_w = grid_w; a.pos = pos; a.pos_rows = nullptr; a.grid_n = grid_h * grid_w;
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state = state;
     hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
@@ -321,11 +321,44 @@ int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const
     a.q = q; a.k = k; a.v = v; a.o = o; a.lam = lam;
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
-    a.grid_w = grid_w; a.pos = pos;
+    a.grid_w = grid_w; a.pos = pos; a.pos_rows = nullptr; a.grid_n = grid_h * grid_w;
     a.gamma = nullptr; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state = state;
     hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_decode_step_gated launch", e);
+    return LASAD_OK;
+}
+
+int lasad_decode_step_rows(const void *q, const void *lam, const void *k, const void *v, void *o,
+                           int io_dtype, int out_dtype, int B, int n_heads, int d,
+                           int grid_h, int grid_w, const int32_t *pos_rows,
+                           const float *gamma, int boundary_mode, float q_scale,
+                           float *state, void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (out_dtype != LASAD_F32 && out_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "out_dtype %d", out_dtype);
+    if (io_dtype == LASAD_F32 && out_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 output");
+    if (!q || !v || !o || !state || !pos_rows) return fail(LASAD_ERR_INVALID_ARG, "a required pointer is NULL");
+    if (lam && gamma) return fail(LASAD_ERR_INVALID_ARG, "give either lam (vector decay) or gamma (scalar decay), not both");
+    if (!lam && (!gamma || !k)) return fail(LASAD_ERR_INVALID_ARG, "the scalar-decay step needs gamma and k");
+    if (!aligned(q, 16) || !aligned(lam, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) ||
+        !aligned(state, 16) || !aligned(pos_rows, 4))
+        return fail(LASAD_ERR_INVALID_ARG, "q, lam, k, v, o and state must be 16-byte aligned");
+    if (o == q || o == v || (lam && o == lam) || (k && o == k)) return fail(LASAD_ERR_INVALID_ARG, "o aliases an input");
+
+    lasad::DecodeArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lam = lam;
+    a.io_dtype = io_dtype; a.out_dtype = out_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d;
+    a.grid_w = grid_w; a.pos = 0; a.pos_rows = pos_rows; a.grid_n = grid_h * grid_w;
+    a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
+    a.state = state;
+    hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_decode_step_rows launch", e);
     return LASAD_OK;
 }
 

@@ -60,17 +60,28 @@ decode_kernel(DecodeArgs a, int n_states)
     const int bh = blockIdx.x * kWaves + wave;
     if (bh >= n_states) return;      // whole wave leaves together; no barrier below
     const int h = bh % a.Hh;
-    const int t = a.pos + 1;
+    const int cg = lane % CG, r0 = lane / CG;
+    const int64_t vec = (int64_t)bh * D;
+    int pos = a.pos;
+    if (a.pos_rows) {                // continuous batching: every batch row at its own raster position
+        pos = a.pos_rows[bh / a.Hh];
+        if (pos < 0 || pos >= a.grid_n) {      // inactive row: state untouched, output row zero (whole wave)
+            if (r0 == 0) {
+                if (OUT_BF16) *(ushort4 *)((uint16_t *)a.o + vec + cg * 4) = make_ushort4(0, 0, 0, 0);
+                else *(float4 *)((float *)a.o + vec + cg * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            return;
+        }
+    }
+    const int t = pos + 1;
     const bool boundary = is_boundary(t, a.grid_w, a.mode);
     const float lam = (boundary || GATED) ? 1.0f : a.gamma[h];
 
-    const int cg = lane % CG, r0 = lane / CG;
     float4 *S = (float4 *)(a.state + (int64_t)bh * D * D);
 
     // Global loads in issue order: the small q, k, v vectors, then the first
     // batch of state pieces; only then are q and k parked in LDS (fp32,
     // wave-private region) so that every lane can read any row's q_i, k_i.
-    const int64_t vec = (int64_t)bh * D;
     constexpr int NQ = (D + 63) / 64;
     float qr[NQ], kr[NQ], lr[NQ];
 #pragma unroll

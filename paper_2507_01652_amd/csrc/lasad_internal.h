@@ -38,6 +38,9 @@ struct DecodeArgs {
     int io_dtype, out_dtype;
     int B, Hh, d;
     int grid_w, pos;
+    const int32_t *pos_rows;     // per batch row positions [B] (device), or NULL: every row at `pos`.
+                                 // A row whose position is outside 0 .. grid_n-1 is inactive.
+    int grid_n;                  // grid_h * grid_w
     const float *gamma;
     int mode;
     float q_scale;
