@@ -224,3 +224,39 @@ def gated_bruteforce(q, lam, v, grid_w, k=None, start_pos=0, mode=RESET_LAST_COL
     if rc != 0:
         raise RuntimeError(f"lasad_oracle_gated_bruteforce failed (rc={rc})")
     return o
+
+
+# ---- Algorithm 1's elementwise steps around the recurrence --------------------------------------
+
+def silu(x):
+    """SiLU(x) = x * sigmoid(x) (Algorithm 1, the line after the projections), fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    return x * sigmoid(x)
+
+
+def sigmoid(x):
+    """1 / (1 + exp(-x)), fp64, evaluated without overflow on either side."""
+    x = np.asarray(x, dtype=np.float64)
+    e = np.exp(-np.abs(x))
+    return np.where(x >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+
+
+def rms_norm(o, weight=None, eps=1e-6):
+    """Norm(o_t) of Algorithm 1's last line, read as a root-mean-square normalisation over the d
+    channels of each head: o / sqrt(mean(o^2) + eps), times an optional per-(head, channel) weight."""
+    o = np.asarray(o, dtype=np.float64)
+    out = o / np.sqrt(np.mean(o * o, axis=-1, keepdims=True) + eps)
+    if weight is not None:
+        out = out * np.asarray(weight, dtype=np.float64)       # [Hh, d] broadcast over [B, n, Hh, d]
+    return out
+
+
+def gated_layer(q_pre, z, v, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mode=RESET_LAST_COL,
+                q_scale=1.0, s0=None, want_state=False):
+    """Algorithm 1's loop body between the two Linear maps: q = SiLU(q_pre), lambda = sigmoid(z),
+    k = 1 - lambda, the spatially aware recurrence, then Norm(o).  Shapes as gated_recurrent."""
+    r = gated_recurrent(silu(q_pre), sigmoid(z), v, grid_w, k=None, start_pos=start_pos, mode=mode,
+                        q_scale=q_scale, s0=s0, want_state=want_state)
+    o, s = (r if want_state else (r, None))
+    o = rms_norm(o, norm_weight, eps)
+    return (o, s) if want_state else o

@@ -1,0 +1,63 @@
+"""Pins of the elementwise steps of Algorithm 1 that surround the recurrence (oracle.silu, oracle.sigmoid,
+oracle.rms_norm, oracle.gated_layer): known values and identities of the two activations, the defining
+properties of a root-mean-square normalisation, and a hand-worked two-token layer."""
+import math
+
+import numpy as np
+
+
+def test_sigmoid_values_and_identities(oracle):
+    assert oracle.sigmoid(0.0) == 0.5
+    assert abs(oracle.sigmoid(math.log(3.0)) - 0.75) < 1e-15          # 1 / (1 + 1/3)
+    assert abs(oracle.sigmoid(-math.log(3.0)) - 0.25) < 1e-15
+    x = np.linspace(-40, 40, 161)
+    s = oracle.sigmoid(x)
+    assert np.allclose(s + oracle.sigmoid(-x), 1.0, atol=1e-15)          # sigma(-x) = 1 - sigma(x)
+    assert np.all(np.diff(s) >= 0) and s[0] < 1e-17 and s[-1] == 1.0
+    assert np.isfinite(oracle.sigmoid(np.array([-800.0, 800.0]))).all()  # no overflow
+    # derivative sigma' = sigma (1 - sigma), by a central difference
+    h = 1e-5
+    d = (oracle.sigmoid(x + h) - oracle.sigmoid(x - h)) / (2 * h)
+    assert np.allclose(d, s * (1 - s), atol=1e-9)
+
+
+def test_silu_values(oracle):
+    assert oracle.silu(0.0) == 0.0
+    assert abs(oracle.silu(math.log(3.0)) - 0.75 * math.log(3.0)) < 1e-15
+    assert abs(oracle.silu(-math.log(3.0)) + 0.25 * math.log(3.0)) < 1e-15
+    assert abs(oracle.silu(50.0) - 50.0) < 1e-12 and abs(oracle.silu(-50.0)) < 1e-12
+    x = np.linspace(-6, 6, 49)
+    assert np.allclose(oracle.silu(x) - oracle.silu(-x), x, atol=1e-14)   # SiLU(x) - SiLU(-x) = x
+
+
+def test_rms_norm_properties(oracle):
+    rng = np.random.default_rng(1)
+    o = rng.standard_normal((2, 5, 3, 8))
+    y = oracle.rms_norm(o, eps=0.0)
+    assert np.allclose(np.sqrt(np.mean(y * y, axis=-1)), 1.0, atol=1e-14)           # unit RMS per token and head
+    assert np.allclose(oracle.rms_norm(7.5 * o, eps=0.0), y, atol=1e-13)             # scale invariant
+    assert np.allclose(oracle.rms_norm(np.array([3.0, -4.0, 0.0, 0.0]), eps=0.0), [1.2, -1.6, 0.0, 0.0])  # rms = 2.5
+    w = rng.standard_normal((3, 8))
+    assert np.allclose(oracle.rms_norm(o, w, eps=0.0), y * w[None, None], atol=1e-14)
+    assert np.allclose(oracle.rms_norm(np.array([2.0, 2.0]), eps=5.0), [2.0 / 3.0] * 2)   # sqrt(4 + 5) = 3
+    assert not oracle.rms_norm(np.zeros(4), eps=1e-6).any()
+
+
+def test_layer_hand_worked(oracle):
+    """Two tokens on a 1 x 2 grid (the second is a row end), d = 2, inputs chosen so that the activations are
+    exact: z = +-ln 3 gives lambda = 0.75 / 0.25, q_pre = ln 3 gives q = 0.75 ln 3.
+      token 1: lambda = (0.75, 0.25), k = (0.25, 0.75), v = (4, 8):  s = [[1, 2], [3, 6]]
+               q = (a, 0) with a = 0.75 ln 3:  o = a (1, 2) -> rms norm (eps 0): (1, 2) / sqrt(2.5)
+      token 2 (boundary, decay 1): lambda = (0.25, 0.25) -> k = (0.75, 0.75), v = (4, 0): s = [[4, 2], [6, 6]]
+               q = (0, a):  o = a (6, 6) -> (1, 1)."""
+    L = math.log(3.0)
+    q_pre = np.array([[L, 0.0], [0.0, L]]).reshape(1, 2, 1, 2)
+    z = np.array([[L, -L], [-L, -L]]).reshape(1, 2, 1, 2)
+    v = np.array([[4.0, 8.0], [4.0, 0.0]]).reshape(1, 2, 1, 2)
+    o, s = oracle.gated_layer(q_pre, z, v, grid_w=2, eps=0.0, want_state=True)
+    assert np.allclose(s[0, 0], [[4.0, 2.0], [6.0, 6.0]], atol=1e-14)
+    assert np.allclose(o[0, 0, 0], np.array([1.0, 2.0]) / math.sqrt(2.5), atol=1e-14)
+    assert np.allclose(o[0, 1, 0], [1.0, 1.0], atol=1e-14)
+    # the same layer assembled by hand from the pinned pieces
+    ref = oracle.rms_norm(oracle.gated_recurrent(oracle.silu(q_pre), oracle.sigmoid(z), v, 2), eps=0.0)
+    assert np.array_equal(o, ref)
