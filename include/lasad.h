@@ -167,6 +167,32 @@ int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const
                             float *state, void *hip_stream);
 
 /*
+ * The loop body of Algorithm 1 between its two Linear maps, fused around the vector-decay
+ * recurrence (head dim 64 for the forward):
+ *     q = SiLU(q_pre),  lambda = sigmoid(z),  k = 1 - lambda,  the recurrence of
+ *     lasad_forward_gated / lasad_decode_step_gated,  o = Norm(o).
+ * Norm is not specified further by the paper; it is taken as a root-mean-square normalisation
+ * over the d channels of each head, o / sqrt(mean_c(o^2) + norm_eps), times norm_weight.
+ *   q_pre, z      pre-activation query and gate, layout and type as q and lam of the gated calls.
+ *   norm_weight   [n_heads, d] fp32 (device, 16-byte aligned), or NULL for ones.
+ *   norm_eps      >= 0; a negative value switches the normalisation off (activations only).
+ * The activations are evaluated in fp32 on load and nothing is rounded between the steps.
+ * Everything else as in the gated calls.
+ */
+int lasad_forward_layer(const void *q_pre, const void *z, const void *v, void *o,
+                        const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
+                        int io_dtype, int out_dtype,
+                        int B, int n_heads, int d, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                        const float *norm_weight, float norm_eps,
+                        const float *state_in, float *state_out, void *hip_stream);
+int lasad_decode_step_layer(const void *q_pre, const void *z, const void *v, void *o,
+                            int io_dtype, int out_dtype, int B, int n_heads, int d,
+                            int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                            const float *norm_weight, float norm_eps,
+                            float *state, void *hip_stream);
+
+/*
  * Decode step with one raster position per batch row (continuous batching: the sequences of a
  * batch are at different points of their images, Section 3.1 raster order; each row's decay is
  * switched off by the boundary rule of Section 3.4 at ITS position).

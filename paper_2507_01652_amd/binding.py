@@ -21,6 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 EXPORTS = (
     "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
+    "lasad_forward_layer", "lasad_decode_step_layer",
     "lasad_decode_step_rows", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_last_error", "lasad_version",
 )
@@ -65,6 +66,10 @@ def load() -> ctypes.CDLL:
     lib.lasad_forward_gated.restype = ci
     lib.lasad_decode_step_gated.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp]
     lib.lasad_decode_step_gated.restype = ci
+    lib.lasad_forward_layer.argtypes = [vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, cf, vp, vp, vp]
+    lib.lasad_forward_layer.restype = ci
+    lib.lasad_decode_step_layer.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, cf, vp, vp]
+    lib.lasad_decode_step_layer.restype = ci
     lib.lasad_decode_step_rows.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, ci, cf, vp, vp]
     lib.lasad_decode_step_rows.restype = ci
     lib.lasad_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
@@ -238,6 +243,54 @@ def lasad_decode_step_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor,
     _check(load().lasad_decode_step_gated(_ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(out),
                                           _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, pos,
                                           boundary_mode, q_scale, _ptr(state), _stream(stream)))
+    return out
+
+
+def lasad_forward_layer(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, grid_h: int, grid_w: int,
+                        norm_weight: torch.Tensor | None = None, norm_eps: float = 1e-6,
+                        start_pos: int = 0, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                        state_in: torch.Tensor | None = None, state_out: torch.Tensor | None = None,
+                        out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                        stream=None) -> torch.Tensor:
+    """Algorithm 1 between its Linear maps: SiLU(q_pre), sigmoid(z), k = 1 - lambda, recurrence, RMS norm.
+    q_pre, z, v: logical [B, n, Hh, 64] views sharing strides; norm_eps < 0 switches the norm off."""
+    B, n, Hh, d = q_pre.shape
+    for t in (z, v):
+        if t.shape != q_pre.shape or t.stride() != q_pre.stride() or t.dtype != q_pre.dtype:
+            raise ValueError("q_pre, z, v must share shape, strides and dtype")
+    if norm_weight is not None and (norm_weight.dtype != torch.float32 or not norm_weight.is_contiguous()
+                                    or norm_weight.numel() != Hh * d):
+        raise ValueError("norm_weight must be contiguous fp32 [Hh, d]")
+    if out is None:
+        out = torch.empty_like(q_pre, dtype=out_dtype or q_pre.dtype)
+    for s in (state_in, state_out):
+        if s is not None and (s.dtype != torch.float32 or not s.is_contiguous() or tuple(s.shape) != (B, Hh, d, d)):
+            raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
+    lq, lo = _layout(q_pre), _layout(out)
+    _check(load().lasad_forward_layer(
+        _ptr(q_pre), _ptr(z), _ptr(v), _ptr(out), ctypes.byref(lq), ctypes.byref(lo),
+        _dtype_code(q_pre), _dtype_code(out), B, Hh, d, grid_h, grid_w, start_pos, n,
+        boundary_mode, q_scale, _ptr(norm_weight), norm_eps, _ptr(state_in), _ptr(state_out), _stream(stream)))
+    return out
+
+
+def lasad_decode_step_layer(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, state: torch.Tensor,
+                            grid_h: int, grid_w: int, pos: int, norm_weight: torch.Tensor | None = None,
+                            norm_eps: float = 1e-6, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                            out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                            stream=None) -> torch.Tensor:
+    """One decode step of the fused layer.  q_pre, z, v: contiguous [B, Hh, d]; state fp32 in place."""
+    B, Hh, d = q_pre.shape
+    for t in (q_pre, z, v):
+        if t.shape != q_pre.shape or t.dtype != q_pre.dtype or not t.is_contiguous():
+            raise ValueError("q_pre, z, v must be contiguous [B, Hh, d] of one dtype")
+    if state.dtype != torch.float32 or not state.is_contiguous() or tuple(state.shape) != (B, Hh, d, d):
+        raise ValueError("state must be contiguous fp32 [B, Hh, d, d]")
+    if out is None:
+        out = torch.empty_like(q_pre, dtype=out_dtype or q_pre.dtype)
+    _check(load().lasad_decode_step_layer(_ptr(q_pre), _ptr(z), _ptr(v), _ptr(out), _dtype_code(q_pre), _dtype_code(out),
+                                          B, Hh, d, grid_h, grid_w, pos, boundary_mode, q_scale,
+                                          _ptr(norm_weight), norm_eps, _ptr(state), _stream(stream)))
     return out
 
 

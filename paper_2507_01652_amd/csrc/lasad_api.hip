@@ -123,6 +123,7 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state_in = state_in; a.state_out = state_out;
     a.seg_states = nullptr; a.n_segments = 1; a.seg_chunks = 0;
+    a.fused_act = 0; a.norm = 0; a.norm_eps = 0.f; a.norm_w = nullptr;
     if (workspace) {
         const size_t need = lasad_forward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype);
         if (workspace_bytes < need)
@@ -168,6 +169,7 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
     a.grid_w = grid_w; a.pos = pos; a.pos_rows = nullptr; a.grid_n = grid_h * grid_w;
+    a.fused_act = 0; a.norm = 0; a.norm_eps = 0.f; a.norm_w = nullptr;
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state = state;
     hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
@@ -175,13 +177,16 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
     return LASAD_OK;
 }
 
-int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
-                        const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
-                        int io_dtype, int out_dtype,
-                        int B, int n_heads, int d, int grid_h, int grid_w,
-                        int start_pos, int n_tokens, int boundary_mode, float q_scale,
-                        const float *state_in, float *state_out, void *hip_stream)
+static int forward_gated_common(const void *q, const void *lam, const void *k, const void *v, void *o,
+                                const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
+                                int io_dtype, int out_dtype,
+                                int B, int n_heads, int d, int grid_h, int grid_w,
+                                int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                                const float *state_in, float *state_out, void *hip_stream,
+                                int layer, const float *norm_weight, float norm_eps)
 {
+    if (layer && d != 64) return fail(LASAD_ERR_UNSUPPORTED, "the fused layer needs head dim 64 (got %d)", d);
+    if (layer && !aligned(norm_weight, 16)) return fail(LASAD_ERR_INVALID_ARG, "norm_weight must be 16-byte aligned");
     if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
     if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
     if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
@@ -217,6 +222,8 @@ int lasad_forward_gated(const void *q, const void *lam, const void *k, const voi
     a.gamma = nullptr; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state_in = state_in; a.state_out = state_out;
     a.seg_states = nullptr; a.n_segments = 1; a.seg_chunks = 0;
+    a.fused_act = layer ? 1 : 0; a.norm = (layer && norm_eps >= 0.f) ? 1 : 0;
+    a.norm_eps = norm_eps; a.norm_w = norm_weight;
     if (n_tokens == 0 && (!state_out || state_out == state_in)) return LASAD_OK;
     hipError_t e;
     if (io_dtype == LASAD_BF16 && d == 64 && n_tokens > 0 && !force_generic())
@@ -298,11 +305,38 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
     return LASAD_OK;
 }
 
-int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
-                            int io_dtype, int out_dtype, int B, int n_heads, int d,
-                            int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
-                            float *state, void *hip_stream)
+int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
+                        const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
+                        int io_dtype, int out_dtype,
+                        int B, int n_heads, int d, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                        const float *state_in, float *state_out, void *hip_stream)
 {
+    return forward_gated_common(q, lam, k, v, o, in_layout, o_layout, io_dtype, out_dtype, B, n_heads, d, grid_h, grid_w,
+                                start_pos, n_tokens, boundary_mode, q_scale, state_in, state_out, hip_stream,
+                                0, nullptr, -1.f);
+}
+
+int lasad_forward_layer(const void *q_pre, const void *z, const void *v, void *o,
+                        const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
+                        int io_dtype, int out_dtype,
+                        int B, int n_heads, int d, int grid_h, int grid_w,
+                        int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                        const float *norm_weight, float norm_eps,
+                        const float *state_in, float *state_out, void *hip_stream)
+{
+    return forward_gated_common(q_pre, z, nullptr, v, o, in_layout, o_layout, io_dtype, out_dtype, B, n_heads, d, grid_h, grid_w,
+                                start_pos, n_tokens, boundary_mode, q_scale, state_in, state_out, hip_stream,
+                                1, norm_weight, norm_eps);
+}
+
+static int decode_gated_common(const void *q, const void *lam, const void *k, const void *v, void *o,
+                               int io_dtype, int out_dtype, int B, int n_heads, int d,
+                               int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                               float *state, void *hip_stream,
+                               int layer, const float *norm_weight, float norm_eps)
+{
+    if (layer && !aligned(norm_weight, 16)) return fail(LASAD_ERR_INVALID_ARG, "norm_weight must be 16-byte aligned");
     if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
     if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
     if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
@@ -322,11 +356,33 @@ int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
     a.grid_w = grid_w; a.pos = pos; a.pos_rows = nullptr; a.grid_n = grid_h * grid_w;
+    a.fused_act = 0; a.norm = 0; a.norm_eps = 0.f; a.norm_w = nullptr;
     a.gamma = nullptr; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state = state;
+    a.fused_act = layer ? 1 : 0; a.norm = (layer && norm_eps >= 0.f) ? 1 : 0;
+    a.norm_eps = norm_eps; a.norm_w = norm_weight;
     hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_decode_step_gated launch", e);
     return LASAD_OK;
+}
+
+int lasad_decode_step_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
+                            int io_dtype, int out_dtype, int B, int n_heads, int d,
+                            int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                            float *state, void *hip_stream)
+{
+    return decode_gated_common(q, lam, k, v, o, io_dtype, out_dtype, B, n_heads, d, grid_h, grid_w, pos, boundary_mode,
+                               q_scale, state, hip_stream, 0, nullptr, -1.f);
+}
+
+int lasad_decode_step_layer(const void *q_pre, const void *z, const void *v, void *o,
+                            int io_dtype, int out_dtype, int B, int n_heads, int d,
+                            int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                            const float *norm_weight, float norm_eps,
+                            float *state, void *hip_stream)
+{
+    return decode_gated_common(q_pre, z, nullptr, v, o, io_dtype, out_dtype, B, n_heads, d, grid_h, grid_w, pos, boundary_mode,
+                               q_scale, state, hip_stream, 1, norm_weight, norm_eps);
 }
 
 int lasad_decode_step_rows(const void *q, const void *lam, const void *k, const void *v, void *o,
@@ -355,6 +411,7 @@ int lasad_decode_step_rows(const void *q, const void *lam, const void *k, const 
     a.io_dtype = io_dtype; a.out_dtype = out_dtype;
     a.B = B; a.Hh = n_heads; a.d = d;
     a.grid_w = grid_w; a.pos = 0; a.pos_rows = pos_rows; a.grid_n = grid_h * grid_w;
+    a.fused_act = 0; a.norm = 0; a.norm_eps = 0.f; a.norm_w = nullptr;
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
     a.state = state;
     hipError_t e = lasad::launch_decode(a, (hipStream_t)hip_stream);

@@ -173,6 +173,7 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
 
     ForwardArgs f;
     f.lam = nullptr;
+    f.fused_act = 0; f.norm = 0; f.norm_eps = 0.f; f.norm_w = nullptr;
     f.io_dtype = b.io_dtype;
     f.B = b.B; f.Hh = b.Hh; f.d = b.d;
     f.grid_w = b.grid_w; f.n_tokens = n;

@@ -89,7 +89,8 @@ decode_kernel(DecodeArgs a, int n_states)
         const int c = lane + 64 * i;
         qr[i] = c < D ? ld_in<IN_BF16>(a.q, vec + c) : 0.f;
         if (GATED) {
-            const float l = c < D ? ld_in<IN_BF16>(a.lam, vec + c) : 1.f;
+            float l = c < D ? ld_in<IN_BF16>(a.lam, vec + c) : 1.f;
+            if (a.fused_act) { l = sigmoid_f32(l); qr[i] = silu_f32(qr[i]); }     // Algorithm 1's activations
             kr[i] = a.k ? (c < D ? ld_in<IN_BF16>(a.k, vec + c) : 0.f) : 1.0f - l;   // key from the base decay
             lr[i] = boundary ? 1.0f : l;
         } else {
@@ -153,8 +154,19 @@ decode_kernel(DecodeArgs a, int n_states)
         acc.z += __shfl_xor(acc.z, off, 64);
         acc.w += __shfl_xor(acc.w, off, 64);
     }
+    float qs = a.q_scale;
+    if (GATED && a.norm) {           // Norm(o): root mean square over the D channels (lanes 0 .. CG-1 hold them)
+        float ss = (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
+#pragma unroll
+        for (int off = CG / 2; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        const float rstd = __builtin_amdgcn_rsqf(qs * qs * ss * (1.0f / D) + a.norm_eps);
+        qs *= rstd;
+        if (a.norm_w) {
+            const float4 w4 = *(const float4 *)(a.norm_w + h * D + cg * 4);
+            acc.x *= w4.x; acc.y *= w4.y; acc.z *= w4.z; acc.w *= w4.w;
+        }
+    }
     if (r0 == 0) {
-        const float qs = a.q_scale;
         if (OUT_BF16) {
             uint16_t *o = (uint16_t *)a.o + vec + cg * 4;
             ushort4 pk;

@@ -89,8 +89,12 @@ __device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
     return make_uint4(keep ? x.x : fill, keep ? x.y : fill, keep ? x.z : fill, keep ? x.w : fill);
 }
 
-template <int OUT_BF16, int OWNKEY>
-__global__ void __launch_bounds__(kThreads, 2)
+// FUSED >= 1 adds Algorithm 1's elementwise steps: q := SiLU(q) and lambda := sigmoid(lambda) while
+// the chunk is prepared; FUSED = 2 also the root-mean-square normalisation of every output token
+// over its 64 channels before it is stored.
+// OCC: workgroups per compute unit the register budget is set for (1: 512 registers per lane).
+template <int OUT_BF16, int OWNKEY, int FUSED, int OCC = 2>
+__global__ void __launch_bounds__(kThreads, OCC)
 forward_gated_mfma_kernel(ForwardArgs a)
 {
     // tiles: Q~ hi, Q~ lo, K~ hi, K~ lo, V (stride TS); S^T hi, lo and the bf16 output tile (stride RS)
@@ -99,6 +103,8 @@ forward_gated_mfma_kernel(ForwardArgs a)
     constexpr int kLdsBytes = kTileHalfs * 2 > kScanFloats * 4 ? kTileHalfs * 2 : kScanFloats * 4;
     __shared__ __attribute__((aligned(16))) unsigned char smem_raw[kLdsBytes];
     __shared__ __attribute__((aligned(16))) float sTot[2][D];  // A_end per key channel, by chunk parity
+    constexpr bool NORM = FUSED == 2;
+    __shared__ float sSS[NORM ? 2 : 1][NORM ? C : 1];          // sum of squares of a token's two channel halves
     uint16_t *sQh = (uint16_t *)smem_raw;
     uint16_t *sQl = sQh + C * RS;
     uint16_t *sKh = sQl + C * RS;
@@ -189,7 +195,8 @@ forward_gated_mfma_kernel(ForwardArgs a)
             const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float l0 = __uint_as_float(lw[e] << 16), l1 = __uint_as_float(lw[e] & 0xffff0000u);
+                float l0 = __uint_as_float(lw[e] << 16), l1 = __uint_as_float(lw[e] & 0xffff0000u);
+                if (FUSED) { l0 = sigmoid_f32(l0); l1 = sigmoid_f32(l1); }
                 const float k0 = OWNKEY ? __uint_as_float(kw[e] << 16) : 1.0f - l0;
                 const float k1 = OWNKEY ? __uint_as_float(kw[e] & 0xffff0000u) : 1.0f - l1;
                 kk[it][2 * e] = k0;
@@ -239,8 +246,9 @@ forward_gated_mfma_kernel(ForwardArgs a)
             for (int e = 0; e < 4; ++e) {
                 const float a0 = lam[it][2 * e], a1 = lam[it][2 * e + 1];
                 split2(kk[it][2 * e] * __builtin_amdgcn_rcpf(a0), kk[it][2 * e + 1] * __builtin_amdgcn_rcpf(a1), kh[e], kl[e], sc);
-                split2(__uint_as_float(qw[e] << 16) * (a0 * a.q_scale), __uint_as_float(qw[e] & 0xffff0000u) * (a1 * a.q_scale),
-                       qh[e], ql[e], sc);
+                float q0 = __uint_as_float(qw[e] << 16), q1 = __uint_as_float(qw[e] & 0xffff0000u);
+                if (FUSED) { q0 = silu_f32(q0); q1 = silu_f32(q1); }
+                split2(q0 * (a0 * a.q_scale), q1 * (a1 * a.q_scale), qh[e], ql[e], sc);
             }
             pkh[it] = make_uint4(kh[0], kh[1], kh[2], kh[3]); pkl[it] = make_uint4(kl[0], kl[1], kl[2], kl[3]);
             pqh[it] = make_uint4(qh[0], qh[1], qh[2], qh[3]); pql[it] = make_uint4(ql[0], ql[1], ql[2], ql[3]);
@@ -248,6 +256,7 @@ forward_gated_mfma_kernel(ForwardArgs a)
     };
 
     const int n_chunks = (n + C - 1) / C;
+    int pending_rows = 0;          // NORM: rows of the output tile in LDS that are not stored yet
     prepare(0);
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
@@ -270,6 +279,17 @@ forward_gated_mfma_kernel(ForwardArgs a)
             return;
         }
         if (chunk + 1 < n_chunks) prefetch(chunk + 1);
+        if (NORM && OUT_BF16 && pending_rows > 0) {       // the previous chunk's normalised tile, 16-byte rows
+            uint16_t *go = (uint16_t *)a.o + o_base;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int row = (tid >> 3) + 32 * it;
+                if (row < pending_rows)
+                    *(uint4 *)(go + (int64_t)(t0 - C + row) * a.out.stride_n + (tid & 7) * 8) =
+                        *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
+            }
+            pending_rows = 0;
+        }
 
         const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
         Frag fqh[4], fql[4];
@@ -374,6 +394,25 @@ forward_gated_mfma_kernel(ForwardArgs a)
             }
         }
 
+        if (NORM) {
+            // ---- Norm(o): every token divided by the root mean square of its 64 channels.  The two
+            // value-channel waves of a query half exchange their sums of squares through LDS. ----
+            float ss = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ss = fmaf(accO[r], accO[r], ss);
+            ss += __shfl_xor(ss, 32);
+            if (g == 0) sSS[wc][i_row] = ss;
+            __syncthreads();                              // (B) tile and S^T reads finished; sums visible
+            const float rstd = __builtin_amdgcn_rsqf((sSS[0][i_row] + sSS[1][i_row]) * (1.0f / D) + a.norm_eps);
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                float4 w4 = make_float4(1.f, 1.f, 1.f, 1.f);
+                if (a.norm_w) w4 = *(const float4 *)(a.norm_w + h * D + wc * 32 + 8 * qd + 4 * g);
+                accO[4 * qd + 0] *= rstd * w4.x; accO[4 * qd + 1] *= rstd * w4.y;
+                accO[4 * qd + 2] *= rstd * w4.z; accO[4 * qd + 3] *= rstd * w4.w;
+            }
+            pending_rows = nt;                            // a bf16 tile is stored after the next barrier
+        }
         // ---- the output tile: a lane owns four consecutive value channels of its query per quad ----
         if (OUT_BF16) {                                   // via LDS for 16-byte coalesced stores
 #pragma unroll
@@ -391,18 +430,31 @@ forward_gated_mfma_kernel(ForwardArgs a)
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
         if (chunk + 1 < n_chunks) prepare(chunk + 1);     // its loads have landed by now
-        __syncthreads();                                  // (B) all reads of the tiles and of S^T finished
-        if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
-            uint16_t *go = (uint16_t *)a.o + o_base;
+        if (!NORM) {
+            __syncthreads();                              // (B) all reads of the tiles and of S^T finished
+            if (OUT_BF16) {                               // coalesced 16-byte stores of the bf16 tile
+                uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int row = (tid >> 3) + 32 * it;
-                if (row < nt)
-                    *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (tid & 7) * 8) =
-                        *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
+                for (int it = 0; it < 2; ++it) {
+                    const int row = (tid >> 3) + 32 * it;
+                    if (row < nt)
+                        *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (tid & 7) * 8) =
+                            *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
+                }
             }
         }
         if (chunk + 1 < n_chunks) publish_state();        // read after the next barrier (A)
+    }
+    if (NORM && OUT_BF16 && pending_rows > 0) {           // the last chunk's normalised tile
+        __syncthreads();
+        uint16_t *go = (uint16_t *)a.o + o_base;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int row = (tid >> 3) + 32 * it;
+            if (row < pending_rows)
+                *(uint4 *)(go + (int64_t)((n_chunks - 1) * C + row) * a.out.stride_n + (tid & 7) * 8) =
+                    *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
+        }
     }
 
     if (a.state_out) {
@@ -422,12 +474,24 @@ hipError_t launch_forward_gated_mfma(const ForwardArgs &a, hipStream_t s)
     if (n_seq > 0x7fffffff) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_seq), block(kThreads);
     const bool out16 = a.out_dtype == LASAD_BF16;
-    if (a.k) {
-        if (out16) hipLaunchKernelGGL((forward_gated_mfma_kernel<1, 1>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_gated_mfma_kernel<0, 1>), grid, block, 0, s, a);
+    if (a.fused_act || a.norm) {
+        if (a.k || !a.fused_act) return hipErrorInvalidValue;      // the fused layer ties the key to the gate
+        if (a.norm) {
+            // The normalised bf16 tile keeps the output accumulators alive across a barrier; at two
+            // workgroups per compute unit that spills registers and measures slower (104 vs 87 us at
+            // the large shape), so this variant takes the one-workgroup register budget.
+            if (out16) hipLaunchKernelGGL((forward_gated_mfma_kernel<1, 0, 2, 1>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((forward_gated_mfma_kernel<0, 0, 2>), grid, block, 0, s, a);
+        } else {
+            if (out16) hipLaunchKernelGGL((forward_gated_mfma_kernel<1, 0, 1>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((forward_gated_mfma_kernel<0, 0, 1>), grid, block, 0, s, a);
+        }
+    } else if (a.k) {
+        if (out16) hipLaunchKernelGGL((forward_gated_mfma_kernel<1, 1, 0>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((forward_gated_mfma_kernel<0, 1, 0>), grid, block, 0, s, a);
     } else {
-        if (out16) hipLaunchKernelGGL((forward_gated_mfma_kernel<1, 0>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_gated_mfma_kernel<0, 0>), grid, block, 0, s, a);
+        if (out16) hipLaunchKernelGGL((forward_gated_mfma_kernel<1, 0, 0>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((forward_gated_mfma_kernel<0, 0, 0>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }

@@ -22,7 +22,7 @@ void launch_nj(const ForwardArgs &a, hipStream_t s)
 {
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     // two workgroups per sequence while that still leaves workgroup slots free on 256 CUs
-    if (n_seq <= 256)
+    if (n_seq <= 256 && !a.norm)     // (the output norm needs all 64 channels of a token in one workgroup)
         hipLaunchKernelGGL((forward_scan_kernel<IN_BF16, OUT_BF16, KIND, 32>), dim3((unsigned)(n_seq * 2)), dim3(kThreads), 0, s, a);
     else
         hipLaunchKernelGGL((forward_scan_kernel<IN_BF16, OUT_BF16, KIND, 64>), dim3((unsigned)n_seq), dim3(kThreads), 0, s, a);

@@ -26,6 +26,11 @@ struct ForwardArgs {
     float q_scale;
     const float *state_in;
     float *state_out;
+    // Algorithm 1's elementwise steps fused around the vector-decay recurrence (lam given, k NULL):
+    int fused_act;               // 1: q := SiLU(q), lam := sigmoid(lam) on load
+    int norm;                    // 1: o := o / sqrt(mean_c(o^2) + norm_eps) * norm_w[h][c] on store
+    float norm_eps;
+    const float *norm_w;         // [Hh][d] fp32, or NULL for ones
     // segment-parallel plan of the MFMA kernel (filled by its launcher)
     float *seg_states;           // workspace: [B*Hh][n_segments-1][d][d] fp32, or NULL
     int n_segments, seg_chunks;
@@ -37,6 +42,9 @@ struct DecodeArgs {
     void *o;
     int io_dtype, out_dtype;
     int B, Hh, d;
+    int fused_act, norm;         // as in ForwardArgs
+    float norm_eps;
+    const float *norm_w;
     int grid_w, pos;
     const int32_t *pos_rows;     // per batch row positions [B] (device), or NULL: every row at `pos`.
                                  // A row whose position is outside 0 .. grid_n-1 is inactive.
@@ -100,6 +108,11 @@ __host__ __device__ inline int cum_exp(int t, int grid_w, int mode)
     if (mode == LASAD_RESET_FIRST_COL) return t - (t + grid_w - 1) / grid_w;
     return t;
 }
+
+// 1 / (1 + exp(-x)) and x / (1 + exp(-x)) in fp32 (hardware exp and reciprocal, ~1 ulp each;
+// exp overflows to inf for very negative x and the reciprocal then returns 0, the right limit)
+__device__ inline float sigmoid_f32(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ inline float silu_f32(float x) { return x * sigmoid_f32(x); }
 
 __device__ inline float bf16_bits_to_float(uint16_t b)
 {

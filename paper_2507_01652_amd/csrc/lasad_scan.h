@@ -151,6 +151,10 @@ struct Loader {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(raw[i][e]);
             }
+            if (KIND != SCALAR && a.fused_act && arr <= 1) {   // Algorithm 1: q := SiLU(q), lambda := sigmoid(lambda)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) f[e] = arr == 0 ? silu_f32(f[e]) : sigmoid_f32(f[e]);
+            }
             const bool past_end = t0 + tok >= a.n_tokens;
             if (past_end) {
 #pragma unroll
@@ -269,10 +273,22 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds)
         for (int i = 0; i < kT * NJ / 2 / kThreads; ++i) {
             const int e = tid + kThreads * i;
             const int tt = e / (NJ / 2), jp = (e - tt * (NJ / 2)) * 2;
-            if (tt < nt) {
-                f2 acc = *(const f2 *)(red + (tt * CG) * NJ + jp);
+            f2 acc = *(const f2 *)(red + (tt * CG) * NJ + jp);
 #pragma unroll
-                for (int g = 1; g < CG; ++g) acc += *(const f2 *)(red + (tt * CG + g) * NJ + jp);
+            for (int g = 1; g < CG; ++g) acc += *(const f2 *)(red + (tt * CG + g) * NJ + jp);
+            if (NJ == kD && a.norm) {
+                // root-mean-square normalisation over the 64 channels of the token: its 32 channel
+                // pairs sit in 32 consecutive lanes
+                float ss = acc[0] * acc[0] + acc[1] * acc[1];
+#pragma unroll
+                for (int off = 16; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+                const float rstd = __builtin_amdgcn_rsqf(ss * (1.0f / kD) + a.norm_eps);
+                const int hh = bh % a.Hh;
+                const float w0 = a.norm_w ? a.norm_w[hh * kD + jp] : 1.0f, w1 = a.norm_w ? a.norm_w[hh * kD + jp + 1] : 1.0f;
+                acc[0] *= rstd * w0;
+                acc[1] *= rstd * w1;
+            }
+            if (tt < nt) {
                 const int64_t oi = out_base + (int64_t)(t0 + tt) * a.out.stride_n + jp;
                 if (OUT_BF16)
                     *(uint32_t *)((uint16_t *)a.o + oi) =
