@@ -393,7 +393,7 @@ forward_mfma_kernel(ForwardArgs a)
             *(uint2 *)&sl[off] = lo;
         }
     };
-    if (have_state) publish_state(0);
+    publish_state(0);          // also when the state is zero: the Q S product below is unconditional
 
     ChunkPos pos;
     pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
@@ -446,9 +446,9 @@ forward_mfma_kernel(ForwardArgs a)
         const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
 
         // ---- scores of key block 0, P^T[j][i] = sum_d K[j][d] Q[i][d] ----
-        f32x16 acc0, acc1, accO;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; accO[r] = 0.f; }
+        // accumulators start from a constant-zero C operand of their first MFMA (no register clears)
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 acc0 = zero16, acc1 = zero16, accO = zero16;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             Frag fk;
@@ -457,15 +457,13 @@ forward_mfma_kernel(ForwardArgs a)
         }
         PROF(8);
         // ---- O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk]  (independent of the scores) ----
-        if (have_state) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                Frag fs;
-                fs.u = *(const uint4 *)&sSh[(wc * 32 + l32) * RS + 16 * s + 8 * g];
-                accO = mfma(fs, fq[s], accO);
-                fs.u = *(const uint4 *)&sSl[(wc * 32 + l32) * RS + 16 * s + 8 * g];
-                accO = mfma(fs, fq[s], accO);
-            }
+        for (int s = 0; s < 4; ++s) {
+            Frag fs;
+            fs.u = *(const uint4 *)&sSh[(wc * 32 + l32) * RS + 16 * s + 8 * g];
+            accO = mfma(fs, fq[s], accO);
+            fs.u = *(const uint4 *)&sSl[(wc * 32 + l32) * RS + 16 * s + 8 * g];
+            accO = mfma(fs, fq[s], accO);
         }
         PROF(9);
         // ---- scores of key block 1 (all masked for the lower query half) ----
