@@ -1,0 +1,160 @@
+// Pieces shared by the chunked scalar-decay matrix-core kernels (lasad_forward_mfma.hip and its
+// eight-wave variant lasad_forward_mfma_ws.hip): tile geometry, per-chunk position bookkeeping,
+// staging of K and V, decayed keys, and the state update.
+#pragma once
+
+#include "lasad_mfma_util.h"
+#include "lasad_internal.h"
+
+namespace lasad {
+namespace fwd {
+
+constexpr int C = 64;      // chunk length (tokens)
+constexpr int D = 64;      // head dim
+constexpr int kThreads = 256;
+constexpr int RS = 72;     // LDS row stride (elements) of tiles read 16 bytes at a time: 144 B
+constexpr int VS = 80;     // LDS row stride of the V tile (transpose reads only): 160 B
+
+
+// number of boundary positions among x small offsets: floor(x / W), 0 <= x < W + 128
+__device__ inline int small_div(int x, int W, float rcpW)
+{
+    if (W > 128) return x >= W ? 1 : 0;
+    int q = (int)((float)x * rcpW);
+    const int r = x - q * W;
+    q += (r >= W) ? 1 : 0;
+    q -= (r < 0) ? 1 : 0;
+    return q;
+}
+
+// Per-chunk position bookkeeping.  col0 = (tokens before the chunk) mod W.  The number of
+// boundary positions among the first j+1 tokens of the chunk is floor((j + xoff) / W) with a
+// small per-chunk offset xoff, so e_j = j + 1 - floor((j + xoff) / W).
+struct ChunkPos {
+    int W, mode, col0;
+    float rcpW;
+    __device__ void init(int start, int grid_w, int boundary_mode)
+    {
+        W = grid_w; mode = boundary_mode; col0 = start % grid_w; rcpW = 1.0f / (float)grid_w;
+    }
+    __device__ int xoff() const
+    {
+        if (mode == LASAD_RESET_LAST_COL) return col0 + 1;
+        if (mode == LASAD_RESET_FIRST_COL) return col0 ? col0 : W;
+        return 0;
+    }
+    __device__ int e_of(int j, int xo) const     // e_j of chunk-local token j
+    {
+        return j + 1 - (mode == LASAD_RESET_NONE ? 0 : small_div(j + xo, W, rcpW));
+    }
+    __device__ void advance()                    // to the next chunk
+    {
+        col0 += C;
+        if (W > 128) col0 -= col0 >= W ? W : 0;
+        else col0 -= W * small_div(col0, W, rcpW);
+    }
+};
+
+// Decayed keys of one chunk, in registers: every thread scales the two 16-byte pieces of K it
+// loaded (rows tid/8 and tid/8 + 32) by c_j = gamma^{-e_j} and splits them into bf16 hi + lo.
+struct StagedKeys {
+    uint4 hi[2], lo[2];
+    float cj[2];
+};
+
+__device__ inline void prepare_keys(StagedKeys &st, uint4 (&rk)[2], uint4 (&rv)[2], int tid, int nt,
+                                    const ChunkPos &pos, float lg, const SplitConst &sc)
+{
+    const int xo = pos.xoff();
+    if (nt < C) {                                   // tail chunk: rows past the end are zero
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+            if ((tid >> 3) + 32 * it >= nt) rk[it] = rv[it] = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int row = (tid >> 3) + 32 * it;
+        const float cj = __builtin_amdgcn_exp2f(-(float)pos.e_of(row, xo) * lg);   // gamma^{-e_j}
+        st.cj[it] = cj;
+        const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2)
+            split2(__uint_as_float(kw[w2] << 16) * cj, __uint_as_float(kw[w2] & 0xffff0000u) * cj,
+                   hi[w2], lo[w2], sc);
+        st.hi[it] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        st.lo[it] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
+}
+
+// Write one chunk's K, V (as loaded), decayed keys (hi, lo) and the table of c_j to LDS.
+template <bool RAW_K>
+__device__ inline void write_tiles(uint16_t *sK, uint16_t *sV, uint16_t *sKh, uint16_t *sKl, float *tabC,
+                                   const uint4 (&rk)[2], const uint4 (&rv)[2], const StagedKeys &st, int tid)
+{
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int row = (tid >> 3) + 32 * it;
+        const int col = (tid & 7) * 8;
+        if ((tid & 7) == 0) tabC[row] = st.cj[it];
+        if (RAW_K) *(uint4 *)&sK[row * RS + col] = rk[it];
+        *(uint4 *)&sV[row * VS + col] = rv[it];
+        *(uint4 *)&sKh[row * VS + col] = st.hi[it];
+        *(uint4 *)&sKl[row * VS + col] = st.lo[it];
+    }
+}
+
+// V fragments of value-channel half wc: channel n = wc*32 + l32, tokens 16*s + 4*g + {0..3}, + 8
+__device__ inline void load_v_frags(Frag (&fv)[4], const uint16_t *sV, int wc, int lane)
+{
+    const int l32 = lane & 31, g = lane >> 5;
+    const int trow = (lane & 15) >> 2;               // row inside the 4-row group this lane points at
+    const int tcol = wc * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        fv[s].h[0] = tr_read(&sV[(16 * s + 4 * g + trow) * VS + tcol]);
+        fv[s].h[1] = tr_read(&sV[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+    }
+}
+
+// S[dk][dv] += sum_j (c_j K[j][dk]) V[j][dv] for the wave's 32 x 32 tile (dk half wa)
+__device__ inline void state_update(f32x16 &accS, const uint16_t *sKh, const uint16_t *sKl,
+                                    const Frag (&fv)[4], int wa, int lane)
+{
+    const int l32 = lane & 31, g = lane >> 5;
+    const int trow = (lane & 15) >> 2;
+    const int tcol = wa * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        Frag fkt;
+        fkt.h[0] = tr_read(&sKh[(16 * s + 4 * g + trow) * VS + tcol]);
+        fkt.h[1] = tr_read(&sKh[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+        accS = mfma(fkt, fv[s], accS);
+        fkt.h[0] = tr_read(&sKl[(16 * s + 4 * g + trow) * VS + tcol]);
+        fkt.h[1] = tr_read(&sKl[(16 * s + 8 + 4 * g + trow) * VS + tcol]);
+        accS = mfma(fkt, fv[s], accS);
+    }
+}
+
+// K/V staging loads of one chunk of a token range [0, n): unconditional, index clamped.
+__device__ inline void load_kv(uint4 (&rk)[2], uint4 (&rv)[2], const uint16_t *gk, const uint16_t *gv,
+                               int t0, int n, int64_t stride_n, int tid)
+{
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int tok = min(t0 + (tid >> 3) + 32 * it, n - 1);
+        const int64_t off = (int64_t)tok * stride_n + (tid & 7) * 8;
+        rk[it] = *(const uint4 *)(gk + off);
+        rv[it] = *(const uint4 *)(gv + off);
+    }
+}
+
+// exponent E(end) - E(begin) of a token range, begin/end = tokens consumed before / after it
+__device__ inline int range_exponent(int begin, int end, int W, int mode)
+{
+    return cum_exp(end, W, mode) - cum_exp(begin, W, mode);
+}
+
+
+}  // namespace fwd
+}  // namespace lasad
