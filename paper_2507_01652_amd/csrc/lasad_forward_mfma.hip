@@ -524,9 +524,11 @@ hipError_t launch_forward_mfma(const ForwardArgs &a_in, hipStream_t s)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    // the full pass: the eight-wave kernel unless LASAD_WS=0 asks for the four-wave one
-    static const bool ws = [] { const char *e = getenv("LASAD_WS"); return !(e && e[0] == '0'); }();
-    if (ws) return launch_forward_mfma_ws(a, s);
+    // The full pass: the twelve-wave kernel while every workgroup gets a compute unit of its own,
+    // else the eight-wave one (LASAD_WS = 12 / 8 / 0 forces one of them or the four-wave kernel).
+    static const int ws = [] { const char *e = getenv("LASAD_WS"); return e ? atoi(e) : -1; }();
+    if (ws == 12 || (ws < 0 && n_seq * a.n_segments <= 256)) return launch_forward_mfma_ws12(a, s);
+    if (ws != 0) return launch_forward_mfma_ws(a, s);
     const dim3 grid((unsigned)(n_seq * a.n_segments));
     if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_kernel<1>, grid, block, 0, s, a);
     else hipLaunchKernelGGL(forward_mfma_kernel<0>, grid, block, 0, s, a);

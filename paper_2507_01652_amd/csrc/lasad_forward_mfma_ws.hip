@@ -25,6 +25,16 @@ using namespace fwd;
 
 constexpr int kWsThreads = 512;
 
+#ifdef LASAD_PROFILE
+// Development aid: cycle stamps of workgroup 0 at phase boundaries of each chunk, for output
+// wave 0 (slots 0-7), output wave 2 (8-15) and state wave 4 (slots 16-23).
+__device__ long long g_prof_ws[24 * 64];
+#define WPROF(slot) do { if (blockIdx.x == 0 && lane == 0 && chunk < 64 && (wave == 0 || wave == 2 || wave == 4)) \
+    g_prof_ws[chunk * 24 + (wave == 4 ? 16 : wave == 2 ? 8 : 0) + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define WPROF(slot) do { } while (0)
+#endif
+
 template <int OUT_BF16>
 __global__ void __launch_bounds__(kWsThreads, 1)
 forward_mfma_ws_kernel(ForwardArgs a)
@@ -120,8 +130,11 @@ forward_mfma_ws_kernel(ForwardArgs a)
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int t0 = chunk * C;
             const int nt = min(C, n - t0);
+            WPROF(0);
             write_tiles<true>(sK, sV, sKh, sKl, tabC, rk, rv, sk, st);
+            WPROF(1);
             __syncthreads();                              // (A) tiles, c_j table and S^T visible
+            WPROF(2);
             if (chunk + 1 < n_chunks) load_kv(rk, rv, gk, gv, t0 + C, n, a.in.stride_n, st);
             Frag fv[4];
             load_v_frags(fv, sV, wc, lane);
@@ -129,12 +142,16 @@ forward_mfma_ws_kernel(ForwardArgs a)
             const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] *= r_end;
+            WPROF(3);
             if (chunk + 1 < n_chunks) {
                 prepare_keys(sk, rk, rv, st, min(C, n - t0 - C), pos, lg, sc);
                 pos.advance();
             }
+            WPROF(4);
             __syncthreads();                              // (B) all reads of the tiles and of S^T finished
+            WPROF(5);
             if (chunk + 1 < n_chunks) publish_state();    // read after the next barrier (A)
+            WPROF(6);
         }
         if (a.state_out && seg == G - 1) {
             float *s1 = a.state_out + (int64_t)bh * D * D;
@@ -167,8 +184,10 @@ forward_mfma_ws_kernel(ForwardArgs a)
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
+        WPROF(0);
         take_q(chunk);
         __syncthreads();                                  // (A)
+        WPROF(1);
         if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
         const int i_row = qa * 32 + l32;
 
@@ -199,6 +218,7 @@ forward_mfma_ws_kernel(ForwardArgs a)
                 acc1 = mfma(fk, fq[s], acc1);
             }
         }
+        WPROF(2);
         Frag fv[4];
         load_v_frags(fv, sV, wc, lane);
 
@@ -240,6 +260,7 @@ forward_mfma_ws_kernel(ForwardArgs a)
                 accO = mfma(fv[2 + s], pl[s], accO);
             }
         }
+        WPROF(3);
         // ---- row factor r_i = 1 / c_i and the output tile ----
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(tabC[i_row]);
 #pragma unroll
@@ -259,7 +280,9 @@ forward_mfma_ws_kernel(ForwardArgs a)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
+        WPROF(4);
         __syncthreads();                                  // (B)
+        WPROF(5);
         if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
             uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
@@ -274,6 +297,13 @@ forward_mfma_ws_kernel(ForwardArgs a)
 }
 
 }  // namespace
+
+#ifdef LASAD_PROFILE
+extern "C" int lasad_debug_read_profile_ws(long long *host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof_ws), sizeof(long long) * n);
+}
+#endif
 
 hipError_t launch_forward_mfma_ws(const ForwardArgs &a, hipStream_t s)
 {

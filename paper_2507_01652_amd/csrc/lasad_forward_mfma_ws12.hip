@@ -1,0 +1,306 @@
+// Twelve-wave variant of the chunked scalar-decay forward for the case that a sequence has a
+// compute unit to itself (at most 256 sequences or segments): three groups of four wavefronts,
+// every LDS buffer doubled, ONE barrier per chunk.
+//
+//   output waves (0-3):  scores, decay + mask + split, P V, Q S, output tile        (chunk c)
+//   state waves  (4-7):  state update K~^T V, scaling, bf16 hi/lo copy of S^T       (chunk c -> c+1)
+//   loader waves (8-11): global loads of K and V, decayed keys, tile writes         (chunk c+1)
+//
+// During chunk c the loader waves fill the other set of tiles for chunk c+1 and the state waves
+// publish the state that chunk c+1 starts from into the other S^T buffer, so nothing is left to
+// do between the end of one chunk's reads and the start of the next chunk's: the workgroup meets
+// one barrier per chunk and the chunk time is that of the slowest group (measured with cycle
+// stamps on the eight-wave kernel: about a third of its chunk time was the serial stretch between
+// its two barriers).  LDS: 2 x 67.6 KB.  Algorithm, layouts and precision: lasad_forward_mfma.hip.
+#include "lasad_forward_mfma_common.h"
+#include "lasad_recurrence.h"
+
+namespace lasad {
+
+namespace {
+
+using namespace fwd;
+
+constexpr int kWs12Threads = 768;
+constexpr int kSetHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;   // one set of tiles
+
+template <int OUT_BF16>
+__global__ void __launch_bounds__(kWs12Threads, 1)
+forward_mfma_ws12_kernel(ForwardArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kSetHalfs];
+    __shared__ __attribute__((aligned(16))) float tabC2[2][C];
+    static_assert(kSetHalfs * 4 >= recurrence_lds_floats<D>() * 4, "fallback needs the LDS block");
+    // buffer set p: K, V, decayed keys hi / lo, S^T hi / lo, output tile
+    auto sK = [&](int p) { return smem + p * kSetHalfs; };
+    auto sV = [&](int p) { return smem + p * kSetHalfs + C * RS; };
+    auto sKh = [&](int p) { return smem + p * kSetHalfs + C * RS + C * VS; };
+    auto sKl = [&](int p) { return smem + p * kSetHalfs + C * RS + 2 * C * VS; };
+    auto sSh = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS; };
+    auto sSl = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS + D * RS; };
+    auto sO = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS + 2 * D * RS; };
+
+    const int G = a.n_segments;
+    const int bh = blockIdx.x / G, seg = blockIdx.x - bh * G;
+    const int b = bh / a.Hh, h = bh - b * a.Hh;
+    const float lg = log2f(a.gamma[h]);
+    const int tid = threadIdx.x;
+    if (!(lg * (float)C > -64.0f)) {   // gamma <= 0.5: separable factors could overflow -> fp32 recurrence
+        if (tid >= kRecThreads || seg != 0) return;       // (finished waves no longer count at barriers)
+        recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);     // whole sequence
+        return;
+    }
+
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int group = wave >> 2;                 // 0 output, 1 state, 2 loader
+    const int w4 = wave & 3;
+    const int wa = w4 >> 1, wc = w4 & 1;         // (query half base | key-channel half), value-channel half
+    const int l32 = lane & 31, g = lane >> 5;
+    const int st = tid & 255;                    // thread index inside its group
+
+    const int seg_t0 = seg * a.seg_chunks * C;                 // first token of this segment
+    const int n = min(a.seg_chunks * C, a.n_tokens - seg_t0);   // tokens in this segment
+    const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + (int64_t)seg_t0 * a.in.stride_n;
+    const uint16_t *gq = (const uint16_t *)a.q + in_base;
+    const uint16_t *gk = (const uint16_t *)a.k + in_base;
+    const uint16_t *gv = (const uint16_t *)a.v + in_base;
+    const int64_t o_base = (int64_t)b * a.out.stride_b + (int64_t)h * a.out.stride_h + (int64_t)seg_t0 * a.out.stride_n;
+    const int n_chunks = (n + C - 1) / C;
+
+    SplitConst sc;
+    sc.init();
+
+    if (group == 2) {
+        // ===================================== loader waves =====================================
+        uint4 rk[2], rv[2];
+        StagedKeys sk;
+        ChunkPos pos;
+        pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
+        load_kv(rk, rv, gk, gv, 0, n, a.in.stride_n, st);
+        prepare_keys(sk, rk, rv, st, min(C, n), pos, lg, sc);
+        pos.advance();
+        write_tiles<true>(sK(0), sV(0), sKh(0), sKl(0), tabC2[0], rk, rv, sk, st);
+        if (n_chunks > 1) load_kv(rk, rv, gk, gv, C, n, a.in.stride_n, st);
+        __syncthreads();
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
+                const int p = (chunk + 1) & 1;
+                prepare_keys(sk, rk, rv, st, min(C, n - (chunk + 1) * C), pos, lg, sc);
+                pos.advance();
+                write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk, rv, sk, st);
+                if (chunk + 2 < n_chunks) load_kv(rk, rv, gk, gv, (chunk + 2) * C, n, a.in.stride_n, st);
+            }
+            __syncthreads();
+        }
+        return;
+    }
+
+    if (group == 1) {
+        // ===================================== state waves =====================================
+        f32x16 accS;                   // S[dk = wa*32 + 8*(r/4) + 4*g + r%4][dv = wc*32 + l32]
+        if (a.state_in) {
+            const float *s0 = a.state_in + (int64_t)bh * D * D;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                accS[r] = s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accS[r] = 0.f;
+        }
+        // incoming state = caller's state folded through the segments before this one
+        for (int sp = 0; sp < seg; ++sp) {
+            const int begin = a.start_pos + sp * a.seg_chunks * C;
+            const int de = range_exponent(begin, begin + a.seg_chunks * C, a.grid_w, a.mode);
+            const float dec = de == 0 ? 1.0f : __builtin_amdgcn_exp2f((float)de * lg);
+            const float *u = a.seg_states + ((int64_t)bh * (G - 1) + sp) * D * D;
+            float ur[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ur[r] = u[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accS[r] = fmaf(dec, accS[r], ur[r]);
+        }
+        auto publish_state = [&](int p) {
+            uint16_t *sh = sSh(p), *sl = sSl(p);
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                uint2 hi, lo;
+                split2(accS[4 * qd + 0], accS[4 * qd + 1], hi.x, lo.x, sc);
+                split2(accS[4 * qd + 2], accS[4 * qd + 3], hi.y, lo.y, sc);
+                const int off = (wc * 32 + l32) * RS + wa * 32 + 8 * qd + 4 * g;
+                *(uint2 *)&sh[off] = hi;
+                *(uint2 *)&sl[off] = lo;
+            }
+        };
+        publish_state(0);
+        __syncthreads();
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            const int p = chunk & 1;
+            const int nt = min(C, n - chunk * C);
+            Frag fv[4];
+            load_v_frags(fv, sV(p), wc, lane);
+            state_update(accS, sKh(p), sKl(p), fv, wa, lane);
+            const float r_end = __builtin_amdgcn_rcpf(tabC2[p][nt - 1]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accS[r] *= r_end;
+            if (chunk + 1 < n_chunks) publish_state(p ^ 1);   // the state chunk + 1 starts from
+            __syncthreads();
+        }
+        if (a.state_out && seg == G - 1) {
+            float *s1 = a.state_out + (int64_t)bh * D * D;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                s1[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32] = accS[r];
+        }
+        return;
+    }
+
+    // ========================================= output waves =========================================
+    Frag fqn[4], fq[4];
+    auto prefetch_q = [&](int chunk) {
+        const int qtok = min(chunk * C + (wa ^ (chunk & 1)) * 32 + l32, n - 1);
+        const uint16_t *p = gq + (int64_t)qtok * a.in.stride_n + 8 * g;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);
+    };
+    auto take_q = [&](int chunk) {                        // prefetched Q fragments -> fq (tail rows zero)
+        const bool live = chunk * C + (wa ^ (chunk & 1)) * 32 + l32 < n;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
+    };
+    auto store_tile = [&](int chunk) {                    // bf16 output tile of a finished chunk, 16-byte rows
+        const uint16_t *bO = sO(chunk & 1);
+        const int t0 = chunk * C, nt = min(C, n - t0);
+        uint16_t *go = (uint16_t *)a.o + o_base;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int row = (st >> 3) + 32 * it;
+            if (row < nt)
+                *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
+                    *(const uint4 *)&bO[row * RS + (st & 7) * 8];
+        }
+    };
+    prefetch_q(0);
+
+    // causal mask of a diagonal 32 x 32 score block: key 8*qd + 4*g + e is at or before query l32
+    const int cq = l32 - 4 * g;
+
+    __syncthreads();
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        const int t0 = chunk * C;
+        const int nt = min(C, n - t0);
+        const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
+        const int p = chunk & 1;
+        const uint16_t *bK = sK(p), *bV = sV(p), *bSh = sSh(p), *bSl = sSl(p);
+        uint16_t *bO = sO(p);
+        const float *bC = tabC2[p];
+        take_q(chunk);
+        if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
+        if (OUT_BF16 && chunk > 0) store_tile(chunk - 1);
+        const int i_row = qa * 32 + l32;
+
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        f32x16 acc0 = zero16, acc1 = zero16, accO = zero16;
+        // ---- scores of key block 0, P^T[j][i] = sum_d K[j][d] Q[i][d] ----
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            Frag fk;
+            fk.u = *(const uint4 *)&bK[l32 * RS + 16 * s + 8 * g];
+            acc0 = mfma(fk, fq[s], acc0);
+        }
+        // ---- O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk] ----
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            Frag fs;
+            fs.u = *(const uint4 *)&bSh[(wc * 32 + l32) * RS + 16 * s + 8 * g];
+            accO = mfma(fs, fq[s], accO);
+            fs.u = *(const uint4 *)&bSl[(wc * 32 + l32) * RS + 16 * s + 8 * g];
+            accO = mfma(fs, fq[s], accO);
+        }
+        // ---- scores of key block 1 (all masked for the lower query half) ----
+        if (qa == 1) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                Frag fk;
+                fk.u = *(const uint4 *)&bK[(32 + l32) * RS + 16 * s + 8 * g];
+                acc1 = mfma(fk, fq[s], acc1);
+            }
+        }
+        Frag fv[4];
+        load_v_frags(fv, bV, wc, lane);
+
+        // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
+        auto mask_split = [&](const f32x16 &acc, int jb, bool diagonal, Frag *ph, Frag *pl) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const float4 c4 = *(const float4 *)&bC[jb * 32 + 8 * qd + 4 * g];
+                float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
+                float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
+                if (diagonal) {
+                    p0 = 8 * qd + 0 <= cq ? p0 : 0.f;
+                    p1 = 8 * qd + 1 <= cq ? p1 : 0.f;
+                    p2 = 8 * qd + 2 <= cq ? p2 : 0.f;
+                    p3 = 8 * qd + 3 <= cq ? p3 : 0.f;
+                }
+                uint2 hi, lo;
+                split2(p0, p1, hi.x, lo.x, sc);
+                split2(p2, p3, hi.y, lo.y, sc);
+                ph[qd / 2].h[qd % 2] = hi;
+                pl[qd / 2].h[qd % 2] = lo;
+            }
+        };
+        {
+            Frag ph[2], pl[2];
+            mask_split(acc0, 0, qa == 0, ph, pl);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                accO = mfma(fv[s], ph[s], accO);
+                accO = mfma(fv[s], pl[s], accO);
+            }
+        }
+        if (qa == 1) {
+            Frag ph[2], pl[2];
+            mask_split(acc1, 1, true, ph, pl);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                accO = mfma(fv[2 + s], ph[s], accO);
+                accO = mfma(fv[2 + s], pl[s], accO);
+            }
+        }
+        // ---- row factor r_i = 1 / c_i and the output tile ----
+        const float osc = a.q_scale * __builtin_amdgcn_rcpf(bC[i_row]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accO[r] *= osc;
+        if (OUT_BF16) {                                   // via LDS for 16-byte coalesced stores
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                uint2 w2;
+                w2.x = pack2(accO[4 * qd + 0], accO[4 * qd + 1]);
+                w2.y = pack2(accO[4 * qd + 2], accO[4 * qd + 3]);
+                *(uint2 *)&bO[i_row * RS + wc * 32 + 8 * qd + 4 * g] = w2;
+            }
+        } else if (i_row < nt) {
+            float *go = (float *)a.o + o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
+                                                       accO[4 * qd + 2], accO[4 * qd + 3]);
+        }
+        __syncthreads();
+    }
+    if (OUT_BF16) store_tile(n_chunks - 1);
+}
+
+}  // namespace
+
+hipError_t launch_forward_mfma_ws12(const ForwardArgs &a, hipStream_t s)
+{
+    if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1) return hipErrorInvalidValue;
+    const int64_t n_seq = (int64_t)a.B * a.Hh;
+    if (n_seq * a.n_segments > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(n_seq * a.n_segments)), block(kWs12Threads);
+    if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_ws12_kernel<1>, grid, block, 0, s, a);
+    else hipLaunchKernelGGL(forward_mfma_ws12_kernel<0>, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace lasad
