@@ -4,7 +4,8 @@
 //
 //   output waves (0-3):  scores, decay + mask + split, P V, Q S, output tile        (chunk c)
 //   state waves  (4-7):  state update K~^T V, scaling, bf16 hi/lo copy of S^T       (chunk c -> c+1)
-//   loader waves (8-11): global loads of K and V, decayed keys, tile writes         (chunk c+1)
+//   loader waves (8-11): global loads of K and V, decayed keys, tile writes         (chunk c+1),
+//                        16-byte stores of the finished output tile                (chunk c-1)
 //
 // During chunk c the loader waves fill the other set of tiles for chunk c+1 and the state waves
 // publish the state that chunk c+1 starts from into the other S^T buffer, so nothing is left to
@@ -12,6 +13,8 @@
 // one barrier per chunk and the chunk time is that of the slowest group (measured with cycle
 // stamps on the eight-wave kernel: about a third of its chunk time was the serial stretch between
 // its two barriers).  LDS: 2 x 67.6 KB.  Algorithm, layouts and precision: lasad_forward_mfma.hip.
+#include <stdlib.h>
+
 #include "lasad_forward_mfma_common.h"
 #include "lasad_recurrence.h"
 
@@ -22,10 +25,22 @@ namespace {
 using namespace fwd;
 
 constexpr int kWs12Threads = 768;
+
+#ifdef LASAD_PROFILE
+// Development aid: cycle stamps of workgroup 0, waves 0 (output), 4 (state), 8 (loader), 8 slots each.
+__device__ long long g_prof_ws12[24 * 64];
+#define WPROF(slot) do { if (blockIdx.x == 0 && lane == 0 && chunk < 64 && first_of_group) \
+    g_prof_ws12[chunk * 24 + 8 * group + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define WPROF(slot) do { } while (0)
+#endif
 constexpr int kSetHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;   // one set of tiles
 
-template <int OUT_BF16>
-__global__ void __launch_bounds__(kWs12Threads, 1)
+// SPLIT = 1: one workgroup (twelve waves) per sequence or segment.  SPLIT = 2: two workgroups, one per
+// value-channel half, each with two output waves, two state waves and four loader waves (the loader
+// work, K and its decayed copies, is done by both); for so few sequences that compute units stay free.
+template <int OUT_BF16, int SPLIT>
+__global__ void __launch_bounds__(SPLIT == 1 ? kWs12Threads : 512, 1)
 forward_mfma_ws12_kernel(ForwardArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kSetHalfs];
@@ -41,22 +56,26 @@ forward_mfma_ws12_kernel(ForwardArgs a)
     auto sO = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS + 2 * D * RS; };
 
     const int G = a.n_segments;
-    const int bh = blockIdx.x / G, seg = blockIdx.x - bh * G;
+    const int blk = blockIdx.x / SPLIT, half = blockIdx.x - blk * SPLIT;     // half: value-channel half if SPLIT == 2
+    const int bh = blk / G, seg = blk - bh * G;
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const float lg = log2f(a.gamma[h]);
     const int tid = threadIdx.x;
     if (!(lg * (float)C > -64.0f)) {   // gamma <= 0.5: separable factors could overflow -> fp32 recurrence
-        if (tid >= kRecThreads || seg != 0) return;       // (finished waves no longer count at barriers)
+        if (tid >= kRecThreads || seg != 0 || half != 0) return;   // (finished waves no longer count at barriers)
         recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);     // whole sequence
         return;
     }
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int group = wave >> 2;                 // 0 output, 1 state, 2 loader
-    const int w4 = wave & 3;
-    const int wa = w4 >> 1, wc = w4 & 1;         // (query half base | key-channel half), value-channel half
+    // SPLIT 1: waves 0-3 output, 4-7 state, 8-11 loader; SPLIT 2: waves 0-1 output, 2-3 state, 4-7 loader
+    const int group = SPLIT == 1 ? wave >> 2 : (wave < 2 ? 0 : wave < 4 ? 1 : 2);
+    const int wa = SPLIT == 1 ? (wave & 3) >> 1 : wave & 1;      // query half base | key-channel half
+    const int wc = SPLIT == 1 ? wave & 1 : half;                 // value-channel half
+    const bool first_of_group = SPLIT == 1 ? (wave & 3) == 0 : (wave == 0 || wave == 2 || wave == 4);
+    (void)first_of_group;
     const int l32 = lane & 31, g = lane >> 5;
-    const int st = tid & 255;                    // thread index inside its group
+    const int st = tid & 255;                    // thread index inside the loader group (and the output group if SPLIT == 1)
 
     const int seg_t0 = seg * a.seg_chunks * C;                 // first token of this segment
     const int n = min(a.seg_chunks * C, a.n_tokens - seg_t0);   // tokens in this segment
@@ -70,6 +89,18 @@ forward_mfma_ws12_kernel(ForwardArgs a)
     SplitConst sc;
     sc.init();
 
+    auto store_tile = [&](int chunk) {                    // bf16 output tile of a finished chunk, 16-byte rows
+        const uint16_t *bO = sO(chunk & 1);
+        const int t0 = chunk * C, nt = min(C, n - t0);
+        uint16_t *go = (uint16_t *)a.o + o_base;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int row = (st >> 3) + 32 * it;
+            if (row < nt && (SPLIT == 1 || ((st & 7) >> 2) == half))
+                *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
+                    *(const uint4 *)&bO[row * RS + (st & 7) * 8];
+        }
+    };
     if (group == 2) {
         // ===================================== loader waves =====================================
         uint4 rk[2], rv[2];
@@ -83,15 +114,21 @@ forward_mfma_ws12_kernel(ForwardArgs a)
         if (n_chunks > 1) load_kv(rk, rv, gk, gv, C, n, a.in.stride_n, st);
         __syncthreads();
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            WPROF(0);
+            if (OUT_BF16 && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
             if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
                 const int p = (chunk + 1) & 1;
                 prepare_keys(sk, rk, rv, st, min(C, n - (chunk + 1) * C), pos, lg, sc);
                 pos.advance();
+                WPROF(1);
                 write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk, rv, sk, st);
                 if (chunk + 2 < n_chunks) load_kv(rk, rv, gk, gv, (chunk + 2) * C, n, a.in.stride_n, st);
             }
+            WPROF(2);
             __syncthreads();
+            WPROF(3);
         }
+        if (OUT_BF16) store_tile(n_chunks - 1);
         return;
     }
 
@@ -136,14 +173,18 @@ forward_mfma_ws12_kernel(ForwardArgs a)
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int p = chunk & 1;
             const int nt = min(C, n - chunk * C);
+            WPROF(0);
             Frag fv[4];
             load_v_frags(fv, sV(p), wc, lane);
             state_update(accS, sKh(p), sKl(p), fv, wa, lane);
             const float r_end = __builtin_amdgcn_rcpf(tabC2[p][nt - 1]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] *= r_end;
+            WPROF(1);
             if (chunk + 1 < n_chunks) publish_state(p ^ 1);   // the state chunk + 1 starts from
+            WPROF(2);
             __syncthreads();
+            WPROF(3);
         }
         if (a.state_out && seg == G - 1) {
             float *s1 = a.state_out + (int64_t)bh * D * D;
@@ -167,18 +208,6 @@ forward_mfma_ws12_kernel(ForwardArgs a)
 #pragma unroll
         for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
     };
-    auto store_tile = [&](int chunk) {                    // bf16 output tile of a finished chunk, 16-byte rows
-        const uint16_t *bO = sO(chunk & 1);
-        const int t0 = chunk * C, nt = min(C, n - t0);
-        uint16_t *go = (uint16_t *)a.o + o_base;
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int row = (st >> 3) + 32 * it;
-            if (row < nt)
-                *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
-                    *(const uint4 *)&bO[row * RS + (st & 7) * 8];
-        }
-    };
     prefetch_q(0);
 
     // causal mask of a diagonal 32 x 32 score block: key 8*qd + 4*g + e is at or before query l32
@@ -193,9 +222,10 @@ forward_mfma_ws12_kernel(ForwardArgs a)
         const uint16_t *bK = sK(p), *bV = sV(p), *bSh = sSh(p), *bSl = sSl(p);
         uint16_t *bO = sO(p);
         const float *bC = tabC2[p];
+        WPROF(0);
         take_q(chunk);
         if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
-        if (OUT_BF16 && chunk > 0) store_tile(chunk - 1);
+        WPROF(1);
         const int i_row = qa * 32 + l32;
 
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -225,6 +255,7 @@ forward_mfma_ws12_kernel(ForwardArgs a)
                 acc1 = mfma(fk, fq[s], acc1);
             }
         }
+        WPROF(2);
         Frag fv[4];
         load_v_frags(fv, bV, wc, lane);
 
@@ -266,6 +297,7 @@ forward_mfma_ws12_kernel(ForwardArgs a)
                 accO = mfma(fv[2 + s], pl[s], accO);
             }
         }
+        WPROF(3);
         // ---- row factor r_i = 1 / c_i and the output tile ----
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(bC[i_row]);
 #pragma unroll
@@ -285,21 +317,38 @@ forward_mfma_ws12_kernel(ForwardArgs a)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
+        WPROF(4);
         __syncthreads();
+        WPROF(5);
     }
-    if (OUT_BF16) store_tile(n_chunks - 1);
 }
 
 }  // namespace
+
+#ifdef LASAD_PROFILE
+extern "C" int lasad_debug_read_profile_ws12(long long *host_out, int n)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof_ws12), sizeof(long long) * n);
+}
+#endif
 
 hipError_t launch_forward_mfma_ws12(const ForwardArgs &a, hipStream_t s)
 {
     if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1) return hipErrorInvalidValue;
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     if (n_seq * a.n_segments > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(n_seq * a.n_segments)), block(kWs12Threads);
-    if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_ws12_kernel<1>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(forward_mfma_ws12_kernel<0>, grid, block, 0, s, a);
+    const int64_t n_wg = n_seq * a.n_segments;
+    static const int split_env = [] { const char *e = getenv("LASAD_SPLIT"); return e ? atoi(e) : 0; }();
+    const bool split = split_env ? split_env == 2 : n_wg * 2 <= 256;   // two workgroups per sequence while compute units stay free
+    if (split) {
+        const dim3 grid((unsigned)(n_wg * 2)), block(512);
+        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 2>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 2>), grid, block, 0, s, a);
+    } else {
+        const dim3 grid((unsigned)n_wg), block(kWs12Threads);
+        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 1>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 1>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
