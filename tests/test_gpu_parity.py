@@ -124,7 +124,8 @@ CASES = [
     ("d128_bf16", 1, 2, 128, 6, 9, "bf16"),
     ("d64_f32", 2, 2, 64, 10, 10, "f32"),
     ("d128_f32", 1, 1, 128, 5, 5, "f32"),
-    ("d64_f32_many_seqs", 6, 50, 64, 3, 13, "f32"),    # > 256 sequences: one workgroup per head in the fp32 kernel
+    ("d64_f32_many_seqs", 6, 50, 64, 3, 13, "f32"),
+    ("bf16_160_seqs", 10, 16, 64, 9, 16, "bf16"),      # between 128 and 256 sequences: one twelve-wave workgroup each    # > 256 sequences: one workgroup per head in the fp32 kernel
 ]
 
 
@@ -310,3 +311,42 @@ def test_decode_equals_forward_on_gpu(lasad, oracle):
     o_fwd, s_fwd = _gpu_forward(lasad, w, qf, kf, vf, g, want_state=True, out_dtype=torch.float32)
     assert rel_err(o_dec.transpose(1, 0, 2, 3), o_fwd) <= TOL["bf16"]
     assert rel_err(s_dec, s_fwd) <= TOL["bf16"]
+
+
+VARIANT_SCRIPT = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + '/tests')
+from paper_2507_01652_amd import binding as lasad, workloads as wl
+from oracle import lasad_oracle as oracle
+from helpers import rel_err
+worst = 0.0
+for B, Hh, H, W in ((2, 3, 13, 17), (1, 2, 40, 33)):
+    w = wl.Workload('variant', B, Hh, 64, H, W, 'bf16', 0.6, 0.999, seed=11 + B)
+    q, k, v, g = wl.prefill_inputs(w)
+    lam, _ = oracle.decay_factors(g, H, W, 0, w.N)
+    s0 = wl.random_state(w, 3)
+    ref, s_ref = oracle.forward_fullmask(q, k, v, lam, s0=s0.astype(np.float64), want_state=True)
+    s1 = torch.empty((B, Hh, 64, 64), dtype=torch.float32, device='cuda')
+    o = lasad.lasad_forward_chunked(*(lasad.to_device(x, 'bf16') for x in (q, k, v)), torch.from_numpy(g).cuda(), H, W,
+                                    state_in=torch.from_numpy(s0).cuda(), state_out=s1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    worst = max(worst, rel_err(o.cpu().numpy(), ref), rel_err(s1.cpu().numpy(), s_ref))
+print('WORST', worst)
+assert worst <= 2e-2
+"""
+
+
+@pytest.mark.parametrize("env", [{"LASAD_WS": "0"}, {"LASAD_WS": "8"}, {"LASAD_WS": "12", "LASAD_SPLIT": "1"},
+                                 {"LASAD_WS": "12", "LASAD_SPLIT": "2"}],
+                         ids=["four_wave", "eight_wave", "twelve_wave_whole", "twelve_wave_split"])
+def test_forward_kernel_variants(env):
+    """Every full-pass kernel variant (the launcher picks one by the number of workgroups; the choice is read
+    from the environment once per process, hence the child process) against the oracle, with and without the
+    segment plan (the second shape is long enough to be cut into segments)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", VARIANT_SCRIPT, root], env={**os.environ, **env},
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
