@@ -13,6 +13,12 @@
 // one barrier per chunk and the chunk time is that of the slowest group (measured with cycle
 // stamps on the eight-wave kernel: about a third of its chunk time was the serial stretch between
 // its two barriers).  LDS: 2 x 67.6 KB.  Algorithm, layouts and precision: lasad_forward_mfma.hip.
+//
+// With at most 128 workgroups a sequence is split into two workgroups by value-channel half
+// (SPLIT = 2), and the output work of a half is spread over FOUR waves: for each query half one
+// wave takes the diagonal score block and the low part of Q S, the other the off-diagonal block
+// (upper query half only) and the high part of Q S.  Each leaves an fp32 partial tile in LDS; the
+// loader waves add the two, convert and store them during the next chunk.
 #include <stdlib.h>
 
 #include "lasad_forward_mfma_common.h"
@@ -24,7 +30,9 @@ namespace {
 
 using namespace fwd;
 
-constexpr int kWs12Threads = 768;
+constexpr int kWs12Threads = 768;     // SPLIT 1: 4 output + 4 state + 4 loader waves
+constexpr int kWs10Threads = 640;     // SPLIT 2: 4 output + 2 state + 4 loader waves
+constexpr int PS = 36;                // row stride (floats) of an fp32 partial output tile [token][32 channels]
 
 #ifdef LASAD_PROFILE
 // Development aid: cycle stamps of workgroup 0, waves 0 (output), 4 (state), 8 (loader), 8 slots each.
@@ -36,24 +44,32 @@ __device__ long long g_prof_ws12[24 * 64];
 #endif
 constexpr int kSetHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;   // one set of tiles
 
+__device__ inline int l32_of(int tid) { return tid & 31; }
+
 // SPLIT = 1: one workgroup (twelve waves) per sequence or segment.  SPLIT = 2: two workgroups, one per
-// value-channel half, each with two output waves, two state waves and four loader waves (the loader
+// value-channel half, each with four output waves, two state waves and four loader waves (the loader
 // work, K and its decayed copies, is done by both); for so few sequences that compute units stay free.
 template <int OUT_BF16, int SPLIT>
-__global__ void __launch_bounds__(SPLIT == 1 ? kWs12Threads : 512, 1)
+__global__ void __launch_bounds__(SPLIT == 1 ? kWs12Threads : kWs10Threads, 1)
 forward_mfma_ws12_kernel(ForwardArgs a)
 {
+    constexpr int SROWS = SPLIT == 1 ? D : D / 2;       // rows (value channels) of the S^T tiles
+    constexpr int oV = C * RS, oKh = oV + C * VS, oKl = oKh + C * VS, oSh = oKl + C * VS;
+    constexpr int oSl = oSh + SROWS * RS, oO = oSl + SROWS * RS;
+    // output area of a set: a bf16 tile (SPLIT 1) or two fp32 partial tiles of 32 channels (SPLIT 2)
+    static_assert(oO + (SPLIT == 1 ? C * RS : 2 * C * PS * 2) == kSetHalfs, "LDS set layout");
     __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kSetHalfs];
     __shared__ __attribute__((aligned(16))) float tabC2[2][C];
     static_assert(kSetHalfs * 4 >= recurrence_lds_floats<D>() * 4, "fallback needs the LDS block");
     // buffer set p: K, V, decayed keys hi / lo, S^T hi / lo, output tile
     auto sK = [&](int p) { return smem + p * kSetHalfs; };
-    auto sV = [&](int p) { return smem + p * kSetHalfs + C * RS; };
-    auto sKh = [&](int p) { return smem + p * kSetHalfs + C * RS + C * VS; };
-    auto sKl = [&](int p) { return smem + p * kSetHalfs + C * RS + 2 * C * VS; };
-    auto sSh = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS; };
-    auto sSl = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS + D * RS; };
-    auto sO = [&](int p) { return smem + p * kSetHalfs + C * RS + 3 * C * VS + 2 * D * RS; };
+    auto sV = [&](int p) { return smem + p * kSetHalfs + oV; };
+    auto sKh = [&](int p) { return smem + p * kSetHalfs + oKh; };
+    auto sKl = [&](int p) { return smem + p * kSetHalfs + oKl; };
+    auto sSh = [&](int p) { return smem + p * kSetHalfs + oSh; };
+    auto sSl = [&](int p) { return smem + p * kSetHalfs + oSl; };
+    auto sO = [&](int p) { return smem + p * kSetHalfs + oO; };
+    auto sPart = [&](int p, int part) { return (float *)(smem + p * kSetHalfs + oO) + part * C * PS; };
 
     const int G = a.n_segments;
     const int blk = blockIdx.x / SPLIT, half = blockIdx.x - blk * SPLIT;     // half: value-channel half if SPLIT == 2
@@ -68,14 +84,16 @@ forward_mfma_ws12_kernel(ForwardArgs a)
     }
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    // SPLIT 1: waves 0-3 output, 4-7 state, 8-11 loader; SPLIT 2: waves 0-1 output, 2-3 state, 4-7 loader
-    const int group = SPLIT == 1 ? wave >> 2 : (wave < 2 ? 0 : wave < 4 ? 1 : 2);
+    // SPLIT 1: waves 0-3 output, 4-7 state, 8-11 loader; SPLIT 2: waves 0-3 output, 4-5 state, 6-9 loader
+    const int group = SPLIT == 1 ? wave >> 2 : (wave < 4 ? 0 : wave < 6 ? 1 : 2);
     const int wa = SPLIT == 1 ? (wave & 3) >> 1 : wave & 1;      // query half base | key-channel half
     const int wc = SPLIT == 1 ? wave & 1 : half;                 // value-channel half
-    const bool first_of_group = SPLIT == 1 ? (wave & 3) == 0 : (wave == 0 || wave == 2 || wave == 4);
-    (void)first_of_group;
+    const int part = wave >> 1;                                  // SPLIT 2 output waves: 0 off-diagonal, 1 diagonal
+    const int srow = SPLIT == 1 ? wc * 32 + l32_of(tid) : l32_of(tid);   // this lane's row of the S^T tiles
+    const bool first_of_group = SPLIT == 1 ? (wave & 3) == 0 : (wave == 0 || wave == 4 || wave == 6);
+    (void)first_of_group; (void)part;
     const int l32 = lane & 31, g = lane >> 5;
-    const int st = tid & 255;                    // thread index inside the loader group (and the output group if SPLIT == 1)
+    const int st = SPLIT == 1 ? tid & 255 : tid - 384;   // thread index inside the loader group
 
     const int seg_t0 = seg * a.seg_chunks * C;                 // first token of this segment
     const int n = min(a.seg_chunks * C, a.n_tokens - seg_t0);   // tokens in this segment
@@ -89,16 +107,35 @@ forward_mfma_ws12_kernel(ForwardArgs a)
     SplitConst sc;
     sc.init();
 
-    auto store_tile = [&](int chunk) {                    // bf16 output tile of a finished chunk, 16-byte rows
-        const uint16_t *bO = sO(chunk & 1);
+    auto store_tile = [&](int chunk) {                    // output tile of a finished chunk, 16-byte pieces
         const int t0 = chunk * C, nt = min(C, n - t0);
-        uint16_t *go = (uint16_t *)a.o + o_base;
+        if (SPLIT == 1) {
+            const uint16_t *bO = sO(chunk & 1);
+            uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int row = (st >> 3) + 32 * it;
-            if (row < nt && (SPLIT == 1 || ((st & 7) >> 2) == half))
-                *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
-                    *(const uint4 *)&bO[row * RS + (st & 7) * 8];
+            for (int it = 0; it < 2; ++it) {
+                const int row = (st >> 3) + 32 * it;
+                if (row < nt)
+                    *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
+                        *(const uint4 *)&bO[row * RS + (st & 7) * 8];
+            }
+        } else {                                          // sum of the two fp32 partial tiles of this channel half
+            const float *x = sPart(chunk & 1, 0), *y = sPart(chunk & 1, 1);
+            const int row = st >> 2, col = (st & 3) * 8;
+            if (row < nt) {
+                const float4 x0 = *(const float4 *)&x[row * PS + col], x1 = *(const float4 *)&x[row * PS + col + 4];
+                const float4 y0 = *(const float4 *)&y[row * PS + col], y1 = *(const float4 *)&y[row * PS + col + 4];
+                const int64_t oi = o_base + (int64_t)(t0 + row) * a.out.stride_n + half * 32 + col;
+                if (OUT_BF16) {
+                    uint4 w;
+                    w.x = pack2(x0.x + y0.x, x0.y + y0.y); w.y = pack2(x0.z + y0.z, x0.w + y0.w);
+                    w.z = pack2(x1.x + y1.x, x1.y + y1.y); w.w = pack2(x1.z + y1.z, x1.w + y1.w);
+                    *(uint4 *)((uint16_t *)a.o + oi) = w;
+                } else {
+                    *(float4 *)((float *)a.o + oi) = make_float4(x0.x + y0.x, x0.y + y0.y, x0.z + y0.z, x0.w + y0.w);
+                    *(float4 *)((float *)a.o + oi + 4) = make_float4(x1.x + y1.x, x1.y + y1.y, x1.z + y1.z, x1.w + y1.w);
+                }
+            }
         }
     };
     if (group == 2) {
@@ -115,7 +152,7 @@ forward_mfma_ws12_kernel(ForwardArgs a)
         __syncthreads();
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             WPROF(0);
-            if (OUT_BF16 && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
+            if ((OUT_BF16 || SPLIT == 2) && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
             if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
                 const int p = (chunk + 1) & 1;
                 prepare_keys(sk, rk, rv, st, min(C, n - (chunk + 1) * C), pos, lg, sc);
@@ -128,7 +165,7 @@ forward_mfma_ws12_kernel(ForwardArgs a)
             __syncthreads();
             WPROF(3);
         }
-        if (OUT_BF16) store_tile(n_chunks - 1);
+        if (OUT_BF16 || SPLIT == 2) store_tile(n_chunks - 1);
         return;
     }
 
@@ -163,7 +200,7 @@ forward_mfma_ws12_kernel(ForwardArgs a)
                 uint2 hi, lo;
                 split2(accS[4 * qd + 0], accS[4 * qd + 1], hi.x, lo.x, sc);
                 split2(accS[4 * qd + 2], accS[4 * qd + 3], hi.y, lo.y, sc);
-                const int off = (wc * 32 + l32) * RS + wa * 32 + 8 * qd + 4 * g;
+                const int off = srow * RS + wa * 32 + 8 * qd + 4 * g;
                 *(uint2 *)&sh[off] = hi;
                 *(uint2 *)&sl[off] = lo;
             }
@@ -227,39 +264,9 @@ forward_mfma_ws12_kernel(ForwardArgs a)
         if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
         WPROF(1);
         const int i_row = qa * 32 + l32;
-
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        f32x16 acc0 = zero16, acc1 = zero16, accO = zero16;
-        // ---- scores of key block 0, P^T[j][i] = sum_d K[j][d] Q[i][d] ----
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            Frag fk;
-            fk.u = *(const uint4 *)&bK[l32 * RS + 16 * s + 8 * g];
-            acc0 = mfma(fk, fq[s], acc0);
-        }
-        // ---- O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk] ----
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            Frag fs;
-            fs.u = *(const uint4 *)&bSh[(wc * 32 + l32) * RS + 16 * s + 8 * g];
-            accO = mfma(fs, fq[s], accO);
-            fs.u = *(const uint4 *)&bSl[(wc * 32 + l32) * RS + 16 * s + 8 * g];
-            accO = mfma(fs, fq[s], accO);
-        }
-        // ---- scores of key block 1 (all masked for the lower query half) ----
-        if (qa == 1) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                Frag fk;
-                fk.u = *(const uint4 *)&bK[(32 + l32) * RS + 16 * s + 8 * g];
-                acc1 = mfma(fk, fq[s], acc1);
-            }
-        }
-        WPROF(2);
-        Frag fv[4];
-        load_v_frags(fv, bV, wc, lane);
 
-        // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
+        // decay + causal mask on the fp32 scores of key block jb, split to bf16 hi + lo
         auto mask_split = [&](const f32x16 &acc, int jb, bool diagonal, Frag *ph, Frag *pl) {
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -279,30 +286,83 @@ forward_mfma_ws12_kernel(ForwardArgs a)
                 pl[qd / 2].h[qd % 2] = lo;
             }
         };
-        {
+        // scores of key block jb: P^T[j][i] = sum_d K[j][d] Q[i][d]
+        auto scores = [&](int jb) {
+            f32x16 acc = zero16;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                Frag fk;
+                fk.u = *(const uint4 *)&bK[(jb * 32 + l32) * RS + 16 * s + 8 * g];
+                acc = mfma(fk, fq[s], acc);
+            }
+            return acc;
+        };
+        // O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk] with one bf16 part of S^T
+        auto inter = [&](f32x16 acc, const uint16_t *bS) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                Frag fs;
+                fs.u = *(const uint4 *)&bS[srow * RS + 16 * s + 8 * g];
+                acc = mfma(fs, fq[s], acc);
+            }
+            return acc;
+        };
+        // O^T += V^T P^T for key block jb (V fragments of that block: 2*jb, 2*jb + 1)
+        auto intra = [&](f32x16 acc, const f32x16 &sc_acc, int jb, bool diagonal) {
+            Frag fv[2];
+            {
+                const int trow = (lane & 15) >> 2;
+                const int tcol = wc * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    fv[s].h[0] = tr_read(&bV[(32 * jb + 16 * s + 4 * g + trow) * VS + tcol]);
+                    fv[s].h[1] = tr_read(&bV[(32 * jb + 16 * s + 8 + 4 * g + trow) * VS + tcol]);
+                }
+            }
             Frag ph[2], pl[2];
-            mask_split(acc0, 0, qa == 0, ph, pl);
+            mask_split(sc_acc, jb, diagonal, ph, pl);
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                accO = mfma(fv[s], ph[s], accO);
-                accO = mfma(fv[s], pl[s], accO);
+                acc = mfma(fv[s], ph[s], acc);
+                acc = mfma(fv[s], pl[s], acc);
             }
-        }
-        if (qa == 1) {
-            Frag ph[2], pl[2];
-            mask_split(acc1, 1, true, ph, pl);
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                accO = mfma(fv[2 + s], ph[s], accO);
-                accO = mfma(fv[2 + s], pl[s], accO);
-            }
+            return acc;
+        };
+
+        f32x16 accO = zero16;
+        if (SPLIT == 1) {
+            const f32x16 acc0 = scores(0);
+            accO = inter(accO, bSh);
+            accO = inter(accO, bSl);
+            f32x16 acc1 = zero16;
+            if (qa == 1) acc1 = scores(1);
+            WPROF(2);
+            accO = intra(accO, acc0, 0, qa == 0);
+            if (qa == 1) accO = intra(accO, acc1, 1, true);
+        } else if (part == 1) {                           // diagonal block of this query half, low part of Q S
+            const f32x16 accd = scores(qa);
+            accO = inter(accO, bSl);
+            WPROF(2);
+            accO = intra(accO, accd, qa, true);
+        } else {                                          // off-diagonal block (upper query half), high part of Q S
+            f32x16 acc0 = zero16;
+            if (qa == 1) acc0 = scores(0);
+            accO = inter(accO, bSh);
+            WPROF(2);
+            if (qa == 1) accO = intra(accO, acc0, 0, false);
         }
         WPROF(3);
         // ---- row factor r_i = 1 / c_i and the output tile ----
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(bC[i_row]);
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[r] *= osc;
-        if (OUT_BF16) {                                   // via LDS for 16-byte coalesced stores
+        if (SPLIT == 2) {                                 // fp32 partial tile [token][32 channels]; the loader waves add the two
+            float *bP = sPart(p, part);
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                *(float4 *)&bP[i_row * PS + 8 * qd + 4 * g] = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
+                                                                         accO[4 * qd + 2], accO[4 * qd + 3]);
+        } else if (OUT_BF16) {                            // via LDS for 16-byte coalesced stores
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
                 uint2 w2;
@@ -341,7 +401,7 @@ hipError_t launch_forward_mfma_ws12(const ForwardArgs &a, hipStream_t s)
     static const int split_env = [] { const char *e = getenv("LASAD_SPLIT"); return e ? atoi(e) : 0; }();
     const bool split = split_env ? split_env == 2 : n_wg * 2 <= 256;   // two workgroups per sequence while compute units stay free
     if (split) {
-        const dim3 grid((unsigned)(n_wg * 2)), block(512);
+        const dim3 grid((unsigned)(n_wg * 2)), block(kWs10Threads);
         if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 2>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 2>), grid, block, 0, s, a);
     } else {
