@@ -32,62 +32,14 @@
 // zero) cannot be factored this way; the workgroup then abandons the chunked walk and redoes
 // its whole sequence with the token-serial fp32 routine (lasad_scan.h), which applies each
 // decay step by step.  Gates from a sigmoid stay many orders of magnitude above that limit.
-#include "lasad_mfma_util.h"
+#include "lasad_forward_gated_common.h"
 #include "lasad_scan.h"
 
 namespace lasad {
 
 namespace {
 
-constexpr int C = 64;      // chunk length (tokens)
-constexpr int D = 64;      // head dim
-constexpr int kThreads = 256;
-#ifndef LASAD_GATED_KS
-#define LASAD_GATED_KS 80
-#endif
-constexpr int TS = 80;     // LDS row stride (bf16 elements) of the V tile (transpose reads): 160 B
-constexpr int KS = LASAD_GATED_KS;   // of the K~ tiles (16-byte row reads and transpose reads)
-constexpr int RS = 72;     // of the Q~, S^T and output tiles (16-byte row reads): 144 B
-constexpr float kMinChunkDecay = 8.6736174e-19f;   // 2^-60
-
-// Running products of eight values along the 32 lanes of each half wavefront: on return x[c]
-// of lane l holds the product over lanes 0..l of its half (inclusive) and e[c] the product over
-// lanes 0..l-1 (1 in lane 0 of a half).  Each DPP step multiplies by the value 1, 2, 4, 8 lanes
-// down the 16-lane row (lanes without a source keep their value), the last one by lane 15 of
-// the row below (rows 1 and 3 only).  The eight chains are interleaved, so every DPP source
-// was written eight instructions earlier; the s_nop covers what preceded the block.
-#define SCAN_STEP(ctrl)                                                                           \
-    "v_mul_f32_dpp %0, %0, %0 " ctrl "\n v_mul_f32_dpp %1, %1, %1 " ctrl "\n"                     \
-    "v_mul_f32_dpp %2, %2, %2 " ctrl "\n v_mul_f32_dpp %3, %3, %3 " ctrl "\n"                     \
-    "v_mul_f32_dpp %4, %4, %4 " ctrl "\n v_mul_f32_dpp %5, %5, %5 " ctrl "\n"                     \
-    "v_mul_f32_dpp %6, %6, %6 " ctrl "\n v_mul_f32_dpp %7, %7, %7 " ctrl "\n"
-__device__ inline void scan_mul32x8(float (&x)[8], float (&e)[8], bool half_start)
-{
-    asm("s_nop 1\n"
-        SCAN_STEP("row_shr:1 row_mask:0xf bank_mask:0xf")
-        SCAN_STEP("row_shr:2 row_mask:0xf bank_mask:0xf")
-        SCAN_STEP("row_shr:4 row_mask:0xf bank_mask:0xf")
-        SCAN_STEP("row_shr:8 row_mask:0xf bank_mask:0xf")
-        SCAN_STEP("row_bcast:15 row_mask:0xa bank_mask:0xf")
-        : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]));
-#pragma unroll
-    for (int c = 0; c < 8; ++c) e[c] = 1.0f;
-    asm("s_nop 1\n"
-        "v_mov_b32_dpp %0, %8 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %1, %9 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
-        "v_mov_b32_dpp %2, %10 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %3, %11 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
-        "v_mov_b32_dpp %4, %12 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %5, %13 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
-        "v_mov_b32_dpp %6, %14 wave_shr:1 row_mask:0xf bank_mask:0xf\n v_mov_b32_dpp %7, %15 wave_shr:1 row_mask:0xf bank_mask:0xf\n"
-        : "+v"(e[0]), "+v"(e[1]), "+v"(e[2]), "+v"(e[3]), "+v"(e[4]), "+v"(e[5]), "+v"(e[6]), "+v"(e[7])
-        : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "v"(x[4]), "v"(x[5]), "v"(x[6]), "v"(x[7]));
-#pragma unroll
-    for (int c = 0; c < 8; ++c) e[c] = half_start ? 1.0f : e[c];
-}
-
-// x where keep, else every 32-bit word = fill (component-wise, so the values stay in registers)
-__device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
-{
-    return make_uint4(keep ? x.x : fill, keep ? x.y : fill, keep ? x.z : fill, keep ? x.w : fill);
-}
+using namespace gated;
 
 // FUSED >= 1 adds Algorithm 1's elementwise steps: q := SiLU(q) and lambda := sigmoid(lambda) while
 // the chunk is prepared; FUSED = 2 also the root-mean-square normalisation of every output token
@@ -132,21 +84,11 @@ forward_gated_mfma_kernel(ForwardArgs a)
     SplitConst sc;
     sc.init();
 
-    // staging loads: token rows 2*l32, 2*l32 + 1 of the chunk, channels 16*wave + 8*g .. +7; unconditional, clamped
+    // staging: token rows 2*l32, 2*l32 + 1 of the chunk, channels 16*wave + 8*g .. +7
     const int pcol = 16 * wave + 8 * g;
-    uint4 rq[2], rl[2], rk[2], rv[2];
-    auto prefetch = [&](int chunk) {
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int tok = min(chunk * C + 2 * l32 + it, n - 1);
-            const int64_t off = (int64_t)tok * a.in.stride_n + pcol;
-            rq[it] = *(const uint4 *)(gq + off);
-            rl[it] = *(const uint4 *)(gl + off);
-            if (OWNKEY) rk[it] = *(const uint4 *)(gk + off);
-            rv[it] = *(const uint4 *)(gv + off);
-        }
-    };
-    prefetch(0);
+    ChunkStage<OWNKEY, (FUSED > 0)> stg;
+    stg.trip = false;
+    stg.fetch(gq, gl, gk, gv, 0, n, a.in.stride_n, l32, pcol);
 
     // --- state accumulators: S[dk = wa*32 + 8*(r/4) + 4*g + r%4][dv = wc*32 + l32] ---
     f32x16 accS;
@@ -177,108 +119,22 @@ forward_gated_mfma_kernel(ForwardArgs a)
     // iff 8*qd + e <= cq
     const int cq = l32 - 4 * g;
 
-    // Operands of one chunk, prepared in registers from the staged pieces: bf16 hi + lo of
-    // K~ = k / A and Q~ = q_scale q A for this lane's two token rows and eight channels.
-    uint4 pkh[2], pkl[2], pqh[2], pql[2], pv[2];
-    bool trip = false;
-    auto prepare = [&](int chunk) {
-        const int t0 = chunk * C, nt = min(C, n - t0);
-        // which of the chunk's 64 tokens sit on a row boundary (bit t), same in every wavefront
-        const unsigned long long bmask = __ballot(is_boundary(a.start_pos + t0 + lane + 1, a.grid_w, a.mode));
-        float *sTotN = sTot[chunk & 1];
-        float lam[2][8], kk[2][8];
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int row = 2 * l32 + it;
-            const bool bnd = (bmask >> row) & 1ull;
-            const uint32_t lw[4] = {rl[it].x, rl[it].y, rl[it].z, rl[it].w};
-            const uint32_t kw[4] = {rk[it].x, rk[it].y, rk[it].z, rk[it].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float l0 = __uint_as_float(lw[e] << 16), l1 = __uint_as_float(lw[e] & 0xffff0000u);
-                if (FUSED) { l0 = sigmoid_f32(l0); l1 = sigmoid_f32(l1); }
-                const float k0 = OWNKEY ? __uint_as_float(kw[e] << 16) : 1.0f - l0;
-                const float k1 = OWNKEY ? __uint_as_float(kw[e] & 0xffff0000u) : 1.0f - l1;
-                kk[it][2 * e] = k0;
-                kk[it][2 * e + 1] = k1;
-                lam[it][2 * e] = bnd ? 1.0f : l0;
-                lam[it][2 * e + 1] = bnd ? 1.0f : l1;
-            }
-            pv[it] = rv[it];
-        }
-        if (nt < C) {                                      // tail chunk: rows past the end get lambda 1, q = k = v = 0
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const bool live = 2 * l32 + it < nt;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    kk[it][c] = live ? kk[it][c] : 0.f;
-                    lam[it][c] = live ? lam[it][c] : 1.0f;
-                }
-                pv[it] = keep_or(live, pv[it], 0u);
-                rq[it] = keep_or(live, rq[it], 0u);
-            }
-        }
-        // product over the token pairs of lanes 0..l32 (tot) and 0..l32-1 (exc), per channel
-        float tot[8], exc[8];
-#pragma unroll
-        for (int c = 0; c < 8; ++c) tot[c] = lam[0][c] * lam[1][c];
-        scan_mul32x8(tot, exc, l32 == 0);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            lam[0][c] *= exc[c];                                // A of token 2*l32
-            lam[1][c] *= lam[0][c];                             // A of token 2*l32 + 1
-        }
-        if (l32 == 31) {                                        // chunk totals A_end of this half's channels
-            *(float4 *)&sTotN[pcol] = make_float4(tot[0], tot[1], tot[2], tot[3]);
-            *(float4 *)&sTotN[pcol + 4] = make_float4(tot[4], tot[5], tot[6], tot[7]);
-        }
-        // A decreases along the tokens: the smallest value of each channel sits in lane 31
-        float amin = lam[1][0];
-#pragma unroll
-        for (int c = 1; c < 8; ++c) amin = fminf(amin, lam[1][c]);
-        trip = !(amin >= kMinChunkDecay);
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const uint32_t qw[4] = {rq[it].x, rq[it].y, rq[it].z, rq[it].w};
-            uint32_t kh[4], kl[4], qh[4], ql[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float a0 = lam[it][2 * e], a1 = lam[it][2 * e + 1];
-                split2(kk[it][2 * e] * __builtin_amdgcn_rcpf(a0), kk[it][2 * e + 1] * __builtin_amdgcn_rcpf(a1), kh[e], kl[e], sc);
-                float q0 = __uint_as_float(qw[e] << 16), q1 = __uint_as_float(qw[e] & 0xffff0000u);
-                if (FUSED) { q0 = silu_f32(q0); q1 = silu_f32(q1); }
-                split2(q0 * (a0 * a.q_scale), q1 * (a1 * a.q_scale), qh[e], ql[e], sc);
-            }
-            pkh[it] = make_uint4(kh[0], kh[1], kh[2], kh[3]); pkl[it] = make_uint4(kl[0], kl[1], kl[2], kl[3]);
-            pqh[it] = make_uint4(qh[0], qh[1], qh[2], qh[3]); pql[it] = make_uint4(ql[0], ql[1], ql[2], ql[3]);
-        }
-    };
-
     const int n_chunks = (n + C - 1) / C;
     int pending_rows = 0;          // NORM: rows of the output tile in LDS that are not stored yet
-    prepare(0);
+    stg.prepare(a, 0, n, lane, pcol, sTot[0], sc);
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
 
         // ---- write the prepared tiles (free since barrier B of the previous chunk) ----
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int row = 2 * l32 + it;
-            *(uint4 *)&sKh[(row) * KS + pcol] = pkh[it];
-            *(uint4 *)&sKl[(row) * KS + pcol] = pkl[it];
-            *(uint4 *)&sQh[(row) * RS + pcol] = pqh[it];
-            *(uint4 *)&sQl[(row) * RS + pcol] = pql[it];
-            *(uint4 *)&sV[row * TS + pcol] = pv[it];
-        }
-        if (__syncthreads_or(trip)) {                     // (A) operand tiles and A_end visible, or give up
+        stg.write(sQh, sQl, sKh, sKl, sV, l32, pcol);
+        if (__syncthreads_or(stg.trip)) {                     // (A) operand tiles and A_end visible, or give up
             // every thread has left the tiles; redo the whole sequence step by step
             scan::scan_sequence<1, OUT_BF16, OWNKEY ? scan::OWNKEY : scan::TIED, 64>(a, bh, 0, (float *)smem_raw);
             return;
         }
-        if (chunk + 1 < n_chunks) prefetch(chunk + 1);
+        if (chunk + 1 < n_chunks) stg.fetch(gq, gl, gk, gv, chunk + 1, n, a.in.stride_n, l32, pcol);
         if (NORM && OUT_BF16 && pending_rows > 0) {       // the previous chunk's normalised tile, 16-byte rows
             uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
@@ -429,7 +285,7 @@ forward_gated_mfma_kernel(ForwardArgs a)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
-        if (chunk + 1 < n_chunks) prepare(chunk + 1);     // its loads have landed by now
+        if (chunk + 1 < n_chunks) stg.prepare(a, chunk + 1, n, lane, pcol, sTot[(chunk + 1) & 1], sc);   // its loads have landed by now
         if (!NORM) {
             __syncthreads();                              // (B) all reads of the tiles and of S^T finished
             if (OUT_BF16) {                               // coalesced 16-byte stores of the bf16 tile
