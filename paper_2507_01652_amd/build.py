@@ -22,6 +22,7 @@ SOURCES = [
     "lasad_forward_mfma_ws.hip",
     "lasad_forward_mfma_ws12.hip",
     "lasad_forward_gated_mfma.hip",
+    "lasad_forward_gated_ws.hip",
     "lasad_decode.hip",
     "lasad_backward.hip",
 ]

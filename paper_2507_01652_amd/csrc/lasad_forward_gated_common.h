@@ -5,6 +5,7 @@
 
 #include "lasad_mfma_util.h"
 #include "lasad_internal.h"
+#include "lasad_scan.h"
 
 namespace lasad {
 namespace gated {
@@ -66,6 +67,8 @@ struct ChunkStage {
     uint4 rq[2], rl[2], rk[2], rv[2];                 // as fetched: q, lambda (or gate logits), own key, v
     uint4 pkh[2], pkl[2], pqh[2], pql[2], pv[2];      // prepared: K~ hi / lo, Q~ hi / lo, v
     bool trip;                                        // some channel's chunk decay is below the limit
+    float lam[2][8], kk[2][8];                        // between the two halves of prepare(): decay (then A) and key, fp32
+    uint4 qc[2];                                      // and the fetched query pieces
 
     // unconditional, clamped 16-byte loads of chunk `chunk` of a sequence of n tokens
     __device__ void fetch(const uint16_t *gq, const uint16_t *gl, const uint16_t *gk, const uint16_t *gv,
@@ -83,15 +86,22 @@ struct ChunkStage {
     }
 
     // K~ = k / A and Q~ = q_scale q A (bf16 hi + lo) for this lane's rows; A_end of the lane's
-    // channels goes to sTotN (written by the lanes that hold the last token pair)
+    // channels goes to sTotN (written by the lanes that hold the last token pair).  Two halves:
+    // prepare_begin() consumes the fetched registers (a caller may issue the next fetch() right
+    // after it), prepare_end() does the scan, the scaling and the splits.
     __device__ void prepare(const ForwardArgs &a, int chunk, int n, int lane, int pcol, float *sTotN,
                             const SplitConst &sc)
+    {
+        prepare_begin(a, chunk, n, lane);
+        prepare_end(a, lane, pcol, sTotN, sc);
+    }
+
+    __device__ void prepare_begin(const ForwardArgs &a, int chunk, int n, int lane)
     {
         const int l32 = lane & 31;
         const int t0 = chunk * C, nt = min(C, n - t0);
         // which of the chunk's 64 tokens sit on a row boundary (bit t), same in every wavefront
         const unsigned long long bmask = __ballot(is_boundary(a.start_pos + t0 + lane + 1, a.grid_w, a.mode));
-                float lam[2][8], kk[2][8];
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int row = 2 * l32 + it;
@@ -124,6 +134,12 @@ struct ChunkStage {
                 rq[it] = keep_or(live, rq[it], 0u);
             }
         }
+        qc[0] = rq[0]; qc[1] = rq[1];
+    }
+
+    __device__ void prepare_end(const ForwardArgs &a, int lane, int pcol, float *sTotN, const SplitConst &sc)
+    {
+        const int l32 = lane & 31;
         // product over the token pairs of lanes 0..l32 (tot) and 0..l32-1 (exc), per channel
         float tot[8], exc[8];
 #pragma unroll
@@ -145,7 +161,7 @@ struct ChunkStage {
         trip = !(amin >= kMinChunkDecay);
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const uint32_t qw[4] = {rq[it].x, rq[it].y, rq[it].z, rq[it].w};
+            const uint32_t qw[4] = {qc[it].x, qc[it].y, qc[it].z, qc[it].w};
             uint32_t kh[4], kl[4], qh[4], ql[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -175,6 +191,16 @@ struct ChunkStage {
         }
     }
 };
+
+// The token-serial redo of one sequence (range fallback of the chunked kernels), as a real call:
+// inlined into a kernel it makes the compiler keep the argument block in scratch memory and
+// reload fields from there inside the chunk loop of the twelve-wave kernel (measured: 18 instead
+// of 11 us at the base shape).  The four-wave kernel is faster with the inlined routine.
+template <int OUT_BF16, int OWNKEY>
+__device__ __noinline__ void redo_sequence(ForwardArgs a, int bh, float *lds)
+{
+    scan::scan_sequence<1, OUT_BF16, OWNKEY ? scan::OWNKEY : scan::TIED, 64>(a, bh, 0, lds);
+}
 
 }  // namespace gated
 }  // namespace lasad

@@ -32,6 +32,8 @@
 // zero) cannot be factored this way; the workgroup then abandons the chunked walk and redoes
 // its whole sequence with the token-serial fp32 routine (lasad_scan.h), which applies each
 // decay step by step.  Gates from a sigmoid stay many orders of magnitude above that limit.
+#include <stdlib.h>
+
 #include "lasad_forward_gated_common.h"
 #include "lasad_scan.h"
 
@@ -55,6 +57,7 @@ forward_gated_mfma_kernel(ForwardArgs a)
     constexpr int kLdsBytes = kTileHalfs * 2 > kScanFloats * 4 ? kTileHalfs * 2 : kScanFloats * 4;
     __shared__ __attribute__((aligned(16))) unsigned char smem_raw[kLdsBytes];
     __shared__ __attribute__((aligned(16))) float sTot[2][D];  // A_end per key channel, by chunk parity
+    __shared__ __attribute__((aligned(16))) int sTrip[2][4];   // range flag of each wave, by chunk parity
     constexpr bool NORM = FUSED == 2;
     __shared__ float sSS[NORM ? 2 : 1][NORM ? C : 1];          // sum of squares of a token's two channel halves
     uint16_t *sQh = (uint16_t *)smem_raw;
@@ -129,7 +132,16 @@ forward_gated_mfma_kernel(ForwardArgs a)
 
         // ---- write the prepared tiles (free since barrier B of the previous chunk) ----
         stg.write(sQh, sQl, sKh, sKl, sV, l32, pcol);
-        if (__syncthreads_or(stg.trip)) {                     // (A) operand tiles and A_end visible, or give up
+        // Range flag: one LDS store per wave before the barrier, four loads after it (an atomic OR by
+        // every thread on one LDS word, as __syncthreads_or does it, serialises: 2 us per chunk).
+        {
+            const bool any = __any(stg.trip);
+            if (lane == 0) sTrip[chunk & 1][wave] = any ? 1 : 0;
+        }
+        __syncthreads();                                      // (A) operand tiles and A_end visible
+        const int4 tf = *(const int4 *)sTrip[chunk & 1];
+        if ((tf.x | tf.y | tf.z | tf.w) != 0) {               // some chunk left the range: give up the chunked walk
+            __syncthreads();
             // every thread has left the tiles; redo the whole sequence step by step
             scan::scan_sequence<1, OUT_BF16, OWNKEY ? scan::OWNKEY : scan::TIED, 64>(a, bh, 0, (float *)smem_raw);
             return;
@@ -328,6 +340,9 @@ hipError_t launch_forward_gated_mfma(const ForwardArgs &a, hipStream_t s)
     if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1 || !a.lam) return hipErrorInvalidValue;
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     if (n_seq > 0x7fffffff) return hipErrorInvalidValue;
+    // while every sequence gets a compute unit of its own: the twelve-wave kernel (LASAD_GATED_WS=0 / 1 forces the choice)
+    static const int ws_env = [] { const char *e = getenv("LASAD_GATED_WS"); return e ? atoi(e) : -1; }();
+    if (!a.norm && (ws_env == 1 || (ws_env < 0 && n_seq <= 256))) return launch_forward_gated_ws(a, s);
     const dim3 grid((unsigned)n_seq), block(kThreads);
     const bool out16 = a.out_dtype == LASAD_BF16;
     if (a.fused_act || a.norm) {

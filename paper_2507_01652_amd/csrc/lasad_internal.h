@@ -86,6 +86,8 @@ hipError_t launch_forward_gated_mfma(const ForwardArgs &a, hipStream_t s);
 hipError_t launch_forward_mfma_ws(const ForwardArgs &a, hipStream_t s);
 // twelve wavefronts, doubled LDS buffers, one barrier per chunk: for workgroups that own a compute unit
 hipError_t launch_forward_mfma_ws12(const ForwardArgs &a, hipStream_t s);
+// the vector-decay kernel with twelve wavefronts per sequence (no fused norm)
+hipError_t launch_forward_gated_ws(const ForwardArgs &a, hipStream_t s);
 // device workspace the MFMA kernel wants for n_seq sequences of n_tokens tokens (0 = none)
 size_t forward_mfma_workspace_bytes(int64_t n_seq, int n_tokens);
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
