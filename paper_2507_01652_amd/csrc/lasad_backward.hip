@@ -91,6 +91,17 @@ backward_finish_kernel(BackwardArgs a)
             *(float4 *)((float *)a.dq + gi) = dq4;
             *(float4 *)((float *)a.dk + gi) = dk4;
         }
+        if (a.dv32) {                                    // dv came in fp32 as well: store it in the caller's type
+            const float4 dv4 = *(const float4 *)(a.dv32 + w_base + t * w_stride_n + c);
+            if (OUT_BF16) {
+                uint2 w;
+                w.x = (uint32_t)float_to_bf16_bits(dv4.x) | ((uint32_t)float_to_bf16_bits(dv4.y) << 16);
+                w.y = (uint32_t)float_to_bf16_bits(dv4.z) | ((uint32_t)float_to_bf16_bits(dv4.w) << 16);
+                *(uint2 *)((uint16_t *)a.dv + gi) = w;
+            } else {
+                *(float4 *)((float *)a.dv + gi) = dv4;
+            }
+        }
     }
     // fixed-order reduction: lanes of a wave (xor butterflies), then the four waves
 #pragma unroll
@@ -144,7 +155,7 @@ static size_t sums_bytes(int64_t n_seq, int n_tokens)
 
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype)
 {
-    const size_t grads = 2 * (size_t)n_seq * n_tokens * d * sizeof(float);
+    const size_t grads = 3 * (size_t)n_seq * n_tokens * d * sizeof(float);
     const size_t sums = sums_bytes(n_seq, n_tokens);
     const size_t fwd = (io_dtype == LASAD_BF16 && d == 64) ? forward_mfma_workspace_bytes(n_seq, n_tokens) : 0;
     return grads + sums + fwd;
@@ -157,14 +168,20 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     const int n = b.n_tokens;
     const int elt = b.io_dtype == LASAD_BF16 ? 2 : 4;
     const int gelt = b.grad_dtype == LASAD_BF16 ? 2 : 4;
-    // workspace: dq32, dk32 ([B][n][Hh][d] fp32), per-sequence sums, forward-kernel workspace
+    // workspace: dq32, dk32, dv32 ([B][n][Hh][d] fp32), per-sequence sums, forward-kernel workspace
     char *ws = (char *)b.workspace;
     const size_t one = (size_t)n_seq * n * b.d * sizeof(float);
     b.dq32 = (float *)ws;
     b.dk32 = (float *)(ws + one);
-    b.seq_sums = (float *)(ws + 2 * one);
-    float *fwd_ws = (float *)(ws + 2 * one + sums_bytes(n_seq, n));
+    b.dv32 = nullptr;
+    b.seq_sums = (float *)(ws + 3 * one);
+    float *fwd_ws = (float *)(ws + 3 * one + sums_bytes(n_seq, n));
     const bool has_fwd_ws = use_mfma && forward_mfma_workspace_bytes(n_seq, n) > 0;
+    // The three passes are independent: one launch runs them side by side when that alone fills
+    // the chip or when a pass would not be cut into segments anyway.  All passes of a launch
+    // store one type, fp32, so a bf16 dv goes through the workspace like dq and dk.
+    const bool merged = use_mfma && (n_seq * 3 >= 192 || !has_fwd_ws);
+    if (merged && b.grad_dtype == LASAD_BF16) b.dv32 = (float *)(ws + 2 * one);
 
     lasad_layout_t wl;                                   // layout of dq32 / dk32
     wl.stride_b = (int64_t)n * b.Hh * b.d; wl.stride_n = (int64_t)b.Hh * b.d; wl.stride_h = b.d;
@@ -182,26 +199,50 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     f.seg_states = has_fwd_ws ? fwd_ws : nullptr; f.n_segments = 1; f.seg_chunks = 0;
     auto run = [&](const ForwardArgs &fa) { return use_mfma ? launch_forward_mfma(fa, s) : launch_forward_generic(fa, s); };
 
-    // dq (fp32, workspace): forward order, (q, k, v) := (d_o, v, k)
-    f.q = b.d_o; f.k = b.v; f.v = b.k; f.o = b.dq32;
-    f.in = b.in; f.out = wl; f.out_dtype = LASAD_F32; f.start_pos = b.start_pos;
-    hipError_t e = run(f);
-    if (e != hipSuccess) return e;
+    const int rev_start = reversed_start(b.start_pos, n, b.grid_w, b.mode);
+    hipError_t e;
+    if (merged) {
+        MultiPass m;
+        m.n_pass = 3;
+        // dq: forward order, (q, k, v) := (d_o, v, k)
+        m.q[0] = b.d_o; m.k[0] = b.v; m.v[0] = b.k; m.o[0] = b.dq32;
+        m.in[0] = b.in; m.out[0] = wl; m.start_pos[0] = b.start_pos;
+        // dv: reversed order, (q, k, v) := (k, q, d_o)
+        m.q[1] = last_token(b.k, b.in, n, elt); m.k[1] = last_token(b.q, b.in, n, elt); m.v[1] = last_token(b.d_o, b.in, n, elt);
+        if (b.dv32) { m.o[1] = (void *)last_token(b.dv32, wl, n, 4); m.out[1] = wl_rev; }
+        else { m.o[1] = (void *)last_token(b.dv, b.grad, n, 4); m.out[1] = grad_rev; }
+        m.in[1] = in_rev; m.start_pos[1] = rev_start;
+        // dk: reversed order, (q, k, v) := (v, d_o, q)
+        m.q[2] = last_token(b.v, b.in, n, elt); m.k[2] = last_token(b.d_o, b.in, n, elt); m.v[2] = last_token(b.q, b.in, n, elt);
+        m.o[2] = (void *)last_token(b.dk32, wl, n, 4);
+        m.in[2] = in_rev; m.out[2] = wl_rev; m.start_pos[2] = rev_start;
+        f.q = m.q[0]; f.k = m.k[0]; f.v = m.v[0]; f.o = m.o[0];
+        f.in = b.in; f.out = wl; f.out_dtype = LASAD_F32; f.start_pos = b.start_pos;
+        f.seg_states = nullptr; f.seg_chunks = (n + 63) / 64;
+        e = launch_forward_mfma_multi(f, m, s);
+        if (e != hipSuccess) return e;
+    } else {
+        // dq (fp32, workspace): forward order, (q, k, v) := (d_o, v, k)
+        f.q = b.d_o; f.k = b.v; f.v = b.k; f.o = b.dq32;
+        f.in = b.in; f.out = wl; f.out_dtype = LASAD_F32; f.start_pos = b.start_pos;
+        e = run(f);
+        if (e != hipSuccess) return e;
 
-    // dv (caller's buffer): reversed order, (q, k, v) := (k, q, d_o)
-    f.q = last_token(b.k, b.in, n, elt); f.k = last_token(b.q, b.in, n, elt); f.v = last_token(b.d_o, b.in, n, elt);
-    f.o = (void *)last_token(b.dv, b.grad, n, gelt);
-    f.in = in_rev; f.out = grad_rev; f.out_dtype = b.grad_dtype;
-    f.start_pos = reversed_start(b.start_pos, n, b.grid_w, b.mode);
-    e = run(f);
-    if (e != hipSuccess) return e;
+        // dv (caller's buffer): reversed order, (q, k, v) := (k, q, d_o)
+        f.q = last_token(b.k, b.in, n, elt); f.k = last_token(b.q, b.in, n, elt); f.v = last_token(b.d_o, b.in, n, elt);
+        f.o = (void *)last_token(b.dv, b.grad, n, gelt);
+        f.in = in_rev; f.out = grad_rev; f.out_dtype = b.grad_dtype;
+        f.start_pos = rev_start;
+        e = run(f);
+        if (e != hipSuccess) return e;
 
-    // dk (fp32, workspace): reversed order, (q, k, v) := (v, d_o, q)
-    f.q = last_token(b.v, b.in, n, elt); f.k = last_token(b.d_o, b.in, n, elt); f.v = last_token(b.q, b.in, n, elt);
-    f.o = (void *)last_token(b.dk32, wl, n, 4);
-    f.out = wl_rev; f.out_dtype = LASAD_F32;
-    e = run(f);
-    if (e != hipSuccess) return e;
+        // dk (fp32, workspace): reversed order, (q, k, v) := (v, d_o, q)
+        f.q = last_token(b.v, b.in, n, elt); f.k = last_token(b.d_o, b.in, n, elt); f.v = last_token(b.q, b.in, n, elt);
+        f.o = (void *)last_token(b.dk32, wl, n, 4);
+        f.out = wl_rev; f.out_dtype = LASAD_F32;
+        e = run(f);
+        if (e != hipSuccess) return e;
+    }
 
     const int nblk = (n + kFinTokens - 1) / kFinTokens;
     if (n_seq * nblk > 0x7fffffff) return hipErrorInvalidValue;

@@ -37,8 +37,14 @@ __device__ long long g_prof_ws[24 * 64];
 
 template <int OUT_BF16>
 __global__ void __launch_bounds__(kWsThreads, 1)
-forward_mfma_ws_kernel(ForwardArgs a)
+forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
 {
+    if (m.n_pass > 1) {                // one of several independent passes of this launch
+        const int y = blockIdx.y;
+        a.q = m.q[y]; a.k = m.k[y]; a.v = m.v[y]; a.o = m.o[y];
+        a.in = m.in[y]; a.out = m.out[y]; a.start_pos = m.start_pos[y];
+    }
+
     constexpr int kLdsHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;
     __shared__ __attribute__((aligned(16))) uint16_t smem[kLdsHalfs];
     __shared__ __attribute__((aligned(16))) float tabC[C];
@@ -305,15 +311,36 @@ extern "C" int lasad_debug_read_profile_ws(long long *host_out, int n)
 }
 #endif
 
+static hipError_t launch_ws8(const ForwardArgs &a, const MultiPass &m, hipStream_t s);
+
 hipError_t launch_forward_mfma_ws(const ForwardArgs &a, hipStream_t s)
+{
+    MultiPass one;
+    one.n_pass = 1;
+    return launch_ws8(a, one, s);
+}
+
+static hipError_t launch_ws8(const ForwardArgs &a, const MultiPass &m, hipStream_t s)
 {
     if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1) return hipErrorInvalidValue;
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     if (n_seq * a.n_segments > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(n_seq * a.n_segments)), block(kWsThreads);
-    if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_ws_kernel<1>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(forward_mfma_ws_kernel<0>, grid, block, 0, s, a);
+    const dim3 grid((unsigned)(n_seq * a.n_segments), (unsigned)m.n_pass), block(kWsThreads);
+    if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_ws_kernel<1>, grid, block, 0, s, a, m);
+    else hipLaunchKernelGGL(forward_mfma_ws_kernel<0>, grid, block, 0, s, a, m);
     return hipGetLastError();
+}
+
+hipError_t launch_ws12_passes(const ForwardArgs &a, const MultiPass &m, hipStream_t s);   // lasad_forward_mfma_ws12.hip
+
+// Several whole-sequence passes in one launch: twelve waves per workgroup while all workgroups of
+// all passes get a compute unit each, else eight waves (two workgroups per compute unit).
+hipError_t launch_forward_mfma_multi(const ForwardArgs &common, const MultiPass &m, hipStream_t s)
+{
+    if (common.n_segments != 1 || m.n_pass < 1 || m.n_pass > 3) return hipErrorInvalidValue;
+    const int64_t n_wg = (int64_t)common.B * common.Hh * m.n_pass;
+    if (n_wg <= 256) return launch_ws12_passes(common, m, s);
+    return launch_ws8(common, m, s);
 }
 
 }  // namespace lasad

@@ -51,8 +51,14 @@ __device__ inline int l32_of(int tid) { return tid & 31; }
 // work, K and its decayed copies, is done by both); for so few sequences that compute units stay free.
 template <int OUT_BF16, int SPLIT>
 __global__ void __launch_bounds__(SPLIT == 1 ? kWs12Threads : kWs10Threads, 1)
-forward_mfma_ws12_kernel(ForwardArgs a)
+forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
 {
+    if (m.n_pass > 1) {                // one of several independent passes of this launch
+        const int y = blockIdx.y;
+        a.q = m.q[y]; a.k = m.k[y]; a.v = m.v[y]; a.o = m.o[y];
+        a.in = m.in[y]; a.out = m.out[y]; a.start_pos = m.start_pos[y];
+    }
+
     constexpr int SROWS = SPLIT == 1 ? D : D / 2;       // rows (value channels) of the S^T tiles
     constexpr int oV = C * RS, oKh = oV + C * VS, oKl = oKh + C * VS, oSh = oKl + C * VS;
     constexpr int oSl = oSh + SROWS * RS, oO = oSl + SROWS * RS;
@@ -392,22 +398,31 @@ extern "C" int lasad_debug_read_profile_ws12(long long *host_out, int n)
 }
 #endif
 
+hipError_t launch_ws12_passes(const ForwardArgs &a, const MultiPass &m, hipStream_t s);
+
 hipError_t launch_forward_mfma_ws12(const ForwardArgs &a, hipStream_t s)
+{
+    MultiPass one;
+    one.n_pass = 1;
+    return launch_ws12_passes(a, one, s);
+}
+
+hipError_t launch_ws12_passes(const ForwardArgs &a, const MultiPass &m, hipStream_t s)
 {
     if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1) return hipErrorInvalidValue;
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     if (n_seq * a.n_segments > 0x7fffffff) return hipErrorInvalidValue;
-    const int64_t n_wg = n_seq * a.n_segments;
+    const int64_t n_wg = n_seq * a.n_segments * m.n_pass;      // workgroups before any split
     static const int split_env = [] { const char *e = getenv("LASAD_SPLIT"); return e ? atoi(e) : 0; }();
     const bool split = split_env ? split_env == 2 : n_wg * 2 <= 256;   // two workgroups per sequence while compute units stay free
     if (split) {
-        const dim3 grid((unsigned)(n_wg * 2)), block(kWs10Threads);
-        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 2>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 2>), grid, block, 0, s, a);
+        const dim3 grid((unsigned)(n_seq * a.n_segments * 2), (unsigned)m.n_pass), block(kWs10Threads);
+        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 2>), grid, block, 0, s, a, m);
+        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 2>), grid, block, 0, s, a, m);
     } else {
-        const dim3 grid((unsigned)n_wg), block(kWs12Threads);
-        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 1>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 1>), grid, block, 0, s, a);
+        const dim3 grid((unsigned)(n_seq * a.n_segments), (unsigned)m.n_pass), block(kWs12Threads);
+        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 1>), grid, block, 0, s, a, m);
+        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 1>), grid, block, 0, s, a, m);
     }
     return hipGetLastError();
 }

@@ -36,6 +36,16 @@ struct ForwardArgs {
     int n_segments, seg_chunks;
 };
 
+// Up to three independent forward passes in one launch of the wave-specialised kernels
+// (blockIdx.y = pass): the fields below replace those of the common ForwardArgs.
+struct MultiPass {
+    int n_pass;                  // 1: the ForwardArgs as they are
+    int start_pos[3];
+    const void *q[3], *k[3], *v[3];
+    void *o[3];
+    lasad_layout_t in[3], out[3];
+};
+
 struct DecodeArgs {
     const void *q, *k, *v;
     const void *lam;             // vector decay [B, Hh, d], or NULL: per-head gamma (k NULL: key = 1 - lam)
@@ -70,7 +80,7 @@ struct BackwardArgs {
     float q_scale;
     void *workspace;
     // carved out of the workspace by the launcher
-    float *dq32, *dk32, *seq_sums;
+    float *dq32, *dk32, *dv32, *seq_sums;      // dv32: NULL when the dv pass wrote the caller's buffer itself
 };
 
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,
@@ -86,6 +96,8 @@ hipError_t launch_forward_gated_mfma(const ForwardArgs &a, hipStream_t s);
 hipError_t launch_forward_mfma_ws(const ForwardArgs &a, hipStream_t s);
 // twelve wavefronts, doubled LDS buffers, one barrier per chunk: for workgroups that own a compute unit
 hipError_t launch_forward_mfma_ws12(const ForwardArgs &a, hipStream_t s);
+// n_pass whole-sequence passes (same shapes, types, gamma; fp32 or bf16 output alike) in ONE launch
+hipError_t launch_forward_mfma_multi(const ForwardArgs &common, const MultiPass &m, hipStream_t s);
 // the vector-decay kernel with twelve wavefronts per sequence (no fused norm)
 hipError_t launch_forward_gated_ws(const ForwardArgs &a, hipStream_t s);
 // device workspace the MFMA kernel wants for n_seq sequences of n_tokens tokens (0 = none)
