@@ -268,7 +268,8 @@ def bench_backward(args, torch, lasad, wl):
     dur_s = (graph_ms if graph_ms is not None else eager_ms) / steps * 1e-3
     res = {"workload": w.name, "value": w.B * w.N / dur_s, "unit": "tokens/s", "ms_per_step": dur_s * 1e3,
            "steps_timed": steps, "eager_ms_per_step": eager_ms / steps, "workspace_bytes": ws_bytes,
-           "launches_per_step": "3 forward-kernel passes (+ their state passes when segmented) + 2 finishing kernels",
+           "launches_per_step": "one launch of the forward kernel over the 3 passes (dq, dv, dk; decay-gradient sums in its "
+                                "epilogue) + 1 reduction kernel; few long sequences: 3 segmented passes + 2 finishing kernels",
            "roofline": {"bound": "hbm", "kernel": "lasad_backward_chunked (all launches of one call)",
                         "achieved": bytes_bwd / dur_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": bytes_bwd / dur_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_bwd,

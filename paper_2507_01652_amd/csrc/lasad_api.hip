@@ -298,7 +298,7 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
     a.B = B; a.Hh = n_heads; a.d = d; a.grid_w = grid_w;
     a.start_pos = start_pos; a.n_tokens = n_tokens;
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
-    a.workspace = workspace; a.dq32 = a.dk32 = a.dv32 = a.seq_sums = nullptr;
+    a.workspace = workspace; a.dq32 = a.dk32 = a.seq_sums = nullptr;
     const bool use_mfma = io_dtype == LASAD_BF16 && d == 64 && !force_generic();
     hipError_t e = lasad::launch_backward(a, use_mfma, s);
     if (e != hipSuccess) return hip_fail("lasad_backward_chunked launch", e);

@@ -91,17 +91,6 @@ backward_finish_kernel(BackwardArgs a)
             *(float4 *)((float *)a.dq + gi) = dq4;
             *(float4 *)((float *)a.dk + gi) = dk4;
         }
-        if (a.dv32) {                                    // dv came in fp32 as well: store it in the caller's type
-            const float4 dv4 = *(const float4 *)(a.dv32 + w_base + t * w_stride_n + c);
-            if (OUT_BF16) {
-                uint2 w;
-                w.x = (uint32_t)float_to_bf16_bits(dv4.x) | ((uint32_t)float_to_bf16_bits(dv4.y) << 16);
-                w.y = (uint32_t)float_to_bf16_bits(dv4.z) | ((uint32_t)float_to_bf16_bits(dv4.w) << 16);
-                *(uint2 *)((uint16_t *)a.dv + gi) = w;
-            } else {
-                *(float4 *)((float *)a.dv + gi) = dv4;
-            }
-        }
     }
     // fixed-order reduction: lanes of a wave (xor butterflies), then the four waves
 #pragma unroll
@@ -127,6 +116,25 @@ backward_dgamma_kernel(const float *sums, const float *gamma, float *dgamma, int
     if (threadIdx.x == 0) dgamma[h] = acc / gamma[h];     // gamma = 0: the formula does not apply (inf or NaN)
 }
 
+// The same from the sums the forward kernels left: [pass (3)][B][Hh][kDotSlots]; pass 1 (dv) has none.
+__global__ void __launch_bounds__(256)
+backward_dgamma_slots_kernel(const float *sums, const float *gamma, float *dgamma, int B, int Hh)
+{
+    __shared__ float red[4];
+    const int h = blockIdx.x;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < 2 * B * kDotSlots; i += 256) {
+        const int pass = (i / (B * kDotSlots)) * 2, r = i % (B * kDotSlots);
+        const int b = r / kDotSlots, slot = r - b * kDotSlots;
+        acc += sums[(((int64_t)pass * B + b) * Hh + h) * kDotSlots + slot];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) dgamma[h] = ((red[0] + red[1]) + (red[2] + red[3])) / gamma[h];
+}
+
 // start column of the reversed passes: with it, reversed step m >= 1 carries the decay of
 // original token n - m
 int reversed_start(int start_pos, int n, int grid_w, int mode)
@@ -147,15 +155,18 @@ const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
 
 }  // namespace
 
+// partial sums of the decay gradient: one per 64-token block of a sequence (finishing kernel) or
+// kDotSlots per pass and sequence (sums taken inside the forward kernels), whichever is more
 static size_t sums_bytes(int64_t n_seq, int n_tokens)
 {
-    const size_t nblk = (size_t)(n_tokens + kFinTokens - 1) / kFinTokens;
-    return ((size_t)n_seq * nblk * sizeof(float) + 255) / 256 * 256;
+    size_t per_seq = (size_t)(n_tokens + kFinTokens - 1) / kFinTokens;
+    if (per_seq < 3 * kDotSlots) per_seq = 3 * kDotSlots;
+    return ((size_t)n_seq * per_seq * sizeof(float) + 255) / 256 * 256;
 }
 
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype)
 {
-    const size_t grads = 3 * (size_t)n_seq * n_tokens * d * sizeof(float);
+    const size_t grads = 2 * (size_t)n_seq * n_tokens * d * sizeof(float);
     const size_t sums = sums_bytes(n_seq, n_tokens);
     const size_t fwd = (io_dtype == LASAD_BF16 && d == 64) ? forward_mfma_workspace_bytes(n_seq, n_tokens) : 0;
     return grads + sums + fwd;
@@ -168,20 +179,19 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     const int n = b.n_tokens;
     const int elt = b.io_dtype == LASAD_BF16 ? 2 : 4;
     const int gelt = b.grad_dtype == LASAD_BF16 ? 2 : 4;
-    // workspace: dq32, dk32, dv32 ([B][n][Hh][d] fp32), per-sequence sums, forward-kernel workspace
+    // workspace: dq32, dk32 ([B][n][Hh][d] fp32), partial sums, forward-kernel workspace
     char *ws = (char *)b.workspace;
     const size_t one = (size_t)n_seq * n * b.d * sizeof(float);
     b.dq32 = (float *)ws;
     b.dk32 = (float *)(ws + one);
-    b.dv32 = nullptr;
-    b.seq_sums = (float *)(ws + 3 * one);
-    float *fwd_ws = (float *)(ws + 3 * one + sums_bytes(n_seq, n));
+    b.seq_sums = (float *)(ws + 2 * one);
+    float *fwd_ws = (float *)(ws + 2 * one + sums_bytes(n_seq, n));
     const bool has_fwd_ws = use_mfma && forward_mfma_workspace_bytes(n_seq, n) > 0;
     // The three passes are independent: one launch runs them side by side when that alone fills
-    // the chip or when a pass would not be cut into segments anyway.  All passes of a launch
-    // store one type, fp32, so a bf16 dv goes through the workspace like dq and dk.
+    // the chip or when a pass would not be cut into segments anyway.  The passes then store dq, dv
+    // and dk in the caller's type themselves and take the decay-gradient sums from their fp32
+    // output tiles, so nothing but those sums goes through the workspace.
     const bool merged = use_mfma && (n_seq * 3 >= 192 || !has_fwd_ws);
-    if (merged && b.grad_dtype == LASAD_BF16) b.dv32 = (float *)(ws + 2 * one);
 
     lasad_layout_t wl;                                   // layout of dq32 / dk32
     wl.stride_b = (int64_t)n * b.Hh * b.d; wl.stride_n = (int64_t)b.Hh * b.d; wl.stride_h = b.d;
@@ -204,23 +214,30 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     if (merged) {
         MultiPass m;
         m.n_pass = 3;
-        // dq: forward order, (q, k, v) := (d_o, v, k)
-        m.q[0] = b.d_o; m.k[0] = b.v; m.v[0] = b.k; m.o[0] = b.dq32;
-        m.in[0] = b.in; m.out[0] = wl; m.start_pos[0] = b.start_pos;
+        // dq: forward order, (q, k, v) := (d_o, v, k); sum + E_t (q_t . dq_t)
+        m.q[0] = b.d_o; m.k[0] = b.v; m.v[0] = b.k; m.o[0] = b.dq;
+        m.in[0] = b.in; m.out[0] = b.grad; m.start_pos[0] = b.start_pos;
+        m.x[0] = b.q; m.x_sign[0] = 1.f; m.x_rev[0] = 0;
         // dv: reversed order, (q, k, v) := (k, q, d_o)
         m.q[1] = last_token(b.k, b.in, n, elt); m.k[1] = last_token(b.q, b.in, n, elt); m.v[1] = last_token(b.d_o, b.in, n, elt);
-        if (b.dv32) { m.o[1] = (void *)last_token(b.dv32, wl, n, 4); m.out[1] = wl_rev; }
-        else { m.o[1] = (void *)last_token(b.dv, b.grad, n, 4); m.out[1] = grad_rev; }
-        m.in[1] = in_rev; m.start_pos[1] = rev_start;
-        // dk: reversed order, (q, k, v) := (v, d_o, q)
+        m.o[1] = (void *)last_token(b.dv, b.grad, n, gelt);
+        m.in[1] = in_rev; m.out[1] = grad_rev; m.start_pos[1] = rev_start;
+        m.x[1] = nullptr; m.x_sign[1] = 0.f; m.x_rev[1] = 1;
+        // dk: reversed order, (q, k, v) := (v, d_o, q); sum - E_t (k_t . dk_t)
         m.q[2] = last_token(b.v, b.in, n, elt); m.k[2] = last_token(b.d_o, b.in, n, elt); m.v[2] = last_token(b.q, b.in, n, elt);
-        m.o[2] = (void *)last_token(b.dk32, wl, n, 4);
-        m.in[2] = in_rev; m.out[2] = wl_rev; m.start_pos[2] = rev_start;
+        m.o[2] = (void *)last_token(b.dk, b.grad, n, gelt);
+        m.in[2] = in_rev; m.out[2] = grad_rev; m.start_pos[2] = rev_start;
+        m.x[2] = last_token(b.k, b.in, n, elt); m.x_sign[2] = -1.f; m.x_rev[2] = 1;
+        m.x_start_pos = b.start_pos;
+        m.x_sums = b.seq_sums;
         f.q = m.q[0]; f.k = m.k[0]; f.v = m.v[0]; f.o = m.o[0];
-        f.in = b.in; f.out = wl; f.out_dtype = LASAD_F32; f.start_pos = b.start_pos;
+        f.in = m.in[0]; f.out = m.out[0]; f.out_dtype = b.grad_dtype; f.start_pos = b.start_pos;
         f.seg_states = nullptr; f.seg_chunks = (n + 63) / 64;
         e = launch_forward_mfma_multi(f, m, s);
         if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(backward_dgamma_slots_kernel, dim3((unsigned)b.Hh), dim3(256), 0, s,
+                           b.seq_sums, b.gamma, b.dgamma, b.B, b.Hh);
+        return hipGetLastError();
     } else {
         // dq (fp32, workspace): forward order, (q, k, v) := (d_o, v, k)
         f.q = b.d_o; f.k = b.v; f.v = b.k; f.o = b.dq32;

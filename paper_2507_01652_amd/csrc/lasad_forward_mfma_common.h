@@ -5,6 +5,7 @@
 
 #include "lasad_mfma_util.h"
 #include "lasad_internal.h"
+#include "lasad_recurrence.h"
 
 namespace lasad {
 namespace fwd {
@@ -155,6 +156,120 @@ __device__ inline int range_exponent(int begin, int end, int W, int mode)
     return cum_exp(end, W, mode) - cum_exp(begin, W, mode);
 }
 
+
+// Decay-gradient term of a backward pass (see MultiPass).  A lane of an output wave holds, in fp32,
+// the 16 channels col + 8*qd + e (qd, e = 0..3) of one output row; it adds
+// sign * E_t * (x_t . o_t) for that row and those channels, chunk after chunk, and the wave's total
+// goes to its slot of x_sums at the end (butterfly over the lanes: fixed order).
+struct GradDot {
+    const uint16_t *gx;          // x of this sequence, or NULL: no sum asked for
+    int64_t stride_n;
+    float sign, acc;
+    int rev, n_total, start_pos, grid_w, mode, e0;
+    uint2 xr[4];
+
+    __device__ void init(const ForwardArgs &a, const MultiPass &m, int y, int64_t in_base)   // y: pass
+    {
+        gx = nullptr;
+        acc = 0.f;
+        if (m.n_pass > 1 && m.x[y]) {
+            gx = (const uint16_t *)m.x[y] + in_base;
+            stride_n = a.in.stride_n;
+            sign = m.x_sign[y];
+            rev = m.x_rev[y];
+            n_total = a.n_tokens;
+            start_pos = m.x_start_pos;
+            grid_w = a.grid_w;
+            mode = a.mode;
+            e0 = cum_exp(start_pos, grid_w, mode);
+        }
+    }
+    // x of row tok (the caller clamps it to the sequence), channels col + 8*qd .. + 3
+    __device__ void fetch(int tok, int col)
+    {
+        if (!gx) return;
+        const uint16_t *p = gx + (int64_t)tok * stride_n + col;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) xr[qd] = *(const uint2 *)(p + 8 * qd);
+    }
+    __device__ void add(const f32x16 &o, int tok, bool live)
+    {
+        if (!gx) return;
+        float d = 0.f;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            d = fmaf(__uint_as_float(xr[qd].x << 16), o[4 * qd + 0], d);
+            d = fmaf(__uint_as_float(xr[qd].x & 0xffff0000u), o[4 * qd + 1], d);
+            d = fmaf(__uint_as_float(xr[qd].y << 16), o[4 * qd + 2], d);
+            d = fmaf(__uint_as_float(xr[qd].y & 0xffff0000u), o[4 * qd + 3], d);
+        }
+        const int t = rev ? n_total - 1 - tok : tok;
+        const int e = cum_exp(start_pos + t + 1, grid_w, mode) - e0;
+        acc = fmaf(live ? sign * (float)e : 0.f, d, acc);
+    }
+    // slot (and zero_slot, if >= 0) of this sequence's entries of x_sums
+    __device__ void finish(const MultiPass &m, int y, int64_t n_seq, int bh, int slot, int zero_slot, int lane)
+    {
+        if (!gx) return;
+        float v = acc;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+        if (lane == 0) {
+            float *dst = m.x_sums + ((int64_t)y * n_seq + bh) * kDotSlots;
+            dst[slot] = v;
+            if (zero_slot >= 0) dst[zero_slot] = 0.f;
+        }
+    }
+};
+
+// The fp32 recurrence over a whole sequence (decay outside the range of the factorised form) with
+// the same sum, taken from the fp32 output values as they are produced.  Run by the first
+// kRecThreads threads of the workgroup; smem as recurrence_sequence wants it.
+struct RecDotHook {
+    const uint16_t *gx;
+    int64_t stride_n;
+    int rev, n_total, start_pos, grid_w, mode, e0;
+    float *acc;
+    __device__ void operator()(int tok, int c, float v) const
+    {
+        const float x = bf16_bits_to_float(gx[(int64_t)tok * stride_n + c]);
+        const int t = rev ? n_total - 1 - tok : tok;
+        const int e = cum_exp(start_pos + t + 1, grid_w, mode) - e0;
+        *acc = fmaf((float)e * x, v, *acc);
+    }
+};
+
+template <int OUT_BF16>
+__device__ inline void recurrence_with_dot(const ForwardArgs &a, const MultiPass &m, int y, int bh, float *smem)
+{
+    if (!(m.n_pass > 1 && m.x[y])) {
+        recurrence_sequence<D, 1, OUT_BF16>(a, bh, smem);
+        return;
+    }
+    const int b = bh / a.Hh, h = bh - b * a.Hh;
+    float acc = 0.f;
+    RecDotHook hook;
+    hook.gx = (const uint16_t *)m.x[y] + (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
+    hook.stride_n = a.in.stride_n;
+    hook.rev = m.x_rev[y]; hook.n_total = a.n_tokens; hook.start_pos = m.x_start_pos;
+    hook.grid_w = a.grid_w; hook.mode = a.mode;
+    hook.e0 = cum_exp(m.x_start_pos, a.grid_w, a.mode);
+    hook.acc = &acc;
+    recurrence_sequence<D, 1, OUT_BF16>(a, bh, smem, hook);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    __syncthreads();                   // the recurrence's last reads of its LDS block
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x < kDotSlots) {     // the total in slot 0, the other slots zero
+        float v = 0.f;
+        if (threadIdx.x == 0) {
+            for (int w = 0; w < kRecThreads / 64; ++w) v += smem[w];
+            v *= m.x_sign[y];
+        }
+        m.x_sums[((int64_t)y * a.B * a.Hh + bh) * kDotSlots + threadIdx.x] = v;
+    }
+}
 
 }  // namespace fwd
 }  // namespace lasad

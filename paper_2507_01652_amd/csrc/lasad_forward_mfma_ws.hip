@@ -35,14 +35,22 @@ __device__ long long g_prof_ws[24 * 64];
 #define WPROF(slot) do { } while (0)
 #endif
 
-template <int OUT_BF16>
-__global__ void __launch_bounds__(kWsThreads, 1)
+// DOT: the variant for passes of the backward that also take the decay-gradient sums (MultiPass::x)
+template <int OUT_BF16, int DOT>
+__global__ void __launch_bounds__(kWsThreads, 4)
 forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
 {
-    if (m.n_pass > 1) {                // one of several independent passes of this launch
-        const int y = blockIdx.y;
-        a.q = m.q[y]; a.k = m.k[y]; a.v = m.v[y]; a.o = m.o[y];
-        a.in = m.in[y]; a.out = m.out[y]; a.start_pos = m.start_pos[y];
+    // Several independent passes in one launch: workgroups come in groups of 8 sequences x n_pass
+    // passes, a sequence's passes 8 workgroup ids apart, so that they run at about the same time on
+    // the same XCD (ids go round the 8 XCDs) and share what they both read through its L2.
+    int pass = 0, wg = blockIdx.x;
+    if (m.n_pass > 1) {
+        const int grp = blockIdx.x / (8 * m.n_pass), r = blockIdx.x - grp * (8 * m.n_pass);
+        pass = r >> 3;
+        wg = grp * 8 + (r & 7);
+        if (wg >= a.B * a.Hh) return;  // (n_segments is 1 here; the last group may be partly empty)
+        a.q = m.q[pass]; a.k = m.k[pass]; a.v = m.v[pass]; a.o = m.o[pass];
+        a.in = m.in[pass]; a.out = m.out[pass]; a.start_pos = m.start_pos[pass];
     }
 
     constexpr int kLdsHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;
@@ -58,13 +66,14 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
     uint16_t *sO = sSl + D * RS;       // bf16 output tile [token][dv]
 
     const int G = a.n_segments;
-    const int bh = blockIdx.x / G, seg = blockIdx.x - bh * G;
+    const int bh = wg / G, seg = wg - bh * G;
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const float lg = log2f(a.gamma[h]);
     const int tid = threadIdx.x;
     if (!(lg * (float)C > -64.0f)) {   // gamma <= 0.5: separable factors could overflow -> fp32 recurrence
         if (tid >= kRecThreads || seg != 0) return;       // (finished waves no longer count at barriers)
-        recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);     // whole sequence
+        if (DOT) recurrence_with_dot<OUT_BF16>(a, m, pass, bh, (float *)smem);
+        else recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);     // whole sequence
         return;
     }
 
@@ -182,6 +191,8 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
     };
     prefetch_q(0);
+    GradDot gd;
+    if (DOT) gd.init(a, m, pass, in_base);
 
     // causal mask of a diagonal 32 x 32 score block: key 8*qd + 4*g + e is at or before query l32
     const int cq = l32 - 4 * g;
@@ -225,6 +236,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             }
         }
         WPROF(2);
+        if (DOT) gd.fetch(min(t0 + i_row, n - 1), wc * 32 + 4 * g);     // (here the Q fragments' registers are free)
         Frag fv[4];
         load_v_frags(fv, sV, wc, lane);
 
@@ -271,6 +283,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(tabC[i_row]);
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[r] *= osc;
+        if (DOT) gd.add(accO, t0 + i_row, i_row < nt);
         if (OUT_BF16) {                                   // via LDS for 16-byte coalesced stores
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -300,6 +313,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             }
         }
     }
+    if (DOT) gd.finish(m, pass, (int64_t)a.B * a.Hh, bh, w4, w4 + 4, lane);
 }
 
 }  // namespace
@@ -325,9 +339,14 @@ static hipError_t launch_ws8(const ForwardArgs &a, const MultiPass &m, hipStream
     if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1) return hipErrorInvalidValue;
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     if (n_seq * a.n_segments > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)(n_seq * a.n_segments), (unsigned)m.n_pass), block(kWsThreads);
-    if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL(forward_mfma_ws_kernel<1>, grid, block, 0, s, a, m);
-    else hipLaunchKernelGGL(forward_mfma_ws_kernel<0>, grid, block, 0, s, a, m);
+    if (m.n_pass > 1 && a.n_segments != 1) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(m.n_pass > 1 ? (n_seq + 7) / 8 * 8 * m.n_pass : n_seq * a.n_segments)), block(kWsThreads);
+    const bool dot = m.n_pass > 1 && (m.x[0] || m.x[1] || m.x[2]);
+    const bool out16 = a.out_dtype == LASAD_BF16;
+    if (dot && out16) hipLaunchKernelGGL((forward_mfma_ws_kernel<1, 1>), grid, block, 0, s, a, m);
+    else if (dot) hipLaunchKernelGGL((forward_mfma_ws_kernel<0, 1>), grid, block, 0, s, a, m);
+    else if (out16) hipLaunchKernelGGL((forward_mfma_ws_kernel<1, 0>), grid, block, 0, s, a, m);
+    else hipLaunchKernelGGL((forward_mfma_ws_kernel<0, 0>), grid, block, 0, s, a, m);
     return hipGetLastError();
 }
 

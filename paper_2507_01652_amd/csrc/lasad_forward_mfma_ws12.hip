@@ -49,7 +49,8 @@ __device__ inline int l32_of(int tid) { return tid & 31; }
 // SPLIT = 1: one workgroup (twelve waves) per sequence or segment.  SPLIT = 2: two workgroups, one per
 // value-channel half, each with four output waves, two state waves and four loader waves (the loader
 // work, K and its decayed copies, is done by both); for so few sequences that compute units stay free.
-template <int OUT_BF16, int SPLIT>
+// DOT: the variant for passes of the backward that also take the decay-gradient sums (MultiPass::x)
+template <int OUT_BF16, int SPLIT, int DOT>
 __global__ void __launch_bounds__(SPLIT == 1 ? kWs12Threads : kWs10Threads, 1)
 forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
 {
@@ -85,7 +86,8 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     const int tid = threadIdx.x;
     if (!(lg * (float)C > -64.0f)) {   // gamma <= 0.5: separable factors could overflow -> fp32 recurrence
         if (tid >= kRecThreads || seg != 0 || half != 0) return;   // (finished waves no longer count at barriers)
-        recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);     // whole sequence
+        if (DOT) recurrence_with_dot<OUT_BF16>(a, m, blockIdx.y, bh, (float *)smem);
+        else recurrence_sequence<D, 1, OUT_BF16>(a, bh, (float *)smem);     // whole sequence
         return;
     }
 
@@ -252,6 +254,8 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
     };
     prefetch_q(0);
+    GradDot gd;
+    if (DOT) gd.init(a, m, blockIdx.y, in_base);
 
     // causal mask of a diagonal 32 x 32 score block: key 8*qd + 4*g + e is at or before query l32
     const int cq = l32 - 4 * g;
@@ -270,6 +274,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
         WPROF(1);
         const int i_row = qa * 32 + l32;
+        if (DOT) gd.fetch(min(t0 + i_row, n - 1), wc * 32 + 4 * g);
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
         // decay + causal mask on the fp32 scores of key block jb, split to bf16 hi + lo
@@ -362,6 +367,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(bC[i_row]);
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[r] *= osc;
+        if (DOT) gd.add(accO, t0 + i_row, i_row < nt);
         if (SPLIT == 2) {                                 // fp32 partial tile [token][32 channels]; the loader waves add the two
             float *bP = sPart(p, part);
 #pragma unroll
@@ -387,6 +393,10 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         __syncthreads();
         WPROF(5);
     }
+    // slots: SPLIT 1 waves 0-3 (4-7 zero); SPLIT 2 channel half * 4 + wave
+    if (!DOT) return;
+    if (SPLIT == 1) gd.finish(m, blockIdx.y, (int64_t)a.B * a.Hh, bh, wave, wave + 4, lane);
+    else gd.finish(m, blockIdx.y, (int64_t)a.B * a.Hh, bh, half * 4 + wave, -1, lane);
 }
 
 }  // namespace
@@ -415,15 +425,19 @@ hipError_t launch_ws12_passes(const ForwardArgs &a, const MultiPass &m, hipStrea
     const int64_t n_wg = n_seq * a.n_segments * m.n_pass;      // workgroups before any split
     static const int split_env = [] { const char *e = getenv("LASAD_SPLIT"); return e ? atoi(e) : 0; }();
     const bool split = split_env ? split_env == 2 : n_wg * 2 <= 256;   // two workgroups per sequence while compute units stay free
+    const bool dot = m.n_pass > 1 && (m.x[0] || m.x[1] || m.x[2]);
+    const bool out16 = a.out_dtype == LASAD_BF16;
+    const dim3 grid((unsigned)(n_seq * a.n_segments * (split ? 2 : 1)), (unsigned)m.n_pass);
+    const dim3 block(split ? kWs10Threads : kWs12Threads);
+#define LASAD_WS12_LAUNCH(O, S, X) hipLaunchKernelGGL((forward_mfma_ws12_kernel<O, S, X>), grid, block, 0, s, a, m)
     if (split) {
-        const dim3 grid((unsigned)(n_seq * a.n_segments * 2), (unsigned)m.n_pass), block(kWs10Threads);
-        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 2>), grid, block, 0, s, a, m);
-        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 2>), grid, block, 0, s, a, m);
+        if (dot) { if (out16) LASAD_WS12_LAUNCH(1, 2, 1); else LASAD_WS12_LAUNCH(0, 2, 1); }
+        else { if (out16) LASAD_WS12_LAUNCH(1, 2, 0); else LASAD_WS12_LAUNCH(0, 2, 0); }
     } else {
-        const dim3 grid((unsigned)(n_seq * a.n_segments), (unsigned)m.n_pass), block(kWs12Threads);
-        if (a.out_dtype == LASAD_BF16) hipLaunchKernelGGL((forward_mfma_ws12_kernel<1, 1>), grid, block, 0, s, a, m);
-        else hipLaunchKernelGGL((forward_mfma_ws12_kernel<0, 1>), grid, block, 0, s, a, m);
+        if (dot) { if (out16) LASAD_WS12_LAUNCH(1, 1, 1); else LASAD_WS12_LAUNCH(0, 1, 1); }
+        else { if (out16) LASAD_WS12_LAUNCH(1, 1, 0); else LASAD_WS12_LAUNCH(0, 1, 0); }
     }
+#undef LASAD_WS12_LAUNCH
     return hipGetLastError();
 }
 

@@ -38,12 +38,26 @@ struct ForwardArgs {
 
 // Up to three independent forward passes in one launch of the wave-specialised kernels
 // (blockIdx.y = pass): the fields below replace those of the common ForwardArgs.
+// Several independent passes of the scalar-decay forward kernels in one launch (blockIdx.y = pass):
+// per-pass operands, layouts and start column; everything else is shared (ForwardArgs).
+// A pass may also accumulate the decay-gradient term of the backward pass,
+//   sign * sum_t E_t (x_t . o_t),   E_t = non-boundary tokens among the first t + 1 of the call,
+// from its fp32 output tiles: x is a fourth bf16 tensor laid out like the pass's inputs, and with
+// x_rev the pass runs the sequence backwards (pass token m is call token n_tokens - 1 - m).  Each
+// workgroup leaves its part of the sum in x_sums[((pass * n_seq) + sequence) * kDotSlots + slot];
+// slots it does not use are written as zero.
+constexpr int kDotSlots = 8;
 struct MultiPass {
-    int n_pass;                  // 1: the ForwardArgs as they are
+    int n_pass;                  // 1: the ForwardArgs as they are (no other member is read)
     int start_pos[3];
     const void *q[3], *k[3], *v[3];
     void *o[3];
     lasad_layout_t in[3], out[3];
+    const void *x[3];            // NULL: no sum for this pass
+    float x_sign[3];
+    int x_rev[3];
+    int x_start_pos;             // start column of the call (not of the reversed passes)
+    float *x_sums;
 };
 
 struct DecodeArgs {
@@ -80,7 +94,7 @@ struct BackwardArgs {
     float q_scale;
     void *workspace;
     // carved out of the workspace by the launcher
-    float *dq32, *dk32, *dv32, *seq_sums;      // dv32: NULL when the dv pass wrote the caller's buffer itself
+    float *dq32, *dk32, *seq_sums;
 };
 
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,

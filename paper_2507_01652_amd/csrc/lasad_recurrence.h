@@ -41,8 +41,13 @@ __device__ inline void rec_store(void *p, int64_t idx, float x)
     else ((float *)p)[idx] = x;
 }
 
-template <int D, int IN_BF16, int OUT_BF16, int GATED = 0>
-__device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem)
+// hook(token, channel, value) sees every output element (fp32, before it is stored) in the thread that stores it
+struct RecNoHook {
+    __device__ void operator()(int, int, float) const {}
+};
+
+template <int D, int IN_BF16, int OUT_BF16, int GATED = 0, class Hook = RecNoHook>
+__device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem, Hook hook = Hook())
 {
     constexpr int G = kRecThreads / D;   // row groups
     constexpr int R = D / G;             // rows of S per thread
@@ -111,6 +116,7 @@ __device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem)
 #pragma unroll
             for (int gg = 0; gg < G; ++gg) acc += red[tt][gg][c];
             rec_store<OUT_BF16>(a.o, out_base + (int64_t)(t0 + tt) * a.out.stride_n + c, a.q_scale * acc);
+            hook(t0 + tt, c, a.q_scale * acc);
         }
         // the next round's staging writes sq/sk/sv (not red); its first barrier
         // orders those writes against this round's reads of red.

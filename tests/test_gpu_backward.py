@@ -152,6 +152,33 @@ def test_backward_dgamma_full_batch(lasad, oracle):
     _check(lasad, oracle, w, grad_bf16=True)
 
 
+@pytest.mark.parametrize("B,Hh,H,W", [(4, 12, 16, 16), (8, 12, 16, 16), (11, 8, 9, 15), (1, 2, 40, 16)],
+                         ids=["48seq_twelve_wave", "96seq_eight_wave", "88seq_tail", "2seq_segmented"])
+def test_backward_launch_shapes(lasad, oracle, B, Hh, H, W):
+    """Every launch shape of the three passes, all gradients against the oracle on the full batch: one merged
+    launch of the twelve-wave kernel (whole and split sequences: the smaller cases above), of the eight-wave
+    kernel (more than 85 sequences), and three separate segmented passes (few long sequences)."""
+    w = wl.Workload("bwd_launch", B, Hh, 64, H, W, "bf16", 0.85, 0.999, seed=31 * B + Hh)
+    _check(lasad, oracle, w, grad_bf16=True)
+    _check(lasad, oracle, w, grad_bf16=False, mode=1, q_scale=0.25)
+
+
+def test_backward_small_gamma_bf16_grads(lasad, oracle):
+    """As test_backward_small_gamma_heads with bf16 gradients (the decay-gradient sums of the fp32 route then
+    are taken from its fp32 values) and enough sequences for the eight-wave launch."""
+    w = wl.Workload("bwd_small_gamma16", 30, 3, 64, 5, 16, "bf16", 0.8, 0.99, seed=6)
+    q, k, v, gam = wl.prefill_inputs(w)
+    gam = np.array([0.3, 0.95, 0.05], dtype=np.float32)
+    g = _d_o(w)
+    dq, dk, dv, dgam = _gpu_backward(lasad, w, q, k, v, g, gam)
+    lam, _ = oracle.decay_factors(gam, w.grid_h, w.grid_w, 0, w.N, 0)
+    rq, rk, rv, rlam = oracle.backward(q, k, v, lam, g)
+    rgam = oracle.dgamma(rlam, w.grid_w, 0, 0)
+    for nm, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        assert parity_err(got.float().cpu().numpy(), ref, True) <= TOL["bf16"], nm
+    _check_dgamma(dgam, rgam, w, q, k, rq, rk, gam, 0, 0, oracle)
+
+
 def test_backward_deterministic(lasad):
     import torch
     w = wl.scaled(wl.BASE_PREFILL, B=2)
