@@ -24,10 +24,17 @@
 //
 //   dL/dgamma_h = (1 / gamma_h) sum_b sum_i E_i (q_i . dq_i - k_i . dk_i).
 //
-// dq and dk are produced in fp32 into the workspace; a finishing kernel (one workgroup per 64
-// tokens of a sequence) forms its part of the sum above (fp32, fixed order) and stores dq, dk in
-// the caller's type and layout, and a last small kernel (one wave per head) adds the partial
-// sums in a fixed order (no atomics).
+// bf16 inputs, head dim 64, enough sequences (or sequences too short to be cut into segments):
+// ONE launch of the wave-specialised forward kernel runs the three passes side by side.  Each
+// pass stores its gradient in the caller's type and layout, and the dq and dk passes add up
+// E_i (q_i . dq_i) and -E_i (k_i . dk_i) from their fp32 output tiles before those are rounded
+// (a per-wave partial sum per sequence, fixed order); a small kernel (one workgroup per head)
+// adds the partial sums in a fixed order (no atomics) and divides by gamma.
+//
+// Otherwise (fp32 inputs, other head dims, few long sequences): three separate passes; dq and dk
+// are produced in fp32 into the workspace, a finishing kernel (one workgroup per 64 tokens of a
+// sequence) forms its part of the sum above (fp32, fixed order) and stores dq, dk in the caller's
+// type and layout, and a last small kernel (one wave per head) adds the partial sums.
 #include "lasad_internal.h"
 
 namespace lasad {

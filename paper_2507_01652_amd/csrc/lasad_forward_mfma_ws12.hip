@@ -79,7 +79,16 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     auto sPart = [&](int p, int part) { return (float *)(smem + p * kSetHalfs + oO) + part * C * PS; };
 
     const int G = a.n_segments;
-    const int blk = blockIdx.x / SPLIT, half = blockIdx.x - blk * SPLIT;     // half: value-channel half if SPLIT == 2
+    // SPLIT 2: the two workgroups of a sequence (half = value-channel half) are 8 workgroup ids apart,
+    // so they start together on the same XCD (ids go round the 8 XCDs) and what both read, Q and
+    // K, comes from memory once
+    int blk = blockIdx.x, half = 0;
+    if (SPLIT == 2) {
+        const int grp = blockIdx.x >> 4, r = blockIdx.x & 15;
+        half = r >> 3;
+        blk = grp * 8 + (r & 7);
+        if (blk >= a.B * a.Hh * G) return;                // (the last group of 16 may be partly empty)
+    }
     const int bh = blk / G, seg = blk - bh * G;
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const float lg = log2f(a.gamma[h]);
@@ -427,7 +436,8 @@ hipError_t launch_ws12_passes(const ForwardArgs &a, const MultiPass &m, hipStrea
     const bool split = split_env ? split_env == 2 : n_wg * 2 <= 256;   // two workgroups per sequence while compute units stay free
     const bool dot = m.n_pass > 1 && (m.x[0] || m.x[1] || m.x[2]);
     const bool out16 = a.out_dtype == LASAD_BF16;
-    const dim3 grid((unsigned)(n_seq * a.n_segments * (split ? 2 : 1)), (unsigned)m.n_pass);
+    const int64_t n_blk = n_seq * a.n_segments;
+    const dim3 grid((unsigned)(split ? (n_blk + 7) / 8 * 16 : n_blk), (unsigned)m.n_pass);
     const dim3 block(split ? kWs10Threads : kWs12Threads);
 #define LASAD_WS12_LAUNCH(O, S, X) hipLaunchKernelGGL((forward_mfma_ws12_kernel<O, S, X>), grid, block, 0, s, a, m)
     if (split) {
