@@ -91,9 +91,12 @@ forward_gated_ws_kernel(ForwardArgs a)
         const int4 f = *(const int4 *)sTrip[par];
         return (f.x | f.y | f.z | f.w) != 0;
     };
+    // (the out-of-line routine takes the arguments by reference: it gets them where the launch put
+    // them, in the kernel-argument segment -- a reference to the by-value parameter would make
+    // every thread of every launch copy the struct to its stack first)
     auto fallback = [&]() {
         if (tid < scan::kThreads)
-            redo_sequence<OUT_BF16, OWNKEY>(a, bh, (float *)smem);
+            redo_sequence<OUT_BF16, OWNKEY>(*(const ForwardArgs *)__builtin_amdgcn_kernarg_segment_ptr(), bh, (float *)smem);
     };
 
     if (group == 2) {
