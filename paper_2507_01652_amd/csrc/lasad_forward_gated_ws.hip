@@ -11,8 +11,12 @@
 // A chunk whose decay leaves the range of the factorisation is seen by the loader waves one
 // chunk ahead; the barrier carries the flag to every wave and the workgroup redoes its sequence
 // with the token-serial fp32 routine (waves 0-3; the others leave).
-// FUSED = 1 applies SiLU to q and the sigmoid to the gate while the chunk is prepared.  (The fused
-// output norm stays with the four-wave kernel.)
+// FUSED = 1 applies SiLU to q and the sigmoid to the gate while the chunk is prepared.
+// NORM = 1 divides every output token by the root mean square of its 64 channels (times a weight):
+// the two output waves that hold a token's channel halves leave their sums of squares in LDS
+// before the chunk's barrier and keep the fp32 tile in registers; after the barrier, before they
+// start the next chunk, they scale, round and write the tile, and the loader waves store it one
+// chunk later than without the norm (one more barrier at the end of the sequence for the last tile).
 #include "lasad_forward_gated_common.h"
 #include "lasad_scan.h"
 
@@ -33,7 +37,7 @@ __device__ long long g_prof_gws[24 * 64];
 #endif
 constexpr int kSetHalfs = 2 * C * RS + 2 * C * KS + C * TS + 2 * D * RS + C * RS;   // one set of tiles
 
-template <int OUT_BF16, int OWNKEY, int FUSED>
+template <int OUT_BF16, int OWNKEY, int FUSED, int NORM>
 __global__ void __launch_bounds__(kWsThreads, 1)
 forward_gated_ws_kernel(ForwardArgs a)
 {
@@ -42,6 +46,7 @@ forward_gated_ws_kernel(ForwardArgs a)
     __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kSetHalfs];
     __shared__ __attribute__((aligned(16))) float sTot[2][D];  // A_end per key channel, by chunk parity
     __shared__ __attribute__((aligned(16))) int sTrip[2][4];   // range flag of each loader wave, by barrier parity
+    __shared__ float sSS[NORM ? 2 : 1][2][NORM ? C : 1];       // sums of squares: chunk parity, channel half, token
     auto sQh = [&](int p) { return smem + p * kSetHalfs; };
     auto sQl = [&](int p) { return smem + p * kSetHalfs + C * RS; };
     auto sKh = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS; };
@@ -135,12 +140,18 @@ forward_gated_ws_kernel(ForwardArgs a)
                 stg.write(sQh(p), sQl(p), sKh(p), sKl(p), sV(p), l32, pcol);
             }
             // the output tile last: the wait for the next loads must not include these stores
-            if (OUT_BF16 && chunk > 0) store_tile(chunk - 1);
+            if (OUT_BF16 && chunk > NORM) store_tile(chunk - 1 - NORM);
             GPROF(4);
             if (barrier_flag(stg.trip)) return;
             GPROF(5);
         }
-        if (OUT_BF16) store_tile(n_chunks - 1);
+        if (OUT_BF16) {
+            if (NORM) {
+                if (n_chunks > 1) store_tile(n_chunks - 2);
+                __syncthreads();                          // the output waves have written the last normalised tile
+            }
+            store_tile(n_chunks - 1);
+        }
         return;
     }
 
@@ -214,15 +225,48 @@ forward_gated_ws_kernel(ForwardArgs a)
 
     // ========================================= output waves =========================================
     const int cq = l32 - 4 * g;        // key 8*qd + 4*g + e of a diagonal block is at or before query l32 iff 8*qd + e <= cq
+    // the output tile of a chunk: a lane owns four consecutive value channels of its query per quad
+    auto put_tile = [&](const f32x16 &acc, int chunk) {
+        const int i_row = (wa ^ (chunk & 1)) * 32 + l32;
+        if (OUT_BF16) {                                   // via LDS; the loader waves store it during a later chunk
+            uint16_t *bO = sO(chunk & 1);
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                uint2 w2;
+                w2.x = pack2(acc[4 * qd + 0], acc[4 * qd + 1]);
+                w2.y = pack2(acc[4 * qd + 2], acc[4 * qd + 3]);
+                *(uint2 *)&bO[i_row * RS + wc * 32 + 8 * qd + 4 * g] = w2;
+            }
+        } else if (chunk * C + i_row < n) {
+            float *go = (float *)a.o + o_base + (int64_t)(chunk * C + i_row) * a.out.stride_n + wc * 32 + 4 * g;
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                *(float4 *)(go + 8 * qd) = make_float4(acc[4 * qd + 0], acc[4 * qd + 1], acc[4 * qd + 2], acc[4 * qd + 3]);
+        }
+    };
+    f32x16 accP;                       // NORM: the fp32 tile of the chunk before, not yet normalised
+    auto finish_tile = [&](int chunk) {                   // after that chunk's barrier: both sums of squares are there
+        const int p = chunk & 1, i_row = (wa ^ p) * 32 + l32;
+        const float rstd = __builtin_amdgcn_rsqf((sSS[p][0][i_row] + sSS[p][1][i_row]) * (1.0f / D) + a.norm_eps);
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            float4 w4 = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (a.norm_w) w4 = *(const float4 *)(a.norm_w + h * D + wc * 32 + 8 * qd + 4 * g);
+            accP[4 * qd + 0] *= rstd * w4.x; accP[4 * qd + 1] *= rstd * w4.y;
+            accP[4 * qd + 2] *= rstd * w4.z; accP[4 * qd + 3] *= rstd * w4.w;
+        }
+        put_tile(accP, chunk);
+    };
     if (barrier_flag(false)) { fallback(); return; }
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
+        (void)t0; (void)nt;
+        if (NORM && chunk > 0) finish_tile(chunk - 1);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
         const int p = chunk & 1;
         const uint16_t *bQh = sQh(p), *bQl = sQl(p), *bKh = sKh(p), *bKl = sKl(p), *bV = sV(p);
         const uint16_t *bSh = sSh(p), *bSl = sSl(p);
-        uint16_t *bO = sO(p);
         const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
         Frag fqh[4], fql[4];
 #pragma unroll
@@ -298,25 +342,23 @@ forward_gated_ws_kernel(ForwardArgs a)
         accO = intra(accO, acc0, 0, qa == 0);
         if (qa == 1) accO = intra(accO, acc1, 1, true);
 
-        // ---- the output tile: a lane owns four consecutive value channels of its query per quad ----
-        if (OUT_BF16) {                                   // via LDS; the loader waves store it during the next chunk
+        if (NORM) {                                       // sums of squares now, the tile after the barrier
+            float ss = 0.f;
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                uint2 w2;
-                w2.x = pack2(accO[4 * qd + 0], accO[4 * qd + 1]);
-                w2.y = pack2(accO[4 * qd + 2], accO[4 * qd + 3]);
-                *(uint2 *)&bO[i_row * RS + wc * 32 + 8 * qd + 4 * g] = w2;
-            }
-        } else if (i_row < nt) {
-            float *go = (float *)a.o + o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd)
-                *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
-                                                       accO[4 * qd + 2], accO[4 * qd + 3]);
+            for (int r = 0; r < 16; ++r) ss = fmaf(accO[r], accO[r], ss);
+            ss += __shfl_xor(ss, 32);
+            if (g == 0) sSS[p][wc][i_row] = ss;
+            accP = accO;
+        } else {
+            put_tile(accO, chunk);
         }
         GPROF(2);
         if (barrier_flag(false)) { fallback(); return; }
         GPROF(3);
+    }
+    if (NORM) {
+        finish_tile(n_chunks - 1);
+        if (OUT_BF16) __syncthreads();                    // (the loader waves store the tile after it)
     }
 }
 
@@ -331,22 +373,24 @@ extern "C" int lasad_debug_read_profile_gws(long long *host_out, int n)
 
 hipError_t launch_forward_gated_ws(const ForwardArgs &a, hipStream_t s)
 {
-    if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1 || !a.lam || a.norm) return hipErrorInvalidValue;
+    if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1 || !a.lam) return hipErrorInvalidValue;
+    if (a.fused_act && a.k) return hipErrorInvalidValue;
     const int64_t n_seq = (int64_t)a.B * a.Hh;
     if (n_seq > 0x7fffffff) return hipErrorInvalidValue;
     const dim3 grid((unsigned)n_seq), block(kWsThreads);
     const bool out16 = a.out_dtype == LASAD_BF16;
-    if (a.fused_act) {
-        if (a.k) return hipErrorInvalidValue;
-        if (out16) hipLaunchKernelGGL((forward_gated_ws_kernel<1, 0, 1>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_gated_ws_kernel<0, 0, 1>), grid, block, 0, s, a);
-    } else if (a.k) {
-        if (out16) hipLaunchKernelGGL((forward_gated_ws_kernel<1, 1, 0>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_gated_ws_kernel<0, 1, 0>), grid, block, 0, s, a);
+#define LASAD_GWS_LAUNCH(K, F, N) do { \
+        if (out16) hipLaunchKernelGGL((forward_gated_ws_kernel<1, K, F, N>), grid, block, 0, s, a); \
+        else hipLaunchKernelGGL((forward_gated_ws_kernel<0, K, F, N>), grid, block, 0, s, a); } while (0)
+    if (a.norm) {                      // (the norm comes with the fused activations only: the layer of Algorithm 1)
+        if (!a.fused_act) return hipErrorInvalidValue;
+        LASAD_GWS_LAUNCH(0, 1, 1);
     } else {
-        if (out16) hipLaunchKernelGGL((forward_gated_ws_kernel<1, 0, 0>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((forward_gated_ws_kernel<0, 0, 0>), grid, block, 0, s, a);
+        if (a.fused_act) LASAD_GWS_LAUNCH(0, 1, 0);
+        else if (a.k) LASAD_GWS_LAUNCH(1, 0, 0);
+        else LASAD_GWS_LAUNCH(0, 0, 0);
     }
+#undef LASAD_GWS_LAUNCH
     return hipGetLastError();
 }
 

@@ -29,7 +29,7 @@ def _pre_inputs(B, n, Hh, d, dtype, seed):
 
 
 @pytest.mark.parametrize("dtype,H,W,B,Hh", [("bf16", 16, 16, 2, 3), ("bf16", 9, 17, 1, 2), ("f32", 7, 9, 2, 2),
-                                             ("bf16", 3, 5, 70, 4), ("bf16", 1, 1, 1, 1)])
+                                             ("bf16", 3, 5, 70, 4), ("bf16", 9, 17, 65, 4), ("bf16", 1, 1, 1, 1)])
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("norm", ["weighted", "plain", "off"])
 def test_forward_layer(lasad, oracle, dtype, H, W, B, Hh, mode, norm):
