@@ -199,3 +199,50 @@ def test_forward_gated_deterministic(lasad):
     o2 = lasad.lasad_forward_gated(tq, tl, tv, w.grid_h, w.grid_w)
     torch.cuda.synchronize()
     assert torch.equal(o1, o2)
+
+
+GATED_VARIANT_SCRIPT = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + '/tests')
+from paper_2507_01652_amd import binding as lasad, workloads as wl
+from oracle import lasad_oracle as oracle
+from helpers import rel_err
+worst = 0.0
+for B, Hh, H, W in ((2, 3, 13, 17), (1, 2, 1, 50)):
+    rng = np.random.default_rng(5 + B)
+    shape = (B, H * W, Hh, 64)
+    q = wl.store_round(rng.standard_normal(shape, dtype=np.float32), 'bf16')
+    z = wl.store_round(rng.standard_normal(shape, dtype=np.float32) + np.float32(2.0), 'bf16')
+    v = wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(8.0), 'bf16')
+    lam = wl.store_round(oracle.sigmoid(z).astype(np.float32), 'bf16')
+    wgt = rng.uniform(0.5, 1.5, size=(Hh, 64)).astype(np.float32)
+    dev = lambda x: lasad.to_device(x, 'bf16')
+    # the vector-decay forward (key tied to the gate) and the fused layer with its norm
+    ref, s_ref = oracle.gated_recurrent(q, lam, v, W, want_state=True)
+    s1 = torch.empty((B, Hh, 64, 64), dtype=torch.float32, device='cuda')
+    o = lasad.lasad_forward_gated(dev(q), dev(lam), dev(v), H, W, state_out=s1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    worst = max(worst, rel_err(o.cpu().numpy(), ref), rel_err(s1.cpu().numpy(), s_ref))
+    ref = oracle.gated_layer(q, z, v, W, norm_weight=wgt, eps=1e-5)
+    for od in (torch.float32, torch.bfloat16):
+        o = lasad.lasad_forward_layer(dev(q), dev(z), dev(v), H, W, norm_weight=torch.from_numpy(wgt).cuda(), norm_eps=1e-5,
+                                      out_dtype=od)
+        torch.cuda.synchronize()
+        worst = max(worst, rel_err(o.float().cpu().numpy(), ref))
+print('WORST', worst)
+assert worst <= 2e-2
+"""
+
+
+@pytest.mark.parametrize("env", [{"LASAD_GATED_WS": "0"}, {"LASAD_GATED_WS": "1"}], ids=["four_wave", "twelve_wave"])
+def test_gated_kernel_variants(env):
+    """Both vector-decay kernels, forced (the launcher's choice is read from the environment once per process,
+    hence the child process), on the forward and on the fused layer, several chunks with a ragged tail and a
+    single short chunk."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", GATED_VARIANT_SCRIPT, root], env={**os.environ, **env},
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
