@@ -20,8 +20,8 @@
  * All tensors here are dense, fp64, in [B][Hh][n][d] order ("head-major");
  * states are [B][Hh][dk][dv] with dv contiguous: S[i][j] = sum_t k_t[i] v_t[j].
  *
- * Gradients (lasad_oracle_backward, lasad_oracle_dgamma) differentiate the same recurrence
- * step by step in reverse.
+ * Gradients (lasad_oracle_backward, lasad_oracle_dgamma, lasad_oracle_gated_backward)
+ * differentiate the same recurrences step by step in reverse.
  *
  * Every function below is pinned by the CPU test-suite against values fixed by
  * the paper's equations (hand-worked recurrences, geometric-series closed
@@ -444,6 +444,97 @@ int lasad_oracle_dgamma(const double *dlam, int B, int n_heads, int n,
         dgamma[h] = acc;
     }
     return 0;
+}
+
+/*
+ * Gradients of the vector-decay recurrence (Section 3.4 / Algorithm 1, zero initial state) by
+ * differentiating it step by step in reverse, exactly as lasad_oracle_backward does for one decay
+ * per token.  With l_t = lambda_t^spatial (1 in every channel at a row boundary, lambda_t elsewhere),
+ *     s_t = diag(l_t) s_{t-1} + k_t v_t^T,        o_t = q_scale * s_t^T q_t,
+ * the state gradient g_t = dL/ds_t obeys g_t = q_scale q_t d_o_t^T + diag(l_{t+1}) g_{t+1}, and
+ *     dq_t = q_scale * s_t d_o_t,   dk_t = g_t v_t,   dv_t = g_t^T k_t,
+ *     dl_t[r] = sum_c g_t[r][c] s_{t-1}[r][c]      (gradient of the decay actually applied).
+ * The gradient handed back for the input lambda_t is
+ *     dlam_t[r] = (t a boundary ? 0 : dl_t[r])  -  (key tied: dk_t[r]),
+ * because at a boundary the applied decay is the constant 1, and a tied key is k_t = 1 - lambda_t
+ * (from the base decay, also at a boundary).  With an own key tensor, dk is returned as well
+ * (dk must then be non-NULL); with the tied key, dk may be NULL.
+ * All tensors [B][Hh][n][d]; the forward states s_0 .. s_n are kept (n+1 matrices per sequence).
+ */
+int lasad_oracle_gated_backward(const double *q, const double *lam, const double *k, const double *v,
+                                double q_scale, const double *d_o,
+                                double *dq, double *dlam, double *dk, double *dv,
+                                int B, int n_heads, int n, int d, int grid_w, int start_pos, int mode)
+{
+    if (!q || !lam || !v || !d_o || !dq || !dlam || !dv || (k && !dk)) return 1;
+    if (B < 1 || n_heads < 1 || n < 0 || d < 1 || grid_w < 1 || start_pos < 0 || mode < 0 || mode > 2) return 1;
+    int status = 0;
+    const int64_t n_seq = (int64_t)B * n_heads;
+    const size_t dd = (size_t)d * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < n_seq; ++bh) {
+        double *S = (double *)calloc((size_t)(n + 1) * dd, sizeof(double));   /* s_0 .. s_n */
+        double *G = (double *)calloc(dd, sizeof(double));
+        double *kt = (double *)calloc((size_t)d, sizeof(double));
+        double *dkt = (double *)calloc((size_t)d, sizeof(double));
+        if (!S || !G || !kt || !dkt) {
+#pragma omp atomic write
+            status = 2;
+            free(S); free(G); free(kt); free(dkt);
+            continue;
+        }
+        for (int t = 0; t < n; ++t) {
+            const size_t off = ((size_t)bh * n + t) * d;
+            const int boundary = is_boundary((int64_t)start_pos + 1 + t, grid_w, mode);
+            const double *Sp = S + (size_t)t * dd;
+            double *Sn = S + (size_t)(t + 1) * dd;
+            for (int r = 0; r < d; ++r) {
+                const double l = lam[off + r];
+                const double kr = k ? k[off + r] : 1.0 - l;
+                const double ls = boundary ? 1.0 : l;
+                for (int c = 0; c < d; ++c)
+                    Sn[(size_t)r * d + c] = ls * Sp[(size_t)r * d + c] + kr * v[off + c];
+            }
+        }
+        for (int t = n - 1; t >= 0; --t) {
+            const size_t off = ((size_t)bh * n + t) * d;
+            const int boundary = is_boundary((int64_t)start_pos + 1 + t, grid_w, mode);
+            const double *St = S + (size_t)(t + 1) * dd;      /* s_t (contains token t) */
+            const double *Sp = S + (size_t)t * dd;            /* s_{t-1} */
+            for (int r = 0; r < d; ++r) kt[r] = k ? k[off + r] : 1.0 - lam[off + r];
+            for (int r = 0; r < d; ++r) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += St[(size_t)r * d + c] * d_o[off + c];
+                dq[off + r] = q_scale * acc;
+            }
+            for (int r = 0; r < d; ++r)
+                for (int c = 0; c < d; ++c)
+                    G[(size_t)r * d + c] += q_scale * q[off + r] * d_o[off + c];
+            for (int r = 0; r < d; ++r) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += G[(size_t)r * d + c] * v[off + c];
+                dkt[r] = acc;
+            }
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int r = 0; r < d; ++r) acc += G[(size_t)r * d + c] * kt[r];
+                dv[off + c] = acc;
+            }
+            for (int r = 0; r < d; ++r) {
+                double dl = 0.0;
+                for (int c = 0; c < d; ++c) dl += G[(size_t)r * d + c] * Sp[(size_t)r * d + c];
+                if (boundary) dl = 0.0;                       /* the applied decay is the constant 1 */
+                if (k) { dk[off + r] = dkt[r]; dlam[off + r] = dl; }
+                else   { if (dk) dk[off + r] = dkt[r]; dlam[off + r] = dl - dkt[r]; }
+            }
+            for (int r = 0; r < d; ++r) {                     /* into g_{t-1}: times the decay applied at t */
+                const double ls = boundary ? 1.0 : lam[off + r];
+                for (int c = 0; c < d; ++c) G[(size_t)r * d + c] *= ls;
+            }
+        }
+        free(S); free(G); free(kt); free(dkt);
+    }
+    return status;
 }
 
 #ifdef _OPENMP

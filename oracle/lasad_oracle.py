@@ -58,6 +58,9 @@ def _load():
         lib.lasad_oracle_bruteforce.restype = ci
         lib.lasad_oracle_gated_recurrent.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp,
                                                      ci, ci, ci, ci, ci, ci, ci]
+        lib.lasad_oracle_gated_backward.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp, dp, dp,
+                                                    ci, ci, ci, ci, ci, ci, ci]
+        lib.lasad_oracle_gated_backward.restype = ci
         lib.lasad_oracle_gated_recurrent.restype = ci
         lib.lasad_oracle_gated_bruteforce.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, ci, ci, ci, ci, ci]
         lib.lasad_oracle_gated_bruteforce.restype = ci
@@ -224,6 +227,29 @@ def gated_bruteforce(q, lam, v, grid_w, k=None, start_pos=0, mode=RESET_LAST_COL
     if rc != 0:
         raise RuntimeError(f"lasad_oracle_gated_bruteforce failed (rc={rc})")
     return o
+
+
+def gated_backward(q, lam, v, d_o, grid_w, k=None, start_pos=0, mode=RESET_LAST_COL, q_scale=1.0):
+    """Gradients of gated_recurrent (zero initial state) for d_o = dL/do.  All [B, n, Hh, d].
+    Tied key (k None): returns (dq, dlam, dv) with dlam the gradient for the lambda INPUT (through the
+    decay where the position is no boundary, and through k = 1 - lambda).  Own key: (dq, dlam, dv, dk)."""
+    q, lam, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, lam, v, d_o))
+    B, n, Hh, d = q.shape
+    assert lam.shape == q.shape and v.shape == q.shape and d_o.shape == q.shape
+    tr = lambda x: np.ascontiguousarray(x.transpose(0, 2, 1, 3))
+    qh, lh, vh, gh = tr(q), tr(lam), tr(v), tr(d_o)
+    kh = None if k is None else tr(np.asarray(k, dtype=np.float64))
+    dq, dl, dv = np.empty_like(qh), np.empty_like(qh), np.empty_like(qh)
+    dk = None if k is None else np.empty_like(qh)
+    rc = _load().lasad_oracle_gated_backward(_dptr(qh), _dptr(lh), _dptr(kh), _dptr(vh), float(q_scale), _dptr(gh),
+                                             _dptr(dq), _dptr(dl), _dptr(dk), _dptr(dv), B, Hh, n, d,
+                                             grid_w, start_pos, mode)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_gated_backward failed (rc={rc})")
+    back = lambda x: np.ascontiguousarray(x.transpose(0, 2, 1, 3))
+    if k is None:
+        return back(dq), back(dl), back(dv)
+    return back(dq), back(dl), back(dv), back(dk)
 
 
 # ---- Algorithm 1's elementwise steps around the recurrence --------------------------------------
