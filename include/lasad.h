@@ -239,6 +239,36 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
                            const float *gamma, int boundary_mode, float q_scale,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Backward pass of lasad_forward_gated (vector decay, Section 3.4 / Algorithm 1) for a call that
+ * starts from a zero state and whose final state is not used: given d_o = dL/do, with
+ * l_t = lambda_t^spatial (1 at a row boundary) and D[i][j][c] = prod_{s=j+1..i} l_s[c],
+ *     dq_i[c] = q_scale sum_{j<=i} (d_o_i . v_j) k_j[c] D[i][j][c]
+ *     dk_j[c] = q_scale sum_{i>=j} (d_o_i . v_j) q_i[c] D[i][j][c]
+ *     dv_j    = q_scale sum_{i>=j} (sum_c q_i[c] k_j[c] D[i][j][c]) d_o_i
+ * and dlam, the gradient for the lambda INPUT: through the decay where the position is not a
+ * boundary (nothing at a boundary, where the applied decay is the constant 1, and nothing at the
+ * first token, whose decay multiplies the zero state), and, with the tied key (k NULL,
+ * k_t = 1 - lambda_t), through the key as well (- dk_t).
+ *   q, lam, k, v, d_o   [B, n_tokens, n_heads, d] views sharing in_layout and io_dtype (device);
+ *                       k NULL: tied key.  Head dim 64 only (LASAD_ERR_UNSUPPORTED otherwise).
+ *   dq, dlam, dk, dv    same logical shape, grad_layout, grad_dtype (fp32, or bf16 with bf16
+ *                       inputs); overwritten; dk must be given exactly when k is; no aliasing.
+ *   lambda must be > 0 wherever it is applied (dlam comes from d/dlog lambda; a zero decay gives
+ *   inf or NaN there, and precision degrades like 1 / lambda for very small decays).
+ *   workspace           device memory of at least lasad_backward_gated_workspace_bytes(...) bytes,
+ *                       256-byte aligned, owned by the caller (LASAD_ERR_WORKSPACE if too small).
+ * Asynchronous on hip_stream; no allocation, no synchronisation; deterministic.
+ */
+size_t lasad_backward_gated_workspace_bytes(int B, int n_heads, int n_tokens, int d);
+int lasad_backward_gated(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+                         void *dq, void *dlam, void *dk, void *dv,
+                         const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                         int io_dtype, int grad_dtype,
+                         int B, int n_heads, int d, int grid_h, int grid_w,
+                         int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Reason for the last non-OK status returned on this thread (static storage). */
 const char *lasad_last_error(void);
 

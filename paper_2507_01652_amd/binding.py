@@ -23,6 +23,7 @@ EXPORTS = (
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
     "lasad_forward_layer", "lasad_decode_step_layer",
     "lasad_decode_step_rows", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
+    "lasad_backward_gated_workspace_bytes", "lasad_backward_gated",
     "lasad_last_error", "lasad_version",
 )
 
@@ -77,6 +78,11 @@ def load() -> ctypes.CDLL:
     lib.lasad_backward_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                            vp, ci, cf, vp, ctypes.c_size_t, vp]
     lib.lasad_backward_chunked.restype = ci
+    lib.lasad_backward_gated_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.lasad_backward_gated_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.lasad_backward_gated.restype = ci
     lib.lasad_last_error.argtypes = []
     lib.lasad_last_error.restype = ctypes.c_char_p
     lib.lasad_version.argtypes = []
@@ -360,6 +366,36 @@ def lasad_backward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_
         B, Hh, d, grid_h, grid_w, start_pos, n, _ptr(gamma), boundary_mode, q_scale,
         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
     return dq, dk, dv, dgamma
+
+
+def lasad_backward_gated_workspace_bytes(B: int, n_heads: int, n_tokens: int, d: int) -> int:
+    return int(load().lasad_backward_gated_workspace_bytes(B, n_heads, n_tokens, d))
+
+
+def lasad_backward_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
+                         grid_h: int, grid_w: int, k: torch.Tensor | None = None, start_pos: int = 0,
+                         boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                         grad_dtype: torch.dtype | None = None, workspace: torch.Tensor | None = None,
+                         stream=None):
+    """Gradients of lasad_forward_gated (zero initial state).  q, lam, v, d_o (and k, or None for the
+    tied key): logical [B, n, Hh, d] views sharing strides and dtype.  Returns (dq, dlam, dv) with the
+    tied key, (dq, dlam, dv, dk) with an own key."""
+    B, n, Hh, d = q.shape
+    for t in (lam, v, d_o) + (() if k is None else (k,)):
+        if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
+            raise ValueError("q, lam, k, v, d_o must share shape, strides and dtype")
+    dq, dlam, dv = (torch.empty_like(q, dtype=grad_dtype or q.dtype) for _ in range(3))
+    dk = None if k is None else torch.empty_like(dq)
+    need = lasad_backward_gated_workspace_bytes(B, Hh, n, d)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    li, lg = _layout(q), _layout(dq)
+    _check(load().lasad_backward_gated(
+        _ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dlam), _ptr(dk), _ptr(dv),
+        ctypes.byref(li), ctypes.byref(lg), _dtype_code(q), _dtype_code(dq),
+        B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale,
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+    return (dq, dlam, dv) if k is None else (dq, dlam, dv, dk)
 
 
 # ---- host <-> device helpers for seeded numpy inputs (no arithmetic) ---------

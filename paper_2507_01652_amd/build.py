@@ -25,6 +25,7 @@ SOURCES = [
     "lasad_forward_gated_ws.hip",
     "lasad_decode.hip",
     "lasad_backward.hip",
+    "lasad_backward_gated.hip",
 ]
 
 # Packed-fp32 instruction selection is switched off for every HIP translation unit.

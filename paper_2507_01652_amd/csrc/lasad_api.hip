@@ -305,6 +305,72 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
     return LASAD_OK;
 }
 
+size_t lasad_backward_gated_workspace_bytes(int B, int n_heads, int n_tokens, int d)
+{
+    if (B < 1 || n_heads < 1 || n_tokens < 1 || d < 1) return 0;
+    return lasad::backward_gated_workspace_bytes((int64_t)B * n_heads, n_tokens, d);
+}
+
+int lasad_backward_gated(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+                         void *dq, void *dlam, void *dk, void *dv,
+                         const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                         int io_dtype, int grad_dtype,
+                         int B, int n_heads, int d, int grid_h, int grid_w,
+                         int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x3fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (d != 64) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (the vector-decay backward supports 64)", d);
+    if (start_pos < 0 || n_tokens < 0 || (int64_t)start_pos + n_tokens > (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "positions %d+1..%d+%d leave the %d x %d grid", start_pos, start_pos, n_tokens, grid_h, grid_w);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (grad_dtype != LASAD_F32 && grad_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "grad_dtype %d", grad_dtype);
+    if (io_dtype == LASAD_F32 && grad_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 gradients");
+    if (!in_layout || !grad_layout) return fail(LASAD_ERR_INVALID_ARG, "layout is NULL");
+    if ((k != nullptr) != (dk != nullptr)) return fail(LASAD_ERR_INVALID_ARG, "dk must be given exactly when k is");
+    if (n_tokens > 0 && (!q || !lam || !v || !d_o || !dq || !dlam || !dv)) return fail(LASAD_ERR_INVALID_ARG, "a tensor pointer is NULL");
+    const int vec = io_dtype == LASAD_BF16 ? 8 : 4, gvec = grad_dtype == LASAD_BF16 ? 8 : 4;
+    if (in_layout->stride_b % vec || in_layout->stride_n % vec || in_layout->stride_h % vec ||
+        in_layout->stride_b < 0 || in_layout->stride_n < 0 || in_layout->stride_h < 0)
+        return fail(LASAD_ERR_INVALID_ARG, "input strides must be non-negative multiples of %d elements", vec);
+    if (grad_layout->stride_b % gvec || grad_layout->stride_n % gvec || grad_layout->stride_h % gvec ||
+        grad_layout->stride_b < 0 || grad_layout->stride_n < 0 || grad_layout->stride_h < 0)
+        return fail(LASAD_ERR_INVALID_ARG, "gradient strides must be non-negative multiples of %d elements", gvec);
+    if (n_tokens > 0 && (in_layout->stride_n < d || grad_layout->stride_n < d))
+        return fail(LASAD_ERR_INVALID_ARG, "token stride smaller than the head dim");
+    if (!aligned(q, 16) || !aligned(lam, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) ||
+        !aligned(dq, 16) || !aligned(dlam, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(workspace, 256))
+        return fail(LASAD_ERR_INVALID_ARG, "tensors must be 16-byte aligned, the workspace 256-byte aligned");
+    const void *ins[5] = {q, lam, k, v, d_o};
+    void *outs[4] = {dq, dlam, dk, dv};
+    for (int i = 0; n_tokens > 0 && i < 4; ++i) {
+        if (!outs[i]) continue;
+        for (int j = 0; j < 5; ++j)
+            if (outs[i] == ins[j]) return fail(LASAD_ERR_INVALID_ARG, "a gradient buffer aliases an input");
+        for (int j = i + 1; j < 4; ++j)
+            if (outs[i] == outs[j]) return fail(LASAD_ERR_INVALID_ARG, "two gradient buffers alias");
+    }
+    if (n_tokens == 0) return LASAD_OK;
+    const size_t need = lasad_backward_gated_workspace_bytes(B, n_heads, n_tokens, d);
+    if (!workspace || workspace_bytes < need)
+        return fail(LASAD_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+
+    lasad::GatedBackwardArgs a;
+    a.q = q; a.lam = lam; a.k = k; a.v = v; a.d_o = d_o;
+    a.dq = dq; a.dlam = dlam; a.dk = dk; a.dv = dv;
+    a.in = *in_layout; a.grad = *grad_layout;
+    a.io_dtype = io_dtype; a.grad_dtype = grad_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d; a.grid_w = grid_w;
+    a.start_pos = start_pos; a.n_tokens = n_tokens;
+    a.mode = boundary_mode; a.q_scale = q_scale;
+    a.workspace = workspace;
+    hipError_t e = lasad::launch_backward_gated(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_backward_gated launch", e);
+    return LASAD_OK;
+}
+
 int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,
                         const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
                         int io_dtype, int out_dtype,

@@ -97,6 +97,22 @@ struct BackwardArgs {
     float *dq32, *dk32, *seq_sums;
 };
 
+// Arguments of one backward call of the vector-decay recurrence, already validated (d == 64).
+struct GatedBackwardArgs {
+    const void *q, *lam, *k, *v, *d_o;   // k NULL: key tied to the decay, k = 1 - lam
+    void *dq, *dlam, *dk, *dv;           // dk NULL with the tied key
+    lasad_layout_t in, grad;
+    int io_dtype, grad_dtype;
+    int B, Hh, d;
+    int grid_w;
+    int start_pos, n_tokens;
+    int mode;
+    float q_scale;
+    void *workspace;
+};
+hipError_t launch_backward_gated(const GatedBackwardArgs &a, hipStream_t s);
+size_t backward_gated_workspace_bytes(int64_t n_seq, int n_tokens, int d);
+
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,
                                 int mode, float *lambda_out, int32_t *cum_out, hipStream_t s);
 hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s);

@@ -34,7 +34,19 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
-enum { SCALAR = 0, TIED = 1, OWNKEY = 2 };   // decay kind: per-head scalar; vector with k = 1 - lambda; vector with own key
+// decay kind: per-head scalar; vector with k = 1 - lambda; vector with own key; and the two walks of the
+// vector-decay BACKWARD passes, which are the same recurrence with the tensors in other roles
+// (ScanRoles): decay per key channel (row of S) as in the forward, or per column of S
+enum { SCALAR = 0, TIED = 1, OWNKEY = 2, ROLES_ROW = 3, ROLES_COL = 4 };
+
+// Which tensor feeds which operand plane of the walk, for the ROLES kinds: plane PQ (row operand of
+// the output contraction, scaled by q_scale), PK (row operand of the rank-1 update), PV (column
+// operand of the update), PL (decay; 1 at a row boundary of the pass's start column).
+struct ScanRoles {
+    const void *ptr[4];
+    int shift[4];         // 0, or -1: the plane of token m holds the tensor's token m - 1 (token 0: a neutral value)
+    int one_minus[4];     // the plane holds 1 - x (a key tied to the decay)
+};
 
 // LDS planes of one staged batch
 enum { PQ = 0, PK = 1, PV = 2, PL = 3 };
@@ -80,7 +92,7 @@ enum { PQ = 0, PK = 1, PV = 2, PL = 3 };
 template <int KIND, int BASE>
 __device__ __forceinline__ void scan8(float *S, float *o, float q, float k, float l, float v)
 {
-    if (KIND == SCALAR) {
+    if (KIND == SCALAR || KIND == ROLES_COL) {            // the decay is a per-lane (per-column) factor
         if (BASE == 0) asm(SCAN8_SCALAR("v_mul_f32_dpp", 0, 1, 2, 3, 4, 5, 6, 7) SCAN8_OPS_FIRST(S, o, q, k, l, v));
         else asm(SCAN8_SCALAR("v_fmac_f32_dpp", 8, 9, 10, 11, 12, 13, 14, 15) SCAN8_OPS_NEXT(S, o, q, k, l, v));
     } else {
@@ -92,7 +104,9 @@ __device__ __forceinline__ void scan8(float *S, float *o, float q, float k, floa
 template <int IN_BF16, int KIND>
 struct Loader {
     static constexpr int VEC = IN_BF16 ? 8 : 4;                 // elements per 16-byte load
-    static constexpr int NA = KIND == OWNKEY ? 4 : 3;           // tensors read from memory
+    static constexpr int NA = KIND >= OWNKEY ? 4 : 3;           // tensors read from memory
+    static constexpr bool ROLES = KIND >= ROLES_ROW;
+    const ScanRoles *roles = nullptr;                           // ROLES kinds only
     static constexpr int PER_ARRAY = kT * kD / VEC;             // 16-byte loads per tensor and batch
     static constexpr int TOTAL = NA * PER_ARRAY;
     static constexpr int NL = (TOTAL + kThreads - 1) / kThreads;   // loads per thread and batch
@@ -109,8 +123,9 @@ struct Loader {
         c0 = (w - tok * (kD / VEC)) * VEC;
     }
 
-    __device__ static const void *tensor(const ForwardArgs &a, int arr)
+    __device__ const void *tensor(const ForwardArgs &a, int arr) const
     {
+        if (ROLES) return roles->ptr[arr];
         if (KIND == SCALAR) return arr == 0 ? a.q : arr == 1 ? a.k : a.v;
         if (KIND == TIED) return arr == 0 ? a.q : arr == 1 ? a.lam : a.v;
         return arr == 0 ? a.q : arr == 1 ? a.lam : arr == 2 ? a.k : a.v;
@@ -124,7 +139,8 @@ struct Loader {
         for (int i = 0; i < NL; ++i) {
             int arr, tok, c0;
             where(i, arr, tok, c0);
-            const int t = min(t0 + tok, a.n_tokens - 1);
+            int t = min(t0 + tok, a.n_tokens - 1);
+            if (ROLES) t = max(t + roles->shift[arr], 0);
             const int64_t idx = in_base + (int64_t)t * a.in.stride_n + c0;
             const char *p = (const char *)tensor(a, arr) + idx * (IN_BF16 ? 2 : 4);
             raw[i] = *(const u4 *)p;
@@ -151,11 +167,34 @@ struct Loader {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(raw[i][e]);
             }
-            if (KIND != SCALAR && a.fused_act && arr <= 1) {   // Algorithm 1: q := SiLU(q), lambda := sigmoid(lambda)
+            if (!ROLES && KIND != SCALAR && a.fused_act && arr <= 1) {   // Algorithm 1: q := SiLU(q), lambda := sigmoid(lambda)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) f[e] = arr == 0 ? silu_f32(f[e]) : sigmoid_f32(f[e]);
             }
             const bool past_end = t0 + tok >= a.n_tokens;
+            if (ROLES) {
+                // plane = tensor index; rows past the end and a shifted read before the first token are neutral
+                if (roles->one_minus[arr]) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) f[e] = 1.0f - f[e];
+                }
+                const bool neutral = past_end || t0 + tok + roles->shift[arr] < 0;
+                if (arr == PL && (neutral || is_boundary(a.start_pos + t0 + tok + 1, a.grid_w, a.mode))) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) f[e] = 1.0f;
+                } else if (neutral) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) f[e] = 0.0f;
+                }
+                if (arr == PQ) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) f[e] *= a.q_scale;
+                }
+                float *dst = st + (arr * kT + tok) * kD + c0;
+#pragma unroll
+                for (int e = 0; e < VEC; e += 4) *(f4 *)(dst + e) = f4{f[e], f[e + 1], f[e + 2], f[e + 3]};
+                continue;
+            }
             if (past_end) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) f[e] = (KIND != SCALAR && arr == 1) ? 1.0f : 0.0f;
@@ -196,7 +235,7 @@ constexpr int lds_floats() { return 2 * (KIND == SCALAR ? 3 : 4) * kT * kD + 2 *
 // Walk sequence bh, value channels j0 .. j0+NJ-1, with the calling 256-thread workgroup.
 // lds: lds_floats<KIND>() floats, 16-byte aligned.
 template <int IN_BF16, int OUT_BF16, int KIND, int NJ>
-__device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds)
+__device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds, const ScanRoles *roles = nullptr)
 {
     constexpr int CG = kThreads / NJ;      // key-channel groups
     constexpr int R = kD / CG;             // key channels per thread (16 or 8)
@@ -230,6 +269,7 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds)
     const int nb = (a.n_tokens + kT - 1) / kT;
 
     Loader<IN_BF16, KIND> ld;
+    ld.roles = roles;
     if (nb > 0) {
         ld.fetch(a, in_base, 0);
         ld.stage(a, 0, s_stage[0]);
@@ -258,6 +298,7 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds)
             float lo;
             if (KIND == SCALAR)
                 lo = (t0 + tt >= a.n_tokens || is_boundary(a.start_pos + t0 + tt + 1, a.grid_w, a.mode)) ? 1.0f : gamma;
+            else if (KIND == ROLES_COL) lo = st[(PL * kT + tt) * kD + j0 + j];
             else lo = st[(PL * kT + tt) * kD + cop];
             float o[4];
             scan8<KIND, 0>(S, o, qo, ko, lo, vj);

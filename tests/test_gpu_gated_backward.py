@@ -1,0 +1,141 @@
+"""GPU parity of the vector-decay backward (lasad_backward_gated) against the CPU oracle's reverse
+differentiation of the recurrence, element by element on seeded inputs."""
+import zlib
+
+import numpy as np
+import pytest
+
+from paper_2507_01652_amd import workloads as wl
+from helpers import TOL, gather_pairs, parity_err, rel_err, sample_pairs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lasad():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2507_01652_amd import binding
+    binding.load()
+    return binding
+
+
+def _inputs(B, n, Hh, d, dtype, seed, own_key, layout="bnhd"):
+    """q, v, d_o ~ N(0,1) / sqrt(d); gates = sigmoid(N(2,1)) (the forward tests' recipe); own key ~ U(0,1)."""
+    rng = np.random.default_rng(seed)
+    shape = (B, n, Hh, d)
+    q, v, g = (wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(np.sqrt(d)), dtype) for _ in range(3))
+    lam = wl.gate_inputs(shape, dtype, seed + 1)
+    k = wl.store_round(rng.uniform(0.0, 1.0, size=shape).astype(np.float32), dtype) if own_key else None
+    out = [q, lam, v, g, k]
+    if layout == "bhnd":
+        out = [None if x is None else np.ascontiguousarray(x.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3) for x in out]
+    return out
+
+
+def _run(lasad, dtype, q, lam, v, g, k, H, W, start=0, mode=0, q_scale=1.0, grad_bf16=False):
+    import torch
+    dev = lambda x: None if x is None else lasad.to_device(x, dtype)
+    res = lasad.lasad_backward_gated(dev(q), dev(lam), dev(v), dev(g), H, W, k=dev(k), start_pos=start,
+                                     boundary_mode=mode, q_scale=q_scale,
+                                     grad_dtype=torch.bfloat16 if grad_bf16 else torch.float32)
+    torch.cuda.synchronize()
+    return [r.float().cpu().numpy() for r in res]
+
+
+def _check(lasad, oracle, B, Hh, H, W, dtype, seed, own_key, start=0, n=None, mode=0, q_scale=1.0, grad_bf16=False,
+           layout="bnhd"):
+    n = H * W - start if n is None else n
+    q, lam, v, g, k = _inputs(B, n, Hh, 64, dtype, seed, own_key, layout)
+    got = _run(lasad, dtype, q, lam, v, g, k, H, W, start, mode, q_scale, grad_bf16)
+    ref = oracle.gated_backward(q, lam, v, g, W, k=k, start_pos=start, mode=mode, q_scale=q_scale)
+    names = ("dq", "dlam", "dv", "dk")
+    for nm, a, r in zip(names, got, ref):
+        assert parity_err(a, r, grad_bf16) <= TOL[dtype], (nm, parity_err(a, r, grad_bf16))
+
+
+CASES = [
+    # name, B, Hh, H, W, dtype
+    ("f32_small", 1, 2, 4, 5, "f32"),
+    ("f32_batches", 2, 2, 7, 9, "f32"),
+    ("bf16_one_batch", 2, 3, 3, 5, "bf16"),
+    ("bf16_batches_and_tail", 2, 2, 13, 17, "bf16"),
+    ("bf16_single_row", 1, 2, 1, 70, "bf16"),
+    ("bf16_single_col", 1, 2, 70, 1, "bf16"),
+    ("bf16_single_token", 1, 2, 1, 1, "bf16"),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("own_key", [False, True], ids=["tied_key", "own_key"])
+def test_backward_gated_shapes(lasad, oracle, case, mode, own_key):
+    name, B, Hh, H, W, dtype = case
+    _check(lasad, oracle, B, Hh, H, W, dtype, zlib.crc32(name.encode()) % 10000 + mode, own_key, mode=mode, q_scale=0.5)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("start,n", [(5, 100), (17, 64), (16, 3)])
+def test_backward_gated_partial_range(lasad, oracle, mode, start, n):
+    """A call over positions start+1 .. start+n (mid-row start and end)."""
+    _check(lasad, oracle, 2, 2, 9, 17, "bf16", 4242 + start, False, start=start, n=n, mode=mode)
+
+
+@pytest.mark.parametrize("layout", ["bnhd", "bhnd"])
+@pytest.mark.parametrize("grad_bf16", [True, False])
+def test_backward_gated_layouts_and_grad_types(lasad, oracle, layout, grad_bf16):
+    _check(lasad, oracle, 2, 3, 10, 12, "bf16", 77, True, grad_bf16=grad_bf16, layout=layout)
+    _check(lasad, oracle, 2, 3, 10, 12, "bf16", 78, False, grad_bf16=grad_bf16, layout=layout)
+
+
+def test_backward_gated_many_sequences(lasad, oracle):
+    """More than 170 sequences: one workgroup per sequence and pass (fewer: two)."""
+    _check(lasad, oracle, 60, 3, 5, 8, "bf16", 9, False)
+
+
+def test_backward_gated_strong_decay(lasad, oracle):
+    """Gate logits around -1.5 (lambda ~ 0.18, some below 0.02): the suffix sums are divided by small numbers."""
+    B, Hh, H, W = 1, 2, 6, 11
+    rng = np.random.default_rng(5)
+    shape = (B, H * W, Hh, 64)
+    q, v, g = (wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(8.0), "bf16") for _ in range(3))
+    lam = wl.store_round((1.0 / (1.0 + np.exp(-(rng.standard_normal(shape) - 1.5)))).astype(np.float32), "bf16")
+    got = _run(lasad, "bf16", q, lam, v, g, None, H, W)
+    ref = oracle.gated_backward(q, lam, v, g, W)
+    for nm, a, r in zip(("dq", "dlam", "dv"), got, ref):
+        assert rel_err(a, r) <= TOL["bf16"], nm
+
+
+@pytest.mark.parametrize("name", ["base_prefill_16x16", "large_prefill_24x24"])
+def test_backward_gated_bench_shapes_sampled(lasad, oracle, name):
+    """The benchmark shapes in the benchmark's launch configuration; the oracle on sampled sequences."""
+    w = wl.CONFIGS[name]
+    q, lam, v, g, _ = _inputs(w.B, w.N, w.Hh, w.d, "bf16", w.seed + 11, False)
+    got = _run(lasad, "bf16", q, lam, v, g, None, w.grid_h, w.grid_w, grad_bf16=True)
+    pairs = sample_pairs(w.B, w.Hh, 8, seed=w.seed)
+    ref = oracle.gated_backward(*(gather_pairs(x, pairs) for x in (q, lam, v, g)), w.grid_w)
+    for nm, a, r in zip(("dq", "dlam", "dv"), got, ref):
+        assert parity_err(gather_pairs(a, pairs), r, True) <= TOL["bf16"], nm
+
+
+def test_backward_gated_deterministic(lasad):
+    import torch
+    q, lam, v, g, _ = _inputs(2, 256, 12, 64, "bf16", 3, False)
+    dev = lambda x: lasad.to_device(x, "bf16")
+    r1 = lasad.lasad_backward_gated(dev(q), dev(lam), dev(v), dev(g), 16, 16)
+    r2 = lasad.lasad_backward_gated(dev(q), dev(lam), dev(v), dev(g), 16, 16)
+    torch.cuda.synchronize()
+    for a, b in zip(r1, r2):
+        assert torch.equal(a, b)
+
+
+def test_backward_gated_rejects_bad_arguments(lasad):
+    import torch
+    q = torch.zeros((1, 8, 2, 32), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(Exception):
+        lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 4)          # head dim 32
+    q = torch.zeros((1, 8, 2, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(Exception):
+        lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 3)          # 8 tokens on a 2 x 3 grid
+    with pytest.raises(Exception):
+        lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 4, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
