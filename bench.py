@@ -325,6 +325,39 @@ def bench_gated(args, torch, lasad, wl):
         g.replay()
         graph_ms = time_region(torch, g.replay)
     dur_s = (graph_ms if graph_ms is not None else eager_ms) / steps * 1e-3
+    # backward of the same call (dq, dlam, dv from q, gate, v, d_o; key tied to the gate)
+    bwd = None
+    if not args.no_backward:
+        td = lasad.to_device(wl.store_round(np.random.default_rng(w.seed + 101).standard_normal(q.shape, dtype=np.float32)
+                                            / np.float32(np.sqrt(w.d)), w.dtype), w.dtype)
+        if args.layout == "bhnd":
+            td = td.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        gsets = min(sets, 8)
+        grads = [tuple(torch.empty_like(tq) for _ in range(3)) for _ in range(gsets)]
+        ws_b = torch.empty((lasad.lasad_backward_gated_workspace_bytes(w.B, w.Hh, w.N, w.d),), dtype=torch.uint8, device="cuda")
+        bsteps = max(1, min(steps, 20))
+
+        def run_bwd(nsteps, first=0):
+            for i in range(nsteps):
+                a, b, c, _ = bufs[(first + i) % sets]
+                lasad.lasad_backward_gated(a, b, c, td, w.grid_h, w.grid_w, grads=grads[(first + i) % gsets], workspace=ws_b)
+
+        run_bwd(3)
+        b_ms = time_region(torch, lambda: run_bwd(bsteps, 3))
+        if not args.no_graph:
+            gb = capture(torch, lambda: run_bwd(bsteps, 3))
+            gb.replay()
+            b_ms = time_region(torch, gb.replay)
+        b_s = b_ms / bsteps * 1e-3
+        bytes_bwd = token_heads * 7 * w.d * 2          # q, gate, v, d_o read + dq, dlam, dv written, bf16
+        bwd = {"workload": w.name + " (q, gate, v, d_o; k = 1 - gate)", "value": w.B * w.N / b_s, "unit": "tokens/s",
+               "ms_per_step": b_s * 1e3, "steps_timed": bsteps,
+               "launches_per_step": "three fp32 token-serial walks in one launch + 1 finishing kernel",
+               "roofline": {"bound": "hbm", "kernel": "lasad_backward_gated (both launches of one call)",
+                            "achieved": bytes_bwd / b_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": bytes_bwd / b_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_bwd,
+                            "traffic": MEASURED_TRAFFIC_BYTES.get("gated_backward:" + w.name)}}
+        del grads, ws_b, td
     # the same launch with Algorithm 1's elementwise steps fused in (SiLU, sigmoid, RMS norm): the gate buffers
     # now hold the pre-sigmoid logits N(2, 1) of the same recipe, q is read as the pre-SiLU query
     tz = lasad.to_device(wl.store_round(np.random.default_rng(w.seed + 7).standard_normal(q.shape, dtype=np.float32)
@@ -352,6 +385,8 @@ def bench_gated(args, torch, lasad, wl):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_fwd / dur_s / 1e9 / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": bytes_fwd,
                      "traffic": MEASURED_TRAFFIC_BYTES.get("gated:" + w.name)}}}
+    if bwd is not None:
+        res["backward"] = bwd
     if not args.no_cpu_baseline:
         from oracle import lasad_oracle as oracle
         n_seq = min(w.B * w.Hh, 4 * oracle.num_threads())

@@ -375,17 +375,25 @@ def lasad_backward_gated_workspace_bytes(B: int, n_heads: int, n_tokens: int, d:
 def lasad_backward_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
                          grid_h: int, grid_w: int, k: torch.Tensor | None = None, start_pos: int = 0,
                          boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
-                         grad_dtype: torch.dtype | None = None, workspace: torch.Tensor | None = None,
-                         stream=None):
+                         grads: tuple | None = None, grad_dtype: torch.dtype | None = None,
+                         workspace: torch.Tensor | None = None, stream=None):
     """Gradients of lasad_forward_gated (zero initial state).  q, lam, v, d_o (and k, or None for the
     tied key): logical [B, n, Hh, d] views sharing strides and dtype.  Returns (dq, dlam, dv) with the
-    tied key, (dq, dlam, dv, dk) with an own key."""
+    tied key, (dq, dlam, dv, dk) with an own key; `grads` may give these output tensors (sharing one set
+    of strides), `workspace` a uint8 device tensor."""
     B, n, Hh, d = q.shape
     for t in (lam, v, d_o) + (() if k is None else (k,)):
         if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
             raise ValueError("q, lam, k, v, d_o must share shape, strides and dtype")
-    dq, dlam, dv = (torch.empty_like(q, dtype=grad_dtype or q.dtype) for _ in range(3))
-    dk = None if k is None else torch.empty_like(dq)
+    if grads is None:
+        grads = tuple(torch.empty_like(q, dtype=grad_dtype or q.dtype) for _ in range(3 if k is None else 4))
+    if len(grads) != (3 if k is None else 4):
+        raise ValueError("grads must hold dq, dlam, dv (and dk with an own key)")
+    dq, dlam, dv = grads[:3]
+    dk = None if k is None else grads[3]
+    for t in grads:
+        if t.shape != q.shape or t.stride() != dq.stride() or t.dtype != dq.dtype:
+            raise ValueError("gradient tensors must share q's shape and one set of strides and dtype")
     need = lasad_backward_gated_workspace_bytes(B, Hh, n, d)
     if workspace is None and need:
         workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
