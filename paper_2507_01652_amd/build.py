@@ -26,6 +26,7 @@ SOURCES = [
     "lasad_decode.hip",
     "lasad_backward.hip",
     "lasad_backward_gated.hip",
+    "lasad_backward_gated_mfma.hip",
 ]
 
 # Packed-fp32 instruction selection is switched off for every HIP translation unit.

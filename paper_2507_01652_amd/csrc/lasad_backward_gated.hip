@@ -19,6 +19,9 @@
 // decay of step m is the lambda of the token one step EARLIER in walking order (l_{t+1}), read with a
 // token shift of -1, and the row-boundary pattern is the forward one mirrored and shifted, i.e. that
 // of another start column (as in the scalar-decay backward).  The three walks run in one launch.
+// With bf16 inputs the three passes run on the matrix cores instead, chunk by chunk
+// (lasad_backward_gated_mfma.hip, one launch per pass); the walks remain the path for fp32 inputs
+// and the range fallback of those kernels (LASAD_GATED_BWD=walk forces them).
 //
 // Decay gradient.  L depends on l only through the products prod_{s=j+1..i} l_s[c] between a key
 // j and a query i, so with r_i[c] = q_i[c] dq_i[c] - k_i[c] dk_i[c]
@@ -31,9 +34,15 @@
 // sums first, then the walk down its range) forms them in a fixed order and stores dq, dk, dlam in
 // the caller's type.  lambda must be > 0 where it is applied, and the result loses precision like
 // 1 / lambda for very small decays (the quotient of a rounded sum).
+#include <stdlib.h>
+#include <string.h>
+
 #include "lasad_scan.h"
 
 namespace lasad {
+
+hipError_t launch_backward_gated_pass(const ForwardArgs &a, const scan::ScanRoles &roles, int kind, int shift,
+                                      int q_one_minus, hipStream_t s);
 
 namespace {
 
@@ -190,12 +199,31 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     w.o[2] = (void *)last_token(dk32, wl, n, 4); w.in[2] = in_rev; w.out[2] = wl_rev; w.start_pos[2] = rev_start;
 
     const bool in16 = b.io_dtype == LASAD_BF16, out16 = b.grad_dtype == LASAD_BF16;
-    if (in16 && out16) launch_walks<1, 1>(w, n_seq, s);
-    else if (in16) launch_walks<1, 0>(w, n_seq, s);
-    else if (!out16) launch_walks<0, 0>(w, n_seq, s);
-    else return hipErrorInvalidValue;
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    static const bool force_walk = [] { const char *e = getenv("LASAD_GATED_BWD"); return e && !strcmp(e, "walk"); }();
+    hipError_t e;
+    if (in16 && !force_walk) {
+        // matrix-core passes: the pass's operands in the forward's fields
+        ForwardArgs p = f;
+        p.q = b.d_o; p.lam = b.lam; p.k = b.k; p.v = b.v; p.o = dq32;                      // dq
+        p.in = b.in; p.out = wl; p.out_dtype = LASAD_F32; p.start_pos = b.start_pos;
+        e = launch_backward_gated_pass(p, w.roles[0], 1, 0, 0, s);
+        if (e != hipSuccess) return e;
+        p.q = b.k ? k_l : lam_l; p.lam = lam_l; p.k = q_l; p.v = g_l; p.o = w.o[1];         // dv
+        p.in = in_rev; p.out = grad_rev; p.out_dtype = b.grad_dtype; p.start_pos = rev_start;
+        e = launch_backward_gated_pass(p, w.roles[1], 0, 1, b.k ? 0 : 1, s);
+        if (e != hipSuccess) return e;
+        p.q = v_l; p.lam = lam_l; p.k = q_l; p.v = g_l; p.o = w.o[2];                       // dk
+        p.out = wl_rev; p.out_dtype = LASAD_F32;
+        e = launch_backward_gated_pass(p, w.roles[2], 1, 1, 0, s);
+        if (e != hipSuccess) return e;
+    } else {
+        if (in16 && out16) launch_walks<1, 1>(w, n_seq, s);
+        else if (in16) launch_walks<1, 0>(w, n_seq, s);
+        else if (!out16) launch_walks<0, 0>(w, n_seq, s);
+        else return hipErrorInvalidValue;
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
 
     const dim3 grid((unsigned)n_seq), block(kFinWaves * 64);
     if (in16 && out16) hipLaunchKernelGGL((backward_gated_finish_kernel<1, 1>), grid, block, 0, s, b, dq32, dk32);

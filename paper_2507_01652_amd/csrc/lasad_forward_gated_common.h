@@ -62,7 +62,11 @@ __device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
 
 // One chunk of staged inputs and prepared operands of a staging thread: lane (l32, g) of staging
 // wave w holds token rows 2*l32, 2*l32 + 1 and channels pcol = 16*w + 8*g .. +7.
-template <int OWNKEY, int FUSED>
+// The backward passes (lasad_backward_gated_mfma.hip) stage the same operands from other tensors:
+// SHIFT = 1 takes the decay of token m from the decay tensor's token m - 1 (none at token 0: the
+// walk runs the sequence backwards and step m applies the decay of the step before it);
+// QMODE = 1 stages Q~ = q_scale A (query 1), QMODE = 2 takes the query as 1 - x from its tensor.
+template <int OWNKEY, int FUSED, int SHIFT = 0, int QMODE = 0>
 struct ChunkStage {
     uint4 rq[2], rl[2], rk[2], rv[2];                 // as fetched: q, lambda (or gate logits), own key, v
     uint4 pkh[2], pkl[2], pqh[2], pql[2], pv[2];      // prepared: K~ hi / lo, Q~ hi / lo, v
@@ -78,8 +82,8 @@ struct ChunkStage {
         for (int it = 0; it < 2; ++it) {
             const int tok = min(chunk * C + 2 * l32 + it, n - 1);
             const int64_t off = (int64_t)tok * stride_n + pcol;
-            rq[it] = *(const uint4 *)(gq + off);
-            rl[it] = *(const uint4 *)(gl + off);
+            if (QMODE != 1) rq[it] = *(const uint4 *)(gq + off);
+            rl[it] = *(const uint4 *)(gl + (SHIFT ? (int64_t)max(tok - 1, 0) * stride_n + pcol : off));
             if (OWNKEY) rk[it] = *(const uint4 *)(gk + off);
             rv[it] = *(const uint4 *)(gv + off);
         }
@@ -116,8 +120,9 @@ struct ChunkStage {
                 const float k1 = OWNKEY ? __uint_as_float(kw[e] & 0xffff0000u) : 1.0f - l1;
                 kk[it][2 * e] = k0;
                 kk[it][2 * e + 1] = k1;
-                lam[it][2 * e] = bnd ? 1.0f : l0;
-                lam[it][2 * e + 1] = bnd ? 1.0f : l1;
+                const bool no_decay = bnd || (SHIFT && t0 + row == 0);
+                lam[it][2 * e] = no_decay ? 1.0f : l0;
+                lam[it][2 * e + 1] = no_decay ? 1.0f : l1;
             }
             pv[it] = rv[it];
         }
@@ -131,10 +136,11 @@ struct ChunkStage {
                     lam[it][c] = live ? lam[it][c] : 1.0f;
                 }
                 pv[it] = keep_or(live, pv[it], 0u);
-                rq[it] = keep_or(live, rq[it], 0u);
+                if (QMODE == 0) rq[it] = keep_or(live, rq[it], 0u);
+                if (QMODE == 2) rq[it] = keep_or(live, rq[it], 0x3f803f80u);     // 1 - 1 = 0
             }
         }
-        qc[0] = rq[0]; qc[1] = rq[1];
+        if (QMODE != 1) { qc[0] = rq[0]; qc[1] = rq[1]; }
     }
 
     __device__ void prepare_end(const ForwardArgs &a, int lane, int pcol, float *sTotN, const SplitConst &sc)
@@ -161,13 +167,16 @@ struct ChunkStage {
         trip = !(amin >= kMinChunkDecay);
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
-            const uint32_t qw[4] = {qc[it].x, qc[it].y, qc[it].z, qc[it].w};
+            uint32_t qw[4] = {0u, 0u, 0u, 0u};
+            if (QMODE != 1) { qw[0] = qc[it].x; qw[1] = qc[it].y; qw[2] = qc[it].z; qw[3] = qc[it].w; }
             uint32_t kh[4], kl[4], qh[4], ql[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float a0 = lam[it][2 * e], a1 = lam[it][2 * e + 1];
                 split2(kk[it][2 * e] * __builtin_amdgcn_rcpf(a0), kk[it][2 * e + 1] * __builtin_amdgcn_rcpf(a1), kh[e], kl[e], sc);
-                float q0 = __uint_as_float(qw[e] << 16), q1 = __uint_as_float(qw[e] & 0xffff0000u);
+                float q0 = 1.0f, q1 = 1.0f;
+                if (QMODE != 1) { q0 = __uint_as_float(qw[e] << 16); q1 = __uint_as_float(qw[e] & 0xffff0000u); }
+                if (QMODE == 2) { q0 = 1.0f - q0; q1 = 1.0f - q1; }
                 if (FUSED) { q0 = silu_f32(q0); q1 = silu_f32(q1); }
                 split2(q0 * (a0 * a.q_scale), q1 * (a1 * a.q_scale), qh[e], ql[e], sc);
             }
