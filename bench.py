@@ -352,7 +352,8 @@ def bench_gated(args, torch, lasad, wl):
         bytes_bwd = token_heads * 7 * w.d * 2          # q, gate, v, d_o read + dq, dlam, dv written, bf16
         bwd = {"workload": w.name + " (q, gate, v, d_o; k = 1 - gate)", "value": w.B * w.N / b_s, "unit": "tokens/s",
                "ms_per_step": b_s * 1e3, "steps_timed": bsteps,
-               "launches_per_step": "three fp32 token-serial walks in one launch + 1 finishing kernel",
+               "launches_per_step": "one launch of the chunked matrix-core kernel over the 3 passes (dq, dv, dk) + 1 finishing kernel "
+                                    "(suffix sums for dlam)",
                "roofline": {"bound": "hbm", "kernel": "lasad_backward_gated (both launches of one call)",
                             "achieved": bytes_bwd / b_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": bytes_bwd / b_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_bwd,

@@ -20,7 +20,7 @@
 // token shift of -1, and the row-boundary pattern is the forward one mirrored and shifted, i.e. that
 // of another start column (as in the scalar-decay backward).  The three walks run in one launch.
 // With bf16 inputs the three passes run on the matrix cores instead, chunk by chunk
-// (lasad_backward_gated_mfma.hip, one launch per pass); the walks remain the path for fp32 inputs
+// (lasad_backward_gated_mfma.hip, again one launch); the walks remain the path for fp32 inputs
 // and the range fallback of those kernels (LASAD_GATED_BWD=walk forces them).
 //
 // Decay gradient.  L depends on l only through the products prod_{s=j+1..i} l_s[c] between a key
@@ -30,9 +30,8 @@
 //
 // and dlam_t = (t a boundary or the first token ? 0 : that suffix sum / lambda_t) - (tied key: dk_t).
 // The suffix sums cancel heavily, so dq and dk go through the workspace in fp32; the finishing kernel
-// (one workgroup of 16 waves per sequence, lane = channel, each wave a contiguous token range: range
-// sums first, then the walk down its range) forms them in a fixed order and stores dq, dk, dlam in
-// the caller's type.  lambda must be > 0 where it is applied, and the result loses precision like
+// (one workgroup per sequence, blocks of 64 tokens from the last to the first) forms them in a fixed
+// order and stores dq, dk, dlam in the caller's type.  lambda must be > 0 where it is applied, and the result loses precision like
 // 1 / lambda for very small decays (the quotient of a rounded sum).
 #include <stdlib.h>
 #include <string.h>
@@ -41,8 +40,7 @@
 
 namespace lasad {
 
-hipError_t launch_backward_gated_pass(const ForwardArgs &a, const scan::ScanRoles &roles, int kind, int shift,
-                                      int q_one_minus, hipStream_t s);
+hipError_t launch_backward_gated_passes(const ForwardArgs *a, const scan::ScanRoles *roles, bool tied, hipStream_t s);
 
 namespace {
 
@@ -70,56 +68,101 @@ backward_gated_walk_kernel(WalkArgs w)
     else scan_sequence<IN_BF16, 0, ROLES_COL, NJ>(a, bh, j0, lds, &w.roles[pass]);     // fp32 into the workspace
 }
 
-constexpr int kFinWaves = 16;
+constexpr int kFinThreads = 1024;
+constexpr int kFinBlock = 64;          // tokens per step of the finishing kernel
 
+// One workgroup per sequence walks it in blocks of 64 tokens from the last block to the first,
+// every thread holding four channels of one token (16-byte loads; the next block's loads are in
+// flight while this one is worked on).  Per block: r = q dq - k dk into LDS, suffix sums down the
+// block's tokens per channel (four 16-token quarters side by side, then their totals), outputs,
+// and the block's total joins the carry.  Every input is read once; the order of all sums is fixed.
 template <int IN_BF16, int OUT_BF16>
-__global__ void __launch_bounds__(kFinWaves * 64)
+__global__ void __launch_bounds__(kFinThreads)
 backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float *dk32)
 {
-    __shared__ float part[kFinWaves][kD];
+    __shared__ __attribute__((aligned(16))) float sR[kFinBlock][kD + 4];
+    __shared__ __attribute__((aligned(16))) float sQtr[4][kD];
+    __shared__ __attribute__((aligned(16))) float sCarry[kD];
     const int bh = blockIdx.x, b = bh / a.Hh, h = bh - b * a.Hh;
-    const int wave = threadIdx.x >> 6, c = threadIdx.x & 63;
+    const int tid = threadIdx.x;
+    const int row = tid >> 4, c4 = (tid & 15) * 4;
     const int n = a.n_tokens;
-    const int per = (n + kFinWaves - 1) / kFinWaves;
-    const int t_lo = min(wave * per, n), t_hi = min(t_lo + per, n);     // this wave's tokens
-    const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + c;
-    const int64_t g_base = (int64_t)b * a.grad.stride_b + (int64_t)h * a.grad.stride_h + c;
-    const int64_t w_base = ((int64_t)b * n * a.Hh + h) * kD + c;         // workspace: [B][n][Hh][d] fp32
+    const int nblk = (n + kFinBlock - 1) / kFinBlock;
+    const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + c4;
+    const int64_t g_base = (int64_t)b * a.grad.stride_b + (int64_t)h * a.grad.stride_h + c4;
+    const int64_t w_base = ((int64_t)b * n * a.Hh + h) * kD + c4;        // workspace: [B][n][Hh][d] fp32
     const int64_t w_stride_n = (int64_t)a.Hh * kD;
-    auto in_val = [&](const void *p, int t) {
+
+    struct Item { f4 q, k, lam, dq, dk; };
+    auto in4 = [&](const void *p, int t) {
         const int64_t i = in_base + (int64_t)t * a.in.stride_n;
-        return IN_BF16 ? bf16_bits_to_float(((const uint16_t *)p)[i]) : ((const float *)p)[i];
+        if (IN_BF16) {
+            const uint2 w = *(const uint2 *)((const uint16_t *)p + i);
+            return f4{__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
+                      __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u)};
+        }
+        return *(const f4 *)((const float *)p + i);
     };
-    auto put = [&](void *p, int t, float x) {
+    auto load = [&](int blk, Item &it) {
+        const int t = min(blk * kFinBlock + row, n - 1);
+        it.q = in4(a.q, t);
+        it.lam = in4(a.lam, t);
+        if (a.k) it.k = in4(a.k, t);
+        else it.k = f4{1.0f, 1.0f, 1.0f, 1.0f} - it.lam;
+        it.dq = *(const f4 *)(dq32 + w_base + t * w_stride_n);
+        it.dk = *(const f4 *)(dk32 + w_base + t * w_stride_n);
+    };
+    auto put4 = [&](void *p, int t, f4 x) {
         const int64_t i = g_base + (int64_t)t * a.grad.stride_n;
-        if (OUT_BF16) ((uint16_t *)p)[i] = float_to_bf16_bits(x);
-        else ((float *)p)[i] = x;
+        if (OUT_BF16) {
+            uint2 w;
+            w.x = (uint32_t)float_to_bf16_bits(x[0]) | ((uint32_t)float_to_bf16_bits(x[1]) << 16);
+            w.y = (uint32_t)float_to_bf16_bits(x[2]) | ((uint32_t)float_to_bf16_bits(x[3]) << 16);
+            *(uint2 *)((uint16_t *)p + i) = w;
+        } else {
+            *(f4 *)((float *)p + i) = x;
+        }
     };
-    auto r_term = [&](int t, float &lam, float &dk) {
-        lam = in_val(a.lam, t);
-        const float k = a.k ? in_val(a.k, t) : 1.0f - lam;
-        dk = dk32[w_base + t * w_stride_n];
-        return in_val(a.q, t) * dq32[w_base + t * w_stride_n] - k * dk;
-    };
-    // sum of this wave's token range, top down (the order of the walk below)
-    float sum = 0.f;
-    for (int t = t_hi - 1; t >= t_lo; --t) {
-        float lam, dk;
-        sum += r_term(t, lam, dk);
-    }
-    part[wave][c] = sum;
-    __syncthreads();
-    float suffix = 0.f;                    // sum over the tokens after this wave's range
-    for (int w2 = kFinWaves - 1; w2 > wave; --w2) suffix += part[w2][c];
-    for (int t = t_hi - 1; t >= t_lo; --t) {
-        float lam, dk;
-        suffix += r_term(t, lam, dk);
-        const bool no_decay = t == 0 || is_boundary(a.start_pos + t + 1, a.grid_w, a.mode);
-        float dl = no_decay ? 0.f : suffix / lam;
-        if (!a.k) dl -= dk;
-        put(a.dlam, t, dl);
-        put(a.dq, t, dq32[w_base + t * w_stride_n]);
-        if (a.k) put(a.dk, t, dk);
+
+    if (tid < kD) sCarry[tid] = 0.f;
+    Item cur;
+    load(nblk - 1, cur);
+    for (int blk = nblk - 1; blk >= 0; --blk) {
+        Item nxt = cur;
+        if (blk > 0) load(blk - 1, nxt);
+        const int t = blk * kFinBlock + row;
+        const bool live = t < n;
+        f4 r = cur.q * cur.dq - cur.k * cur.dk;
+        if (!live) r = f4{0.f, 0.f, 0.f, 0.f};
+        *(f4 *)&sR[row][c4] = r;
+        __syncthreads();
+        if (tid < 4 * kD) {                // suffix sums inside a quarter of the block, top down
+            const int c = tid & (kD - 1), qtr = tid >> 6;
+            float acc = 0.f;
+#pragma unroll
+            for (int tt = 15; tt >= 0; --tt) {
+                acc += sR[16 * qtr + tt][c];
+                sR[16 * qtr + tt][c] = acc;
+            }
+            sQtr[qtr][c] = acc;
+        }
+        __syncthreads();
+        {
+            f4 suffix = *(const f4 *)&sR[row][c4] + *(const f4 *)&sCarry[c4];
+            for (int q2 = 3; q2 > (row >> 4); --q2) suffix += *(const f4 *)&sQtr[q2][c4];
+            const bool no_decay = t == 0 || is_boundary(a.start_pos + t + 1, a.grid_w, a.mode);
+            f4 dl = suffix / cur.lam;
+            if (no_decay) dl = f4{0.f, 0.f, 0.f, 0.f};
+            if (!a.k) dl -= cur.dk;
+            if (live) {
+                put4(a.dlam, t, dl);
+                put4(a.dq, t, cur.dq);
+                if (a.k) put4(a.dk, t, cur.dk);
+            }
+        }
+        __syncthreads();
+        if (tid < kD) sCarry[tid] += (sQtr[3][tid] + sQtr[2][tid]) + (sQtr[1][tid] + sQtr[0][tid]);
+        cur = nxt;
     }
 }
 
@@ -203,18 +246,14 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     hipError_t e;
     if (in16 && !force_walk) {
         // matrix-core passes: the pass's operands in the forward's fields
-        ForwardArgs p = f;
-        p.q = b.d_o; p.lam = b.lam; p.k = b.k; p.v = b.v; p.o = dq32;                      // dq
-        p.in = b.in; p.out = wl; p.out_dtype = LASAD_F32; p.start_pos = b.start_pos;
-        e = launch_backward_gated_pass(p, w.roles[0], 1, 0, 0, s);
-        if (e != hipSuccess) return e;
-        p.q = b.k ? k_l : lam_l; p.lam = lam_l; p.k = q_l; p.v = g_l; p.o = w.o[1];         // dv
-        p.in = in_rev; p.out = grad_rev; p.out_dtype = b.grad_dtype; p.start_pos = rev_start;
-        e = launch_backward_gated_pass(p, w.roles[1], 0, 1, b.k ? 0 : 1, s);
-        if (e != hipSuccess) return e;
-        p.q = v_l; p.lam = lam_l; p.k = q_l; p.v = g_l; p.o = w.o[2];                       // dk
-        p.out = wl_rev; p.out_dtype = LASAD_F32;
-        e = launch_backward_gated_pass(p, w.roles[2], 1, 1, 0, s);
+        ForwardArgs p[3] = {f, f, f};
+        p[0].q = b.d_o; p[0].lam = b.lam; p[0].k = b.k; p[0].v = b.v; p[0].o = dq32;                  // dq
+        p[0].in = b.in; p[0].out = wl; p[0].out_dtype = LASAD_F32; p[0].start_pos = b.start_pos;
+        p[1].q = b.k ? k_l : lam_l; p[1].lam = lam_l; p[1].k = q_l; p[1].v = g_l; p[1].o = w.o[1];     // dv
+        p[1].in = in_rev; p[1].out = grad_rev; p[1].out_dtype = b.grad_dtype; p[1].start_pos = rev_start;
+        p[2] = p[1];
+        p[2].q = v_l; p[2].o = w.o[2]; p[2].out = wl_rev; p[2].out_dtype = LASAD_F32;                  // dk
+        e = launch_backward_gated_passes(p, w.roles, b.k == nullptr, s);
         if (e != hipSuccess) return e;
     } else {
         if (in16 && out16) launch_walks<1, 1>(w, n_seq, s);
@@ -225,7 +264,7 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
         if (e != hipSuccess) return e;
     }
 
-    const dim3 grid((unsigned)n_seq), block(kFinWaves * 64);
+    const dim3 grid((unsigned)n_seq), block(kFinThreads);
     if (in16 && out16) hipLaunchKernelGGL((backward_gated_finish_kernel<1, 1>), grid, block, 0, s, b, dq32, dk32);
     else if (in16) hipLaunchKernelGGL((backward_gated_finish_kernel<1, 0>), grid, block, 0, s, b, dq32, dk32);
     else hipLaunchKernelGGL((backward_gated_finish_kernel<0, 0>), grid, block, 0, s, b, dq32, dk32);

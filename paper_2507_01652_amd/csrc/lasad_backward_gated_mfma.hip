@@ -37,16 +37,12 @@ __device__ __noinline__ void redo_roles(ForwardArgs a, scan::ScanRoles r, int bh
     else scan::scan_sequence<1, OUT_BF16, scan::ROLES_ROW, 64>(a, bh, 0, lds, &r);
 }
 
+// One pass for sequence bh by the calling twelve-wave workgroup.  smem: 2 * kBwdSetHalfs bf16 elements.
 template <int OUT_BF16, int OWNKEY, int SHIFT, int QMODE, int COL>
-__global__ void __launch_bounds__(kBwdThreads, 1)
-backward_gated_ws_kernel(ForwardArgs a, scan::ScanRoles roles)
+__device__ __forceinline__ void pass_body(const ForwardArgs &a, const scan::ScanRoles &roles, int bh,
+                                          uint16_t *smem, float (*sTot)[D], int (*sTrip)[4])
 {
     static_assert(!COL || (QMODE == 1 && !OUT_BF16), "column passes: query of ones, fp32 output");
-    constexpr int kScanFloats = scan::lds_floats<scan::ROLES_ROW>();
-    static_assert(2 * kBwdSetHalfs * 2 >= kScanFloats * 4, "the fallback needs the LDS block");
-    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBwdSetHalfs];
-    __shared__ __attribute__((aligned(16))) float sTot[2][D];  // A_end per key channel, by chunk parity
-    __shared__ __attribute__((aligned(16))) int sTrip[2][4];   // range flag of each loader wave, by barrier parity
     auto sQh = [&](int p) { return smem + p * kBwdSetHalfs; };
     auto sQl = [&](int p) { return smem + p * kBwdSetHalfs + C * RS; };
     auto sKh = [&](int p) { return smem + p * kBwdSetHalfs + 2 * C * RS; };
@@ -56,7 +52,6 @@ backward_gated_ws_kernel(ForwardArgs a, scan::ScanRoles roles)
     auto sSl = [&](int p) { return smem + p * kBwdSetHalfs + 2 * C * RS + 2 * C * KS + C * TS + D * RS; };
     auto sO = [&](int p) { return smem + p * kBwdSetHalfs + 2 * C * RS + 2 * C * KS + C * TS + 2 * D * RS; };
 
-    const int bh = blockIdx.x;
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -377,33 +372,53 @@ backward_gated_ws_kernel(ForwardArgs a, scan::ScanRoles roles)
     }
 }
 
+struct PassSet {
+    ForwardArgs a[3];              // dq, dv, dk: the pass's operands in the forward's fields
+    scan::ScanRoles roles[3];      // the same passes for the token-serial walk (range fallback)
+};
+
+// The three passes of a call in one launch.  Workgroups come in groups of 8 sequences x 3 passes,
+// a sequence's passes 8 workgroup ids apart: they start together on the same XCD (ids go round
+// the 8 XCDs) and share what they both read through its L2 (dv and dk walk the same q, d_o and
+// lambda rows in the same order).  TIED: the key is 1 - lambda.
+template <int OUT_BF16, int TIED>
+__global__ void __launch_bounds__(kBwdThreads, 1)
+backward_gated_passes_kernel(PassSet ps)
+{
+    constexpr int kScanFloats = scan::lds_floats<scan::ROLES_ROW>();
+    static_assert(2 * kBwdSetHalfs * 2 >= kScanFloats * 4, "the fallback needs the LDS block");
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBwdSetHalfs];
+    __shared__ __attribute__((aligned(16))) float sTot[2][D];  // A_end per key channel, by chunk parity
+    __shared__ __attribute__((aligned(16))) int sTrip[2][4];   // range flag of each loader wave, by barrier parity
+    const int grp = blockIdx.x / 24, r = blockIdx.x - grp * 24;
+    const int pass = r >> 3, bh = grp * 8 + (r & 7);
+    if (bh >= ps.a[0].B * ps.a[0].Hh) return;                  // (the last group may be partly empty)
+    if (pass == 0) pass_body<0, TIED ? 0 : 1, 0, 1, 1>(ps.a[0], ps.roles[0], bh, smem, sTot, sTrip);
+    else if (pass == 1) pass_body<OUT_BF16, 1, 1, TIED ? 2 : 0, 0>(ps.a[1], ps.roles[1], bh, smem, sTot, sTrip);
+    else pass_body<0, 1, 1, 1, 1>(ps.a[2], ps.roles[2], bh, smem, sTot, sTrip);
+}
+
 }  // namespace
 
-// One pass of the vector-decay backward with the matrix-core kernel.  a: the pass's operands in the
-// forward's fields (q: query-side tensor, lam: decay, k: own key or NULL, v: value-side tensor);
-// roles: the same pass for the token-serial walk (range fallback).  kind 0: ROW pass, query taken
-// as 1 - x when q_one_minus; kind 1: COL pass; shift: decay of step m from the decay tensor's
-// step m - 1.
-hipError_t launch_backward_gated_pass(const ForwardArgs &a, const scan::ScanRoles &roles, int kind, int shift,
-                                      int q_one_minus, hipStream_t s)
+// The three passes of the vector-decay backward with the matrix-core kernel, one launch.
+// a[0..2], roles[0..2]: dq (column pass, forward order), dv (row pass, reversed; its query tensor
+// is lambda itself when tied), dk (column pass, reversed), as lasad_backward_gated.hip sets them up.
+hipError_t launch_backward_gated_passes(const ForwardArgs *a, const scan::ScanRoles *roles, bool tied, hipStream_t s)
 {
-    if (a.d != D || a.io_dtype != LASAD_BF16 || a.n_tokens < 1 || !a.lam) return hipErrorInvalidValue;
-    const int64_t n_seq = (int64_t)a.B * a.Hh;
-    if (n_seq > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)n_seq), block(kBwdThreads);
-    const bool out16 = a.out_dtype == LASAD_BF16;
-#define LASAD_BWD_LAUNCH(O, K, S, Q, C_) hipLaunchKernelGGL((backward_gated_ws_kernel<O, K, S, Q, C_>), grid, block, 0, s, a, roles)
-    if (kind == 0) {                   // dv: own key (the forward's q), shifted decay
-        if (!a.k || !shift) return hipErrorInvalidValue;
-        if (q_one_minus) { if (out16) LASAD_BWD_LAUNCH(1, 1, 1, 2, 0); else LASAD_BWD_LAUNCH(0, 1, 1, 2, 0); }
-        else { if (out16) LASAD_BWD_LAUNCH(1, 1, 1, 0, 0); else LASAD_BWD_LAUNCH(0, 1, 1, 0, 0); }
+    if (a[0].d != D || a[0].io_dtype != LASAD_BF16 || a[0].n_tokens < 1) return hipErrorInvalidValue;
+    const int64_t n_seq = (int64_t)a[0].B * a[0].Hh;
+    if ((n_seq + 7) / 8 * 24 > 0x7fffffff) return hipErrorInvalidValue;
+    PassSet ps;
+    for (int i = 0; i < 3; ++i) { ps.a[i] = a[i]; ps.roles[i] = roles[i]; }
+    const dim3 grid((unsigned)((n_seq + 7) / 8 * 24)), block(kBwdThreads);
+    const bool out16 = a[1].out_dtype == LASAD_BF16;
+    if (tied) {
+        if (out16) hipLaunchKernelGGL((backward_gated_passes_kernel<1, 1>), grid, block, 0, s, ps);
+        else hipLaunchKernelGGL((backward_gated_passes_kernel<0, 1>), grid, block, 0, s, ps);
     } else {
-        if (out16) return hipErrorInvalidValue;
-        if (shift) { if (!a.k) return hipErrorInvalidValue; LASAD_BWD_LAUNCH(0, 1, 1, 1, 1); }
-        else if (a.k) LASAD_BWD_LAUNCH(0, 1, 0, 1, 1);
-        else LASAD_BWD_LAUNCH(0, 0, 0, 1, 1);
+        if (out16) hipLaunchKernelGGL((backward_gated_passes_kernel<1, 0>), grid, block, 0, s, ps);
+        else hipLaunchKernelGGL((backward_gated_passes_kernel<0, 0>), grid, block, 0, s, ps);
     }
-#undef LASAD_BWD_LAUNCH
     return hipGetLastError();
 }
 
