@@ -139,3 +139,39 @@ def test_backward_gated_rejects_bad_arguments(lasad):
         lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 3)          # 8 tokens on a 2 x 3 grid
     with pytest.raises(Exception):
         lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 4, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+
+
+WALK_SCRIPT = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + '/tests')
+from paper_2507_01652_amd import binding as lasad, workloads as wl
+from oracle import lasad_oracle as oracle
+from helpers import rel_err
+worst = 0.0
+for B, Hh, H, W, own in ((2, 3, 13, 17, False), (1, 2, 5, 50, True)):
+    rng = np.random.default_rng(5 + B)
+    shape = (B, H * W, Hh, 64)
+    q, v, g = (wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(8.0), 'bf16') for _ in range(3))
+    lam = wl.gate_inputs(shape, 'bf16', 6 + B)
+    k = wl.store_round(rng.uniform(0.0, 1.0, size=shape).astype(np.float32), 'bf16') if own else None
+    dev = lambda x: None if x is None else lasad.to_device(x, 'bf16')
+    got = lasad.lasad_backward_gated(dev(q), dev(lam), dev(v), dev(g), H, W, k=dev(k), grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ref = oracle.gated_backward(q, lam, v, g, W, k=k)
+    for a, r in zip(got, ref):
+        worst = max(worst, rel_err(a.cpu().numpy(), r))
+print('WORST', worst)
+assert worst <= 2e-2
+"""
+
+
+def test_backward_gated_walk_kernels_on_bf16():
+    """The token-serial walks forced for bf16 inputs (the choice is read from the environment once per process,
+    hence the child process); by default bf16 takes the matrix-core passes and only fp32 inputs the walks."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", WALK_SCRIPT, root], env={**os.environ, "LASAD_GATED_BWD": "walk"},
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
