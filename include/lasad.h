@@ -136,6 +136,27 @@ int lasad_decode_step(const void *q, const void *k, const void *v, void *o,
                       float *state, void *hip_stream);
 
 /*
+ * The same decode step from a key / value cache instead of the d x d state, for the first
+ * positions of a sequence that started from a zero state at position 0: the recurrence unrolled,
+ *     o = q_scale sum_{j<=pos} lambda_{j+1} .. lambda_pos (q . k_j) v_j     (Section 3.4, first equation),
+ * reads (pos + 1) rows of k and v where the state form moves the whole fp32 state (the memory
+ * trade Section 1 describes for a growing cache), which is less traffic while pos + 1 < d for
+ * fp32 rows (2 d for bf16: the first 128 positions at d = 64).  This step's k and v are appended to the caches (row pos) by the call.
+ *   q, k, v          [B, n_heads, d] contiguous, io_dtype; o same shape, out_dtype.
+ *   k_cache, v_cache [B, n_heads, cache_tokens, d] contiguous, io_dtype, owned by the caller; rows
+ *                    0 .. pos-1 must hold the earlier steps' k and v; pos < cache_tokens.
+ *   d                32, 64 or 128.
+ * To continue with lasad_decode_step, build the state once with lasad_forward_chunked over the
+ * cached rows (layout strides {n_heads*cache_tokens*d, d, cache_tokens*d}, state_out).
+ */
+int lasad_decode_step_cached(const void *q, const void *k, const void *v, void *o,
+                             void *k_cache, void *v_cache, int cache_tokens,
+                             int io_dtype, int out_dtype, int B, int n_heads, int d,
+                             int grid_h, int grid_w, int pos,
+                             const float *gamma, int boundary_mode, float q_scale,
+                             void *hip_stream);
+
+/*
  * Vector, data-dependent decay: the recurrence exactly as Section 3.4 / Algorithm 1 write it.
  * Every token carries a decay vector lambda_t in [0, 1]^d over the key channels,
  *     s_t = diag(lambda_t^spatial) s_{t-1} + k_t v_t^T,   o_t^T = q_scale * q_t^T s_t,

@@ -22,7 +22,7 @@ EXPORTS = (
     "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
     "lasad_forward_layer", "lasad_decode_step_layer",
-    "lasad_decode_step_rows", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
+    "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_backward_gated_workspace_bytes", "lasad_backward_gated",
     "lasad_last_error", "lasad_version",
 )
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.lasad_decode_step_layer.restype = ci
     lib.lasad_decode_step_rows.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, ci, cf, vp, vp]
     lib.lasad_decode_step_rows.restype = ci
+    lib.lasad_decode_step_cached.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, cf, vp]
+    lib.lasad_decode_step_cached.restype = ci
     lib.lasad_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.lasad_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.lasad_backward_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
@@ -200,6 +202,33 @@ def lasad_decode_step(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: 
     _check(load().lasad_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _dtype_code(q), _dtype_code(out),
                                     B, Hh, d, grid_h, grid_w, pos, _ptr(gamma), boundary_mode, q_scale,
                                     _ptr(state), _stream(stream)))
+    return out
+
+
+def lasad_decode_step_cached(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: torch.Tensor,
+                             k_cache: torch.Tensor, v_cache: torch.Tensor, grid_h: int, grid_w: int, pos: int,
+                             boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                             out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                             stream=None) -> torch.Tensor:
+    """The decode step at position `pos` from key / value caches (contiguous [B, Hh, T, d] of q's dtype,
+    rows 0..pos-1 filled by the earlier steps; this step's k, v are appended as row pos).  Returns o."""
+    B, Hh, d = q.shape
+    for t in (q, k, v):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("q, k, v must be contiguous [B, Hh, d] of one dtype")
+    for t in (k_cache, v_cache):
+        if t.dim() != 4 or tuple(t.shape[:2]) != (B, Hh) or t.shape[3] != d or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("caches must be contiguous [B, Hh, T, d] of q's dtype")
+    if k_cache.shape != v_cache.shape:
+        raise ValueError("k_cache and v_cache differ in shape")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hh, d]")
+    assert gamma.dtype == torch.float32 and gamma.is_contiguous() and tuple(gamma.shape) == (Hh,)
+    _check(load().lasad_decode_step_cached(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(k_cache), _ptr(v_cache),
+                                           k_cache.shape[2], _dtype_code(q), _dtype_code(out), B, Hh, d,
+                                           grid_h, grid_w, pos, _ptr(gamma), boundary_mode, q_scale, _stream(stream)))
     return out
 
 

@@ -24,6 +24,7 @@ SOURCES = [
     "lasad_forward_gated_mfma.hip",
     "lasad_forward_gated_ws.hip",
     "lasad_decode.hip",
+    "lasad_decode_cached.hip",
     "lasad_backward.hip",
     "lasad_backward_gated.hip",
     "lasad_backward_gated_mfma.hip",

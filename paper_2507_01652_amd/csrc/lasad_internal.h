@@ -97,6 +97,21 @@ struct BackwardArgs {
     float *dq32, *dk32, *seq_sums;
 };
 
+// Arguments of one decode step from a key / value cache, already validated.
+struct CachedDecodeArgs {
+    const void *q, *k, *v;       // [B, Hh, d]
+    void *o;
+    void *k_cache, *v_cache;     // [B, Hh, cache_tokens, d], type io_dtype; row pos is written, rows 0..pos-1 read
+    int io_dtype, out_dtype;
+    int B, Hh, d;
+    int cache_tokens;
+    int grid_w, pos;
+    const float *gamma;
+    int mode;
+    float q_scale;
+};
+hipError_t launch_decode_cached(const CachedDecodeArgs &a, hipStream_t s);
+
 // Arguments of one backward call of the vector-decay recurrence, already validated (d == 64).
 struct GatedBackwardArgs {
     const void *q, *lam, *k, *v, *d_o;   // k NULL: key tied to the decay, k = 1 - lam
