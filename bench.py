@@ -211,6 +211,42 @@ def bench_decode(args, torch, lasad, wl):
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_per_launch,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
     }
+    # The same walk with the first positions served from a key / value cache (fewer bytes than the state while
+    # t < 2 d), the state built from the cache once, and the state form for the rest.  As above every launch
+    # works on the next of L buffer sets; a launch's cost depends on its position only.
+    switch = min(2 * w.d, w.steps)
+    # (capacity switch + 8 rows: with a power-of-two distance between the sequences' caches the first rows of all
+    # caches fall on the same few memory channels and the early steps run at a fraction of the bandwidth)
+    cap = switch + 8
+    kcs = [torch.zeros((w.B, w.Hh, cap, w.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    vcs = [torch.zeros_like(kcs[0]) for _ in range(L)]
+    fwd_out = torch.empty((w.B, switch, w.Hh, w.d), dtype=torch.bfloat16, device="cuda")
+    as_seq = lambda c: c.permute(0, 2, 1, 3)
+
+    def run_hybrid(nsteps):
+        for i in range(nsteps):
+            t, l = i % w.steps, i % L
+            if t < switch:
+                lasad.lasad_decode_step_cached(tq[t], tk[t], tv[t], tg, kcs[l], vcs[l], w.grid_h, w.grid_w, t, out=outs[l])
+            else:
+                if t == switch:
+                    lasad.lasad_forward_chunked(as_seq(kcs[l][:, :, :switch]), as_seq(kcs[l][:, :, :switch]),
+                                                as_seq(vcs[l][:, :, :switch]), tg, w.grid_h, w.grid_w,
+                                                state_out=states[l], out=fwd_out, use_workspace=False)
+                lasad.lasad_decode_step(tq[t], tk[t], tv[t], tg, states[l], w.grid_h, w.grid_w, t, out=outs[l])
+
+    run_hybrid(w.steps)
+    hyb_ms = time_region(torch, lambda: run_hybrid(n_steps))
+    if not args.no_graph:
+        gh = capture(torch, lambda: run_hybrid(n_steps))
+        gh.replay()
+        hyb_ms = time_region(torch, gh.replay)
+    res["cache_then_state"] = {
+        "what": f"positions 0..{switch - 1} from a k/v cache (lasad_decode_step_cached), the state built from the cache by one "
+                "lasad_forward_chunked call per walk, lasad_decode_step afterwards",
+        "ms_per_step": hyb_ms / n_steps, "value": n_steps / (hyb_ms * 1e-3), "unit": "steps/s",
+        "speedup_vs_state_form": total_ms / hyb_ms}
+    del kcs, vcs, fwd_out
     if not args.no_cpu_baseline:
         import numpy as np
         from oracle import lasad_oracle as oracle

@@ -7,11 +7,15 @@
 // A caller switches to the state form by building the state from the cache with one
 // lasad_forward_chunked call (state_out) over the cached rows.
 //
-// One 256-thread workgroup per (batch, head).  Tokens go in tiles of 256: thread j forms the
-// decayed score of token j against the query (its own k row, 16-byte loads), then thread
-// (channel c, part p) adds score_j v_j[c] over the tokens j = p mod PARTS (v rows read by
-// consecutive lanes); the parts are added in a fixed order.  The step's own k and v come from the
-// call's arguments and are appended to the cache by the same launch.
+// One wavefront per (batch, head), four to a workgroup (the form is meant for few cached tokens:
+// a whole workgroup per sequence spent its time on launch and barriers).  A token's k (and v) row is
+// read by D / 8 consecutive lanes (bf16; D / 4 for fp32) with one 16-byte load each, so the
+// wavefront takes 64 / (D / 8) tokens per step, four steps in flight.  A lane keeps its 8 query
+// entries and 8 output accumulators in registers: partial dot over its channels, butterfly over
+// the lanes of the token, decay weight, then score * v into the accumulators; at the end the
+// accumulators are added over the token slots by butterflies (fixed order).  No LDS, no barrier.
+// The step's own k and v come from the call's arguments and are appended to the cache by the
+// same launch.
 #include "lasad_internal.h"
 
 namespace lasad {
@@ -20,94 +24,110 @@ namespace {
 
 constexpr int kCdThreads = 256;
 
-template <int IN_BF16>
-__device__ inline float cd_load(const void *p, int64_t i)
+template <int IN_BF16, int VEC>
+__device__ inline void cd_unpack(const uint4 w, float (&f)[VEC])
 {
-    return IN_BF16 ? bf16_bits_to_float(((const uint16_t *)p)[i]) : ((const float *)p)[i];
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+    if (IN_BF16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = __uint_as_float(ww[e] << 16);
+            f[2 * e + 1] = __uint_as_float(ww[e] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(ww[e]);
+    }
 }
 
 template <int IN_BF16, int OUT_BF16, int D>
 __global__ void __launch_bounds__(kCdThreads)
 decode_cached_kernel(CachedDecodeArgs a)
 {
-    constexpr int PARTS = kCdThreads / D;
     constexpr int VEC = IN_BF16 ? 8 : 4;                  // elements per 16-byte load
-    __shared__ __attribute__((aligned(16))) float sQ[D];
-    __shared__ float sS[kCdThreads];
-    __shared__ float sRed[PARTS][D];
-    const int bh = blockIdx.x, h = bh % a.Hh;
-    const int tid = threadIdx.x;
+    constexpr int LPT = D / VEC;                          // lanes per token row
+    constexpr int TPW = 64 / LPT;                         // tokens per step
+    constexpr int UNROLL = 4;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int64_t bh = (int64_t)blockIdx.x * 4 + wave;
+    if (bh >= (int64_t)a.B * a.Hh) return;
+    const int h = (int)(bh % a.Hh);
+    const int piece = lane % LPT, slot = lane / LPT;      // 16-byte piece of the row; token slot in the wavefront
     const int pos = a.pos;
-    const int64_t tok_base = (int64_t)bh * D;                              // q, k, v, o: [B, Hh, d]
-    const int64_t cache_base = (int64_t)bh * a.cache_tokens * D;          // caches: [B, Hh, T, d]
     const int elt = IN_BF16 ? 2 : 4;
+    const char *q_row = (const char *)a.q + (bh * D + piece * VEC) * elt;               // q, k, v, o: [B, Hh, d]
+    const char *k_row = (const char *)a.k + (bh * D + piece * VEC) * elt;
+    const char *v_row = (const char *)a.v + (bh * D + piece * VEC) * elt;
+    const int64_t cache_off = (bh * a.cache_tokens * D + piece * VEC) * elt;            // caches: [B, Hh, T, d]
+    const char *kc = (const char *)a.k_cache + cache_off, *vc = (const char *)a.v_cache + cache_off;
 
-    if (tid < D) sQ[tid] = cd_load<IN_BF16>(a.q, tok_base + tid);
-    if (tid < 2 * D / VEC) {                                              // append this step's k and v rows
-        const int which = tid / (D / VEC), piece = tid - which * (D / VEC);
-        const char *src = (const char *)(which ? a.v : a.k) + (tok_base + piece * VEC) * elt;
-        char *dst = (char *)(which ? a.v_cache : a.k_cache) + (cache_base + (int64_t)pos * D + piece * VEC) * elt;
-        *(uint4 *)dst = *(const uint4 *)src;
+    float qf[VEC];
+    cd_unpack<IN_BF16, VEC>(*(const uint4 *)q_row, qf);
+    if (slot < 2) {                                       // append this step's k and v rows
+        char *dst = (char *)(slot ? a.v_cache : a.k_cache) + cache_off + (int64_t)pos * D * elt;
+        *(uint4 *)dst = *(const uint4 *)(slot ? v_row : k_row);
     }
     const float lg = log2f(a.gamma[h]);
     const int e_now = cum_exp(pos + 1, a.grid_w, a.mode);
-    __syncthreads();
 
-    const int c = tid % D, part = tid / D;
-    float acc = 0.f;
-    for (int j0 = 0; j0 <= pos; j0 += kCdThreads) {
-        {   // score of token j0 + tid
-            const int j = j0 + tid;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    for (int j0 = 0; j0 <= pos; j0 += UNROLL * TPW) {
+        uint4 kw[UNROLL], vw[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            // (row pos comes from the arguments: the append above is not ordered against these loads)
+            const int jc = min(j0 + u * TPW + slot, pos);
+            kw[u] = *(const uint4 *)(jc == pos ? k_row : kc + (int64_t)jc * D * elt);
+            vw[u] = *(const uint4 *)(jc == pos ? v_row : vc + (int64_t)jc * D * elt);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int j = j0 + u * TPW + slot;
+            const int jc = min(j, pos);
+            float kf[VEC], vf[VEC];
+            cd_unpack<IN_BF16, VEC>(kw[u], kf);
+            cd_unpack<IN_BF16, VEC>(vw[u], vf);
             float s = 0.f;
-            if (j <= pos) {
-                const char *row = j == pos ? (const char *)a.k + tok_base * elt
-                                           : (const char *)a.k_cache + (cache_base + (int64_t)j * D) * elt;
 #pragma unroll
-                for (int i = 0; i < D / VEC; ++i) {
-                    const uint4 w = *(const uint4 *)(row + i * 16);
-                    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-                    if (IN_BF16) {
+            for (int e = 0; e < VEC; ++e) s = fmaf(qf[e], kf[e], s);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            s = fmaf(__uint_as_float(ww[e] << 16), sQ[i * 8 + 2 * e], s);
-                            s = fmaf(__uint_as_float(ww[e] & 0xffff0000u), sQ[i * 8 + 2 * e + 1], s);
-                        }
-                    } else {
+            for (int off = LPT / 2; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+            const int de = e_now - cum_exp(jc + 1, a.grid_w, a.mode);        // decays applied after token j
+            s *= de == 0 ? 1.0f : __builtin_amdgcn_exp2f((float)de * lg);
+            s = j <= pos ? s : 0.f;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) s = fmaf(__uint_as_float(ww[e]), sQ[i * 4 + e], s);
-                    }
-                }
-                const int de = e_now - cum_exp(j + 1, a.grid_w, a.mode);     // decays applied after token j
-                s *= de == 0 ? 1.0f : __builtin_amdgcn_exp2f((float)de * lg);
-            }
-            sS[tid] = s;
+            for (int e = 0; e < VEC; ++e) acc[e] = fmaf(s, vf[e], acc[e]);
         }
-        __syncthreads();
-        const int nj = min(kCdThreads, pos + 1 - j0);
-        for (int jj = part; jj < nj; jj += PARTS) {
-            const int j = j0 + jj;
-            const float vj = j == pos ? cd_load<IN_BF16>(a.v, tok_base + c)
-                                      : cd_load<IN_BF16>(a.v_cache, cache_base + (int64_t)j * D + c);
-            acc = fmaf(sS[jj], vj, acc);
-        }
-        __syncthreads();
     }
-    sRed[part][c] = acc;
-    __syncthreads();
-    if (tid < D) {
-        float o = 0.f;
+    // over the token slots of the wavefront
 #pragma unroll
-        for (int p = 0; p < PARTS; ++p) o += sRed[p][tid];
-        o *= a.q_scale;
-        if (OUT_BF16) ((uint16_t *)a.o)[tok_base + tid] = float_to_bf16_bits(o);
-        else ((float *)a.o)[tok_base + tid] = o;
+    for (int off = LPT; off < 64; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+    if (slot == 0) {
+        if (OUT_BF16) {
+            uint4 w;
+            w.x = (uint32_t)float_to_bf16_bits(a.q_scale * acc[0]) | ((uint32_t)float_to_bf16_bits(a.q_scale * acc[1]) << 16);
+            w.y = (uint32_t)float_to_bf16_bits(a.q_scale * acc[2]) | ((uint32_t)float_to_bf16_bits(a.q_scale * acc[3]) << 16);
+            w.z = (uint32_t)float_to_bf16_bits(a.q_scale * acc[4 % VEC]) | ((uint32_t)float_to_bf16_bits(a.q_scale * acc[5 % VEC]) << 16);
+            w.w = (uint32_t)float_to_bf16_bits(a.q_scale * acc[6 % VEC]) | ((uint32_t)float_to_bf16_bits(a.q_scale * acc[7 % VEC]) << 16);
+            *(uint4 *)((uint16_t *)a.o + bh * D + piece * VEC) = w;         // (bf16 output implies bf16 input: VEC = 8)
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; e += 4)
+                *(float4 *)((float *)a.o + bh * D + piece * VEC + e) =
+                    make_float4(a.q_scale * acc[e], a.q_scale * acc[e + 1], a.q_scale * acc[e + 2], a.q_scale * acc[e + 3]);
+        }
     }
 }
 
 template <int D>
 void launch_d(const CachedDecodeArgs &a, hipStream_t s)
 {
-    const dim3 grid((unsigned)((int64_t)a.B * a.Hh)), block(kCdThreads);
+    const dim3 grid((unsigned)(((int64_t)a.B * a.Hh + 3) / 4)), block(kCdThreads);
     const bool in16 = a.io_dtype == LASAD_BF16, out16 = a.out_dtype == LASAD_BF16;
     if (in16 && out16) hipLaunchKernelGGL((decode_cached_kernel<1, 1, D>), grid, block, 0, s, a);
     else if (in16) hipLaunchKernelGGL((decode_cached_kernel<1, 0, D>), grid, block, 0, s, a);
