@@ -30,16 +30,19 @@ using namespace gated;
 constexpr int kBwdThreads = 768;
 constexpr int kBwdSetHalfs = 2 * C * RS + 2 * C * KS + C * TS + 2 * D * RS + C * RS;   // one set of tiles
 
+// The token-serial walk of a pass, out of line.  It is handed the arguments where the launch put
+// them (the kernel-argument segment): references to the kernel's by-value parameter, or copies,
+// would make every thread of every launch write them to its stack first.
 template <int OUT_BF16, int COL>
-__device__ __noinline__ void redo_roles(ForwardArgs a, scan::ScanRoles r, int bh, float *lds)
+__device__ __noinline__ void redo_roles(const ForwardArgs *a, const scan::ScanRoles *r, int bh, float *lds)
 {
-    if (COL) scan::scan_sequence<1, 0, scan::ROLES_COL, 64>(a, bh, 0, lds, &r);
-    else scan::scan_sequence<1, OUT_BF16, scan::ROLES_ROW, 64>(a, bh, 0, lds, &r);
+    if (COL) scan::scan_sequence<1, 0, scan::ROLES_COL, 64>(*a, bh, 0, lds, r);
+    else scan::scan_sequence<1, OUT_BF16, scan::ROLES_ROW, 64>(*a, bh, 0, lds, r);
 }
 
 // One pass for sequence bh by the calling twelve-wave workgroup.  smem: 2 * kBwdSetHalfs bf16 elements.
 template <int OUT_BF16, int OWNKEY, int SHIFT, int QMODE, int COL>
-__device__ __forceinline__ void pass_body(const ForwardArgs &a, const scan::ScanRoles &roles, int bh,
+__device__ __forceinline__ void pass_body(const ForwardArgs &a, const ForwardArgs *ka, const scan::ScanRoles *kr, int bh,
                                           uint16_t *smem, float (*sTot)[D], int (*sTrip)[4])
 {
     static_assert(!COL || (QMODE == 1 && !OUT_BF16), "column passes: query of ones, fp32 output");
@@ -88,7 +91,7 @@ __device__ __forceinline__ void pass_body(const ForwardArgs &a, const scan::Scan
         return (f.x | f.y | f.z | f.w) != 0;
     };
     auto fallback = [&]() {
-        if (tid < scan::kThreads) redo_roles<OUT_BF16, COL>(a, roles, bh, (float *)smem);
+        if (tid < scan::kThreads) redo_roles<OUT_BF16, COL>(ka, kr, bh, (float *)smem);     // ka, kr: in the kernel-argument segment
     };
 
     if (group == 2) {
@@ -393,9 +396,10 @@ backward_gated_passes_kernel(PassSet ps)
     const int grp = blockIdx.x / 24, r = blockIdx.x - grp * 24;
     const int pass = r >> 3, bh = grp * 8 + (r & 7);
     if (bh >= ps.a[0].B * ps.a[0].Hh) return;                  // (the last group may be partly empty)
-    if (pass == 0) pass_body<0, TIED ? 0 : 1, 0, 1, 1>(ps.a[0], ps.roles[0], bh, smem, sTot, sTrip);
-    else if (pass == 1) pass_body<OUT_BF16, 1, 1, TIED ? 2 : 0, 0>(ps.a[1], ps.roles[1], bh, smem, sTot, sTrip);
-    else pass_body<0, 1, 1, 1, 1>(ps.a[2], ps.roles[2], bh, smem, sTot, sTrip);
+    const PassSet *kp = (const PassSet *)__builtin_amdgcn_kernarg_segment_ptr();
+    if (pass == 0) pass_body<0, TIED ? 0 : 1, 0, 1, 1>(ps.a[0], &kp->a[0], &kp->roles[0], bh, smem, sTot, sTrip);
+    else if (pass == 1) pass_body<OUT_BF16, 1, 1, TIED ? 2 : 0, 0>(ps.a[1], &kp->a[1], &kp->roles[1], bh, smem, sTot, sTrip);
+    else pass_body<0, 1, 1, 1, 1>(ps.a[2], &kp->a[2], &kp->roles[2], bh, smem, sTot, sTrip);
 }
 
 }  // namespace
