@@ -76,9 +76,14 @@ constexpr int kFinBlock = 64;          // tokens per step of the finishing kerne
 // flight while this one is worked on).  Per block: r = q dq - k dk into LDS, suffix sums down the
 // block's tokens per channel (four 16-token quarters side by side, then their totals), outputs,
 // and the block's total joins the carry.  Every input is read once; the order of all sums is fixed.
-template <int IN_BF16, int OUT_BF16>
+// Few long sequences are cut into n_seg segments of seg_blocks blocks with a workgroup each
+// (blockIdx.y): a first launch (TOTALS) only adds up r over each segment, the second starts every
+// segment from the totals of the segments after it.  seg_totals: [sequence][segment][d] fp32.
+// (fp64 sums were tried: no gain in accuracy, the error left is that of the fp32 dq and dk.)
+template <int IN_BF16, int OUT_BF16, int TOTALS>
 __global__ void __launch_bounds__(kFinThreads)
-backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float *dk32)
+backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float *dk32,
+                             float *seg_totals, int n_seg, int seg_blocks)
 {
     __shared__ __attribute__((aligned(16))) float sR[kFinBlock][kD + 4];
     __shared__ __attribute__((aligned(16))) float sQtr[4][kD];
@@ -124,12 +129,35 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         }
     };
 
-    if (tid < kD) sCarry[tid] = 0.f;
+    const int seg = blockIdx.y;
+    const int blk_lo = seg * seg_blocks, blk_hi = min(blk_lo + seg_blocks, nblk) - 1;     // this workgroup's blocks
+    float *totals = seg_totals + ((int64_t)bh * n_seg) * kD;
+    if (TOTALS) {
+        f4 sum = f4{0.f, 0.f, 0.f, 0.f};
+        for (int blk = blk_hi; blk >= blk_lo; --blk) {
+            Item it;
+            load(blk, it);
+            if (blk * kFinBlock + row < n) sum += it.q * it.dq - it.k * it.dk;
+        }
+        *(f4 *)&sR[row][c4] = sum;
+        __syncthreads();
+        if (tid < kD) {
+            float acc = 0.f;
+            for (int r2 = kFinBlock - 1; r2 >= 0; --r2) acc += sR[r2][tid];
+            totals[seg * kD + tid] = acc;
+        }
+        return;
+    }
+    if (tid < kD) {
+        float carry = 0.f;
+        for (int s2 = n_seg - 1; s2 > seg; --s2) carry += totals[s2 * kD + tid];
+        sCarry[tid] = carry;
+    }
     Item cur;
-    load(nblk - 1, cur);
-    for (int blk = nblk - 1; blk >= 0; --blk) {
+    load(blk_hi, cur);
+    for (int blk = blk_hi; blk >= blk_lo; --blk) {
         Item nxt = cur;
-        if (blk > 0) load(blk - 1, nxt);
+        if (blk > blk_lo) load(blk - 1, nxt);
         const int t = blk * kFinBlock + row;
         const bool live = t < n;
         f4 r = cur.q * cur.dq - cur.k * cur.dk;
@@ -196,7 +224,8 @@ void launch_walks(const WalkArgs &w, int64_t n_seq, hipStream_t s)
 
 size_t backward_gated_workspace_bytes(int64_t n_seq, int n_tokens, int d)
 {
-    return 2 * (size_t)n_seq * n_tokens * d * sizeof(float);
+    // dq and dk in fp32, then the finishing kernel's segment totals (at most 8 segments per sequence)
+    return 2 * (size_t)n_seq * n_tokens * d * sizeof(float) + (size_t)n_seq * 8 * d * sizeof(float);
 }
 
 hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
@@ -264,10 +293,30 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
         if (e != hipSuccess) return e;
     }
 
-    const dim3 grid((unsigned)n_seq), block(kFinThreads);
-    if (in16 && out16) hipLaunchKernelGGL((backward_gated_finish_kernel<1, 1>), grid, block, 0, s, b, dq32, dk32);
-    else if (in16) hipLaunchKernelGGL((backward_gated_finish_kernel<1, 0>), grid, block, 0, s, b, dq32, dk32);
-    else hipLaunchKernelGGL((backward_gated_finish_kernel<0, 0>), grid, block, 0, s, b, dq32, dk32);
+    // finishing kernel: one workgroup per sequence, or several segments per sequence when there are
+    // few long ones (then a first launch for the segment totals)
+    const int nblk = (n + kFinBlock - 1) / kFinBlock;
+    int n_seg = 1;
+    if (n_seq < 256 && nblk >= 8) {
+        n_seg = (int)(512 / n_seq);
+        if (n_seg > 8) n_seg = 8;
+        if (n_seg > nblk / 4) n_seg = nblk / 4;
+        if (n_seg < 1) n_seg = 1;
+    }
+    const int seg_blocks = (nblk + n_seg - 1) / n_seg;
+    n_seg = (nblk + seg_blocks - 1) / seg_blocks;
+    float *seg_totals = dk32 + (size_t)n_seq * n * b.d;          // after the two gradient tensors
+    const dim3 grid((unsigned)n_seq, (unsigned)n_seg), block(kFinThreads);
+#define LASAD_FIN_LAUNCH(I, O, T) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks)
+    if (n_seg > 1) {
+        if (in16) LASAD_FIN_LAUNCH(1, 0, 1); else LASAD_FIN_LAUNCH(0, 0, 1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (in16 && out16) LASAD_FIN_LAUNCH(1, 1, 0);
+    else if (in16) LASAD_FIN_LAUNCH(1, 0, 0);
+    else LASAD_FIN_LAUNCH(0, 0, 0);
+#undef LASAD_FIN_LAUNCH
     return hipGetLastError();
 }
 

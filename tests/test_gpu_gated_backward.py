@@ -51,7 +51,11 @@ def _check(lasad, oracle, B, Hh, H, W, dtype, seed, own_key, start=0, n=None, mo
     ref = oracle.gated_backward(q, lam, v, g, W, k=k, start_pos=start, mode=mode, q_scale=q_scale)
     names = ("dq", "dlam", "dv", "dk")
     for nm, a, r in zip(names, got, ref):
-        assert parity_err(a, r, grad_bf16) <= TOL[dtype], (nm, parity_err(a, r, grad_bf16))
+        # dlam is a suffix sum of q dq - k dk divided by lambda: the relative error that dq and dk may carry (the
+        # tolerance) is divided by the smallest decay of the input on its way into dlam (only matters for fp32,
+        # where the tolerance is near the rounding level of the fp32 walks)
+        tol = TOL[dtype] / float(lam.min()) if nm == "dlam" and dtype == "f32" else TOL[dtype]
+        assert parity_err(a, r, grad_bf16) <= tol, (nm, parity_err(a, r, grad_bf16))
 
 
 CASES = [
@@ -91,6 +95,13 @@ def test_backward_gated_layouts_and_grad_types(lasad, oracle, layout, grad_bf16)
 def test_backward_gated_many_sequences(lasad, oracle):
     """More than 170 sequences: one workgroup per sequence and pass (fewer: two)."""
     _check(lasad, oracle, 60, 3, 5, 8, "bf16", 9, False)
+
+
+@pytest.mark.parametrize("H,W,own_key", [(40, 16, False), (64, 20, True), (29, 17, False)])
+def test_backward_gated_long_sequences(lasad, oracle, H, W, own_key):
+    """Few long sequences: the finishing kernel works on several segments per sequence (two launches)."""
+    _check(lasad, oracle, 1, 2, H, W, "bf16", 300 + H, own_key, grad_bf16=True)
+    _check(lasad, oracle, 1, 2, H, W, "f32", 400 + H, own_key)
 
 
 def test_backward_gated_strong_decay(lasad, oracle):
