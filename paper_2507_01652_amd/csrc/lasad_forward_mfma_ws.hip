@@ -14,6 +14,8 @@
 // overlap their vector, matrix and LDS work, and the serial chain from one chunk to the next
 // shrinks to the state waves' part.  With a segment plan the state waves fold the partial states
 // of the earlier segments into their incoming state, as in the four-wave kernel.
+#include <stdlib.h>
+
 #include "lasad_forward_mfma_common.h"
 #include "lasad_recurrence.h"
 
@@ -358,7 +360,8 @@ hipError_t launch_forward_mfma_multi(const ForwardArgs &common, const MultiPass 
 {
     if (common.n_segments != 1 || m.n_pass < 1 || m.n_pass > 3) return hipErrorInvalidValue;
     const int64_t n_wg = (int64_t)common.B * common.Hh * m.n_pass;
-    if (n_wg <= 256) return launch_ws12_passes(common, m, s);
+    static const int ws = [] { const char *e = getenv("LASAD_WS_MULTI"); return e ? atoi(e) : -1; }();
+    if (ws == 12 || (ws < 0 && n_wg <= 256)) return launch_ws12_passes(common, m, s);
     return launch_ws8(common, m, s);
 }
 
