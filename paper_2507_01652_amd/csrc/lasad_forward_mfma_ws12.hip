@@ -42,6 +42,12 @@ __device__ long long g_prof_ws12[24 * 64];
 #else
 #define WPROF(slot) do { } while (0)
 #endif
+#ifdef LASAD_PROFILE
+// kernel entry (slot 7 of chunk 0) and the loader waves' last store (slot 23 of chunk 0) of workgroup 0
+#define WPROF_MARK(idx) do { if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) g_prof_ws12[idx] = __builtin_readcyclecounter(); } while (0)
+#else
+#define WPROF_MARK(idx) do { } while (0)
+#endif
 constexpr int kSetHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;   // one set of tiles
 
 __device__ inline int l32_of(int tid) { return tid & 31; }
@@ -78,6 +84,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     auto sO = [&](int p) { return smem + p * kSetHalfs + oO; };
     auto sPart = [&](int p, int part) { return (float *)(smem + p * kSetHalfs + oO) + part * C * PS; };
 
+    if (threadIdx.x == 0) WPROF_MARK(7);
     const int G = a.n_segments;
     // SPLIT 2: the two workgroups of a sequence (half = value-channel half) are 8 workgroup ids apart,
     // so they start together on the same XCD (ids go round the 8 XCDs) and what both read, Q and
@@ -183,6 +190,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
             WPROF(3);
         }
         if (OUT_BF16 || SPLIT == 2) store_tile(n_chunks - 1);
+        if (first_of_group) WPROF_MARK(23);
         return;
     }
 
