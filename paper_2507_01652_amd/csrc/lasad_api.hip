@@ -317,7 +317,7 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
     }
     hipStream_t s = (hipStream_t)hip_stream;
     if (n_tokens == 0) {
-        hipError_t e = hipMemsetAsync(dgamma, 0, sizeof(float) * (size_t)n_heads, s);
+        hipError_t e = lasad::launch_zero_f32(dgamma, n_heads, s);
         if (e != hipSuccess) return hip_fail("lasad_backward_chunked", e);
         return LASAD_OK;
     }

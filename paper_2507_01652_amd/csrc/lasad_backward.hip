@@ -164,6 +164,22 @@ const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
 
 // partial sums of the decay gradient: one per 64-token block of a sequence (finishing kernel) or
 // kDotSlots per pass and sequence (sums taken inside the forward kernels), whichever is more
+namespace {
+__global__ void zero_f32_kernel(float *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+}  // namespace
+
+// p[0..n) = 0 by a kernel (a memset node in a captured graph is best avoided on this platform)
+hipError_t launch_zero_f32(float *p, int n, hipStream_t s)
+{
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
 static size_t sums_bytes(int64_t n_seq, int n_tokens)
 {
     size_t per_seq = (size_t)(n_tokens + kFinTokens - 1) / kFinTokens;

@@ -151,6 +151,7 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 // Backward of the scalar-decay forward: three runs of the forward kernels (MFMA kernel if
 // use_mfma, else the generic / scan kernels) plus two small finishing kernels.
 hipError_t launch_backward(const BackwardArgs &a, bool use_mfma, hipStream_t s);
+hipError_t launch_zero_f32(float *p, int n, hipStream_t s);
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype);
 
 // ---- device helpers -----------------------------------------------------------

@@ -203,3 +203,14 @@ def test_backward_rejects_bad_arguments(lasad):
     assert e.value.status == 3       # workspace too small
     with pytest.raises(lasad.LasadError):
         lasad.lasad_backward_chunked(tq, tk, tv, tq.clone(), tg, w.grid_h, w.grid_w, grads=(tq, tk, tv))   # aliasing
+
+
+def test_backward_empty_call(lasad):
+    """No tokens: dgamma is zero, nothing else is touched."""
+    import torch
+    q = torch.zeros((2, 0, 3, 64), dtype=torch.bfloat16, device="cuda")
+    gam = torch.full((3,), 0.9, dtype=torch.float32, device="cuda")
+    dgam = torch.full((3,), 7.0, dtype=torch.float32, device="cuda")
+    lasad.lasad_backward_chunked(q, q.clone(), q.clone(), q.clone(), gam, 4, 4, dgamma=dgam)
+    torch.cuda.synchronize()
+    assert not dgam.cpu().numpy().any()

@@ -186,3 +186,11 @@ def test_backward_gated_walk_kernels_on_bf16():
     r = subprocess.run([sys.executable, "-c", WALK_SCRIPT, root], env={**os.environ, "LASAD_GATED_BWD": "walk"},
                        capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+def test_backward_gated_empty_call(lasad):
+    import torch
+    q = torch.zeros((2, 0, 3, 64), dtype=torch.bfloat16, device="cuda")
+    res = lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 4, 4)
+    torch.cuda.synchronize()
+    assert all(r.shape == q.shape for r in res)
