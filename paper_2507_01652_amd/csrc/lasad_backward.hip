@@ -142,24 +142,6 @@ backward_dgamma_slots_kernel(const float *sums, const float *gamma, float *dgamm
     if (threadIdx.x == 0) dgamma[h] = ((red[0] + red[1]) + (red[2] + red[3])) / gamma[h];
 }
 
-// start column of the reversed passes: with it, reversed step m >= 1 carries the decay of
-// original token n - m
-int reversed_start(int start_pos, int n, int grid_w, int mode)
-{
-    const int64_t W = grid_w;
-    int64_t s = 0;
-    if (mode == LASAD_RESET_LAST_COL) s = -((int64_t)start_pos + n + 2);
-    else if (mode == LASAD_RESET_FIRST_COL) s = -((int64_t)start_pos + n);
-    s %= W;
-    if (s < 0) s += W;
-    return (int)s;
-}
-
-const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
-{
-    return (const char *)p + (int64_t)(n - 1) * l.stride_n * elt;
-}
-
 }  // namespace
 
 // partial sums of the decay gradient: one per 64-token block of a sequence (finishing kernel) or

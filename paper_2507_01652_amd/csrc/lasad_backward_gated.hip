@@ -194,22 +194,6 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
     }
 }
 
-int reversed_start(int start_pos, int n, int grid_w, int mode)
-{
-    const int64_t W = grid_w;
-    int64_t s = 0;
-    if (mode == LASAD_RESET_LAST_COL) s = -((int64_t)start_pos + n + 2);
-    else if (mode == LASAD_RESET_FIRST_COL) s = -((int64_t)start_pos + n);
-    s %= W;
-    if (s < 0) s += W;
-    return (int)s;
-}
-
-const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
-{
-    return p ? (const char *)p + (int64_t)(n - 1) * l.stride_n * elt : nullptr;
-}
-
 template <int IN_BF16, int OUT_BF16>
 void launch_walks(const WalkArgs &w, int64_t n_seq, hipStream_t s)
 {

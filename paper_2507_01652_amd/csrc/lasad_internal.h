@@ -154,6 +154,28 @@ hipError_t launch_backward(const BackwardArgs &a, bool use_mfma, hipStream_t s);
 hipError_t launch_zero_f32(float *p, int n, hipStream_t s);
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype);
 
+// ---- host helpers of the backward passes ---------------------------------------
+
+// Start column for a pass that walks a call's n tokens backwards: with it, reversed step m >= 1
+// meets the boundary test of original token n - m (the one whose decay the step applies); the
+// mirrored and shifted boundary pattern of a raster grid is again "every W-th position".
+inline int reversed_start(int start_pos, int n, int grid_w, int mode)
+{
+    const int64_t W = grid_w;
+    int64_t s = 0;
+    if (mode == LASAD_RESET_LAST_COL) s = -((int64_t)start_pos + n + 2);
+    else if (mode == LASAD_RESET_FIRST_COL) s = -((int64_t)start_pos + n);
+    s %= W;
+    if (s < 0) s += W;
+    return (int)s;
+}
+
+// address of the last of n tokens of a tensor (the base of a walk with a negative token stride)
+inline const void *last_token(const void *p, const lasad_layout_t &l, int n, int elt)
+{
+    return p ? (const char *)p + (int64_t)(n - 1) * l.stride_n * elt : nullptr;
+}
+
 // ---- device helpers -----------------------------------------------------------
 
 // Is 1-indexed raster position t one where the decay is switched off
