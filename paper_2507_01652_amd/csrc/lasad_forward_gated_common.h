@@ -66,7 +66,8 @@ __device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
 // SHIFT = 1 takes the decay of token m from the decay tensor's token m - 1 (none at token 0: the
 // walk runs the sequence backwards and step m applies the decay of the step before it);
 // QMODE = 1 stages Q~ = q_scale A (query 1), QMODE = 2 takes the query as 1 - x from its tensor.
-template <int OWNKEY, int FUSED, int SHIFT = 0, int QMODE = 0>
+// WITH_V = 0 leaves the V tile to somebody else (the state waves of the twelve-wave kernel).
+template <int OWNKEY, int FUSED, int SHIFT = 0, int QMODE = 0, int WITH_V = 1>
 struct ChunkStage {
     uint4 rq[2], rl[2], rk[2], rv[2];                 // as fetched: q, lambda (or gate logits), own key, v
     uint4 pkh[2], pkl[2], pqh[2], pql[2], pv[2];      // prepared: K~ hi / lo, Q~ hi / lo, v
@@ -85,7 +86,7 @@ struct ChunkStage {
             if (QMODE != 1) rq[it] = *(const uint4 *)(gq + off);
             rl[it] = *(const uint4 *)(gl + (SHIFT ? (int64_t)max(tok - 1, 0) * stride_n + pcol : off));
             if (OWNKEY) rk[it] = *(const uint4 *)(gk + off);
-            rv[it] = *(const uint4 *)(gv + off);
+            if (WITH_V) rv[it] = *(const uint4 *)(gv + off);
         }
     }
 
@@ -124,7 +125,7 @@ struct ChunkStage {
                 lam[it][2 * e] = no_decay ? 1.0f : l0;
                 lam[it][2 * e + 1] = no_decay ? 1.0f : l1;
             }
-            pv[it] = rv[it];
+            if (WITH_V) pv[it] = rv[it];
         }
         if (nt < C) {                                      // tail chunk: rows past the end get lambda 1, q = k = v = 0
 #pragma unroll
@@ -135,7 +136,7 @@ struct ChunkStage {
                     kk[it][c] = live ? kk[it][c] : 0.f;
                     lam[it][c] = live ? lam[it][c] : 1.0f;
                 }
-                pv[it] = keep_or(live, pv[it], 0u);
+                if (WITH_V) pv[it] = keep_or(live, pv[it], 0u);
                 if (QMODE == 0) rq[it] = keep_or(live, rq[it], 0u);
                 if (QMODE == 2) rq[it] = keep_or(live, rq[it], 0x3f803f80u);     // 1 - 1 = 0
             }
@@ -196,7 +197,7 @@ struct ChunkStage {
             *(uint4 *)&sKl[row * KS + pcol] = pkl[it];
             *(uint4 *)&sQh[row * RS + pcol] = pqh[it];
             *(uint4 *)&sQl[row * RS + pcol] = pql[it];
-            *(uint4 *)&sV[row * TS + pcol] = pv[it];
+            if (WITH_V) *(uint4 *)&sV[row * TS + pcol] = pv[it];
         }
     }
 };
