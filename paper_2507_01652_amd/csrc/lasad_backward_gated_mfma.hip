@@ -97,7 +97,7 @@ __device__ __forceinline__ void pass_body(const ForwardArgs &a, const ForwardArg
     if (group == 2) {
         // ===================================== loader waves =====================================
         const int pcol = 16 * w4 + 8 * g;
-        ChunkStage<OWNKEY, 0, SHIFT, QMODE> stg;
+        ChunkStage<OWNKEY, 0, SHIFT, QMODE, 0> stg;    // (the V tile is the state waves' job)
         stg.trip = false;
         auto store_tile = [&](int chunk) {                // bf16 output tile of a finished chunk, 16-byte rows
             const uint16_t *bO = sO(chunk & 1);
@@ -148,7 +148,27 @@ __device__ __forceinline__ void pass_body(const ForwardArgs &a, const ForwardArg
                 *(uint2 *)&sl[off] = lo;
             }
         };
+        // the state waves also stage the V tile (a plain copy, one chunk ahead, rows past the end zeroed)
+        uint4 rvs[2];
+        auto load_v = [&](int chunk) {
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int tok = min(chunk * C + (st >> 3) + 32 * it, n - 1);
+                rvs[it] = *(const uint4 *)(gv + (int64_t)tok * a.in.stride_n + (st & 7) * 8);
+            }
+        };
+        auto write_v = [&](int chunk) {
+            uint16_t *bVw = sV(chunk & 1);
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int row = (st >> 3) + 32 * it;
+                *(uint4 *)&bVw[row * TS + (st & 7) * 8] = keep_or(chunk * C + row < n, rvs[it], 0u);
+            }
+        };
+        load_v(0);
         publish_state(0);
+        write_v(0);
+        if (n_chunks > 1) load_v(1);
         if (barrier_flag(false)) return;
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int p = chunk & 1;
@@ -176,7 +196,11 @@ __device__ __forceinline__ void pass_body(const ForwardArgs &a, const ForwardArg
                 accS[4 * qd + 0] *= t4.x; accS[4 * qd + 1] *= t4.y;
                 accS[4 * qd + 2] *= t4.z; accS[4 * qd + 3] *= t4.w;
             }
-            if (chunk + 1 < n_chunks) publish_state(p ^ 1);   // the state chunk + 1 starts from
+            if (chunk + 1 < n_chunks) {
+                publish_state(p ^ 1);                         // the state chunk + 1 starts from
+                write_v(chunk + 1);
+                if (chunk + 2 < n_chunks) load_v(chunk + 2);
+            }
             if (barrier_flag(false)) return;
         }
         return;
