@@ -36,23 +36,23 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 # runs (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a 256 MiB device copy; the
 # summaries are profiles/*_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "base_prefill_16x16": 12790907,      # algorithmic 12582912
-    "large_prefill_24x24": 151166184,    # algorithmic 150994944
-    "highres_64x64": 305360485,          # algorithmic 201326592; the segment plan re-reads K, V once
-    "ar_decode_16x16": 170453638,        # algorithmic 170393600
+    "base_prefill_16x16": 12790897,      # algorithmic 12582912
+    "large_prefill_24x24": 151165314,    # algorithmic 150994944
+    "highres_64x64": 305359035,          # algorithmic 201326592; the segment plan re-reads K, V once
+    "ar_decode_16x16": 170450250,        # algorithmic 170393600
     # vector-decay kernels (key tied to the gate): same algorithmic bytes as the scalar ones
-    "gated:base_prefill_16x16": 12844153,    # algorithmic 12582912
-    "gated:large_prefill_24x24": 158471856,  # algorithmic 150994944
-    "gated:highres_64x64": 201564837,        # algorithmic 201326592 (single launch, no segment plan)
-    "gated:ar_decode_16x16": 170444881,      # algorithmic 170393600
+    "gated:base_prefill_16x16": 12848132,    # algorithmic 12582912
+    "gated:large_prefill_24x24": 158456651,  # algorithmic 150994944
+    "gated:highres_64x64": 201568660,        # algorithmic 201326592 (single launch, no segment plan)
+    "gated:ar_decode_16x16": 170440626,      # algorithmic 170393600
     # backward of the scalar-decay forward (3 passes in one launch; operands shared through the L2 of an XCD)
-    "backward:base_prefill_16x16": 23852569,     # algorithmic 22020096
-    "backward:large_prefill_24x24": 395408347,   # algorithmic 264241152
-    "backward:highres_64x64": 658540963,         # algorithmic 352321536
+    "backward:base_prefill_16x16": 23863829,     # algorithmic 22020096
+    "backward:large_prefill_24x24": 394224084,   # algorithmic 264241152
+    "backward:highres_64x64": 657526650,         # algorithmic 352321536
     # backward of the vector-decay forward (dq, dk make a round trip through the fp32 workspace)
-    "gated_backward:base_prefill_16x16": 54209916,     # algorithmic 22020096
-    "gated_backward:large_prefill_24x24": 695507555,   # algorithmic 264241152
-    "gated_backward:highres_64x64": 1314963935,        # algorithmic 352321536
+    "gated_backward:base_prefill_16x16": 54200309,     # algorithmic 22020096
+    "gated_backward:large_prefill_24x24": 695739431,   # algorithmic 264241152
+    "gated_backward:highres_64x64": 1304384502,        # algorithmic 352321536
 }
 
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
