@@ -105,6 +105,32 @@ __device__ inline void write_tiles(uint16_t *sK, uint16_t *sV, uint16_t *sKh, ui
     }
 }
 
+// Decay and causal mask on the fp32 scores of key block jb (this lane: query column l32, keys
+// 8*qd + 4*g + e), split into bf16 hi + lo operand fragments of the next MFMA.  tabC: the chunk's
+// c_j table; cq = l32 - 4*g: key 8*qd + 4*g + e of a diagonal block is at or before the query iff
+// 8*qd + e <= cq.
+__device__ __forceinline__ void mask_split(const f32x16 &acc, const float *tabC, int jb, bool diagonal, int cq, int g,
+                                           const SplitConst &sc, Frag *ph, Frag *pl)
+{
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+        const float4 c4 = *(const float4 *)&tabC[jb * 32 + 8 * qd + 4 * g];
+        float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
+        float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
+        if (diagonal) {
+            p0 = 8 * qd + 0 <= cq ? p0 : 0.f;
+            p1 = 8 * qd + 1 <= cq ? p1 : 0.f;
+            p2 = 8 * qd + 2 <= cq ? p2 : 0.f;
+            p3 = 8 * qd + 3 <= cq ? p3 : 0.f;
+        }
+        uint2 hi, lo;
+        split2(p0, p1, hi.x, lo.x, sc);
+        split2(p2, p3, hi.y, lo.y, sc);
+        ph[qd / 2].h[qd % 2] = hi;
+        pl[qd / 2].h[qd % 2] = lo;
+    }
+}
+
 // V fragments of value-channel half wc: channel n = wc*32 + l32, tokens 16*s + 4*g + {0..3}, + 8
 __device__ inline void load_v_frags(Frag (&fv)[4], const uint16_t *sV, int wc, int lane)
 {

@@ -242,29 +242,9 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         Frag fv[4];
         load_v_frags(fv, sV, wc, lane);
 
-        // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
-        auto mask_split = [&](const f32x16 &acc, int jb, bool diagonal, Frag *ph, Frag *pl) {
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const float4 c4 = *(const float4 *)&tabC[jb * 32 + 8 * qd + 4 * g];
-                float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
-                float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
-                if (diagonal) {
-                    p0 = 8 * qd + 0 <= cq ? p0 : 0.f;
-                    p1 = 8 * qd + 1 <= cq ? p1 : 0.f;
-                    p2 = 8 * qd + 2 <= cq ? p2 : 0.f;
-                    p3 = 8 * qd + 3 <= cq ? p3 : 0.f;
-                }
-                uint2 hi, lo;
-                split2(p0, p1, hi.x, lo.x, sc);
-                split2(p2, p3, hi.y, lo.y, sc);
-                ph[qd / 2].h[qd % 2] = hi;
-                pl[qd / 2].h[qd % 2] = lo;
-            }
-        };
         {
             Frag ph[2], pl[2];
-            mask_split(acc0, 0, qa == 0, ph, pl);
+            mask_split(acc0, tabC, 0, qa == 0, cq, g, sc, ph, pl);
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 accO = mfma(fv[s], ph[s], accO);
@@ -273,7 +253,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         }
         if (qa == 1) {
             Frag ph[2], pl[2];
-            mask_split(acc1, 1, true, ph, pl);
+            mask_split(acc1, tabC, 1, true, cq, g, sc, ph, pl);
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 accO = mfma(fv[2 + s], ph[s], accO);

@@ -294,26 +294,6 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         if (DOT) gd.fetch(min(t0 + i_row, n - 1), wc * 32 + 4 * g);
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-        // decay + causal mask on the fp32 scores of key block jb, split to bf16 hi + lo
-        auto mask_split = [&](const f32x16 &acc, int jb, bool diagonal, Frag *ph, Frag *pl) {
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const float4 c4 = *(const float4 *)&bC[jb * 32 + 8 * qd + 4 * g];
-                float p0 = acc[4 * qd + 0] * c4.x, p1 = acc[4 * qd + 1] * c4.y;
-                float p2 = acc[4 * qd + 2] * c4.z, p3 = acc[4 * qd + 3] * c4.w;
-                if (diagonal) {
-                    p0 = 8 * qd + 0 <= cq ? p0 : 0.f;
-                    p1 = 8 * qd + 1 <= cq ? p1 : 0.f;
-                    p2 = 8 * qd + 2 <= cq ? p2 : 0.f;
-                    p3 = 8 * qd + 3 <= cq ? p3 : 0.f;
-                }
-                uint2 hi, lo;
-                split2(p0, p1, hi.x, lo.x, sc);
-                split2(p2, p3, hi.y, lo.y, sc);
-                ph[qd / 2].h[qd % 2] = hi;
-                pl[qd / 2].h[qd % 2] = lo;
-            }
-        };
         // scores of key block jb: P^T[j][i] = sum_d K[j][d] Q[i][d]
         auto scores = [&](int jb) {
             f32x16 acc = zero16;
@@ -348,7 +328,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
                 }
             }
             Frag ph[2], pl[2];
-            mask_split(sc_acc, jb, diagonal, ph, pl);
+            mask_split(sc_acc, bC, jb, diagonal, cq, g, sc, ph, pl);
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 acc = mfma(fv[s], ph[s], acc);
