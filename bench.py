@@ -483,6 +483,19 @@ def bench_gated(args, torch, lasad, wl):
     return res
 
 
+def measure_copy_peak(torch):
+    """Streaming ceiling of this GPU as a plain device copy reaches it: 1 GiB read + 1 GiB written per copy."""
+    n = 1 << 30
+    src = torch.empty((n,), dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    reps = 10
+    ms = time_region(torch, lambda: [dst.copy_(src) for _ in range(reps)])
+    del src, dst
+    return 2.0 * n * reps / (ms * 1e-3) / 1e9
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -502,6 +515,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    copy_gbs = measure_copy_peak(torch)
     pre = bench_prefill(args, torch, lasad, wl)
     w = pre["workload"]
     line = {
@@ -516,11 +530,16 @@ def main():
                    "buffer_sets_in_rotation": pre["buffer_sets"]},
         "eager_ms_per_step": pre["eager_ms_per_step"],
         "roofline": pre["roofline"], "roofline_mfma": pre["roofline_mfma"],
+        "hbm_copy_measured": {"value": copy_gbs, "unit": "GB/s",
+                              "what": "1 GiB device-to-device copy (read + written bytes over time), the streaming rate a "
+                                      "plain copy kernel reaches on this GPU; roofline.frac stays against the published 8 TB/s"},
     }
+    line["roofline"]["frac_of_measured_copy"] = line["roofline"]["achieved"] / copy_gbs
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline_prefill(pre)
     if args.decode_walks > 0:
         line["decode"] = bench_decode(args, torch, lasad, wl)
+        line["decode"]["roofline"]["frac_of_measured_copy"] = line["decode"]["roofline"]["achieved"] / copy_gbs
     if not args.no_backward:
         line["backward"] = bench_backward(args, torch, lasad, wl)
     if not args.no_gated:
