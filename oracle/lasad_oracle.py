@@ -286,3 +286,26 @@ def gated_layer(q_pre, z, v, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mo
     o, s = (r if want_state else (r, None))
     o = rms_norm(o, norm_weight, eps)
     return (o, s) if want_state else o
+
+
+def gated_layer_backward(q_pre, z, v, d_out, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mode=RESET_LAST_COL,
+                         q_scale=1.0):
+    """Gradients of gated_layer (zero initial state) for d_out = dL/d(layer output): the chain rule through
+    Norm (root mean square over the d channels, optional weight), the vector-decay recurrence
+    (lasad_oracle_gated_backward, tied key) and the two activations.  Returns dq_pre, dz, dv [B, n, Hh, d] and
+    dweight [Hh, d] (zeros when there is no weight)."""
+    q_pre, z, v, d_out = (np.asarray(x, dtype=np.float64) for x in (q_pre, z, v, d_out))
+    d = q_pre.shape[-1]
+    q, lam = silu(q_pre), sigmoid(z)
+    o = gated_recurrent(q, lam, v, grid_w, k=None, start_pos=start_pos, mode=mode, q_scale=q_scale)
+    # y = o * rstd * w, rstd = (mean(o^2) + eps)^(-1/2)
+    rstd = 1.0 / np.sqrt(np.mean(o * o, axis=-1, keepdims=True) + eps)
+    w = np.ones(q_pre.shape[-2:]) if norm_weight is None else np.asarray(norm_weight, dtype=np.float64)
+    gw = d_out * w                                               # dL/d(o * rstd)
+    d_o = rstd * gw - o * (rstd ** 3) * np.sum(gw * o, axis=-1, keepdims=True) / d
+    dweight = np.sum(d_out * o * rstd, axis=(0, 1)) if norm_weight is not None else np.zeros(q_pre.shape[-2:])
+    dq, dlam, dv = gated_backward(q, lam, v, d_o, grid_w, k=None, start_pos=start_pos, mode=mode, q_scale=q_scale)
+    sg = sigmoid(q_pre)
+    dq_pre = dq * sg * (1.0 + q_pre * (1.0 - sg))                # SiLU'(x) = s (1 + x (1 - s))
+    dz = dlam * lam * (1.0 - lam)                                # sigmoid'(z) = lam (1 - lam)
+    return dq_pre, dz, dv, dweight

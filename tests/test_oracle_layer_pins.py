@@ -4,6 +4,7 @@ properties of a root-mean-square normalisation, and a hand-worked two-token laye
 import math
 
 import numpy as np
+import pytest
 
 
 def test_sigmoid_values_and_identities(oracle):
@@ -61,3 +62,50 @@ def test_layer_hand_worked(oracle):
     # the same layer assembled by hand from the pinned pieces
     ref = oracle.rms_norm(oracle.gated_recurrent(oracle.silu(q_pre), oracle.sigmoid(z), v, 2), eps=0.0)
     assert np.array_equal(o, ref)
+
+
+# ---- gradients of the layer ---------------------------------------------------------------------
+
+def _num_grad(f, x, h):
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + h
+        fp = f()
+        x[i] = old - h
+        fm = f()
+        x[i] = old
+        g[i] = (fp - fm) / (2 * h)
+    return g
+
+
+@pytest.mark.parametrize("weighted", [False, True])
+@pytest.mark.parametrize("mode", [0, 2])
+def test_layer_backward_against_finite_differences_of_the_layer(oracle, weighted, mode):
+    """gated_layer_backward against central differences of gated_layer (pinned above) in every input entry."""
+    rng = np.random.default_rng(7 + mode)
+    B, Hh, H, W, d = 1, 2, 2, 3, 3
+    n = H * W
+    q, z, v, g = (rng.standard_normal((B, n, Hh, d)) for _ in range(4))
+    w = rng.uniform(0.5, 1.5, size=(Hh, d)) if weighted else None
+    kw = dict(norm_weight=w, eps=1e-3, mode=mode, q_scale=0.8)
+    dq, dz, dv, dw = oracle.gated_layer_backward(q, z, v, g, W, **kw)
+    loss = lambda: float((oracle.gated_layer(q, z, v, W, **kw) * g).sum())
+    assert np.allclose(dq, _num_grad(loss, q, 1e-5), rtol=1e-6, atol=1e-8)
+    assert np.allclose(dz, _num_grad(loss, z, 1e-5), rtol=1e-6, atol=1e-8)
+    assert np.allclose(dv, _num_grad(loss, v, 1e-5), rtol=1e-6, atol=1e-8)
+    if weighted:
+        assert np.allclose(dw, _num_grad(loss, w, 1e-5), rtol=1e-6, atol=1e-8)
+    else:
+        assert not dw.any()
+
+
+def test_layer_backward_is_blind_to_the_scale_of_v(oracle):
+    """With eps = 0 the normalisation removes any common factor of the recurrence output, and that output is
+    linear in v: scaling v leaves the layer output unchanged, so the gradient is orthogonal to v, <dv, v> = 0."""
+    rng = np.random.default_rng(3)
+    q, z, v, g = (rng.standard_normal((1, 6, 1, 4)) for _ in range(4))
+    _, _, dv, _ = oracle.gated_layer_backward(q, z, v, g, 3, eps=0.0)
+    assert abs(float((dv * v).sum())) <= 1e-10 * float(np.abs(dv * v).sum())
