@@ -290,6 +290,64 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
                          int start_pos, int n_tokens, int boundary_mode, float q_scale,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Backward pass of lasad_forward_layer (Algorithm 1 between its two Linear maps; Norm as read
+ * there: root mean square over the d channels of a head, times norm_weight) for a call that starts
+ * from a zero state and whose final state is not used.  Given d_out = dL/d(layer output), the chain
+ * rule runs through the normalisation (the recurrence output o is recomputed, not stored by the
+ * forward), the recurrence (lasad_backward_gated with the tied key) and the two activations:
+ *     dq_pre = dq * SiLU'(q_pre),   dz = dlam * lambda (1 - lambda),   dv,
+ *     dweight[h][c] = sum over batch and tokens of d_out * o * rstd.
+ *   q_pre, z, v     [B, n_tokens, n_heads, d] views sharing in_layout and io_dtype (device); head dim 64.
+ *   d_out           same logical shape and type, its own dout_layout.
+ *   dq_pre, dz, dv  same logical shape, grad_layout, grad_dtype (fp32, or bf16 with bf16 inputs);
+ *                   overwritten; no aliasing.
+ *   norm_weight     [n_heads, d] fp32 or NULL (ones); norm_eps < 0: no normalisation, as in the forward.
+ *   dweight         [n_heads, d] fp32 (device), overwritten, or NULL.  Without norm_weight: the gradient at a
+ *                   weight of ones; without a normalisation: zeros.
+ *   workspace       device memory of at least lasad_backward_layer_workspace_bytes(...) bytes, 256-byte
+ *                   aligned, owned by the caller (LASAD_ERR_WORKSPACE if too small).  It holds o in fp32,
+ *                   the gradient that enters the recurrence (in the inputs' type and WITH THE INPUTS'
+ *                   STRIDES, so its size follows the span of in_layout) and the recurrence's own workspace.
+ * The gate must not saturate to lambda = 0 where a decay is applied (see lasad_backward_gated).
+ * Precision: with bf16 inputs the gradient that enters the recurrence is rounded to bf16 on its way
+ * through the workspace.  It is orthogonal to o, and where the state is close to rank one (the
+ * first tokens of a sequence) dq and dz are small differences of larger terms, so that rounding
+ * shows there several times larger than the rounding of an input does (measured up to 7e-2 of
+ * the RMS against 1e-2 for dv); fp32 inputs keep it in fp32.
+ * Asynchronous on hip_stream; no allocation, no synchronisation; deterministic.
+ */
+size_t lasad_backward_layer_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype,
+                                            const lasad_layout_t *in_layout);
+int lasad_backward_layer(const void *q_pre, const void *z, const void *v, const void *d_out,
+                         void *dq_pre, void *dz, void *dv, float *dweight,
+                         const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
+                         const lasad_layout_t *grad_layout,
+                         int io_dtype, int grad_dtype,
+                         int B, int n_heads, int d, int grid_h, int grid_w,
+                         int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                         const float *norm_weight, float norm_eps,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The first part of lasad_backward_layer alone: the gradient d_o = dL/do that leaves the
+ * normalisation and enters the recurrence, and dweight.  With gw = d_out * norm_weight,
+ *     d_o = rstd gw - o rstd^3 mean_c(gw o),   rstd = (mean_c(o^2) + norm_eps)^(-1/2),
+ * o the recurrence output of Algorithm 1 for q_pre, z, v (recomputed here).  norm_eps >= 0.
+ *   d_o   [B, n_tokens, n_heads, d], d_o_layout, type io_dtype; overwritten.
+ * lasad_backward_layer computes exactly this tensor (same kernels, same rounding to io_dtype) and
+ * feeds it to the recurrence's backward; the latter alone is lasad_backward_layer with
+ * norm_eps < 0 and d_out := d_o.  Workspace and everything else as in lasad_backward_layer.
+ */
+int lasad_backward_layer_norm(const void *q_pre, const void *z, const void *v, const void *d_out,
+                              void *d_o, float *dweight,
+                              const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
+                              const lasad_layout_t *d_o_layout, int io_dtype,
+                              int B, int n_heads, int d, int grid_h, int grid_w,
+                              int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                              const float *norm_weight, float norm_eps,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Reason for the last non-OK status returned on this thread (static storage). */
 const char *lasad_last_error(void);
 

@@ -288,24 +288,42 @@ def gated_layer(q_pre, z, v, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mo
     return (o, s) if want_state else o
 
 
-def gated_layer_backward(q_pre, z, v, d_out, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mode=RESET_LAST_COL,
-                         q_scale=1.0):
-    """Gradients of gated_layer (zero initial state) for d_out = dL/d(layer output): the chain rule through
-    Norm (root mean square over the d channels, optional weight), the vector-decay recurrence
-    (lasad_oracle_gated_backward, tied key) and the two activations.  Returns dq_pre, dz, dv [B, n, Hh, d] and
-    dweight [Hh, d] (zeros when there is no weight)."""
+def layer_norm_backward(q_pre, z, v, d_out, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mode=RESET_LAST_COL,
+                        q_scale=1.0):
+    """The normalisation's part of the layer's backward: d_o = dL/d(recurrence output) [B, n, Hh, d] and
+    dweight [Hh, d] (without a weight: the gradient at a weight of ones) for d_out = dL/d(layer output).
+    y = o rstd w with rstd = (mean_c(o^2) + eps)^(-1/2), so with gw = d_out w:
+    d_o = rstd gw - o rstd^3 mean_c(gw o)."""
     q_pre, z, v, d_out = (np.asarray(x, dtype=np.float64) for x in (q_pre, z, v, d_out))
     d = q_pre.shape[-1]
-    q, lam = silu(q_pre), sigmoid(z)
-    o = gated_recurrent(q, lam, v, grid_w, k=None, start_pos=start_pos, mode=mode, q_scale=q_scale)
-    # y = o * rstd * w, rstd = (mean(o^2) + eps)^(-1/2)
+    o = gated_recurrent(silu(q_pre), sigmoid(z), v, grid_w, k=None, start_pos=start_pos, mode=mode, q_scale=q_scale)
     rstd = 1.0 / np.sqrt(np.mean(o * o, axis=-1, keepdims=True) + eps)
     w = np.ones(q_pre.shape[-2:]) if norm_weight is None else np.asarray(norm_weight, dtype=np.float64)
-    gw = d_out * w                                               # dL/d(o * rstd)
+    gw = d_out * w
     d_o = rstd * gw - o * (rstd ** 3) * np.sum(gw * o, axis=-1, keepdims=True) / d
-    dweight = np.sum(d_out * o * rstd, axis=(0, 1)) if norm_weight is not None else np.zeros(q_pre.shape[-2:])
-    dq, dlam, dv = gated_backward(q, lam, v, d_o, grid_w, k=None, start_pos=start_pos, mode=mode, q_scale=q_scale)
+    dweight = np.sum(d_out * o * rstd, axis=(0, 1))
+    return d_o, dweight
+
+
+def layer_core_backward(q_pre, z, v, d_o, grid_w, start_pos=0, mode=RESET_LAST_COL, q_scale=1.0):
+    """The recurrence's and the activations' part: dq_pre, dz, dv for d_o = dL/d(recurrence output), through
+    lasad_oracle_gated_backward (tied key) and SiLU'(x) = s (1 + x (1 - s)), s = sigmoid(x); sigmoid' = lam (1 - lam)."""
+    q_pre, z = np.asarray(q_pre, dtype=np.float64), np.asarray(z, dtype=np.float64)
+    lam = sigmoid(z)
+    dq, dlam, dv = gated_backward(silu(q_pre), lam, v, d_o, grid_w, k=None, start_pos=start_pos, mode=mode, q_scale=q_scale)
     sg = sigmoid(q_pre)
-    dq_pre = dq * sg * (1.0 + q_pre * (1.0 - sg))                # SiLU'(x) = s (1 + x (1 - s))
-    dz = dlam * lam * (1.0 - lam)                                # sigmoid'(z) = lam (1 - lam)
+    return dq * sg * (1.0 + q_pre * (1.0 - sg)), dlam * lam * (1.0 - lam), dv
+
+
+def gated_layer_backward(q_pre, z, v, d_out, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mode=RESET_LAST_COL,
+                         q_scale=1.0, store_d_o=None):
+    """Gradients of gated_layer (zero initial state) for d_out = dL/d(layer output): layer_norm_backward, then
+    layer_core_backward.  Returns dq_pre, dz, dv [B, n, Hh, d] and dweight [Hh, d].
+    store_d_o: None, or a function applied to the gradient between the two parts: the rounding of a pipeline
+    that STORES this tensor in a narrow type there (the gradient is orthogonal to the recurrence output, so
+    what follows is sensitive to that rounding)."""
+    d_o, dweight = layer_norm_backward(q_pre, z, v, d_out, grid_w, norm_weight, eps, start_pos, mode, q_scale)
+    if store_d_o is not None:
+        d_o = np.asarray(store_d_o(d_o), dtype=np.float64)
+    dq_pre, dz, dv = layer_core_backward(q_pre, z, v, d_o, grid_w, start_pos, mode, q_scale)
     return dq_pre, dz, dv, dweight

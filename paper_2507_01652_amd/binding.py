@@ -24,6 +24,7 @@ EXPORTS = (
     "lasad_forward_layer", "lasad_decode_step_layer",
     "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_backward_gated_workspace_bytes", "lasad_backward_gated",
+    "lasad_backward_layer_workspace_bytes", "lasad_backward_layer", "lasad_backward_layer_norm",
     "lasad_last_error", "lasad_version",
 )
 
@@ -85,6 +86,14 @@ def load() -> ctypes.CDLL:
     lib.lasad_backward_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                          ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.lasad_backward_gated.restype = ci
+    lib.lasad_backward_layer_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, lp]
+    lib.lasad_backward_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_layer.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                         ctypes.c_float, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.lasad_backward_layer.restype = ci
+    lib.lasad_backward_layer_norm.argtypes = [vp, vp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                              ctypes.c_float, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.lasad_backward_layer_norm.restype = ci
     lib.lasad_last_error.argtypes = []
     lib.lasad_last_error.restype = ctypes.c_char_p
     lib.lasad_version.argtypes = []
@@ -433,6 +442,82 @@ def lasad_backward_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, d_
         B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale,
         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
     return (dq, dlam, dv) if k is None else (dq, dlam, dv, dk)
+
+
+def lasad_backward_layer_workspace_bytes(q_pre: torch.Tensor) -> int:
+    B, n, Hh, d = q_pre.shape
+    lq = _layout(q_pre)
+    return int(load().lasad_backward_layer_workspace_bytes(B, Hh, n, d, _dtype_code(q_pre), ctypes.byref(lq)))
+
+
+def lasad_backward_layer(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, d_out: torch.Tensor,
+                         grid_h: int, grid_w: int, norm_weight: torch.Tensor | None = None, norm_eps: float = 1e-6,
+                         start_pos: int = 0, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                         grads: tuple | None = None, grad_dtype: torch.dtype | None = None,
+                         dweight: torch.Tensor | None = None, want_dweight: bool = True,
+                         workspace: torch.Tensor | None = None, stream=None):
+    """Gradients of lasad_forward_layer (zero initial state).  q_pre, z, v: logical [B, n, Hh, 64] views
+    sharing strides and dtype; d_out of the same shape and dtype with strides of its own.  Returns
+    (dq_pre, dz, dv, dweight); dweight is fp32 [Hh, d], or None with want_dweight=False."""
+    B, n, Hh, d = q_pre.shape
+    for t in (z, v):
+        if t.shape != q_pre.shape or t.stride() != q_pre.stride() or t.dtype != q_pre.dtype:
+            raise ValueError("q_pre, z, v must share shape, strides and dtype")
+    if d_out.shape != q_pre.shape or d_out.dtype != q_pre.dtype:
+        raise ValueError("d_out must have q_pre's shape and dtype")
+    if norm_weight is not None and (norm_weight.dtype != torch.float32 or not norm_weight.is_contiguous()
+                                    or norm_weight.numel() != Hh * d):
+        raise ValueError("norm_weight must be contiguous fp32 [Hh, d]")
+    if grads is None:
+        grads = tuple(torch.empty_like(q_pre, dtype=grad_dtype or q_pre.dtype) for _ in range(3))
+    dq, dz, dv = grads
+    for t in grads:
+        if t.shape != q_pre.shape or t.stride() != dq.stride() or t.dtype != dq.dtype:
+            raise ValueError("gradient tensors must share q_pre's shape and one set of strides and dtype")
+    if dweight is None and want_dweight:
+        dweight = torch.empty((Hh, d), dtype=torch.float32, device=q_pre.device)
+    if dweight is not None and (dweight.dtype != torch.float32 or not dweight.is_contiguous() or dweight.numel() != Hh * d):
+        raise ValueError("dweight must be contiguous fp32 [Hh, d]")
+    need = lasad_backward_layer_workspace_bytes(q_pre)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q_pre.device)
+    li, lo, lg = _layout(q_pre), _layout(d_out), _layout(dq)
+    _check(load().lasad_backward_layer(
+        _ptr(q_pre), _ptr(z), _ptr(v), _ptr(d_out), _ptr(dq), _ptr(dz), _ptr(dv), _ptr(dweight),
+        ctypes.byref(li), ctypes.byref(lo), ctypes.byref(lg), _dtype_code(q_pre), _dtype_code(dq),
+        B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale, _ptr(norm_weight), norm_eps,
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+    return dq, dz, dv, dweight
+
+
+def lasad_backward_layer_norm(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, d_out: torch.Tensor,
+                              grid_h: int, grid_w: int, norm_weight: torch.Tensor | None = None, norm_eps: float = 1e-6,
+                              start_pos: int = 0, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                              d_o: torch.Tensor | None = None, want_dweight: bool = True,
+                              workspace: torch.Tensor | None = None, stream=None):
+    """The normalisation's part of lasad_backward_layer alone: returns (d_o, dweight), d_o = dL/d(recurrence
+    output) in the inputs' dtype."""
+    B, n, Hh, d = q_pre.shape
+    for t in (z, v):
+        if t.shape != q_pre.shape or t.stride() != q_pre.stride() or t.dtype != q_pre.dtype:
+            raise ValueError("q_pre, z, v must share shape, strides and dtype")
+    if d_out.shape != q_pre.shape or d_out.dtype != q_pre.dtype:
+        raise ValueError("d_out must have q_pre's shape and dtype")
+    if d_o is None:
+        d_o = torch.empty(q_pre.shape, dtype=q_pre.dtype, device=q_pre.device)
+    if d_o.shape != q_pre.shape or d_o.dtype != q_pre.dtype:
+        raise ValueError("d_o must have q_pre's shape and dtype")
+    dweight = torch.empty((Hh, d), dtype=torch.float32, device=q_pre.device) if want_dweight else None
+    need = lasad_backward_layer_workspace_bytes(q_pre)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q_pre.device)
+    li, lo, ld = _layout(q_pre), _layout(d_out), _layout(d_o)
+    _check(load().lasad_backward_layer_norm(
+        _ptr(q_pre), _ptr(z), _ptr(v), _ptr(d_out), _ptr(d_o), _ptr(dweight),
+        ctypes.byref(li), ctypes.byref(lo), ctypes.byref(ld), _dtype_code(q_pre),
+        B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale, _ptr(norm_weight), norm_eps,
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+    return d_o, dweight
 
 
 # ---- host <-> device helpers for seeded numpy inputs (no arithmetic) ---------

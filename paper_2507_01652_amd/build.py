@@ -28,6 +28,7 @@ SOURCES = [
     "lasad_backward.hip",
     "lasad_backward_gated.hip",
     "lasad_backward_gated_mfma.hip",
+    "lasad_backward_layer.hip",
 ]
 
 # Packed-fp32 instruction selection is switched off for every HIP translation unit.

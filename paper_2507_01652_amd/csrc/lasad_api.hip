@@ -400,9 +400,125 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
     a.start_pos = start_pos; a.n_tokens = n_tokens;
     a.mode = boundary_mode; a.q_scale = q_scale;
     a.workspace = workspace;
+    a.fused_act = 0;
     hipError_t e = lasad::launch_backward_gated(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_backward_gated launch", e);
     return LASAD_OK;
+}
+
+static bool bad_strides(const lasad_layout_t *l, int vec)
+{
+    return l->stride_b % vec || l->stride_n % vec || l->stride_h % vec || l->stride_b < 0 || l->stride_n < 0 || l->stride_h < 0;
+}
+
+size_t lasad_backward_layer_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype,
+                                            const lasad_layout_t *in_layout)
+{
+    if (B < 1 || n_heads < 1 || n_tokens < 1 || d < 1 || !in_layout) return 0;
+    if (in_layout->stride_b < 0 || in_layout->stride_n < 0 || in_layout->stride_h < 0) return 0;
+    return lasad::backward_layer_workspace_bytes(B, n_heads, n_tokens, d, io_dtype, *in_layout);
+}
+
+// d_o_out NULL: the whole backward (gradients dq_pre, dz, dv with grad_layout / grad_dtype);
+// else only the normalisation's part: d_o_out (grad_layout, io_dtype) and dweight.
+static int backward_layer_common(const void *q_pre, const void *z, const void *v, const void *d_out,
+                                 void *dq_pre, void *dz, void *dv, void *d_o_out, float *dweight,
+                                 const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
+                                 const lasad_layout_t *grad_layout,
+                                 int io_dtype, int grad_dtype,
+                                 int B, int n_heads, int d, int grid_h, int grid_w,
+                                 int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                                 const float *norm_weight, float norm_eps,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const bool norm_only = d_o_out != nullptr;
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x3fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (d != 64) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (the layer backward supports 64)", d);
+    if (start_pos < 0 || n_tokens < 0 || (int64_t)start_pos + n_tokens > (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "positions %d+1..%d+%d leave the %d x %d grid", start_pos, start_pos, n_tokens, grid_h, grid_w);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (grad_dtype != LASAD_F32 && grad_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "grad_dtype %d", grad_dtype);
+    if (io_dtype == LASAD_F32 && grad_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 gradients");
+    if (!in_layout || !dout_layout || !grad_layout) return fail(LASAD_ERR_INVALID_ARG, "layout is NULL");
+    if (n_tokens > 0 && (!q_pre || !z || !v || !d_out)) return fail(LASAD_ERR_INVALID_ARG, "a tensor pointer is NULL");
+    if (norm_only && norm_eps < 0.f) return fail(LASAD_ERR_INVALID_ARG, "norm_eps < 0: there is no normalisation to differentiate");
+    const int vec = io_dtype == LASAD_BF16 ? 8 : 4, gvec = grad_dtype == LASAD_BF16 ? 8 : 4;
+    if (bad_strides(in_layout, vec) || bad_strides(dout_layout, vec))
+        return fail(LASAD_ERR_INVALID_ARG, "input strides must be non-negative multiples of %d elements", vec);
+    if (bad_strides(grad_layout, gvec))
+        return fail(LASAD_ERR_INVALID_ARG, "gradient strides must be non-negative multiples of %d elements", gvec);
+    if (n_tokens > 0 && (in_layout->stride_n < d || dout_layout->stride_n < d || grad_layout->stride_n < d))
+        return fail(LASAD_ERR_INVALID_ARG, "token stride smaller than the head dim");
+    if (!aligned(q_pre, 16) || !aligned(z, 16) || !aligned(v, 16) || !aligned(d_out, 16) || !aligned(dq_pre, 16) ||
+        !aligned(dz, 16) || !aligned(dv, 16) || !aligned(d_o_out, 16) || !aligned(dweight, 16) || !aligned(norm_weight, 16) || !aligned(workspace, 256))
+        return fail(LASAD_ERR_INVALID_ARG, "tensors must be 16-byte aligned, the workspace 256-byte aligned");
+    const void *ins[4] = {q_pre, z, v, d_out};
+    void *outs[3] = {norm_only ? d_o_out : dq_pre, dz, dv};
+    const int n_outs = norm_only ? 1 : 3;
+    for (int i = 0; n_tokens > 0 && i < n_outs; ++i) {
+        for (int j = 0; j < 4; ++j)
+            if (outs[i] == ins[j]) return fail(LASAD_ERR_INVALID_ARG, "a gradient buffer aliases an input");
+        for (int j = i + 1; j < n_outs; ++j)
+            if (outs[i] == outs[j]) return fail(LASAD_ERR_INVALID_ARG, "two gradient buffers alias");
+    }
+    if (n_tokens == 0) {
+        if (dweight) {
+            hipError_t e0 = lasad::launch_zero_f32(dweight, n_heads * d, (hipStream_t)hip_stream);
+            if (e0 != hipSuccess) return hip_fail("lasad_backward_layer launch", e0);
+        }
+        return LASAD_OK;
+    }
+    const size_t need = lasad_backward_layer_workspace_bytes(B, n_heads, n_tokens, d, io_dtype, in_layout);
+    if (!workspace || workspace_bytes < need)
+        return fail(LASAD_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+
+    lasad::LayerBackwardArgs a;
+    a.q_pre = q_pre; a.z = z; a.v = v; a.d_out = d_out;
+    a.dq_pre = dq_pre; a.dz = dz; a.dv = dv; a.dweight = dweight;
+    a.d_o_out = d_o_out; a.d_o_l = *grad_layout;
+    a.in = *in_layout; a.dout = *dout_layout; a.grad = *grad_layout;
+    a.io_dtype = io_dtype; a.grad_dtype = grad_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d; a.grid_w = grid_w;
+    a.start_pos = start_pos; a.n_tokens = n_tokens;
+    a.mode = boundary_mode; a.q_scale = q_scale;
+    a.norm_w = norm_weight; a.norm_eps = norm_eps;
+    a.workspace = workspace;
+    hipError_t e = lasad::launch_backward_layer(a, !force_generic(), (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_backward_layer launch", e);
+    return LASAD_OK;
+}
+
+int lasad_backward_layer(const void *q_pre, const void *z, const void *v, const void *d_out,
+                         void *dq_pre, void *dz, void *dv, float *dweight,
+                         const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
+                         const lasad_layout_t *grad_layout,
+                         int io_dtype, int grad_dtype,
+                         int B, int n_heads, int d, int grid_h, int grid_w,
+                         int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                         const float *norm_weight, float norm_eps,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (n_tokens > 0 && (!dq_pre || !dz || !dv)) return fail(LASAD_ERR_INVALID_ARG, "a tensor pointer is NULL");
+    return backward_layer_common(q_pre, z, v, d_out, dq_pre, dz, dv, nullptr, dweight, in_layout, dout_layout, grad_layout,
+                                 io_dtype, grad_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens, boundary_mode,
+                                 q_scale, norm_weight, norm_eps, workspace, workspace_bytes, hip_stream);
+}
+
+int lasad_backward_layer_norm(const void *q_pre, const void *z, const void *v, const void *d_out,
+                              void *d_o, float *dweight,
+                              const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
+                              const lasad_layout_t *d_o_layout, int io_dtype,
+                              int B, int n_heads, int d, int grid_h, int grid_w,
+                              int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                              const float *norm_weight, float norm_eps,
+                              void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!d_o) return fail(LASAD_ERR_INVALID_ARG, "d_o is NULL");
+    return backward_layer_common(q_pre, z, v, d_out, nullptr, nullptr, nullptr, d_o, dweight, in_layout, dout_layout, d_o_layout,
+                                 io_dtype, io_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens, boundary_mode,
+                                 q_scale, norm_weight, norm_eps, workspace, workspace_bytes, hip_stream);
 }
 
 int lasad_forward_gated(const void *q, const void *lam, const void *k, const void *v, void *o,

@@ -98,7 +98,7 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
     const int64_t w_base = ((int64_t)b * n * a.Hh + h) * kD + c4;        // workspace: [B][n][Hh][d] fp32
     const int64_t w_stride_n = (int64_t)a.Hh * kD;
 
-    struct Item { f4 q, k, lam, dq, dk; };
+    struct Item { f4 q, k, lam, dq, dk, dact; };     // dact: d(activation)/d(input) of q, fused activations only
     auto in4 = [&](const void *p, int t) {
         const int64_t i = in_base + (int64_t)t * a.in.stride_n;
         if (IN_BF16) {
@@ -112,6 +112,15 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         const int t = min(blk * kFinBlock + row, n - 1);
         it.q = in4(a.q, t);
         it.lam = in4(a.lam, t);
+        if (a.fused_act) {                 // q = SiLU(x), SiLU'(x) = s (1 + x (1 - s)) with s = sigmoid(x); lambda = sigmoid(z)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float x = it.q[e], sg = sigmoid_f32(x);
+                it.q[e] = x * sg;
+                it.dact[e] = sg * (1.0f + x * (1.0f - sg));
+                it.lam[e] = sigmoid_f32(it.lam[e]);
+            }
+        }
         if (a.k) it.k = in4(a.k, t);
         else it.k = f4{1.0f, 1.0f, 1.0f, 1.0f} - it.lam;
         it.dq = *(const f4 *)(dq32 + w_base + t * w_stride_n);
@@ -182,9 +191,14 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
             f4 dl = suffix / cur.lam;
             if (no_decay) dl = f4{0.f, 0.f, 0.f, 0.f};
             if (!a.k) dl -= cur.dk;
+            f4 dqo = cur.dq;
+            if (a.fused_act) {             // chain rule to the pre-activation inputs; sigmoid' = lambda (1 - lambda)
+                dl = dl * cur.lam * (f4{1.0f, 1.0f, 1.0f, 1.0f} - cur.lam);
+                dqo = dqo * cur.dact;
+            }
             if (live) {
                 put4(a.dlam, t, dl);
-                put4(a.dq, t, cur.dq);
+                put4(a.dq, t, dqo);
                 if (a.k) put4(a.dk, t, cur.dk);
             }
         }
@@ -235,7 +249,8 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     WalkArgs w;
     ForwardArgs &f = w.common;
     f.q = f.k = f.v = f.lam = nullptr; f.o = nullptr;
-    f.fused_act = 0; f.norm = 0; f.norm_eps = 0.f; f.norm_w = nullptr;
+    if (b.fused_act && b.k) return hipErrorInvalidValue;
+    f.fused_act = b.fused_act; f.norm = 0; f.norm_eps = 0.f; f.norm_w = nullptr;
     f.io_dtype = b.io_dtype; f.out_dtype = b.grad_dtype;
     f.in = b.in; f.out = b.grad;
     f.B = b.B; f.Hh = b.Hh; f.d = b.d;
@@ -245,13 +260,14 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     f.seg_states = nullptr; f.n_segments = 1; f.seg_chunks = 0;
     // planes: PQ (output row operand), PK (update row operand), PV (update column operand), PL (decay)
     // dq, forward order: g, v, k, lambda
-    w.roles[0] = ScanRoles{{b.d_o, b.v, b.k ? b.k : b.lam, b.lam}, {0, 0, 0, 0}, {0, 0, b.k ? 0 : 1, 0}};
+    const int sg = b.fused_act ? ACT_SIGMOID : ACT_NONE, si = b.fused_act ? ACT_SILU : ACT_NONE;
+    w.roles[0] = ScanRoles{{b.d_o, b.v, b.k ? b.k : b.lam, b.lam}, {0, 0, 0, 0}, {0, 0, b.k ? 0 : 1, 0}, {0, 0, b.k ? 0 : sg, sg}};
     w.o[0] = dq32; w.in[0] = b.in; w.out[0] = wl; w.start_pos[0] = b.start_pos;
     // dv, reversed order: k, q, g, lambda of the step before
-    w.roles[1] = ScanRoles{{b.k ? k_l : lam_l, q_l, g_l, lam_l}, {0, 0, 0, -1}, {b.k ? 0 : 1, 0, 0, 0}};
+    w.roles[1] = ScanRoles{{b.k ? k_l : lam_l, q_l, g_l, lam_l}, {0, 0, 0, -1}, {b.k ? 0 : 1, 0, 0, 0}, {b.k ? 0 : sg, si, 0, sg}};
     w.o[1] = (void *)last_token(b.dv, b.grad, n, gelt); w.in[1] = in_rev; w.out[1] = grad_rev; w.start_pos[1] = rev_start;
     // dk, reversed order: v, g, q, lambda of the step before
-    w.roles[2] = ScanRoles{{v_l, g_l, q_l, lam_l}, {0, 0, 0, -1}, {0, 0, 0, 0}};
+    w.roles[2] = ScanRoles{{v_l, g_l, q_l, lam_l}, {0, 0, 0, -1}, {0, 0, 0, 0}, {0, 0, si, sg}};
     w.o[2] = (void *)last_token(dk32, wl, n, 4); w.in[2] = in_rev; w.out[2] = wl_rev; w.start_pos[2] = rev_start;
 
     const bool in16 = b.io_dtype == LASAD_BF16, out16 = b.grad_dtype == LASAD_BF16;

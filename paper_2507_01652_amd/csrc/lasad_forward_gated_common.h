@@ -66,6 +66,10 @@ __device__ inline uint4 keep_or(bool keep, uint4 x, uint32_t fill)
 // SHIFT = 1 takes the decay of token m from the decay tensor's token m - 1 (none at token 0: the
 // walk runs the sequence backwards and step m applies the decay of the step before it);
 // QMODE = 1 stages Q~ = q_scale A (query 1), QMODE = 2 takes the query as 1 - x from its tensor.
+// FUSED = 1 reads pre-activation tensors (Algorithm 1): the decay tensor holds gate logits (sigmoid
+// on load, also where it feeds the QMODE = 2 query), a QMODE = 0 query and an own key hold the
+// pre-activation query (SiLU on load; an own key together with FUSED occurs in the backward passes
+// only, whose key operand is the forward's query).
 // WITH_V = 0 leaves the V tile to somebody else (the state waves of the twelve-wave kernel).
 template <int OWNKEY, int FUSED, int SHIFT = 0, int QMODE = 0, int WITH_V = 1>
 struct ChunkStage {
@@ -117,8 +121,9 @@ struct ChunkStage {
             for (int e = 0; e < 4; ++e) {
                 float l0 = __uint_as_float(lw[e] << 16), l1 = __uint_as_float(lw[e] & 0xffff0000u);
                 if (FUSED) { l0 = sigmoid_f32(l0); l1 = sigmoid_f32(l1); }
-                const float k0 = OWNKEY ? __uint_as_float(kw[e] << 16) : 1.0f - l0;
-                const float k1 = OWNKEY ? __uint_as_float(kw[e] & 0xffff0000u) : 1.0f - l1;
+                float k0 = OWNKEY ? __uint_as_float(kw[e] << 16) : 1.0f - l0;
+                float k1 = OWNKEY ? __uint_as_float(kw[e] & 0xffff0000u) : 1.0f - l1;
+                if (OWNKEY && FUSED) { k0 = silu_f32(k0); k1 = silu_f32(k1); }
                 kk[it][2 * e] = k0;
                 kk[it][2 * e + 1] = k1;
                 const bool no_decay = bnd || (SHIFT && t0 + row == 0);
@@ -138,7 +143,8 @@ struct ChunkStage {
                 }
                 if (WITH_V) pv[it] = keep_or(live, pv[it], 0u);
                 if (QMODE == 0) rq[it] = keep_or(live, rq[it], 0u);
-                if (QMODE == 2) rq[it] = keep_or(live, rq[it], 0x3f803f80u);     // 1 - 1 = 0
+                // a query of zero: 1 - 1, or 1 - sigmoid(100) (= 1 - 1 in fp32)
+                if (QMODE == 2) rq[it] = keep_or(live, rq[it], FUSED ? 0x42c842c8u : 0x3f803f80u);
             }
         }
         if (QMODE != 1) { qc[0] = rq[0]; qc[1] = rq[1]; }
@@ -177,8 +183,9 @@ struct ChunkStage {
                 split2(kk[it][2 * e] * __builtin_amdgcn_rcpf(a0), kk[it][2 * e + 1] * __builtin_amdgcn_rcpf(a1), kh[e], kl[e], sc);
                 float q0 = 1.0f, q1 = 1.0f;
                 if (QMODE != 1) { q0 = __uint_as_float(qw[e] << 16); q1 = __uint_as_float(qw[e] & 0xffff0000u); }
+                if (QMODE == 2 && FUSED) { q0 = sigmoid_f32(q0); q1 = sigmoid_f32(q1); }
                 if (QMODE == 2) { q0 = 1.0f - q0; q1 = 1.0f - q1; }
-                if (FUSED) { q0 = silu_f32(q0); q1 = silu_f32(q1); }
+                if (QMODE == 0 && FUSED) { q0 = silu_f32(q0); q1 = silu_f32(q1); }
                 split2(q0 * (a0 * a.q_scale), q1 * (a1 * a.q_scale), qh[e], ql[e], sc);
             }
             pkh[it] = make_uint4(kh[0], kh[1], kh[2], kh[3]); pkl[it] = make_uint4(kl[0], kl[1], kl[2], kl[3]);

@@ -124,8 +124,31 @@ struct GatedBackwardArgs {
     int mode;
     float q_scale;
     void *workspace;
+    int fused_act;                       // 1: q and lam hold Algorithm 1's pre-activation query and gate logits
+                                         // (tied key only); dq and dlam are then the gradients of THOSE tensors
 };
 hipError_t launch_backward_gated(const GatedBackwardArgs &a, hipStream_t s);
+
+// Arguments of one backward call of the fused layer (Algorithm 1 between its Linear maps), validated.
+struct LayerBackwardArgs {
+    const void *q_pre, *z, *v, *d_out;
+    void *dq_pre, *dz, *dv;
+    void *d_o_out;                       // not NULL: stop after the normalisation's backward and leave the gradient
+    lasad_layout_t d_o_l;                //   that enters the recurrence here (type io_dtype, this layout)
+    float *dweight;                      // [Hh, d], or NULL
+    lasad_layout_t in, dout, grad;
+    int io_dtype, grad_dtype;
+    int B, Hh, d;
+    int grid_w;
+    int start_pos, n_tokens;
+    int mode;
+    float q_scale;
+    const float *norm_w;                 // [Hh, d] or NULL (ones)
+    float norm_eps;                      // < 0: no normalisation
+    void *workspace;
+};
+hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipStream_t s);
+size_t backward_layer_workspace_bytes(int B, int Hh, int n_tokens, int d, int io_dtype, const lasad_layout_t &in);
 size_t backward_gated_workspace_bytes(int64_t n_seq, int n_tokens, int d);
 
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,

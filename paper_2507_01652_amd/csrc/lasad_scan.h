@@ -46,7 +46,9 @@ struct ScanRoles {
     const void *ptr[4];
     int shift[4];         // 0, or -1: the plane of token m holds the tensor's token m - 1 (token 0: a neutral value)
     int one_minus[4];     // the plane holds 1 - x (a key tied to the decay)
+    int act[4];           // applied to the tensor's value first: 0 nothing, 1 SiLU, 2 sigmoid (Algorithm 1's activations)
 };
+enum { ACT_NONE = 0, ACT_SILU = 1, ACT_SIGMOID = 2 };
 
 // LDS planes of one staged batch
 enum { PQ = 0, PK = 1, PV = 2, PL = 3 };
@@ -174,6 +176,10 @@ struct Loader {
             const bool past_end = t0 + tok >= a.n_tokens;
             if (ROLES) {
                 // plane = tensor index; rows past the end and a shifted read before the first token are neutral
+                if (roles->act[arr]) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) f[e] = roles->act[arr] == ACT_SILU ? silu_f32(f[e]) : sigmoid_f32(f[e]);
+                }
                 if (roles->one_minus[arr]) {
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) f[e] = 1.0f - f[e];

@@ -96,10 +96,9 @@ def test_layer_backward_against_finite_differences_of_the_layer(oracle, weighted
     assert np.allclose(dq, _num_grad(loss, q, 1e-5), rtol=1e-6, atol=1e-8)
     assert np.allclose(dz, _num_grad(loss, z, 1e-5), rtol=1e-6, atol=1e-8)
     assert np.allclose(dv, _num_grad(loss, v, 1e-5), rtol=1e-6, atol=1e-8)
-    if weighted:
-        assert np.allclose(dw, _num_grad(loss, w, 1e-5), rtol=1e-6, atol=1e-8)
-    else:
-        assert not dw.any()
+    if not weighted:                       # without a weight: the gradient at a weight of ones
+        w = kw["norm_weight"] = np.ones((Hh, d))
+    assert np.allclose(dw, _num_grad(loss, w, 1e-5), rtol=1e-6, atol=1e-8)
 
 
 def test_layer_backward_is_blind_to_the_scale_of_v(oracle):
@@ -109,3 +108,19 @@ def test_layer_backward_is_blind_to_the_scale_of_v(oracle):
     q, z, v, g = (rng.standard_normal((1, 6, 1, 4)) for _ in range(4))
     _, _, dv, _ = oracle.gated_layer_backward(q, z, v, g, 3, eps=0.0)
     assert abs(float((dv * v).sum())) <= 1e-10 * float(np.abs(dv * v).sum())
+
+
+def test_layer_backward_storage_hook_is_applied_to_the_recurrence_gradient_only(oracle):
+    """store_d_o = identity changes nothing; store_d_o = 0 leaves only the weight gradient (which does not pass
+    through the recurrence); scaling by 2 doubles the three tensor gradients (they are linear in that gradient)."""
+    rng = np.random.default_rng(11)
+    q, z, v, g = (rng.standard_normal((1, 6, 2, 4)) for _ in range(4))
+    w = rng.uniform(0.5, 1.5, size=(2, 4))
+    base = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w)
+    same = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w, store_d_o=lambda x: x)
+    none = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w, store_d_o=lambda x: 0 * x)
+    twice = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w, store_d_o=lambda x: 2 * x)
+    for i in range(3):
+        assert np.array_equal(base[i], same[i]) and not none[i].any()
+        assert np.allclose(twice[i], 2 * base[i], rtol=1e-12, atol=0)
+    assert np.array_equal(base[3], none[3]) and np.array_equal(base[3], twice[3])
