@@ -36,23 +36,27 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 # runs (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a 256 MiB device copy; the
 # summaries are profiles/*_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "base_prefill_16x16": 12790897,      # algorithmic 12582912
-    "large_prefill_24x24": 151165314,    # algorithmic 150994944
-    "highres_64x64": 305359035,          # algorithmic 201326592; the segment plan re-reads K, V once
-    "ar_decode_16x16": 170450250,        # algorithmic 170393600
+    "base_prefill_16x16": 12790816,      # algorithmic 12582912
+    "large_prefill_24x24": 151151931,    # algorithmic 150994944
+    "highres_64x64": 305350943,          # algorithmic 201326592; the segment plan re-reads K, V once
+    "ar_decode_16x16": 170453204,        # algorithmic 170393600
     # vector-decay kernels (key tied to the gate): same algorithmic bytes as the scalar ones
-    "gated:base_prefill_16x16": 12848132,    # algorithmic 12582912
-    "gated:large_prefill_24x24": 158456651,  # algorithmic 150994944
-    "gated:highres_64x64": 201568660,        # algorithmic 201326592 (single launch, no segment plan)
-    "gated:ar_decode_16x16": 170440626,      # algorithmic 170393600
+    "gated:base_prefill_16x16": 12847215,    # algorithmic 12582912
+    "gated:large_prefill_24x24": 158462920,  # algorithmic 150994944
+    "gated:highres_64x64": 201572870,        # algorithmic 201326592 (single launch, no segment plan)
+    "gated:ar_decode_16x16": 170444572,      # algorithmic 170393600
     # backward of the scalar-decay forward (3 passes in one launch; operands shared through the L2 of an XCD)
-    "backward:base_prefill_16x16": 23863829,     # algorithmic 22020096
-    "backward:large_prefill_24x24": 394224084,   # algorithmic 264241152
-    "backward:highres_64x64": 657526650,         # algorithmic 352321536
+    "backward:base_prefill_16x16": 23861382,     # algorithmic 22020096
+    "backward:large_prefill_24x24": 394843741,   # algorithmic 264241152
+    "backward:highres_64x64": 659146800,         # algorithmic 352321536
     # backward of the vector-decay forward (dq, dk make a round trip through the fp32 workspace)
-    "gated_backward:base_prefill_16x16": 54200309,     # algorithmic 22020096
-    "gated_backward:large_prefill_24x24": 695739431,   # algorithmic 264241152
-    "gated_backward:highres_64x64": 1304384502,        # algorithmic 352321536
+    "gated_backward:base_prefill_16x16": 54272135,     # algorithmic 22020096
+    "gated_backward:large_prefill_24x24": 696592910,   # algorithmic 264241152
+    "gated_backward:highres_64x64": 1304432879,        # algorithmic 352321536
+    # backward of the fused layer (adds the recomputed forward with o in fp32 and the bf16 round trip of d_o)
+    "layer_backward:base_prefill_16x16": 83224117,     # algorithmic 22020096
+    "layer_backward:large_prefill_24x24": 1045217668,  # algorithmic 264241152
+    "layer_backward:highres_64x64": 1762872867,        # algorithmic 352321536
 }
 
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
@@ -422,6 +426,40 @@ def bench_gated(args, torch, lasad, wl):
         gl = capture(torch, lambda: run_layer(steps, 5))
         gl.replay()
         layer_ms = time_region(torch, gl.replay)
+    # backward of the fused layer: forward recomputation (o in fp32), norm backward, the three passes with the
+    # activations on load, finishing kernel with the chain rule, weight-gradient sum
+    layer_bwd = None
+    if not args.no_backward:
+        td = lasad.to_device(wl.store_round(np.random.default_rng(w.seed + 101).standard_normal(q.shape, dtype=np.float32)
+                                            / np.float32(np.sqrt(w.d)), w.dtype), w.dtype)
+        gsets = min(sets, 8)
+        grads = [tuple(torch.empty_like(tq) for _ in range(3)) for _ in range(gsets)]
+        dwt = torch.empty((w.Hh, w.d), dtype=torch.float32, device="cuda")
+        ws_l = torch.empty((lasad.lasad_backward_layer_workspace_bytes(tq),), dtype=torch.uint8, device="cuda")
+        lsteps = max(1, min(steps, 20))
+
+        def run_lbwd(nsteps, first=0):
+            for i in range(nsteps):
+                a, b, c, _ = bufs[(first + i) % sets]
+                lasad.lasad_backward_layer(a, b, c, td, w.grid_h, w.grid_w, grads=grads[(first + i) % gsets], dweight=dwt,
+                                           workspace=ws_l)
+
+        run_lbwd(3)
+        lb_ms = time_region(torch, lambda: run_lbwd(lsteps, 3))
+        if not args.no_graph:
+            glb = capture(torch, lambda: run_lbwd(lsteps, 3))
+            glb.replay()
+            lb_ms = time_region(torch, glb.replay)
+        lb_s = lb_ms / lsteps * 1e-3
+        bytes_lb = token_heads * 7 * w.d * 2           # q_pre, z, v, d_out read + dq_pre, dz, dv written, bf16
+        layer_bwd = {"workload": w.name + " (q_pre, z, v, d_out; SiLU, sigmoid gate, tied key, RMS norm)",
+                     "value": w.B * w.N / lb_s, "unit": "tokens/s", "ms_per_step": lb_s * 1e3, "steps_timed": lsteps,
+                     "launches_per_step": "forward recomputation + norm backward + 3-pass kernel + finishing kernel + weight-gradient sum",
+                     "roofline": {"bound": "hbm", "kernel": "lasad_backward_layer (all launches of one call)",
+                                  "achieved": bytes_lb / lb_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": bytes_lb / lb_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_lb,
+                                  "traffic": MEASURED_TRAFFIC_BYTES.get("layer_backward:" + w.name)}}
+        del grads, ws_l, td, dwt
     res = {"forward": {
         "workload": w.name + " (q, gate, v; k = 1 - gate)",
         "fused_layer_ms_per_step": layer_ms / steps, "value": w.B * w.N / dur_s, "unit": "tokens/s",
@@ -432,6 +470,8 @@ def bench_gated(args, torch, lasad, wl):
                      "traffic": MEASURED_TRAFFIC_BYTES.get("gated:" + w.name)}}}
     if bwd is not None:
         res["backward"] = bwd
+    if layer_bwd is not None:
+        res["layer_backward"] = layer_bwd
     if not args.no_cpu_baseline:
         from oracle import lasad_oracle as oracle
         n_seq = min(w.B * w.Hh, 4 * oracle.num_threads())

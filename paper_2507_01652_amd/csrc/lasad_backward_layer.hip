@@ -96,24 +96,25 @@ norm_backward_kernel(LayerBackwardArgs a, const float *o32, void *d_o, lasad_lay
     }
 }
 
-// dweight[h][c] = sum over batch rows and token blocks of the partial sums; one workgroup per head,
-// 16 threads per channel take every 16th item, then one thread adds the 16 in order.
+// dweight[h][c] = sum over batch rows and token blocks of the partial sums.  A workgroup owns 16
+// channels of one head: 64 threads per channel take every 64th item, then one thread per channel adds
+// the 64 in order.
 __global__ void __launch_bounds__(1024)
 weight_grad_kernel(const float *wpart, float *dweight, int B, int Hh, int nblk)
 {
-    __shared__ float sP[16][kD];
-    const int h = blockIdx.x, c = threadIdx.x & (kD - 1), g = threadIdx.x >> 6;
+    __shared__ float sP[64][17];
+    const int h = blockIdx.x >> 2, c = (blockIdx.x & 3) * 16 + (threadIdx.x & 15), g = threadIdx.x >> 4;
     const int items = B * nblk;
     float acc = 0.f;
-    for (int i = g; i < items; i += 16) {
+    for (int i = g; i < items; i += 64) {
         const int b = i / nblk, blk = i - b * nblk;
         acc += wpart[(((int64_t)b * Hh + h) * nblk + blk) * kD + c];
     }
-    sP[g][c] = acc;
+    sP[g][threadIdx.x & 15] = acc;
     __syncthreads();
-    if (threadIdx.x < kD) {
+    if (threadIdx.x < 16) {
         float s = 0.f;
-        for (int i = 0; i < 16; ++i) s += sP[i][c];
+        for (int i = 0; i < 64; ++i) s += sP[i][threadIdx.x];
         dweight[h * kD + c] = s;
     }
 }
@@ -191,7 +192,7 @@ hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipS
     }
     if (a.d_o_out) {                                                    // the normalisation's part only
         if (a.dweight) {
-            if (norm) hipLaunchKernelGGL(weight_grad_kernel, dim3((unsigned)a.Hh), dim3(1024), 0, s, wpart, a.dweight, a.B, a.Hh, nblk);
+            if (norm) hipLaunchKernelGGL(weight_grad_kernel, dim3((unsigned)a.Hh * 4), dim3(1024), 0, s, wpart, a.dweight, a.B, a.Hh, nblk);
             else return launch_zero_f32(a.dweight, a.Hh * a.d, s);
         }
         return hipGetLastError();
@@ -210,7 +211,7 @@ hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipS
     if (e != hipSuccess) return e;
     if (a.dweight) {                                                    // 4. weight gradient (zero without a norm)
         if (norm) {
-            hipLaunchKernelGGL(weight_grad_kernel, dim3((unsigned)a.Hh), dim3(1024), 0, s, wpart, a.dweight, a.B, a.Hh, nblk);
+            hipLaunchKernelGGL(weight_grad_kernel, dim3((unsigned)a.Hh * 4), dim3(1024), 0, s, wpart, a.dweight, a.B, a.Hh, nblk);
             e = hipGetLastError();
         } else {
             e = launch_zero_f32(a.dweight, a.Hh * a.d, s);
