@@ -102,3 +102,55 @@ def test_decode_and_decay_reject_bad_arguments(lib):
                                              vp(0x2000), vp(0x3000), None)
     assert dk(sp=1) == 1 and dk(n=-2) == 1 and dk(gw=0) == 1 and dk(mode=-1) == 1
     assert dk(Hh=0) == 1 and dk(gamma=None) == 1
+
+
+def _backward_layer(lib, norm_only=False, **kw):
+    dense = Layout(4 * 2 * 64, 2 * 64, 64)
+    a = dict(q=0x1000, z=0x2000, v=0x3000, g=0x4000, dq=0x5000, dz=0x6000, dv=0x7000, dw=0x8000, d_o=0x5000,
+             li=dense, lo=dense, lg=dense, io=1, gd=1, B=1, Hh=2, d=64, gh=2, gw=2, sp=0, n=4, mode=0, qs=1.0,
+             w=0x9000, eps=1e-6, ws=0x10000, ws_bytes=0)
+    a.update(kw)
+    vp, cf = ctypes.c_void_p, ctypes.c_float
+    tail = (a["B"], a["Hh"], a["d"], a["gh"], a["gw"], a["sp"], a["n"], a["mode"], cf(a["qs"]), vp(a["w"]), cf(a["eps"]),
+            vp(a["ws"]), ctypes.c_size_t(a["ws_bytes"]), None)
+    if norm_only:
+        return lib.lasad_backward_layer_norm(vp(a["q"]), vp(a["z"]), vp(a["v"]), vp(a["g"]), vp(a["d_o"]), vp(a["dw"]),
+                                             ctypes.byref(a["li"]), ctypes.byref(a["lo"]), ctypes.byref(a["lg"]),
+                                             a["io"], *tail)
+    return lib.lasad_backward_layer(vp(a["q"]), vp(a["z"]), vp(a["v"]), vp(a["g"]), vp(a["dq"]), vp(a["dz"]), vp(a["dv"]),
+                                    vp(a["dw"]), ctypes.byref(a["li"]), ctypes.byref(a["lo"]), ctypes.byref(a["lg"]),
+                                    a["io"], a["gd"], *tail)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=32), 2), (dict(B=0), 1), (dict(gw=0), 1), (dict(mode=5), 1), (dict(sp=3, n=2), 1), (dict(io=3), 1),
+    (dict(io=0, gd=1), 2), (dict(q=None), 1), (dict(g=None), 1), (dict(dz=None), 1), (dict(dq=0x1000), 1),
+    (dict(dz=0x5000), 1), (dict(dw=0x8004), 1), (dict(w=0x9008), 1), (dict(lo=Layout(512, 100, 64)), 1),
+    (dict(lg=Layout(512, 32, 64)), 1), (dict(ws=0x10010), 1),
+    (dict(), 3), (dict(ws=None, ws_bytes=1 << 30), 3),          # workspace too small / missing
+])
+def test_backward_layer_rejects_bad_arguments_before_launch(lib, kw, code):
+    """Validation failures only: nothing is launched (the pointers are fake)."""
+    assert _backward_layer(lib, **kw) == code
+    assert len(lib.lasad_last_error()) > 0
+
+
+def test_backward_layer_norm_rejects_bad_arguments_and_sizes_its_workspace(lib):
+    assert _backward_layer(lib, norm_only=True, d_o=None) == 1
+    assert _backward_layer(lib, norm_only=True, eps=-1.0) == 1          # no normalisation to differentiate
+    assert _backward_layer(lib, norm_only=True, d_o=0x4000) == 1        # aliases d_out
+    assert _backward_layer(lib, norm_only=True) == 3                    # workspace too small
+    lib.lasad_backward_layer_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_gated_workspace_bytes.restype = ctypes.c_size_t
+    size = lambda l, io=1: lib.lasad_backward_layer_workspace_bytes(2, 3, 100, 64, io, ctypes.byref(l))
+    dense = Layout(100 * 3 * 64, 3 * 64, 64)
+    wide = Layout(100 * 9 * 64, 9 * 64, 64)                              # q_pre, z, v cut from one projection
+    core = lib.lasad_backward_gated_workspace_bytes(2, 3, 100, 64)
+    n_el = 2 * 3 * 100 * 64
+    # the recurrence's workspace, o in fp32, d_o in the inputs' type over the span of the input view, partial sums
+    assert size(dense) >= core + 4 * n_el + 2 * n_el + 2 * 3 * 2 * 64 * 4
+    assert size(dense) < core + 4 * n_el + 2 * n_el + 2 * 3 * 2 * 64 * 4 + 5 * 256
+    assert size(wide) - size(dense) >= 2 * (3 * n_el - 3 * 64 * 2 - n_el) - 256
+    assert size(dense, io=0) - size(dense) >= 2 * n_el - 256
+    assert lib.lasad_backward_layer_workspace_bytes(0, 3, 100, 64, 1, ctypes.byref(dense)) == 0
+    assert lib.lasad_backward_layer_workspace_bytes(2, 3, 100, 64, 1, None) == 0

@@ -42,6 +42,9 @@ def test_graph_replays_match_eager(lasad):
     ws_f = torch.empty(max(1, lasad.lasad_forward_workspace_bytes(B, Hh, n, d, lasad.BF16)), dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(lasad.lasad_backward_workspace_bytes(B, Hh, n, d, lasad.BF16), dtype=torch.uint8, device="cuda")
     ws_g = torch.empty(lasad.lasad_backward_gated_workspace_bytes(B, Hh, n, d), dtype=torch.uint8, device="cuda")
+    lgrads = tuple(torch.empty_like(q) for _ in range(3))
+    dwt = torch.empty(Hh, d, device="cuda")
+    ws_l = torch.empty(lasad.lasad_backward_layer_workspace_bytes(q), dtype=torch.uint8, device="cuda")
 
     def run():
         lasad.lasad_forward_chunked(q, k, v, gam, H, W, out=o, workspace=ws_f)
@@ -49,11 +52,12 @@ def test_graph_replays_match_eager(lasad):
         lasad.lasad_forward_gated(q, lam, v, H, W, out=og)
         lasad.lasad_forward_layer(q, lam, v, H, W, out=ol)
         lasad.lasad_backward_gated(q, lam, v, g, H, W, grads=ggrads, workspace=ws_g)
+        lasad.lasad_backward_layer(q, lam, v, g, H, W, grads=lgrads, dweight=dwt, workspace=ws_l)
         state.zero_()
         lasad.lasad_decode_step(qs, ks, vs, gam, state, H, W, 3, out=od)
         lasad.lasad_decode_step_cached(qs, ks, vs, gam, kc, vc, H, W, 3, out=oc)
 
-    outputs = lambda: [t.clone() for t in (o, og, ol, *grads, dgam, *ggrads, od, oc, state, kc, vc)]
+    outputs = lambda: [t.clone() for t in (o, og, ol, *grads, dgam, *ggrads, *lgrads, dwt, od, oc, state, kc, vc)]
     run()                                   # warm-up (loads the code objects)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
