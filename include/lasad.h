@@ -307,14 +307,14 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
  *                   weight of ones; without a normalisation: zeros.
  *   workspace       device memory of at least lasad_backward_layer_workspace_bytes(...) bytes, 256-byte
  *                   aligned, owned by the caller (LASAD_ERR_WORKSPACE if too small).  It holds o in fp32,
- *                   the gradient that enters the recurrence (in the inputs' type and WITH THE INPUTS'
- *                   STRIDES, so its size follows the span of in_layout) and the recurrence's own workspace.
+ *                   the gradient that enters the recurrence (in the inputs' type, bf16 twice, and WITH THE
+ *                   INPUTS' STRIDES, so its size follows the span of in_layout) and the recurrence's own
+ *                   workspace.
  * The gate must not saturate to lambda = 0 where a decay is applied (see lasad_backward_gated).
- * Precision: with bf16 inputs the gradient that enters the recurrence is rounded to bf16 on its way
- * through the workspace.  It is orthogonal to o, and where the state is close to rank one (the
- * first tokens of a sequence) dq and dz are small differences of larger terms, so that rounding
- * shows there several times larger than the rounding of an input does (measured up to 7e-2 of
- * the RMS against 1e-2 for dv); fp32 inputs keep it in fp32.
+ * Precision: the gradient that enters the recurrence is orthogonal to o, and where the state is
+ * close to rank one (the first tokens of a sequence) dq and dz are small differences of larger
+ * terms.  With bf16 inputs that gradient therefore crosses the workspace as a bf16 pair hi + lo,
+ * both parts used where the cancellation happens; fp32 inputs keep it in fp32.
  * Asynchronous on hip_stream; no allocation, no synchronisation; deterministic.
  */
 size_t lasad_backward_layer_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype,
@@ -335,9 +335,10 @@ int lasad_backward_layer(const void *q_pre, const void *z, const void *v, const 
  *     d_o = rstd gw - o rstd^3 mean_c(gw o),   rstd = (mean_c(o^2) + norm_eps)^(-1/2),
  * o the recurrence output of Algorithm 1 for q_pre, z, v (recomputed here).  norm_eps >= 0.
  *   d_o   [B, n_tokens, n_heads, d], d_o_layout, type io_dtype; overwritten.
- * lasad_backward_layer computes exactly this tensor (same kernels, same rounding to io_dtype) and
- * feeds it to the recurrence's backward; the latter alone is lasad_backward_layer with
- * norm_eps < 0 and d_out := d_o.  Workspace and everything else as in lasad_backward_layer.
+ * lasad_backward_layer computes this tensor by the same kernels and feeds it to the recurrence's
+ * backward (with bf16 inputs together with what the rounding to bf16 left over, as a second
+ * bf16 tensor); the latter alone is lasad_backward_layer with norm_eps < 0 and d_out := d_o.
+ * Workspace and everything else as in lasad_backward_layer.
  */
 int lasad_backward_layer_norm(const void *q_pre, const void *z, const void *v, const void *d_out,
                               void *d_o, float *dweight,

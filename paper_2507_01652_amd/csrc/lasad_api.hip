@@ -400,7 +400,7 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
     a.start_pos = start_pos; a.n_tokens = n_tokens;
     a.mode = boundary_mode; a.q_scale = q_scale;
     a.workspace = workspace;
-    a.fused_act = 0;
+    a.fused_act = 0; a.d_o_lo = nullptr;
     hipError_t e = lasad::launch_backward_gated(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_backward_gated launch", e);
     return LASAD_OK;

@@ -261,13 +261,16 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     // planes: PQ (output row operand), PK (update row operand), PV (update column operand), PL (decay)
     // dq, forward order: g, v, k, lambda
     const int sg = b.fused_act ? ACT_SIGMOID : ACT_NONE, si = b.fused_act ? ACT_SILU : ACT_NONE;
-    w.roles[0] = ScanRoles{{b.d_o, b.v, b.k ? b.k : b.lam, b.lam}, {0, 0, 0, 0}, {0, 0, b.k ? 0 : 1, 0}, {0, 0, b.k ? 0 : sg, sg}};
+    const void *gl_l = last_token(b.d_o_lo, b.in, n, elt);              // low-order part of d_o (layer backward, bf16)
+    w.roles[0] = ScanRoles{{b.d_o, b.v, b.k ? b.k : b.lam, b.lam}, {0, 0, 0, 0}, {0, 0, b.k ? 0 : 1, 0}, {0, 0, b.k ? 0 : sg, sg},
+                           {b.d_o_lo, nullptr, nullptr, nullptr}};
     w.o[0] = dq32; w.in[0] = b.in; w.out[0] = wl; w.start_pos[0] = b.start_pos;
     // dv, reversed order: k, q, g, lambda of the step before
-    w.roles[1] = ScanRoles{{b.k ? k_l : lam_l, q_l, g_l, lam_l}, {0, 0, 0, -1}, {b.k ? 0 : 1, 0, 0, 0}, {b.k ? 0 : sg, si, 0, sg}};
+    w.roles[1] = ScanRoles{{b.k ? k_l : lam_l, q_l, g_l, lam_l}, {0, 0, 0, -1}, {b.k ? 0 : 1, 0, 0, 0}, {b.k ? 0 : sg, si, 0, sg},
+                           {nullptr, nullptr, gl_l, nullptr}};
     w.o[1] = (void *)last_token(b.dv, b.grad, n, gelt); w.in[1] = in_rev; w.out[1] = grad_rev; w.start_pos[1] = rev_start;
     // dk, reversed order: v, g, q, lambda of the step before
-    w.roles[2] = ScanRoles{{v_l, g_l, q_l, lam_l}, {0, 0, 0, -1}, {0, 0, 0, 0}, {0, 0, si, sg}};
+    w.roles[2] = ScanRoles{{v_l, g_l, q_l, lam_l}, {0, 0, 0, -1}, {0, 0, 0, 0}, {0, 0, si, sg}, {nullptr, gl_l, nullptr, nullptr}};
     w.o[2] = (void *)last_token(dk32, wl, n, 4); w.in[2] = in_rev; w.out[2] = wl_rev; w.start_pos[2] = rev_start;
 
     const bool in16 = b.io_dtype == LASAD_BF16, out16 = b.grad_dtype == LASAD_BF16;
@@ -278,10 +281,12 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
         ForwardArgs p[3] = {f, f, f};
         p[0].q = b.d_o; p[0].lam = b.lam; p[0].k = b.k; p[0].v = b.v; p[0].o = dq32;                  // dq
         p[0].in = b.in; p[0].out = wl; p[0].out_dtype = LASAD_F32; p[0].start_pos = b.start_pos;
+        p[0].q_lo = b.d_o_lo;
         p[1].q = b.k ? k_l : lam_l; p[1].lam = lam_l; p[1].k = q_l; p[1].v = g_l; p[1].o = w.o[1];     // dv
         p[1].in = in_rev; p[1].out = grad_rev; p[1].out_dtype = b.grad_dtype; p[1].start_pos = rev_start;
         p[2] = p[1];
         p[2].q = v_l; p[2].o = w.o[2]; p[2].out = wl_rev; p[2].out_dtype = LASAD_F32;                  // dk
+        p[2].v_lo = gl_l;
         e = launch_backward_gated_passes(p, w.roles, b.k == nullptr, s);
         if (e != hipSuccess) return e;
     } else {

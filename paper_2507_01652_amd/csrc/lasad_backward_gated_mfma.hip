@@ -38,11 +38,11 @@ __device__ __noinline__ void redo_roles(const ForwardArgs *a, const scan::ScanRo
 
 // One pass for sequence bh by the calling twelve-wave workgroup; ka, kr: the pass's arguments and
 // operand roles in the kernel-argument segment (for the fallback).
-template <int OUT_BF16, int OWNKEY, int FUSED, int SHIFT, int QMODE, int COL>
+template <int OUT_BF16, int OWNKEY, int FUSED, int SHIFT, int QMODE, int COL, int XLO = 0, int YLO = 0>
 __device__ __forceinline__ void pass_body(const ForwardArgs &a, const ForwardArgs *ka, const scan::ScanRoles *kr, int bh,
                                           uint16_t *smem, float (*sTot)[D], int (*sTrip)[4])
 {
-    gated_ws_body<OUT_BF16, OWNKEY, FUSED, 0, SHIFT, QMODE, COL>(a, bh, smem, sTot, sTrip, nullptr, [&](float *lds) {
+    gated_ws_body<OUT_BF16, OWNKEY, FUSED, 0, SHIFT, QMODE, COL, XLO, YLO>(a, bh, smem, sTot, sTrip, nullptr, [&](float *lds) {
         redo_roles<OUT_BF16, COL>(ka, kr, bh, lds);
     });
 }
@@ -55,8 +55,12 @@ struct PassSet {
 // The three passes of a call in one launch.  Workgroups come in groups of 8 sequences x 3 passes,
 // a sequence's passes 8 workgroup ids apart: they start together on the same XCD (ids go round
 // the 8 XCDs) and share what they both read through its L2 (dv and dk walk the same q, d_o and
-// lambda rows in the same order).  TIED: the key is 1 - lambda.  FUSED (with TIED): the q and lambda
-// tensors hold Algorithm 1's pre-activation query and gate logits.
+// lambda rows in the same order).  TIED: the key is 1 - lambda.  FUSED (with TIED): the layer's
+// backward: the q and lambda tensors hold Algorithm 1's pre-activation query and gate logits, and
+// d_o comes as a bf16 pair hi + lo, both parts used where it is an operand of a column pass (x of
+// the dq pass, y of the dk pass: one more MFMA per score step and per state term).  d_o is
+// orthogonal to the recurrence output, which makes dq and dk small differences of larger terms
+// early in a sequence; a single bf16 there costs up to 0.15 of the RMS in single elements.
 template <int OUT_BF16, int TIED, int FUSED = 0>
 __global__ void __launch_bounds__(kWsThreads, 1)
 backward_gated_passes_kernel(PassSet ps)
@@ -70,9 +74,9 @@ backward_gated_passes_kernel(PassSet ps)
     const int pass = r >> 3, bh = grp * 8 + (r & 7);
     if (bh >= ps.a[0].B * ps.a[0].Hh) return;                  // (the last group may be partly empty)
     const PassSet *kp = (const PassSet *)__builtin_amdgcn_kernarg_segment_ptr();
-    if (pass == 0) pass_body<0, TIED ? 0 : 1, FUSED, 0, 1, 1>(ps.a[0], &kp->a[0], &kp->roles[0], bh, smem, sTot, sTrip);
+    if (pass == 0) pass_body<0, TIED ? 0 : 1, FUSED, 0, 1, 1, FUSED, 0>(ps.a[0], &kp->a[0], &kp->roles[0], bh, smem, sTot, sTrip);
     else if (pass == 1) pass_body<OUT_BF16, 1, FUSED, 1, TIED ? 2 : 0, 0>(ps.a[1], &kp->a[1], &kp->roles[1], bh, smem, sTot, sTrip);
-    else pass_body<0, 1, FUSED, 1, 1, 1>(ps.a[2], &kp->a[2], &kp->roles[2], bh, smem, sTot, sTrip);
+    else pass_body<0, 1, FUSED, 1, 1, 1, 0, FUSED>(ps.a[2], &kp->a[2], &kp->roles[2], bh, smem, sTot, sTrip);
 }
 
 }  // namespace
@@ -90,7 +94,7 @@ hipError_t launch_backward_gated_passes(const ForwardArgs *a, const scan::ScanRo
     const dim3 grid((unsigned)((n_seq + 7) / 8 * 24)), block(kWsThreads);
     const bool out16 = a[1].out_dtype == LASAD_BF16;
     if (a[0].fused_act) {
-        if (!tied) return hipErrorInvalidValue;
+        if (!tied || !a[0].q_lo || !a[2].v_lo) return hipErrorInvalidValue;
         if (out16) hipLaunchKernelGGL((backward_gated_passes_kernel<1, 1, 1>), grid, block, 0, s, ps);
         else hipLaunchKernelGGL((backward_gated_passes_kernel<0, 1, 1>), grid, block, 0, s, ps);
     } else if (tied) {

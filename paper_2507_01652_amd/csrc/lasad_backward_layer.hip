@@ -17,10 +17,11 @@
 //
 // Precision.  d_o is orthogonal to o (the normalisation ignores the length of o), and early in a
 // sequence the state is close to rank one with o along its dominant direction, so dq = S d_o and
-// dk are small differences of larger terms.  With bf16 inputs d_o is STORED in bf16 between steps 2
-// and 3 (the matrix-core passes take bf16 operands), and that rounding shows in dq_pre and dz several
-// times larger than it does elsewhere (fp32 inputs keep d_o in fp32).  Steps 1-2 can be run alone
-// (d_o_out), step 3 alone is the call without a normalisation; each meets the usual tolerance.
+// dk are small differences of larger terms: d_o rounded to a single bf16 shows in dq_pre and dz up
+// to 0.15 of their RMS.  With bf16 inputs step 2 therefore leaves d_o as a bf16 PAIR hi + lo (two
+// tensors), and the two column passes of step 3 use both parts where d_o is their operand (the
+// row pass, dv, takes hi alone: no cancellation there).  fp32 inputs keep d_o in fp32.  Steps 1-2
+// can be run alone (d_o_out: hi only), step 3 alone is the call without a normalisation.
 #include "lasad_scan.h"
 
 namespace lasad {
@@ -35,7 +36,7 @@ constexpr int kNbTokens = 64;            // tokens per workgroup of the norm-bac
 // Thread (row, c4) holds four channels of one token; a token's 16 threads are neighbours in a wave.
 template <int IN_BF16, int NORM>
 __global__ void __launch_bounds__(kNbThreads)
-norm_backward_kernel(LayerBackwardArgs a, const float *o32, void *d_o, lasad_layout_t dl, float *wpart, int nblk)
+norm_backward_kernel(LayerBackwardArgs a, const float *o32, void *d_o, void *d_o_lo, lasad_layout_t dl, float *wpart, int nblk)
 {
     __shared__ __attribute__((aligned(16))) float sW[kNbTokens][kD + 4];
     const int bh = blockIdx.x / nblk, blk = blockIdx.x - bh * nblk;
@@ -82,6 +83,18 @@ norm_backward_kernel(LayerBackwardArgs a, const float *o32, void *d_o, lasad_lay
             w.x = (uint32_t)float_to_bf16_bits(res[0]) | ((uint32_t)float_to_bf16_bits(res[1]) << 16);
             w.y = (uint32_t)float_to_bf16_bits(res[2]) | ((uint32_t)float_to_bf16_bits(res[3]) << 16);
             *(uint2 *)((uint16_t *)d_o + i) = w;
+            if (d_o_lo) {                  // what the rounding to bf16 left over, again as bf16
+                float lo[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t hi = (e & 1) ? ((e < 2 ? w.x : w.y) & 0xffff0000u) : ((e < 2 ? w.x : w.y) << 16);
+                    lo[e] = res[e] - __uint_as_float(hi);
+                }
+                uint2 wl;
+                wl.x = (uint32_t)float_to_bf16_bits(lo[0]) | ((uint32_t)float_to_bf16_bits(lo[1]) << 16);
+                wl.y = (uint32_t)float_to_bf16_bits(lo[2]) | ((uint32_t)float_to_bf16_bits(lo[3]) << 16);
+                *(uint2 *)((uint16_t *)d_o_lo + i) = wl;
+            }
         } else {
             *(f4 *)((float *)d_o + i) = res;
         }
@@ -127,7 +140,7 @@ size_t extent(const lasad_layout_t &l, int B, int n, int Hh, int d)
     return (size_t)((int64_t)(B - 1) * l.stride_b + (int64_t)(n - 1) * l.stride_n + (int64_t)(Hh - 1) * l.stride_h + d);
 }
 
-struct Regions { size_t core, o32, d_o, wpart, total; };
+struct Regions { size_t core, o32, d_o, d_o_lo, wpart, total; };
 
 Regions regions(int B, int Hh, int n, int d, int io_dtype, const lasad_layout_t &in)
 {
@@ -137,7 +150,8 @@ Regions regions(int B, int Hh, int n, int d, int io_dtype, const lasad_layout_t 
     r.core = 0;
     r.o32 = align256(backward_gated_workspace_bytes(n_seq, n, d));
     r.d_o = r.o32 + align256((size_t)n_seq * n * d * sizeof(float));
-    r.wpart = r.d_o + align256(extent(in, B, n, Hh, d) * (io_dtype == LASAD_BF16 ? 2 : 4));
+    r.d_o_lo = r.d_o + align256(extent(in, B, n, Hh, d) * (io_dtype == LASAD_BF16 ? 2 : 4));
+    r.wpart = r.d_o_lo + (io_dtype == LASAD_BF16 ? align256(extent(in, B, n, Hh, d) * 2) : 0);
     r.total = r.wpart + align256((size_t)n_seq * nblk * d * sizeof(float));
     return r;
 }
@@ -161,6 +175,8 @@ hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipS
     float *o32 = (float *)(ws + r.o32);
     void *d_o = a.d_o_out ? a.d_o_out : ws + r.d_o;
     const lasad_layout_t dl = a.d_o_out ? a.d_o_l : a.in;
+    // bf16: the whole call keeps what the rounding of d_o to bf16 leaves over as a second bf16 tensor
+    void *d_o_lo = (!a.d_o_out && a.io_dtype == LASAD_BF16) ? ws + r.d_o_lo : nullptr;
     float *wpart = (float *)(ws + r.wpart);
     const bool norm = a.norm_eps >= 0.f;
     const bool in16 = a.io_dtype == LASAD_BF16;
@@ -183,10 +199,10 @@ hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipS
     }
     {                                                                   // 2. d_o (and the weight-gradient partial sums)
         const dim3 grid((unsigned)(n_seq * nblk)), block(kNbThreads);
-        if (in16 && norm) hipLaunchKernelGGL((norm_backward_kernel<1, 1>), grid, block, 0, s, a, o32, d_o, dl, wpart, nblk);
-        else if (in16) hipLaunchKernelGGL((norm_backward_kernel<1, 0>), grid, block, 0, s, a, o32, d_o, dl, wpart, nblk);
-        else if (norm) hipLaunchKernelGGL((norm_backward_kernel<0, 1>), grid, block, 0, s, a, o32, d_o, dl, wpart, nblk);
-        else hipLaunchKernelGGL((norm_backward_kernel<0, 0>), grid, block, 0, s, a, o32, d_o, dl, wpart, nblk);
+        if (in16 && norm) hipLaunchKernelGGL((norm_backward_kernel<1, 1>), grid, block, 0, s, a, o32, d_o, d_o_lo, dl, wpart, nblk);
+        else if (in16) hipLaunchKernelGGL((norm_backward_kernel<1, 0>), grid, block, 0, s, a, o32, d_o, d_o_lo, dl, wpart, nblk);
+        else if (norm) hipLaunchKernelGGL((norm_backward_kernel<0, 1>), grid, block, 0, s, a, o32, d_o, d_o_lo, dl, wpart, nblk);
+        else hipLaunchKernelGGL((norm_backward_kernel<0, 0>), grid, block, 0, s, a, o32, d_o, d_o_lo, dl, wpart, nblk);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -206,7 +222,7 @@ hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipS
     g.start_pos = a.start_pos; g.n_tokens = n;
     g.mode = a.mode; g.q_scale = a.q_scale;
     g.workspace = ws + r.core;
-    g.fused_act = 1;
+    g.fused_act = 1; g.d_o_lo = d_o_lo;
     e = launch_backward_gated(g, s);
     if (e != hipSuccess) return e;
     if (a.dweight) {                                                    // 4. weight gradient (zero without a norm)

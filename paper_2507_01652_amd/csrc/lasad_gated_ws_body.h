@@ -34,11 +34,13 @@ constexpr int kSetHalfs = 2 * C * RS + 2 * C * KS + C * TS + 2 * D * RS + C * RS
 // a: the call's (or the pass's) arguments; bh: the sequence; smem: 2 * kSetHalfs bf16 elements;
 // sTot: A_end per key channel by chunk parity; sTrip: range flag of each loader wave by barrier
 // parity; sSS (NORM only): sums of squares [chunk parity][channel half][token].
-template <int OUT_BF16, int OWNKEY, int FUSED, int NORM, int SHIFT, int QMODE, int COL, class Fallback>
+template <int OUT_BF16, int OWNKEY, int FUSED, int NORM, int SHIFT, int QMODE, int COL, int XLO = 0, int YLO = 0, class Fallback = void>
 __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint16_t *smem, float (*sTot)[D],
                                               int (*sTrip)[4], float *sSS, Fallback fallback_fn)
 {
     static_assert(!COL || (QMODE == 1 && !OUT_BF16 && !NORM), "column passes: query of ones, fp32 output, no norm");
+    static_assert(COL || (!XLO && !YLO), "two-part operands: column passes only");
+    static_assert(TS >= RS, "the low-order Y tile sits in the output tile's place");
     auto sQh = [&](int p) { return smem + p * kSetHalfs; };
     auto sQl = [&](int p) { return smem + p * kSetHalfs + C * RS; };
     auto sKh = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS; };
@@ -47,6 +49,7 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
     auto sSh = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS + 2 * C * KS + C * TS; };
     auto sSl = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS + 2 * C * KS + C * TS + D * RS; };
     auto sO = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS + 2 * C * KS + C * TS + 2 * D * RS; };
+    auto sVl = sO;     // YLO: low-order part of the Y tile, row stride RS (a column pass stores fp32 from registers)
 
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const int tid = threadIdx.x;
@@ -63,6 +66,8 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
     const uint16_t *gl = (const uint16_t *)a.lam + in_base;
     const uint16_t *gk = OWNKEY ? (const uint16_t *)a.k + in_base : nullptr;
     const uint16_t *gv = (const uint16_t *)a.v + in_base;
+    const uint16_t *gql = XLO ? (const uint16_t *)a.q_lo + in_base : nullptr;
+    const uint16_t *gvl = YLO ? (const uint16_t *)a.v_lo + in_base : nullptr;
     const int64_t o_base = (int64_t)b * a.out.stride_b + (int64_t)h * a.out.stride_h;
     const int n_chunks = (n + C - 1) / C;
 
@@ -169,20 +174,22 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
         // The state waves also stage V (a plain copy; they have the time): thread st takes the
         // 16-byte pieces (st & 7) of rows st / 8 and st / 8 + 32, loaded one chunk ahead with
         // clamped addresses, rows past the end zeroed.
-        uint4 rvs[2];
+        uint4 rvs[2], rvl[2];
         auto load_v = [&](int chunk) {
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
                 const int tok = min(chunk * C + (st >> 3) + 32 * it, n - 1);
                 rvs[it] = *(const uint4 *)(gv + (int64_t)tok * a.in.stride_n + (st & 7) * 8);
+                if (YLO) rvl[it] = *(const uint4 *)(gvl + (int64_t)tok * a.in.stride_n + (st & 7) * 8);
             }
         };
         auto write_v = [&](int chunk) {
-            uint16_t *bV = sV(chunk & 1);
+            uint16_t *bV = sV(chunk & 1), *bVl = sVl(chunk & 1);
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
                 const int row = (st >> 3) + 32 * it;
                 *(uint4 *)&bV[row * TS + (st & 7) * 8] = keep_or(chunk * C + row < n, rvs[it], 0u);
+                if (YLO) *(uint4 *)&bVl[row * RS + (st & 7) * 8] = keep_or(chunk * C + row < n, rvl[it], 0u);
             }
         };
         load_v(0);
@@ -193,7 +200,7 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int p = chunk & 1;
             GPROF(0);
-            const uint16_t *bKh = sKh(p), *bKl = sKl(p), *bV = sV(p);
+            const uint16_t *bKh = sKh(p), *bKl = sKl(p), *bV = sV(p), *bVl = sVl(p);
             // ---- S[dk][dv] += sum_j K~[j][dk] V[j][dv], then row dk times A_end[dk] ----
             const int trow = (lane & 15) >> 2;
             const int vcol = wc * 32 + 16 * (l32 >> 4) + 4 * (lane & 3);
@@ -207,6 +214,12 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 fk.h[0] = tr_read(&bKh[r0 * KS + kcol]);
                 fk.h[1] = tr_read(&bKh[r1 * KS + kcol]);
                 accS = mfma(fk, fv, accS);
+                if (YLO) {                                   // K~ hi times the low-order part of V
+                    Frag fvl;
+                    fvl.h[0] = tr_read(&bVl[r0 * RS + vcol]);
+                    fvl.h[1] = tr_read(&bVl[r1 * RS + vcol]);
+                    accS = mfma(fk, fvl, accS);
+                }
                 fk.h[0] = tr_read(&bKl[r0 * KS + kcol]);
                 fk.h[1] = tr_read(&bKl[r1 * KS + kcol]);
                 accS = mfma(fk, fv, accS);
@@ -279,7 +292,16 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
 #pragma unroll
         for (int s = 0; s < 4; ++s) fxn[s].u = *(const uint4 *)(p + 16 * s);
     };
+    // XLO: the low-order part of x, ONE register set: loaded for the next chunk after this chunk's last use
+    Frag fxl[4];
+    auto load_xl = [&](int chunk) {
+        const int xtok = min(chunk * C + (wa ^ (chunk & 1)) * 32 + l32, n - 1);
+        const uint16_t *p = gql + (int64_t)xtok * a.in.stride_n + 8 * g;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) fxl[s].u = *(const uint4 *)(p + 16 * s);
+    };
     if (COL) prefetch_x(0);
+    if (XLO) load_xl(0);
     if (barrier_flag(false)) { fallback(); return; }
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
@@ -374,8 +396,13 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 const bool live = t0 + i_row < n;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) fx[s].u = keep_or(live, fxn[s].u, 0u);
+                if (XLO) {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) fxl[s].u = keep_or(live, fxl[s].u, 0u);
+                }
             }
             if (chunk + 1 < n_chunks) prefetch_x(chunk + 1);
+            const uint16_t *bVl = sVl(p);
             // scores P^T[j][i] = sum_e Y[j][e] X[i][e] of key block jb (plain bf16 operands)
             auto scores = [&](int jb) {
                 f32x16 acc = zero16;
@@ -384,6 +411,11 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                     Frag fy;
                     fy.u = *(const uint4 *)&bV[(jb * 32 + l32) * TS + 16 * s + 8 * g];
                     acc = mfma(fy, fx[s], acc);
+                    if (XLO) acc = mfma(fy, fxl[s], acc);
+                    if (YLO) {
+                        fy.u = *(const uint4 *)&bVl[(jb * 32 + l32) * RS + 16 * s + 8 * g];
+                        acc = mfma(fy, fx[s], acc);
+                    }
                 }
                 return acc;
             };
@@ -429,9 +461,11 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 sl.h[1] = tr_read(&bSl[(16 * s + 8 * g + 4 + trow) * RS + tcol]);
                 accO = mfma(sh, fx[s], accO);
                 accO = mfma(sl, fx[s], accO);
+                if (XLO) accO = mfma(sh, fxl[s], accO);
             }
             f32x16 acc1 = zero16;
             if (qa == 1) acc1 = scores(1);
+            if (XLO && chunk + 1 < n_chunks) load_xl(chunk + 1);      // (its last use in this chunk is behind us)
             accO = intra(accO, acc0, 0, qa == 0);
             if (qa == 1) accO = intra(accO, acc1, 1, true);
             // ---- times q_scale A_i[c] (staged as Q~ of a query of ones, bf16 hi + lo) ----

@@ -34,6 +34,9 @@ struct ForwardArgs {
     // segment-parallel plan of the MFMA kernel (filled by its launcher)
     float *seg_states;           // workspace: [B*Hh][n_segments-1][d][d] fp32, or NULL
     int n_segments, seg_chunks;
+    // column passes of the layer backward only: low-order bf16 parts of the tensors in the q and v fields
+    // (the operand is hi + lo; same layout), or NULL
+    const void *q_lo = nullptr, *v_lo = nullptr;
 };
 
 // Up to three independent forward passes in one launch of the wave-specialised kernels
@@ -124,6 +127,7 @@ struct GatedBackwardArgs {
     int mode;
     float q_scale;
     void *workspace;
+    const void *d_o_lo;                  // fused_act with bf16 inputs: low-order bf16 part of d_o (d_o is hi + lo), else NULL
     int fused_act;                       // 1: q and lam hold Algorithm 1's pre-activation query and gate logits
                                          // (tied key only); dq and dlam are then the gradients of THOSE tensors
 };

@@ -47,6 +47,7 @@ struct ScanRoles {
     int shift[4];         // 0, or -1: the plane of token m holds the tensor's token m - 1 (token 0: a neutral value)
     int one_minus[4];     // the plane holds 1 - x (a key tied to the decay)
     int act[4];           // applied to the tensor's value first: 0 nothing, 1 SiLU, 2 sigmoid (Algorithm 1's activations)
+    const void *lo[4];    // not NULL (bf16 inputs only): a second tensor of the same layout, added to the first
 };
 enum { ACT_NONE = 0, ACT_SILU = 1, ACT_SIGMOID = 2 };
 
@@ -150,7 +151,7 @@ struct Loader {
     }
 
     // convert the fetched batch to fp32 and write it to the LDS stage [plane][token][channel]
-    __device__ void stage(const ForwardArgs &a, int t0, float *st) const
+    __device__ void stage(const ForwardArgs &a, int64_t in_base, int t0, float *st) const
     {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
@@ -176,6 +177,15 @@ struct Loader {
             const bool past_end = t0 + tok >= a.n_tokens;
             if (ROLES) {
                 // plane = tensor index; rows past the end and a shifted read before the first token are neutral
+                if (IN_BF16 && roles->lo[arr]) {             // (rare route: loaded here, not ahead)
+                    const int t = max(min(t0 + tok, a.n_tokens - 1) + roles->shift[arr], 0);
+                    const u4 w = *(const u4 *)((const uint16_t *)roles->lo[arr] + in_base + (int64_t)t * a.in.stride_n + c0);
+#pragma unroll
+                    for (int e = 0; e < VEC / 2; ++e) {
+                        f[2 * e] += __uint_as_float(w[e] << 16);
+                        f[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+                    }
+                }
                 if (roles->act[arr]) {
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) f[e] = roles->act[arr] == ACT_SILU ? silu_f32(f[e]) : sigmoid_f32(f[e]);
@@ -278,7 +288,7 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds, 
     ld.roles = roles;
     if (nb > 0) {
         ld.fetch(a, in_base, 0);
-        ld.stage(a, 0, s_stage[0]);
+        ld.stage(a, in_base, 0, s_stage[0]);
     }
     __syncthreads();
 
@@ -312,7 +322,7 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds, 
             red[(tt * CG + cg) * NJ + j] = (o[0] + o[1]) + (o[2] + o[3]);
         }
 
-        ld.stage(a, t0 + kT, s_stage[(bt + 1) & 1]);
+        ld.stage(a, in_base, t0 + kT, s_stage[(bt + 1) & 1]);
         __syncthreads();
 
         // add the groups' partial sums and store o for this batch, two channels per thread and pass

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2507_01652_amd import workloads as wl
-from helpers import TOL, gather_pairs, parity_err, rel_err, sample_pairs
+from helpers import TOL, parity_err, rel_err, sample_pairs
 
 pytestmark = pytest.mark.gpu
 
@@ -29,11 +29,6 @@ def _inputs(B, n, Hh, d, dtype, seed):
     v = wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(np.sqrt(d)), dtype)
     g = wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(np.sqrt(d)), dtype)
     return q, z, v, g
-
-
-def _store(dtype):
-    """Rounding to the storage type, as a function for the oracle's store_d_o hook."""
-    return None if dtype == "f32" else (lambda x: wl.store_round(np.asarray(x, dtype=np.float32), dtype))
 
 
 def _weight(Hh, d, seed=3):
@@ -64,41 +59,37 @@ def _tol(nm, dtype, z):
 
 def _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, w, eps, dtype="bf16", start=0, mode=0, q_scale=1.0,
                  grad_bf16=False):
-    """The layer's backward in its two parts, each against the oracle, and the whole call against their chain.
-
-    With bf16 inputs the library stores the gradient d_o between the normalisation's and the recurrence's backward
-    in bf16.  d_o is orthogonal to the recurrence output, which makes dq and dz at the first tokens of a sequence
-    small differences of larger terms: ONE element of d_o rounded the other way (the library computes d_o from an
-    fp32 o, the oracle from an fp64 one) moves them by more than the tolerance, so the whole call cannot be held
-    against an oracle that rounds at the same point.  Instead:
-      1. lasad_backward_layer_norm: d_o (to the tolerance plus its own storage rounding) and dweight;
-      2. the recurrence + activations part (the call without a normalisation) on the ORACLE's d_o, rounded;
-      3. the whole call must equal part 2 run on the library's own d_o, bit for bit, and give part 1's dweight.
-    test_backward_layer_against_the_unrounded_oracle records what the storage rounding costs end to end."""
+    """The whole call against the oracle, and its two parts as calls of their own:
+      1. lasad_backward_layer_norm: d_o (to the tolerance plus its storage rounding) and dweight;
+      2. the recurrence + activations part (the call without a normalisation) on the oracle's d_o, rounded to the
+         storage type (an input like any other).
+    The whole call keeps d_o as a bf16 pair between the two parts, so it is held against the UNROUNDED oracle."""
     import torch
     kw = dict(start=start, mode=mode, q_scale=q_scale)
+    okw = dict(start_pos=start, mode=mode, q_scale=q_scale)
     wt = None if w is None else torch.from_numpy(w).cuda()
-    d_o_ref, dw_ref = oracle.layer_norm_backward(q, z, v, g, W, norm_weight=w, eps=eps, start_pos=start, mode=mode,
-                                                 q_scale=q_scale)
+    d_o_ref, dw_ref = oracle.layer_norm_backward(q, z, v, g, W, norm_weight=w, eps=eps, **okw)
     d_o, dw = lasad.lasad_backward_layer_norm(*dev_in, H, W, norm_weight=wt, norm_eps=eps, start_pos=start,
                                               boundary_mode=mode, q_scale=q_scale)
     torch.cuda.synchronize()
     # d_o depends on the DIRECTION of o_t: a token whose o nearly cancels (a short o_t, hence a large d_o_t) carries
     # the fp32 rounding of o, relative to that short length, into d_o.  With fp32 inputs the tolerance sits at the
     # rounding level, so it gets a factor 10 for this (measured 2.4e-5); with bf16 inputs it is far above it.
+    cond = 10 if dtype == "f32" else 1
     err = parity_err(d_o.float().cpu().numpy(), d_o_ref, dtype == "bf16")
-    assert err <= (10 * TOL[dtype] if dtype == "f32" else TOL[dtype]), ("d_o", err)
+    assert err <= cond * TOL[dtype], ("d_o", err)
     assert rel_err(dw.cpu().numpy(), dw_ref) <= TOL[dtype], "dweight"
     d_o_in = wl.store_round(d_o_ref.astype(np.float32), dtype)
     got = _call(lasad, dtype, (*dev_in[:3], lasad.to_device(d_o_in, dtype)), H, W, None, -1.0, grad_bf16=grad_bf16, **kw)
-    ref = oracle.layer_core_backward(q, z, v, d_o_in, W, start_pos=start, mode=mode, q_scale=q_scale)
+    ref = oracle.layer_core_backward(q, z, v, d_o_in, W, **okw)
     for nm, a, r in zip(("dq_pre", "dz", "dv"), got, ref):
         err = parity_err(a.float().cpu().numpy(), r, grad_bf16)
         assert err <= _tol(nm, dtype, z), (nm, err)
     whole = _call(lasad, dtype, dev_in, H, W, w, eps, grad_bf16=grad_bf16, **kw)
-    chain = _call(lasad, dtype, (*dev_in[:3], d_o), H, W, None, -1.0, grad_bf16=grad_bf16, **kw)
-    for nm, a, b in zip(("dq_pre", "dz", "dv"), whole, chain):
-        assert torch.equal(a, b), nm
+    ref = oracle.gated_layer_backward(q, z, v, g, W, norm_weight=w, eps=eps, **okw)
+    for nm, a, r in zip(("dq_pre", "dz", "dv"), whole, ref):
+        err = parity_err(a.float().cpu().numpy(), r, grad_bf16)
+        assert err <= cond * _tol(nm, dtype, z), (nm, err)
     assert torch.equal(whole[3], dw)
 
 
@@ -115,13 +106,11 @@ def _check(lasad, oracle, B, Hh, H, W, dtype, seed, norm="weighted", start=0, n=
         assert not got[3].any()
         return
     dev_in = tuple(lasad.to_device(x, dtype) for x in (q, z, v, g))
-    _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, w, 1e-5, dtype, start, mode, q_scale, grad_bf16)
-    if dtype == "f32":                                   # nothing is rounded in between: the whole call, directly
-        got = _run(lasad, dtype, q, z, v, g, H, W, w, 1e-5, start, mode, q_scale)
-        ref = oracle.gated_layer_backward(q, z, v, g, W, norm_weight=w, eps=1e-5, start_pos=start, mode=mode, q_scale=q_scale)
-        for nm, a, r in zip(("dq_pre", "dz", "dv"), got, ref):       # (through d_o: the same factor 10)
-            assert parity_err(a, r, False) <= 10 * _tol(nm, dtype, z), (nm, parity_err(a, r, False))
-        assert rel_err(got[3], ref[3]) <= TOL[dtype]
+    # one token: o is a multiple of v_0 whatever q and z are, so with a tiny eps the layer output does not depend on
+    # them at all and dq_pre, dz are nothing but the residue of a total cancellation; an eps of the size of
+    # mean(o^2) leaves a gradient to compare
+    eps = 1e-5 if n > 1 else 1e-2
+    _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, w, eps, dtype, start, mode, q_scale, grad_bf16)
 
 
 CASES = [
@@ -177,53 +166,27 @@ def test_backward_layer_strong_gates_take_the_serial_route(lasad, oracle):
     _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, None, 1e-5)
 
 
-def test_backward_layer_bench_shape_sampled(lasad, oracle):
-    """The base benchmark shape in the benchmark's launch configuration, part by part as in _check_parts, the
-    oracle on sampled sequences (dweight sums over the batch: compared for two heads, over all batch rows)."""
+@pytest.mark.parametrize("name", ["base_prefill_16x16", "large_prefill_24x24"])
+def test_backward_layer_bench_shapes_sampled(lasad, oracle, name):
+    """The benchmark shapes in the benchmark's launch configuration; the oracle on sampled sequences (dweight sums
+    over the batch: compared for one head over sampled batch rows by linearity is not possible, so for the base shape
+    it is compared in full for two heads)."""
     import torch
-    w = wl.BASE_PREFILL
+    w = wl.CONFIGS[name]
     q, z, v, g = _inputs(w.B, w.N, w.Hh, w.d, "bf16", w.seed + 21)
     wt = _weight(w.Hh, w.d)
-    dev_in = tuple(lasad.to_device(x, "bf16") for x in (q, z, v, g))
-    wdev = torch.from_numpy(wt).cuda()
-    d_o, dw = lasad.lasad_backward_layer_norm(*dev_in, w.grid_h, w.grid_w, norm_weight=wdev, norm_eps=1e-6)
-    whole = lasad.lasad_backward_layer(*dev_in, w.grid_h, w.grid_w, norm_weight=wdev, norm_eps=1e-6)
-    chain = lasad.lasad_backward_layer(*dev_in[:3], d_o, w.grid_h, w.grid_w, norm_eps=-1.0)
-    torch.cuda.synchronize()
-    for a, b in zip(whole[:3], chain[:3]):
-        assert torch.equal(a, b)
-    assert torch.equal(whole[3], dw)
-    d_o_ref, dw_ref = oracle.layer_norm_backward(q[:, :, :2], z[:, :, :2], v[:, :, :2], g[:, :, :2], w.grid_w,
-                                                 norm_weight=wt[:2], eps=1e-6)
-    assert parity_err(d_o[:, :, :2].float().cpu().numpy(), d_o_ref, True) <= TOL["bf16"]
-    assert rel_err(dw[:2].cpu().numpy(), dw_ref) <= TOL["bf16"]
-    # the recurrence's part on the oracle's (rounded) d_o of the two heads, zero elsewhere; sampled sequences of them
-    d_o_in = np.zeros_like(q)
-    d_o_in[:, :, :2] = wl.store_round(d_o_ref.astype(np.float32), "bf16")
-    got = lasad.lasad_backward_layer(*dev_in[:3], lasad.to_device(d_o_in, "bf16"), w.grid_h, w.grid_w, norm_eps=-1.0)
-    torch.cuda.synchronize()
-    pairs = [(b, h) for b in range(w.B) for h in range(2)][::2]
-    sel = lambda x: gather_pairs(x, pairs)
-    ref = oracle.layer_core_backward(sel(q), sel(z), sel(v), sel(d_o_in), w.grid_w)
-    for nm, a, r in zip(("dq_pre", "dz", "dv"), got, ref):
-        assert parity_err(sel(a.float().cpu().numpy()), r, True) <= TOL["bf16"], nm
-
-
-def test_backward_layer_against_the_unrounded_oracle(lasad, oracle):
-    """The whole call, bf16 inputs, against the oracle WITHOUT the storage rounding of the intermediate gradient:
-    what that rounding costs end to end.  d_o is orthogonal to the recurrence output, and the state is close to
-    rank one early in a sequence and wherever the gates are alike, so dq = S d_o (and dk, hence dz) is a small
-    difference of larger terms there: single elements are off by 0.15 of the RMS (measured), while the error over
-    all elements stays at the level of one bf16 rounding (RMS 3e-3) and dv is not affected.  fp32 inputs keep
-    the gradient in fp32 (test_backward_layer_shapes holds them to the fp32 tolerance)."""
-    B, Hh, H, W = 2, 3, 9, 17
-    q, z, v, g = _inputs(B, H * W, Hh, 64, "bf16", 321)
-    got = _run(lasad, "bf16", q, z, v, g, H, W, None, 1e-5)
-    ref = oracle.gated_layer_backward(q, z, v, g, W, eps=1e-5)
-    for nm, a, r in zip(("dq_pre", "dz", "dv"), got, ref):
-        rms_err = float(np.sqrt(np.mean((a - r) ** 2) / np.mean(r ** 2)))
-        assert rms_err <= TOL["bf16"] / 4, (nm, rms_err)
-        assert parity_err(a, r, False) <= (TOL["bf16"] if nm == "dv" else 0.25), (nm, parity_err(a, r, False))
+    got = _run(lasad, "bf16", q, z, v, g, w.grid_h, w.grid_w, wt, 1e-6, grad_bf16=True)
+    pairs = sample_pairs(w.B, w.Hh, 8, seed=w.seed)
+    ref = [oracle.gated_layer_backward(q[b:b + 1, :, h:h + 1], z[b:b + 1, :, h:h + 1], v[b:b + 1, :, h:h + 1],
+                                       g[b:b + 1, :, h:h + 1], w.grid_w, norm_weight=wt[h:h + 1], eps=1e-6)
+           for b, h in pairs]
+    for i, nm in enumerate(("dq_pre", "dz", "dv")):
+        r = np.concatenate([x[i] for x in ref], axis=0)
+        a = np.concatenate([got[i][b:b + 1, :, h:h + 1] for b, h in pairs], axis=0)
+        assert parity_err(a, r, True) <= TOL["bf16"], (nm, parity_err(a, r, True))
+    if name == "base_prefill_16x16":
+        full = oracle.layer_norm_backward(q[:, :, :2], z[:, :, :2], v[:, :, :2], g[:, :, :2], w.grid_w, norm_weight=wt[:2], eps=1e-6)
+        assert rel_err(got[3][:2], full[1]) <= TOL["bf16"]
 
 
 def test_backward_layer_deterministic_and_workspace_check(lasad):
