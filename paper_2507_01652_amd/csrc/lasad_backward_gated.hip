@@ -68,7 +68,6 @@ backward_gated_walk_kernel(WalkArgs w)
     else scan_sequence<IN_BF16, 0, ROLES_COL, NJ>(a, bh, j0, lds, &w.roles[pass]);     // fp32 into the workspace
 }
 
-constexpr int kFinThreads = 1024;
 constexpr int kFinBlock = 64;          // tokens per step of the finishing kernel
 
 // One workgroup per sequence walks it in blocks of 64 tokens from the last block to the first,
@@ -79,18 +78,23 @@ constexpr int kFinBlock = 64;          // tokens per step of the finishing kerne
 // Few long sequences are cut into n_seg segments of seg_blocks blocks with a workgroup each
 // (blockIdx.y): a first launch (TOTALS) only adds up r over each segment, the second starts every
 // segment from the totals of the segments after it.  seg_totals: [sequence][segment][d] fp32.
+// The channels are independent: with few workgroups a sequence's channels are further divided between
+// 64 / CH workgroups (blockIdx.z) of 16 CH threads, which shortens nothing of the chain of blocks but
+// puts more of them in flight.
 // (fp64 sums were tried: no gain in accuracy, the error left is that of the fp32 dq and dk.)
-template <int IN_BF16, int OUT_BF16, int TOTALS>
-__global__ void __launch_bounds__(kFinThreads)
+template <int IN_BF16, int OUT_BF16, int TOTALS, int CH>
+__global__ void __launch_bounds__(16 * CH)
 backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float *dk32,
                              float *seg_totals, int n_seg, int seg_blocks)
 {
-    __shared__ __attribute__((aligned(16))) float sR[kFinBlock][kD + 4];
-    __shared__ __attribute__((aligned(16))) float sQtr[4][kD];
-    __shared__ __attribute__((aligned(16))) float sCarry[kD];
+    constexpr int LPR = CH / 4;            // threads per token
+    __shared__ __attribute__((aligned(16))) float sR[kFinBlock][CH + 4];
+    __shared__ __attribute__((aligned(16))) float sQtr[4][CH];
+    __shared__ __attribute__((aligned(16))) float sCarry[CH];
     const int bh = blockIdx.x, b = bh / a.Hh, h = bh - b * a.Hh;
     const int tid = threadIdx.x;
-    const int row = tid >> 4, c4 = (tid & 15) * 4;
+    const int ch0 = blockIdx.z * CH;       // this workgroup's first channel
+    const int row = tid / LPR, c4l = (tid % LPR) * 4, c4 = ch0 + c4l;
     const int n = a.n_tokens;
     const int nblk = (n + kFinBlock - 1) / kFinBlock;
     const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + c4;
@@ -140,7 +144,7 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
 
     const int seg = blockIdx.y;
     const int blk_lo = seg * seg_blocks, blk_hi = min(blk_lo + seg_blocks, nblk) - 1;     // this workgroup's blocks
-    float *totals = seg_totals + ((int64_t)bh * n_seg) * kD;
+    float *totals = seg_totals + ((int64_t)bh * n_seg) * kD + ch0;
     if (TOTALS) {
         f4 sum = f4{0.f, 0.f, 0.f, 0.f};
         for (int blk = blk_hi; blk >= blk_lo; --blk) {
@@ -148,16 +152,16 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
             load(blk, it);
             if (blk * kFinBlock + row < n) sum += it.q * it.dq - it.k * it.dk;
         }
-        *(f4 *)&sR[row][c4] = sum;
+        *(f4 *)&sR[row][c4l] = sum;
         __syncthreads();
-        if (tid < kD) {
+        if (tid < CH) {
             float acc = 0.f;
             for (int r2 = kFinBlock - 1; r2 >= 0; --r2) acc += sR[r2][tid];
             totals[seg * kD + tid] = acc;
         }
         return;
     }
-    if (tid < kD) {
+    if (tid < CH) {
         float carry = 0.f;
         for (int s2 = n_seg - 1; s2 > seg; --s2) carry += totals[s2 * kD + tid];
         sCarry[tid] = carry;
@@ -171,10 +175,10 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         const bool live = t < n;
         f4 r = cur.q * cur.dq - cur.k * cur.dk;
         if (!live) r = f4{0.f, 0.f, 0.f, 0.f};
-        *(f4 *)&sR[row][c4] = r;
+        *(f4 *)&sR[row][c4l] = r;
         __syncthreads();
-        if (tid < 4 * kD) {                // suffix sums inside a quarter of the block, top down
-            const int c = tid & (kD - 1), qtr = tid >> 6;
+        if (tid < 4 * CH) {                // suffix sums inside a quarter of the block, top down
+            const int c = tid % CH, qtr = tid / CH;
             float acc = 0.f;
 #pragma unroll
             for (int tt = 15; tt >= 0; --tt) {
@@ -185,8 +189,8 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         }
         __syncthreads();
         {
-            f4 suffix = *(const f4 *)&sR[row][c4] + *(const f4 *)&sCarry[c4];
-            for (int q2 = 3; q2 > (row >> 4); --q2) suffix += *(const f4 *)&sQtr[q2][c4];
+            f4 suffix = *(const f4 *)&sR[row][c4l] + *(const f4 *)&sCarry[c4l];
+            for (int q2 = 3; q2 > (row >> 4); --q2) suffix += *(const f4 *)&sQtr[q2][c4l];
             const bool no_decay = t == 0 || is_boundary(a.start_pos + t + 1, a.grid_w, a.mode);
             f4 dl = suffix / cur.lam;
             if (no_decay) dl = f4{0.f, 0.f, 0.f, 0.f};
@@ -203,7 +207,7 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
             }
         }
         __syncthreads();
-        if (tid < kD) sCarry[tid] += (sQtr[3][tid] + sQtr[2][tid]) + (sQtr[1][tid] + sQtr[0][tid]);
+        if (tid < CH) sCarry[tid] += (sQtr[3][tid] + sQtr[2][tid]) + (sQtr[1][tid] + sQtr[0][tid]);
         cur = nxt;
     }
 }
@@ -311,8 +315,13 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     const int seg_blocks = (nblk + n_seg - 1) / n_seg;
     n_seg = (nblk + seg_blocks - 1) / seg_blocks;
     float *seg_totals = dk32 + (size_t)n_seq * n * b.d;          // after the two gradient tensors
-    const dim3 grid((unsigned)n_seq, (unsigned)n_seg), block(kFinThreads);
-#define LASAD_FIN_LAUNCH(I, O, T) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks)
+    // few workgroups: 16 channels per workgroup (four workgroups of 256 threads per sequence and segment)
+    const bool narrow = n_seq * n_seg < 256;      // (at 480 workgroups the narrow rows already cost more than they gain)
+    const dim3 grid((unsigned)n_seq, (unsigned)n_seg, narrow ? 4 : 1), block(narrow ? 256 : 1024);
+#define LASAD_FIN_LAUNCH(I, O, T) do { \
+        if (narrow) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 16>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks); \
+        else hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 64>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks); \
+    } while (0)
     if (n_seg > 1) {
         if (in16) LASAD_FIN_LAUNCH(1, 0, 1); else LASAD_FIN_LAUNCH(0, 0, 1);
         e = hipGetLastError();
