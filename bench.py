@@ -36,27 +36,27 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 # runs (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a 256 MiB device copy; the
 # summaries are profiles/*_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "base_prefill_16x16": 12790857,      # algorithmic 12582912
-    "large_prefill_24x24": 151152626,    # algorithmic 150994944
-    "highres_64x64": 305351613,          # algorithmic 201326592; the segment plan re-reads K, V once
-    "ar_decode_16x16": 170453790,        # algorithmic 170393600
+    "base_prefill_16x16": 12790811,      # algorithmic 12582912
+    "large_prefill_24x24": 151152333,    # algorithmic 150994944
+    "highres_64x64": 305351320,          # algorithmic 201326592; the segment plan re-reads K, V once
+    "ar_decode_16x16": 170453679,        # algorithmic 170393600
     # vector-decay kernels (key tied to the gate): same algorithmic bytes as the scalar ones
-    "gated:base_prefill_16x16": 12839066,    # algorithmic 12582912
-    "gated:large_prefill_24x24": 158462690,  # algorithmic 150994944
-    "gated:highres_64x64": 201565121,        # algorithmic 201326592 (single launch, no segment plan)
-    "gated:ar_decode_16x16": 170444386,      # algorithmic 170393600
+    "gated:base_prefill_16x16": 12839020,    # algorithmic 12582912
+    "gated:large_prefill_24x24": 158462226,  # algorithmic 150994944
+    "gated:highres_64x64": 201564895,        # algorithmic 201326592 (single launch, no segment plan)
+    "gated:ar_decode_16x16": 170444251,      # algorithmic 170393600
     # backward of the scalar-decay forward (3 passes in one launch; operands shared through the L2 of an XCD)
-    "backward:base_prefill_16x16": 23861583,     # algorithmic 22020096
-    "backward:large_prefill_24x24": 394706472,   # algorithmic 264241152
-    "backward:highres_64x64": 659106082,         # algorithmic 352321536
+    "backward:base_prefill_16x16": 23862317,     # algorithmic 22020096
+    "backward:large_prefill_24x24": 394549254,   # algorithmic 264241152
+    "backward:highres_64x64": 658803305,         # algorithmic 352321536
     # backward of the vector-decay forward (dq, dk make a round trip through the fp32 workspace)
-    "gated_backward:base_prefill_16x16": 54270437,     # algorithmic 22020096
-    "gated_backward:large_prefill_24x24": 696763748,   # algorithmic 264241152
-    "gated_backward:highres_64x64": 1304294087,        # algorithmic 352321536
+    "gated_backward:base_prefill_16x16": 54266073,     # algorithmic 22020096
+    "gated_backward:large_prefill_24x24": 696467867,   # algorithmic 264241152
+    "gated_backward:highres_64x64": 1304421401,        # algorithmic 352321536
     # backward of the fused layer (adds the recomputed forward with o in fp32 and the bf16 round trip of d_o)
-    "layer_backward:base_prefill_16x16": 89686927,     # algorithmic 22020096
-    "layer_backward:large_prefill_24x24": 1153140617,  # algorithmic 264241152
-    "layer_backward:highres_64x64": 1971826753,        # algorithmic 352321536
+    "layer_backward:base_prefill_16x16": 89688632,     # algorithmic 22020096
+    "layer_backward:large_prefill_24x24": 1153303753,  # algorithmic 264241152
+    "layer_backward:highres_64x64": 1972316628,        # algorithmic 352321536
 }
 
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
