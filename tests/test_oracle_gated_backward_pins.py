@@ -97,3 +97,35 @@ def test_tied_key_is_the_own_key_result_minus_dk(oracle):
     pos = np.arange(1, n + 1)
     assert np.all(olam[:, pos % W == 0] == 0.0)           # boundary positions: no gradient through the decay
     assert np.all(olam[:, 0] == 0.0)                      # first token: its decay multiplies the zero state
+
+
+@pytest.mark.parametrize("own_key", [False, True])
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_against_torch_autograd_of_a_mask_form(oracle, mode, own_key):
+    """Automatic differentiation (torch, fp64) of an independent implementation: the recurrence unrolled as a
+    per-channel mask, o_i = q_scale sum_{j<=i} (sum_c q_i[c] k_j[c] D[i][j][c]) v_j, with D from cumulative
+    log-decays that skip the boundary positions; the key either given or 1 - lambda."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(100 + 2 * mode + own_key)
+    B, Hh, H, W, d, start = 1, 2, 3, 4, 3, 2
+    n = H * W - start
+    q, v, g = (rng.standard_normal((B, n, Hh, d)) for _ in range(3))
+    lam = rng.uniform(0.3, 0.99, size=(B, n, Hh, d))
+    k = rng.uniform(0.0, 1.0, size=(B, n, Hh, d)) if own_key else None
+    tq, tl, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, lam, v))
+    tk = torch.tensor(k, dtype=torch.float64, requires_grad=True) if own_key else None
+    key = tk if own_key else 1.0 - tl
+    pos = start + np.arange(1, n + 1)
+    boundary = (pos % W == 0) if mode == 0 else ((pos - 1) % W == 0) if mode == 1 else np.zeros(n, dtype=bool)
+    keep = torch.tensor(~boundary, dtype=torch.float64)[None, :, None, None]
+    cl = torch.cumsum(torch.log(tl) * keep, dim=1)
+    D = torch.exp(cl[:, :, None] - cl[:, None, :])
+    causal = torch.tril(torch.ones(n, n, dtype=torch.float64))[None, :, :, None]
+    scores = torch.einsum("bihc,bjhc,bijhc->bijh", tq, key, D) * causal * 0.6
+    o = torch.einsum("bijh,bjhe->bihe", scores, tv)
+    (o * torch.tensor(g)).sum().backward()
+    res = oracle.gated_backward(q, lam, v, g, W, k=k, start_pos=start, mode=mode, q_scale=0.6)
+    want = [tq.grad, tl.grad, tv.grad] + ([tk.grad] if own_key else [])
+    # the first token's decay multiplies the zero state: the oracle returns 0 there by definition, and so does autograd
+    for got, w in zip(res, want):
+        assert np.allclose(got, w.numpy(), rtol=1e-9, atol=1e-11)

@@ -124,3 +124,35 @@ def test_layer_backward_storage_hook_is_applied_to_the_recurrence_gradient_only(
         assert np.array_equal(base[i], same[i]) and not none[i].any()
         assert np.allclose(twice[i], 2 * base[i], rtol=1e-12, atol=0)
     assert np.array_equal(base[3], none[3]) and np.array_equal(base[3], twice[3])
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_layer_backward_against_torch_autograd_of_a_mask_form(oracle, mode):
+    """Automatic differentiation (torch, fp64) of an independent implementation of the whole layer: activations,
+    tied key, the recurrence unrolled as a per-channel mask o_i = sum_{j<=i} sum_c q_i[c] k_j[c] D[i][j][c] v_j with
+    D from cumulative log-decays (0 at boundary positions), then the root-mean-square normalisation."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(21 + mode)
+    B, Hh, H, W, d = 2, 2, 3, 4, 5
+    n = H * W
+    q, z, v, g = (rng.standard_normal((B, n, Hh, d)) for _ in range(4))
+    w = rng.uniform(0.5, 1.5, size=(Hh, d))
+    eps, qs = 1e-4, 0.7
+    tq, tz, tv, tw = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, z, v, w))
+    lam = torch.sigmoid(tz)
+    key = 1.0 - lam
+    pos = np.arange(1, n + 1)
+    boundary = (pos % W == 0) if mode == 0 else ((pos - 1) % W == 0)
+    keep = torch.tensor(~boundary, dtype=torch.float64)[None, :, None, None]
+    cl = torch.cumsum(torch.log(lam) * keep, dim=1)                          # [B, n, Hh, d]
+    D = torch.exp(cl[:, :, None] - cl[:, None, :])                           # [B, i, j, Hh, d]
+    causal = torch.tril(torch.ones(n, n, dtype=torch.float64))[None, :, :, None]
+    scores = torch.einsum("bihc,bjhc,bijhc->bijh", torch.nn.functional.silu(tq), key, D) * causal * qs
+    o = torch.einsum("bijh,bjhe->bihe", scores, tv)
+    y = o * torch.rsqrt((o * o).mean(dim=-1, keepdim=True) + eps) * tw
+    assert np.allclose(y.detach().numpy(), oracle.gated_layer(q, z, v, W, norm_weight=w, eps=eps, mode=mode, q_scale=qs),
+                       rtol=1e-10, atol=1e-12)
+    (y * torch.tensor(g)).sum().backward()
+    dq, dz, dv, dw = oracle.gated_layer_backward(q, z, v, g, W, norm_weight=w, eps=eps, mode=mode, q_scale=qs)
+    for got, want in ((dq, tq.grad), (dz, tz.grad), (dv, tv.grad), (dw, tw.grad)):
+        assert np.allclose(got, want.numpy(), rtol=1e-9, atol=1e-11)
