@@ -201,3 +201,14 @@ def test_backward_layer_deterministic_and_workspace_check(lasad):
     small = torch.empty((1024,), dtype=torch.uint8, device="cuda")
     with pytest.raises(lasad.LasadError):
         lasad.lasad_backward_layer(dev(q), dev(z), dev(v), dev(g), 16, 16, workspace=small)
+
+
+def test_backward_layer_empty_call_zeroes_the_weight_gradient(lasad):
+    import torch
+    B, Hh, d = 2, 3, 64
+    e = torch.empty((B, 0, Hh, d), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((Hh, d), 7.0, device="cuda")
+    dq, dz, dv, dw2 = lasad.lasad_backward_layer(e, e.clone(), e.clone(), e.clone(), 4, 4, dweight=dw)
+    torch.cuda.synchronize()
+    assert dw2 is dw and not dw.any()
+    assert dq.numel() == 0 and dz.numel() == 0 and dv.numel() == 0
