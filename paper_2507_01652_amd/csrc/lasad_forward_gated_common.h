@@ -214,9 +214,9 @@ struct ChunkStage {
 // reload fields from there inside the chunk loop of the twelve-wave kernel (measured: 18 instead
 // of 11 us at the base shape).  The four-wave kernel is faster with the inlined routine.
 template <int OUT_BF16, int OWNKEY>
-__device__ __noinline__ void redo_sequence(ForwardArgs a, int bh, float *lds)
+__device__ __noinline__ void redo_sequence(const ForwardArgs *a, int bh, float *lds)
 {
-    scan::scan_sequence<1, OUT_BF16, OWNKEY ? scan::OWNKEY : scan::TIED, 64>(a, bh, 0, lds);
+    scan::scan_sequence<1, OUT_BF16, OWNKEY ? scan::OWNKEY : scan::TIED, 64>(*a, bh, 0, lds);
 }
 
 }  // namespace gated

@@ -61,7 +61,7 @@ forward_gated_ws_kernel(ForwardArgs a)
     // every thread of every launch copy the struct to its stack first)
     const int bh = blockIdx.x;
     gated_ws_body<OUT_BF16, OWNKEY, FUSED, NORM, 0, 0, 0>(a, bh, smem, sTot, sTrip, sSS, [&](float *lds) {
-        redo_sequence<OUT_BF16, OWNKEY>(*(const ForwardArgs *)__builtin_amdgcn_kernarg_segment_ptr(), bh, lds);
+        redo_sequence<OUT_BF16, OWNKEY>((const ForwardArgs *)__builtin_amdgcn_kernarg_segment_ptr(), bh, lds);
     });
 }
 
