@@ -212,3 +212,14 @@ def test_backward_layer_empty_call_zeroes_the_weight_gradient(lasad):
     torch.cuda.synchronize()
     assert dw2 is dw and not dw.any()
     assert dq.numel() == 0 and dz.numel() == 0 and dv.numel() == 0
+
+
+def test_backward_layer_head_major_inputs(lasad, oracle):
+    """q_pre, z, v, d_out stored [B, Hh, n, d] (views permuted to the logical [B, n, Hh, d]), gradients token-major."""
+    B, Hh, H, W = 2, 3, 7, 13
+    q, z, v, g = _inputs(B, H * W, Hh, 64, "bf16", 77)
+    w = _weight(Hh, 64)
+    to_hm = lambda x: lasad.to_device(np.ascontiguousarray(x.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3), "bf16")
+    dev_in = tuple(to_hm(x) for x in (q, z, v, g))
+    assert dev_in[0].stride(1) == 64 and dev_in[0].stride(2) == H * W * 64
+    _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, w, 1e-5)
