@@ -1,27 +1,37 @@
 #!/usr/bin/env python3
 """Benchmark of the LASAD hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--legs a,b]
 
-A prefill "step" is one lasad_forward_chunked call over the whole token grid of the chosen
-workload (the decay factors are computed inside the kernel from each token's position); the
-default workload is the base-size layer prefill (batch 8, 12 heads, d 64, 16x16 grid, bf16).
-A decode "step" is one lasad_decode_step call for the AR-decode workload (batch 256, 20 heads,
-fp32 64x64 states), walked over the 16x16 grid in raster order.  Inputs are seeded synthetic
-tensors resident in HBM before the timed region.  Every step works on a different buffer set
-(more than 1 GB in rotation) so that nothing is served from a cache left warm by the previous
-step.  The K timed steps are captured once into a HIP graph and replayed as one submission
-(the eager per-call figure is reported next to it).
+A prefill "step" is one lasad_forward_chunked call over the whole token grid of a workload (the
+decay factors are computed inside the kernel from each token's position).  The headline workload
+is the large-size layer prefill (batch 32, 16 heads, d 64, 24x24 grid, bf16: the 384-pixel
+generation shape); the base-size (16x16) and the high-resolution (64x64) prefill are timed the
+same way as nested legs, and the three together give the time per token-head against the
+sequence length (`linear_in_n`).  A decode "step" is one lasad_decode_step call for the
+AR-decode workload (batch 256, 20 heads, fp32 64x64 states), walked over the 16x16 grid in
+raster order.
 
-Prints ONE JSON line: whole-job prefill tokens/s as `value`, the roofline of the forward
-kernel, the CPU oracle timed on the host cores (`cpu_baseline`), and the decode leg under
-`decode` with its own roofline and CPU baseline.
+Inputs are seeded synthetic tensors resident in HBM before the timed region.  Cold caches,
+whatever K is: every step works on the next of several buffer sets (more than 1 GB in rotation),
+and before every timed region a 1 GiB copy sweeps the caches (the last-level cache holds 256 MB),
+so that nothing a step reads was left there by an earlier step, the warm-up or the capture.  The
+K timed steps are captured once into a HIP graph and replayed as one submission; the figure is
+the median of several such replays, each after its own sweep (the eager per-call figure is
+reported next to it).  Timing is by HIP events on the stream the kernels run on.
+
+Prints ONE JSON line: whole-job prefill tokens/s of the headline workload as `value`, the
+roofline of its forward kernel, the CPU oracle timed on the host cores (`cpu_baseline`), the
+other prefill shapes under `prefill_legs`, `linear_in_n`, and the decode, backward and
+vector-decay legs with their own rooflines and CPU baselines.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -32,164 +42,171 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak
 
-# HBM bytes per step (read + write, all kernels of the step) measured with two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a 256 MiB device copy; the
-# summaries are profiles/*_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {
-    "base_prefill_16x16": 12790811,      # algorithmic 12582912
-    "large_prefill_24x24": 151152333,    # algorithmic 150994944
-    "highres_64x64": 305351320,          # algorithmic 201326592; the segment plan re-reads K, V once
-    "ar_decode_16x16": 170453679,        # algorithmic 170393600
-    # vector-decay kernels (key tied to the gate): same algorithmic bytes as the scalar ones
-    "gated:base_prefill_16x16": 12839020,    # algorithmic 12582912
-    "gated:large_prefill_24x24": 158462226,  # algorithmic 150994944
-    "gated:highres_64x64": 201564895,        # algorithmic 201326592 (single launch, no segment plan)
-    "gated:ar_decode_16x16": 170444251,      # algorithmic 170393600
-    # backward of the scalar-decay forward (3 passes in one launch; operands shared through the L2 of an XCD)
-    "backward:base_prefill_16x16": 23862317,     # algorithmic 22020096
-    "backward:large_prefill_24x24": 394549254,   # algorithmic 264241152
-    "backward:highres_64x64": 658803305,         # algorithmic 352321536
-    # backward of the vector-decay forward (dq, dk make a round trip through the fp32 workspace)
-    "gated_backward:base_prefill_16x16": 54266073,     # algorithmic 22020096
-    "gated_backward:large_prefill_24x24": 696467867,   # algorithmic 264241152
-    "gated_backward:highres_64x64": 1304421401,        # algorithmic 352321536
-    # backward of the fused layer (adds the recomputed forward with o in fp32 and the bf16 round trip of d_o)
-    "layer_backward:base_prefill_16x16": 89688632,     # algorithmic 22020096
-    "layer_backward:large_prefill_24x24": 1153303753,  # algorithmic 264241152
-    "layer_backward:highres_64x64": 1972316628,        # algorithmic 352321536
-}
-
 PREFILL_WORKLOADS = {"base_prefill": "base_prefill_16x16", "large_prefill": "large_prefill_24x24",
                      "highres_prefill": "highres_64x64"}
 
+# rocprofv3 --pmc summaries (FETCH_SIZE + WRITE_SIZE per step, scaled on a copy of known size) of earlier runs
+# of this file; `roofline.traffic` quotes them, it is not measured in the run that prints the line.
+TRAFFIC_FILES = {
+    "forward": "forward_mfma_{w}_traffic.txt",
+    "decode": "decode_kernel_{w}_traffic.txt",
+    "gated": "forward_gated_mfma_{w}_traffic.txt",
+    "gated_decode": "decode_kernel_gated_{w}_traffic.txt",
+    "backward": "backward_{w}_traffic.txt",
+    "gated_backward": "backward_gated_{w}_traffic.txt",
+    "layer_backward": "backward_layer_{w}_traffic.txt",
+}
 
-def parse():
+
+def measured_traffic(kind: str, workload: str):
+    """HBM bytes per step from profiles/<kernel>_<workload>_traffic.txt, or None if there is no such summary."""
+    path = os.path.join(ROOT, "profiles", TRAFFIC_FILES[kind].format(w=workload))
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"HBM traffic per step.*?=\s*(\d+)\s*bytes", text)
+    return int(m.group(1)) if m else None
+
+
+def parse(argv=None):
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=200)
-    p.add_argument("--warmup", type=int, default=20)
-    p.add_argument("--workload", default="base_prefill", choices=sorted(PREFILL_WORKLOADS))
+    p.add_argument("--steps", type=int, default=40)
+    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--workload", default="large_prefill", choices=sorted(PREFILL_WORKLOADS),
+                   help="headline prefill workload (also the shape of the backward and vector-decay legs)")
+    p.add_argument("--legs", default="base_prefill,highres_prefill",
+                   help="other prefill workloads timed as nested legs (comma separated, '' = none)")
+    p.add_argument("--replays", type=int, default=5, help="timed graph replays per figure (the median is reported)")
     p.add_argument("--decode-walks", type=int, default=4, help="timed raster walks of 256 decode steps (0 = skip)")
     p.add_argument("--decode-layers", type=int, default=8, help="state sets in rotation (layers of a model)")
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--no-backward", action="store_true", help="skip the backward-pass leg")
+    p.add_argument("--no-backward", action="store_true", help="skip the backward-pass legs")
     p.add_argument("--no-gated", action="store_true",
-                   help="skip the vector-decay (per-channel gate) forward and decode legs")
+                   help="skip the vector-decay (per-channel gate) forward, backward and decode legs")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
     p.add_argument("--layout", default="bnhd", choices=["bnhd", "bhnd"],
                    help="memory order of q, k, v, o: [B, N, Hh, d] (default) or [B, Hh, N, d]")
     p.add_argument("--buffer-sets", type=int, default=0,
-                   help="prefill buffer sets in rotation (0 = enough for > 1 GB; 1 = warm caches)")
+                   help="prefill buffer sets in rotation (0 = enough for > 1 GB; 1 with --warm = warm caches)")
+    p.add_argument("--warm", action="store_true", help="no cache sweep before the timed regions (for comparison)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run three plain 256 MiB device copies (reference dispatches of known "
                         "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    return p.parse_args()
+    return p.parse_args(argv)
 
 
-def time_region(torch, fn):
-    """Run fn() between two events on the current stream; returns milliseconds."""
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    fn()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1)
+class Timer:
+    """Event timing of step sequences on torch's current stream, with a cache sweep before every timed region."""
 
+    def __init__(self, torch, args):
+        self.torch, self.args = torch, args
+        self.sweep_src = self.sweep_dst = None
+        if not args.warm:
+            n = 512 << 20          # 512 MiB read + 512 MiB written: four times the last-level cache
+            self.sweep_src = torch.empty((n,), dtype=torch.uint8, device="cuda").fill_(1)
+            self.sweep_dst = torch.empty_like(self.sweep_src)
 
-def capture(torch, fn):
-    torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):     # launches go to the capturing stream (the binding reads the current stream)
+    def sweep(self):
+        if self.sweep_src is not None:
+            self.sweep_dst.copy_(self.sweep_src)
+
+    def region(self, fn):
+        """Milliseconds of fn() between two events on the current stream, after a cache sweep."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        self.sweep()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         fn()
-    torch.cuda.synchronize()
-    return g
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    def steps(self, run, steps, warmup):
+        """run(n, first) issues steps first .. first+n-1.  Returns (ms per step, eager ms per step, replay list):
+        `warmup` untimed steps, `steps` eager steps timed once, then the same steps as a HIP graph replayed
+        args.replays times (median)."""
+        torch = self.torch
+        run(warmup, 0)
+        eager = self.region(lambda: run(steps, warmup)) / steps
+        if self.args.no_graph:
+            return eager, eager, None
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):     # launches go to the capturing stream (the binding reads the current stream)
+            run(steps, warmup)
+        torch.cuda.synchronize()
+        g.replay()                    # untimed: the first replay uploads the graph
+        reps = [self.region(g.replay) / steps for _ in range(max(1, self.args.replays))]
+        return statistics.median(reps), eager, reps
 
 
-def bench_prefill(args, torch, lasad, wl):
-    import numpy as np
-    w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
+def n_sets(args, bytes_per_step, cap=96):
+    return args.buffer_sets if args.buffer_sets > 0 else max(4, min(cap, -(-(1 << 30) // bytes_per_step)))
+
+
+def hbm_roofline(kernel, bytes_per_launch, dur_s, traffic):
+    achieved = bytes_per_launch / dur_s / 1e9
+    return {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_per_launch,
+            "traffic": traffic, "traffic_source": "profiles/ (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier "
+                                                  "run of this file; not measured in this run)"}
+
+
+def bench_prefill(args, timer, torch, lasad, wl, name):
+    w = wl.CONFIGS[PREFILL_WORKLOADS[name]]
     q, k, v, gam = wl.prefill_inputs(w, layout=args.layout)
     tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
     tg = torch.from_numpy(gam).cuda()
     token_heads = w.B * w.N * w.Hh
     bytes_per_launch = token_heads * 4 * w.d * 2            # q, k, v read + o written, bf16
-    sets = args.buffer_sets if args.buffer_sets > 0 else max(4, min(96, -(-(1 << 30) // bytes_per_launch)))
+    sets = n_sets(args, bytes_per_launch)
     bufs = [(tq, tk, tv, torch.empty_like(tq))]
     for _ in range(sets - 1):
         bufs.append((tq.clone(), tk.clone(), tv.clone(), torch.empty_like(tq)))
     ws_bytes = lasad.lasad_forward_workspace_bytes(w.B, w.Hh, w.N, w.d, lasad.BF16)
     ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda") if ws_bytes else None
 
-    def step(i):
-        a, b, c, o = bufs[i % sets]
-        lasad.lasad_forward_chunked(a, b, c, tg, w.grid_h, w.grid_w, out=o, workspace=ws)
-
     def run(nsteps, first=0):
         for i in range(nsteps):
-            step(first + i)
+            a, b, c, o = bufs[(first + i) % sets]
+            lasad.lasad_forward_chunked(a, b, c, tg, w.grid_h, w.grid_w, out=o, workspace=ws)
 
-    run(args.warmup)
-    eager_ms = time_region(torch, lambda: run(args.steps, args.warmup))
-    graph_ms = None
-    if not args.no_graph:
-        g = capture(torch, lambda: run(args.steps, args.warmup))
-        g.replay()
-        graph_ms = time_region(torch, g.replay)
-    total_ms = graph_ms if graph_ms is not None else eager_ms
-    ms_per_step = total_ms / args.steps
+    ms_per_step, eager_ms, reps = timer.steps(run, args.steps, args.warmup)
     dur_s = ms_per_step * 1e-3
-    tokens_per_s = w.B * w.N / dur_s
-    # For information only (never `value`): the same steps issued alternately on two streams, so that the launch
-    # and drain of one step overlap the other step's work, as independent batches in flight would.
-    two_ms = None
-    if not args.no_graph:
-        side = torch.cuda.Stream()
-        ws2 = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda") if ws_bytes else None
-
-        def run_two(nsteps, first=0):
-            main = torch.cuda.current_stream()
-            side.wait_stream(main)
-            for i in range(nsteps):
-                a, b, c, o = bufs[(first + i) % sets]
-                if i % 2 == 0:
-                    lasad.lasad_forward_chunked(a, b, c, tg, w.grid_h, w.grid_w, out=o, workspace=ws)
-                else:
-                    with torch.cuda.stream(side):
-                        lasad.lasad_forward_chunked(a, b, c, tg, w.grid_h, w.grid_w, out=o, workspace=ws2)
-            main.wait_stream(side)
-
-        g2 = capture(torch, lambda: run_two(args.steps, args.warmup))
-        g2.replay()
-        two_ms = time_region(torch, g2.replay) / args.steps
-
     C = 64
     useful_flops = token_heads * (2 * w.d * (C + 1) + 4 * w.d * w.d)   # causal-useful, chunk 64
     executed_flops = token_heads * (4 * C * w.d + 4 * w.d * w.d)
-    achieved_gbs = bytes_per_launch / dur_s / 1e9
     res = {
-        "workload": w, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_s,
-        "eager_ms_per_step": eager_ms / args.steps, "graph_ms_per_step": None if graph_ms is None else graph_ms / args.steps,
-        "buffer_sets": sets, "workspace_bytes": ws_bytes, "two_streams_ms_per_step": two_ms,
-        "roofline": {"bound": "hbm", "kernel": "lasad_forward_chunked", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-                     "algorithmic_bytes_per_launch": bytes_per_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+        "workload": w.name, "value": w.B * w.N / dur_s, "unit": "tokens/s", "ms_per_step": ms_per_step,
+        "steps": args.steps, "eager_ms_per_step": eager_ms, "replays_ms_per_step": reps,
+        "ns_per_token_head": dur_s * 1e9 / token_heads,
+        "config": {"workload": w.name, "batch": w.B, "heads": w.Hh, "head_dim": w.d,
+                   "grid": [w.grid_h, w.grid_w], "tokens_per_step": w.B * w.N, "chunk": 64,
+                   "io": "bf16 q,k,v in, bf16 o out, fp32 accumulation", "layout": args.layout,
+                   "timing": ("eager launches" if reps is None else
+                              f"HIP graph replay of the timed steps, median of {len(reps)} replays") +
+                             ("" if args.warm else ", caches swept before every timed region"),
+                   "buffer_sets_in_rotation": sets, "workspace_bytes": ws_bytes},
+        "roofline": hbm_roofline("lasad_forward_chunked", bytes_per_launch, dur_s, measured_traffic("forward", w.name)),
         "roofline_mfma": {"bound": "mfma", "achieved": useful_flops / dur_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                           "unit": "TFLOP/s", "frac": useful_flops / dur_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                           "flops_counted": "causal-useful, chunk 64",
                           "executed_frac": executed_flops / dur_s / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-        "inputs": (q, k, v, gam),
     }
+    del bufs, ws
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_prefill(w, (q, k, v, gam))
     return res
 
 
-def cpu_baseline_prefill(res, budget_s=20.0):
+def cpu_baseline_prefill(w, inputs, budget_s=20.0):
     """The fp64 full-mask oracle on a bounded sample of the same workload."""
     import numpy as np
     from oracle import lasad_oracle as oracle
-    w = res["workload"]
-    q, k, v, gam = res["inputs"]
+    q, k, v, gam = inputs
     cores = oracle.num_threads()
     # cost model: 4 N^2 d flops per sequence at roughly 1 GFLOP/s per core
     per_seq = 4.0 * w.N * w.N * w.d / 1e9
@@ -210,7 +227,7 @@ def cpu_baseline_prefill(res, budget_s=20.0):
                       f"{passes} pass(es), {dt:.2f} s wall; tokens/s = passes*sequences*N/heads/time"}
 
 
-def bench_decode(args, torch, lasad, wl):
+def bench_decode(args, timer, torch, lasad, wl):
     w = wl.AR_DECODE
     q, k, v, gam = wl.decode_inputs(w)
     tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
@@ -220,30 +237,20 @@ def bench_decode(args, torch, lasad, wl):
     outs = [torch.empty((w.B, w.Hh, w.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
     n_steps = args.decode_walks * w.steps
 
-    def run(nsteps):
-        for i in range(nsteps):
+    def run(nsteps, first=0):
+        for i in range(first, first + nsteps):
             t = i % w.steps
             lasad.lasad_decode_step(tq[t], tk[t], tv[t], tg, states[i % L], w.grid_h, w.grid_w, t, out=outs[i % L])
 
-    run(w.steps)    # one untimed walk
-    eager_ms = time_region(torch, lambda: run(n_steps))
-    graph_ms = None
-    if not args.no_graph:
-        g = capture(torch, lambda: run(n_steps))
-        g.replay()
-        graph_ms = time_region(torch, g.replay)
-    total_ms = graph_ms if graph_ms is not None else eager_ms
-    dur_s = total_ms / n_steps * 1e-3
+    ms_per_step, eager_ms, reps = timer.steps(run, n_steps, w.steps)     # one untimed walk first
+    dur_s = ms_per_step * 1e-3
     n_states = w.B * w.Hh
     bytes_per_launch = n_states * (2 * w.d * w.d * 4 + 4 * w.d * 2)   # state read + write, q k v o bf16
-    achieved = bytes_per_launch / dur_s / 1e9
     res = {
         "workload": w.name, "value": 1.0 / dur_s, "unit": "steps/s", "tokens_per_s": w.B / dur_s,
-        "ms_per_step": dur_s * 1e3, "steps_timed": n_steps, "state_sets_in_rotation": L,
-        "eager_ms_per_step": eager_ms / n_steps, "graph_ms_per_step": None if graph_ms is None else graph_ms / n_steps,
-        "roofline": {"bound": "hbm", "kernel": "lasad_decode_step", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_per_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)},
+        "ms_per_step": ms_per_step, "steps_timed": n_steps, "state_sets_in_rotation": L,
+        "eager_ms_per_step": eager_ms, "replays_ms_per_step": reps,
+        "roofline": hbm_roofline("lasad_decode_step", bytes_per_launch, dur_s, measured_traffic("decode", w.name)),
     }
     # The same walk with the first positions served from a key / value cache (fewer bytes than the state while
     # t < 2 d), the state built from the cache once, and the state form for the rest.  As above every launch
@@ -257,8 +264,8 @@ def bench_decode(args, torch, lasad, wl):
     fwd_out = torch.empty((w.B, switch, w.Hh, w.d), dtype=torch.bfloat16, device="cuda")
     as_seq = lambda c: c.permute(0, 2, 1, 3)
 
-    def run_hybrid(nsteps):
-        for i in range(nsteps):
+    def run_hybrid(nsteps, first=0):
+        for i in range(first, first + nsteps):
             t, l = i % w.steps, i % L
             if t < switch:
                 lasad.lasad_decode_step_cached(tq[t], tk[t], tv[t], tg, kcs[l], vcs[l], w.grid_h, w.grid_w, t, out=outs[l])
@@ -269,17 +276,12 @@ def bench_decode(args, torch, lasad, wl):
                                                 state_out=states[l], out=fwd_out, use_workspace=False)
                 lasad.lasad_decode_step(tq[t], tk[t], tv[t], tg, states[l], w.grid_h, w.grid_w, t, out=outs[l])
 
-    run_hybrid(w.steps)
-    hyb_ms = time_region(torch, lambda: run_hybrid(n_steps))
-    if not args.no_graph:
-        gh = capture(torch, lambda: run_hybrid(n_steps))
-        gh.replay()
-        hyb_ms = time_region(torch, gh.replay)
+    hyb_ms, _, _ = timer.steps(run_hybrid, n_steps, w.steps)
     res["cache_then_state"] = {
         "what": f"positions 0..{switch - 1} from a k/v cache (lasad_decode_step_cached), the state built from the cache by one "
                 "lasad_forward_chunked call per walk, lasad_decode_step afterwards",
-        "ms_per_step": hyb_ms / n_steps, "value": n_steps / (hyb_ms * 1e-3), "unit": "steps/s",
-        "speedup_vs_state_form": total_ms / hyb_ms}
+        "ms_per_step": hyb_ms, "value": 1.0 / (hyb_ms * 1e-3), "unit": "steps/s",
+        "speedup_vs_state_form": ms_per_step / hyb_ms}
     del kcs, vcs, fwd_out
     if not args.no_cpu_baseline:
         import numpy as np
@@ -299,9 +301,9 @@ def bench_decode(args, torch, lasad, wl):
     return res
 
 
-def bench_backward(args, torch, lasad, wl):
+def bench_backward(args, timer, torch, lasad, wl):
     """Backward leg: one lasad_backward_chunked call (dq, dk, dv, dgamma from q, k, v, d_o) per step over the
-    prefill workload's shape, timed like the forward."""
+    headline workload's shape, timed like the forward."""
     import numpy as np
     w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
     q, k, v, gam = wl.prefill_inputs(w, layout=args.layout)
@@ -313,7 +315,7 @@ def bench_backward(args, torch, lasad, wl):
     tg = torch.from_numpy(gam).cuda()
     token_heads = w.B * w.N * w.Hh
     bytes_bwd = token_heads * 7 * w.d * 2             # q, k, v, d_o read + dq, dk, dv written, bf16
-    sets = max(4, min(64, -(-(1 << 30) // bytes_bwd)))
+    sets = n_sets(args, bytes_bwd, cap=64)
     bufs = []
     for i in range(sets):
         ins = (tq, tk, tv, td) if i == 0 else tuple(x.clone() for x in (tq, tk, tv, td))
@@ -328,22 +330,15 @@ def bench_backward(args, torch, lasad, wl):
             a, b, c, d_o, grads = bufs[(first + i) % sets]
             lasad.lasad_backward_chunked(a, b, c, d_o, tg, w.grid_h, w.grid_w, grads=grads, dgamma=dgam, workspace=ws)
 
-    run(min(args.warmup, 5))
-    eager_ms = time_region(torch, lambda: run(steps, 5))
-    graph_ms = None
-    if not args.no_graph:
-        g_ = capture(torch, lambda: run(steps, 5))
-        g_.replay()
-        graph_ms = time_region(torch, g_.replay)
-    dur_s = (graph_ms if graph_ms is not None else eager_ms) / steps * 1e-3
-    res = {"workload": w.name, "value": w.B * w.N / dur_s, "unit": "tokens/s", "ms_per_step": dur_s * 1e3,
-           "steps_timed": steps, "eager_ms_per_step": eager_ms / steps, "workspace_bytes": ws_bytes,
+    ms_per_step, eager_ms, reps = timer.steps(run, steps, min(args.warmup, 5))
+    dur_s = ms_per_step * 1e-3
+    res = {"workload": w.name, "value": w.B * w.N / dur_s, "unit": "tokens/s", "ms_per_step": ms_per_step,
+           "steps_timed": steps, "eager_ms_per_step": eager_ms, "workspace_bytes": ws_bytes,
            "launches_per_step": "one launch of the forward kernel over the 3 passes (dq, dv, dk; decay-gradient sums in its "
                                 "epilogue) + 1 reduction kernel; few long sequences: 3 segmented passes + 2 finishing kernels",
-           "roofline": {"bound": "hbm", "kernel": "lasad_backward_chunked (all launches of one call)",
-                        "achieved": bytes_bwd / dur_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": bytes_bwd / dur_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_bwd,
-                        "traffic": MEASURED_TRAFFIC_BYTES.get("backward:" + w.name)}}
+           "roofline": hbm_roofline("lasad_backward_chunked (all launches of one call)", bytes_bwd, dur_s,
+                                    measured_traffic("backward", w.name))}
+    del bufs, ws
     if not args.no_cpu_baseline:
         from oracle import lasad_oracle as oracle
         n_seq = min(w.B * w.Hh, 2 * oracle.num_threads())
@@ -364,8 +359,8 @@ def bench_backward(args, torch, lasad, wl):
     return res
 
 
-def bench_gated(args, torch, lasad, wl):
-    """Vector-decay legs (Section 3.4 as written, key tied to the gate): the forward over the prefill
+def bench_gated(args, timer, torch, lasad, wl):
+    """Vector-decay legs (Section 3.4 as written, key tied to the gate): the forward over the headline
     workload's shape and the decode step over the AR-decode shape, timed like the scalar legs."""
     import numpy as np
     w = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
@@ -376,27 +371,23 @@ def bench_gated(args, torch, lasad, wl):
     tq, tl, tv = (lasad.to_device(x, w.dtype) for x in (q, lam, v))
     token_heads = w.B * w.N * w.Hh
     bytes_fwd = token_heads * 4 * w.d * 2               # q, lambda, v read + o written, bf16
-    sets = max(4, min(96, -(-(1 << 30) // bytes_fwd)))
+    sets = n_sets(args, bytes_fwd)
     bufs = [(tq, tl, tv, torch.empty_like(tq))]
     for _ in range(sets - 1):
         bufs.append((tq.clone(), tl.clone(), tv.clone(), torch.empty_like(tq)))
     steps = max(1, min(args.steps, 50))
+    warm = min(args.warmup, 5)
 
     def run(nsteps, first=0):
         for i in range(nsteps):
             a, b, c, o = bufs[(first + i) % sets]
             lasad.lasad_forward_gated(a, b, c, w.grid_h, w.grid_w, out=o)
 
-    run(min(args.warmup, 5))
-    eager_ms = time_region(torch, lambda: run(steps, 5))
-    graph_ms = None
-    if not args.no_graph:
-        g = capture(torch, lambda: run(steps, 5))
-        g.replay()
-        graph_ms = time_region(torch, g.replay)
-    dur_s = (graph_ms if graph_ms is not None else eager_ms) / steps * 1e-3
+    fwd_ms, eager_ms, _ = timer.steps(run, steps, warm)
+    dur_s = fwd_ms * 1e-3
     # backward of the same call (dq, dlam, dv from q, gate, v, d_o; key tied to the gate)
     bwd = None
+    bytes_bwd = token_heads * 7 * w.d * 2          # four tensors read + three gradients written, bf16
     if not args.no_backward:
         td = lasad.to_device(wl.store_round(np.random.default_rng(w.seed + 101).standard_normal(q.shape, dtype=np.float32)
                                             / np.float32(np.sqrt(w.d)), w.dtype), w.dtype)
@@ -412,22 +403,14 @@ def bench_gated(args, torch, lasad, wl):
                 a, b, c, _ = bufs[(first + i) % sets]
                 lasad.lasad_backward_gated(a, b, c, td, w.grid_h, w.grid_w, grads=grads[(first + i) % gsets], workspace=ws_b)
 
-        run_bwd(3)
-        b_ms = time_region(torch, lambda: run_bwd(bsteps, 3))
-        if not args.no_graph:
-            gb = capture(torch, lambda: run_bwd(bsteps, 3))
-            gb.replay()
-            b_ms = time_region(torch, gb.replay)
-        b_s = b_ms / bsteps * 1e-3
-        bytes_bwd = token_heads * 7 * w.d * 2          # q, gate, v, d_o read + dq, dlam, dv written, bf16
+        b_ms, _, _ = timer.steps(run_bwd, bsteps, 3)
+        b_s = b_ms * 1e-3
         bwd = {"workload": w.name + " (q, gate, v, d_o; k = 1 - gate)", "value": w.B * w.N / b_s, "unit": "tokens/s",
-               "ms_per_step": b_s * 1e3, "steps_timed": bsteps,
+               "ms_per_step": b_ms, "steps_timed": bsteps,
                "launches_per_step": "one launch of the chunked matrix-core kernel over the 3 passes (dq, dv, dk) + 1 finishing kernel "
                                     "(suffix sums for dlam)",
-               "roofline": {"bound": "hbm", "kernel": "lasad_backward_gated (both launches of one call)",
-                            "achieved": bytes_bwd / b_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": bytes_bwd / b_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_bwd,
-                            "traffic": MEASURED_TRAFFIC_BYTES.get("gated_backward:" + w.name)}}
+               "roofline": hbm_roofline("lasad_backward_gated (both launches of one call)", bytes_bwd, b_s,
+                                        measured_traffic("gated_backward", w.name))}
         del grads, ws_b, td
     # the same launch with Algorithm 1's elementwise steps fused in (SiLU, sigmoid, RMS norm): the gate buffers
     # now hold the pre-sigmoid logits N(2, 1) of the same recipe, q is read as the pre-SiLU query
@@ -442,13 +425,8 @@ def bench_gated(args, torch, lasad, wl):
             a, b, c, o = bufs[(first + i) % sets]
             lasad.lasad_forward_layer(a, b, c, w.grid_h, w.grid_w, out=o)
 
-    run_layer(min(args.warmup, 5))
-    layer_ms = time_region(torch, lambda: run_layer(steps, 5))
-    if not args.no_graph:
-        gl = capture(torch, lambda: run_layer(steps, 5))
-        gl.replay()
-        layer_ms = time_region(torch, gl.replay)
-    # backward of the fused layer: forward recomputation (o in fp32), norm backward, the three passes with the
+    layer_ms, _, _ = timer.steps(run_layer, steps, warm)
+    # backward of the fused layer: forward recomputation, norm backward, the three passes with the
     # activations on load, finishing kernel with the chain rule, weight-gradient sum
     layer_bwd = None
     if not args.no_backward:
@@ -466,30 +444,19 @@ def bench_gated(args, torch, lasad, wl):
                 lasad.lasad_backward_layer(a, b, c, td, w.grid_h, w.grid_w, grads=grads[(first + i) % gsets], dweight=dwt,
                                            workspace=ws_l)
 
-        run_lbwd(3)
-        lb_ms = time_region(torch, lambda: run_lbwd(lsteps, 3))
-        if not args.no_graph:
-            glb = capture(torch, lambda: run_lbwd(lsteps, 3))
-            glb.replay()
-            lb_ms = time_region(torch, glb.replay)
-        lb_s = lb_ms / lsteps * 1e-3
-        bytes_lb = token_heads * 7 * w.d * 2           # q_pre, z, v, d_out read + dq_pre, dz, dv written, bf16
+        lb_ms, _, _ = timer.steps(run_lbwd, lsteps, 3)
+        lb_s = lb_ms * 1e-3
         layer_bwd = {"workload": w.name + " (q_pre, z, v, d_out; SiLU, sigmoid gate, tied key, RMS norm)",
-                     "value": w.B * w.N / lb_s, "unit": "tokens/s", "ms_per_step": lb_s * 1e3, "steps_timed": lsteps,
+                     "value": w.B * w.N / lb_s, "unit": "tokens/s", "ms_per_step": lb_ms, "steps_timed": lsteps,
                      "launches_per_step": "forward recomputation + norm backward + 3-pass kernel + finishing kernel + weight-gradient sum",
-                     "roofline": {"bound": "hbm", "kernel": "lasad_backward_layer (all launches of one call)",
-                                  "achieved": bytes_lb / lb_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                  "frac": bytes_lb / lb_s / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes_per_launch": bytes_lb,
-                                  "traffic": MEASURED_TRAFFIC_BYTES.get("layer_backward:" + w.name)}}
+                     "roofline": hbm_roofline("lasad_backward_layer (all launches of one call)", bytes_bwd, lb_s,
+                                              measured_traffic("layer_backward", w.name))}
         del grads, ws_l, td, dwt
     res = {"forward": {
         "workload": w.name + " (q, gate, v; k = 1 - gate)",
-        "fused_layer_ms_per_step": layer_ms / steps, "value": w.B * w.N / dur_s, "unit": "tokens/s",
-        "ms_per_step": dur_s * 1e3, "steps_timed": steps, "eager_ms_per_step": eager_ms / steps,
-        "roofline": {"bound": "hbm", "kernel": "lasad_forward_gated", "achieved": bytes_fwd / dur_s / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_fwd / dur_s / 1e9 / HBM_PEAK_GBS,
-                     "algorithmic_bytes_per_launch": bytes_fwd,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get("gated:" + w.name)}}}
+        "fused_layer_ms_per_step": layer_ms, "value": w.B * w.N / dur_s, "unit": "tokens/s",
+        "ms_per_step": fwd_ms, "steps_timed": steps, "eager_ms_per_step": eager_ms,
+        "roofline": hbm_roofline("lasad_forward_gated", bytes_fwd, dur_s, measured_traffic("gated", w.name))}}
     if bwd is not None:
         res["backward"] = bwd
     if layer_bwd is not None:
@@ -521,31 +488,22 @@ def bench_gated(args, torch, lasad, wl):
         outs = [torch.empty((wd.B, wd.Hh, wd.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
         n_steps = args.decode_walks * wd.steps
 
-        def drun(nsteps):
-            for i in range(nsteps):
+        def drun(nsteps, first=0):
+            for i in range(first, first + nsteps):
                 t = i % wd.steps
                 lasad.lasad_decode_step_gated(tq[t], tl[t], tv[t], states[i % L], wd.grid_h, wd.grid_w, t, out=outs[i % L])
 
-        drun(wd.steps)
-        eager_ms = time_region(torch, lambda: drun(n_steps))
-        graph_ms = None
-        if not args.no_graph:
-            g = capture(torch, lambda: drun(n_steps))
-            g.replay()
-            graph_ms = time_region(torch, g.replay)
-        dur_s = (graph_ms if graph_ms is not None else eager_ms) / n_steps * 1e-3
+        d_ms, d_eager, _ = timer.steps(drun, n_steps, wd.steps)
+        dur_s = d_ms * 1e-3
         bytes_dec = wd.B * wd.Hh * (2 * wd.d * wd.d * 4 + 4 * wd.d * 2)
         res["decode"] = {
             "workload": wd.name + " (q, gate, v; k = 1 - gate)", "value": 1.0 / dur_s, "unit": "steps/s",
-            "ms_per_step": dur_s * 1e3, "steps_timed": n_steps, "eager_ms_per_step": eager_ms / n_steps,
-            "roofline": {"bound": "hbm", "kernel": "lasad_decode_step_gated", "achieved": bytes_dec / dur_s / 1e9,
-                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_dec / dur_s / 1e9 / HBM_PEAK_GBS,
-                         "algorithmic_bytes_per_launch": bytes_dec,
-                         "traffic": MEASURED_TRAFFIC_BYTES.get("gated:" + wd.name)}}
+            "ms_per_step": d_ms, "steps_timed": n_steps, "eager_ms_per_step": d_eager,
+            "roofline": hbm_roofline("lasad_decode_step_gated", bytes_dec, dur_s, measured_traffic("gated_decode", wd.name))}
     return res
 
 
-def measure_copy_peak(torch):
+def measure_copy_peak(torch, timer):
     """Streaming ceiling of this GPU as a plain device copy reaches it: 1 GiB read + 1 GiB written per copy."""
     n = 1 << 30
     src = torch.empty((n,), dtype=torch.uint8, device="cuda").fill_(1)
@@ -553,7 +511,7 @@ def measure_copy_peak(torch):
     for _ in range(2):
         dst.copy_(src)
     reps = 10
-    ms = time_region(torch, lambda: [dst.copy_(src) for _ in range(reps)])
+    ms = timer.region(lambda: [dst.copy_(src) for _ in range(reps)])
     del src, dst
     return 2.0 * n * reps / (ms * 1e-3) / 1e9
 
@@ -577,36 +535,47 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    copy_gbs = measure_copy_peak(torch)
-    pre = bench_prefill(args, torch, lasad, wl)
-    w = pre["workload"]
+    timer = Timer(torch, args)
+    copy_gbs = measure_copy_peak(torch, timer)
+    pre = bench_prefill(args, timer, torch, lasad, wl, args.workload)
     line = {
-        "metric": "lasad_prefill_tokens_per_s", "value": pre["tokens_per_s"], "unit": "tokens/s",
+        "metric": "lasad_prefill_tokens_per_s", "value": pre["value"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": pre["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.B, "heads": w.Hh, "head_dim": w.d,
-                   "grid": [w.grid_h, w.grid_w], "tokens_per_step": w.B * w.N, "chunk": 64,
-                   "io": "bf16 q,k,v in, bf16 o out, fp32 accumulation", "layout": args.layout,
-                   "timing": "HIP graph replay of the timed steps" if pre["graph_ms_per_step"] is not None else "eager launches",
-                   "buffer_sets_in_rotation": pre["buffer_sets"]},
-        "eager_ms_per_step": pre["eager_ms_per_step"],
-        "two_streams_ms_per_step": pre["two_streams_ms_per_step"],     # information only: two independent steps in flight
+        "config": pre["config"],
+        "eager_ms_per_step": pre["eager_ms_per_step"], "replays_ms_per_step": pre["replays_ms_per_step"],
         "roofline": pre["roofline"], "roofline_mfma": pre["roofline_mfma"],
         "hbm_copy_measured": {"value": copy_gbs, "unit": "GB/s",
                               "what": "1 GiB device-to-device copy (read + written bytes over time), the streaming rate a "
                                       "plain copy kernel reaches on this GPU; roofline.frac stays against the published 8 TB/s"},
     }
     line["roofline"]["frac_of_measured_copy"] = line["roofline"]["achieved"] / copy_gbs
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline_prefill(pre)
+    if "cpu_baseline" in pre:
+        line["cpu_baseline"] = pre["cpu_baseline"]
+    legs = {pre["workload"]: pre}
+    for name in [x for x in args.legs.split(",") if x and x != args.workload]:
+        if name not in PREFILL_WORKLOADS:
+            raise SystemExit(f"bench.py: unknown prefill leg {name!r}")
+        leg = bench_prefill(args, timer, torch, lasad, wl, name)
+        leg["roofline"]["frac_of_measured_copy"] = leg["roofline"]["achieved"] / copy_gbs
+        legs[leg["workload"]] = leg
+    line["prefill_legs"] = {k: v for k, v in legs.items() if k != pre["workload"]}
+    # time per token-head against the sequence length: the method is linear in N (Section 1, Section 3.2), so the
+    # figures of the shapes that fill the GPU should agree
+    per = {k: {"n_tokens": v["config"]["grid"][0] * v["config"]["grid"][1], "ns_per_token_head": v["ns_per_token_head"],
+               "frac_hbm": v["roofline"]["frac"]} for k, v in legs.items()}
+    line["linear_in_n"] = {"per_workload": per, "unit": "ns per token-head (one head's token: 512 B moved)"}
+    if "large_prefill_24x24" in per and "highres_64x64" in per:
+        line["linear_in_n"]["highres_over_large"] = (per["highres_64x64"]["ns_per_token_head"] /
+                                                     per["large_prefill_24x24"]["ns_per_token_head"])
     if args.decode_walks > 0:
-        line["decode"] = bench_decode(args, torch, lasad, wl)
+        line["decode"] = bench_decode(args, timer, torch, lasad, wl)
         line["decode"]["roofline"]["frac_of_measured_copy"] = line["decode"]["roofline"]["achieved"] / copy_gbs
     if not args.no_backward:
-        line["backward"] = bench_backward(args, torch, lasad, wl)
+        line["backward"] = bench_backward(args, timer, torch, lasad, wl)
     if not args.no_gated:
-        line["gated"] = bench_gated(args, torch, lasad, wl)
+        line["gated"] = bench_gated(args, timer, torch, lasad, wl)
     print(json.dumps(line), flush=True)
 
 

@@ -334,7 +334,8 @@ int lasad_backward_layer(const void *q_pre, const void *z, const void *v, const 
  * normalisation and enters the recurrence, and dweight.  With gw = d_out * norm_weight,
  *     d_o = rstd gw - o rstd^3 mean_c(gw o),   rstd = (mean_c(o^2) + norm_eps)^(-1/2),
  * o the recurrence output of Algorithm 1 for q_pre, z, v (recomputed here).  norm_eps >= 0.
- *   d_o   [B, n_tokens, n_heads, d], d_o_layout, type io_dtype; overwritten.
+ *   d_o   [B, n_tokens, n_heads, d], d_o_layout, type d_o_dtype (io_dtype, or LASAD_F32 also with bf16
+ *         inputs: the value before its rounding to bf16); overwritten.
  * lasad_backward_layer computes this tensor by the same kernels and feeds it to the recurrence's
  * backward (with bf16 inputs together with what the rounding to bf16 left over, as a second
  * bf16 tensor); the latter alone is lasad_backward_layer with norm_eps < 0 and d_out := d_o.
@@ -343,7 +344,7 @@ int lasad_backward_layer(const void *q_pre, const void *z, const void *v, const 
 int lasad_backward_layer_norm(const void *q_pre, const void *z, const void *v, const void *d_out,
                               void *d_o, float *dweight,
                               const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
-                              const lasad_layout_t *d_o_layout, int io_dtype,
+                              const lasad_layout_t *d_o_layout, int io_dtype, int d_o_dtype,
                               int B, int n_heads, int d, int grid_h, int grid_w,
                               int start_pos, int n_tokens, int boundary_mode, float q_scale,
                               const float *norm_weight, float norm_eps,

@@ -316,14 +316,9 @@ def layer_core_backward(q_pre, z, v, d_o, grid_w, start_pos=0, mode=RESET_LAST_C
 
 
 def gated_layer_backward(q_pre, z, v, d_out, grid_w, norm_weight=None, eps=1e-6, start_pos=0, mode=RESET_LAST_COL,
-                         q_scale=1.0, store_d_o=None):
+                         q_scale=1.0):
     """Gradients of gated_layer (zero initial state) for d_out = dL/d(layer output): layer_norm_backward, then
-    layer_core_backward.  Returns dq_pre, dz, dv [B, n, Hh, d] and dweight [Hh, d].
-    store_d_o: None, or a function applied to the gradient between the two parts: the rounding of a pipeline
-    that STORES this tensor in a narrow type there (the gradient is orthogonal to the recurrence output, so
-    what follows is sensitive to that rounding)."""
+    layer_core_backward.  Returns dq_pre, dz, dv [B, n, Hh, d] and dweight [Hh, d]."""
     d_o, dweight = layer_norm_backward(q_pre, z, v, d_out, grid_w, norm_weight, eps, start_pos, mode, q_scale)
-    if store_d_o is not None:
-        d_o = np.asarray(store_d_o(d_o), dtype=np.float64)
     dq_pre, dz, dv = layer_core_backward(q_pre, z, v, d_o, grid_w, start_pos, mode, q_scale)
     return dq_pre, dz, dv, dweight

@@ -91,7 +91,7 @@ def load() -> ctypes.CDLL:
     lib.lasad_backward_layer.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                          ctypes.c_float, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.lasad_backward_layer.restype = ci
-    lib.lasad_backward_layer_norm.argtypes = [vp, vp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+    lib.lasad_backward_layer_norm.argtypes = [vp, vp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                               ctypes.c_float, vp, ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.lasad_backward_layer_norm.restype = ci
     lib.lasad_last_error.argtypes = []
@@ -122,6 +122,16 @@ def _ptr(t):
 def _stream(stream) -> ctypes.c_void_p:
     s = torch.cuda.current_stream() if stream is None else stream
     return ctypes.c_void_p(s.cuda_stream)
+
+
+def _scratch(nbytes: int, device, stream) -> torch.Tensor:
+    """A workspace from torch's caching allocator that stays reserved until the work queued on `stream`
+    (None: the current stream) has run: a block freed on another stream could be handed out again while
+    the kernels still use it."""
+    t = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+    if stream is not None and stream != torch.cuda.current_stream():
+        t.record_stream(stream)
+    return t
 
 
 def _layout(t: torch.Tensor) -> Layout:
@@ -180,7 +190,7 @@ def lasad_forward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gam
     if workspace is None and use_workspace and n > 0:
         need = lasad_forward_workspace_bytes(B, Hh, n, d, _dtype_code(q))
         if need:
-            workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+            workspace = _scratch(need, q.device, stream)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().lasad_forward_chunked(
         _ptr(q), _ptr(k), _ptr(v), _ptr(out), ctypes.byref(lq), ctypes.byref(lo),
@@ -396,7 +406,7 @@ def lasad_backward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_
         dgamma = torch.empty((Hh,), dtype=torch.float32, device=q.device)
     need = lasad_backward_workspace_bytes(B, Hh, n, d, _dtype_code(q))
     if workspace is None and need:
-        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     li, lg = _layout(q), _layout(dq)
     _check(load().lasad_backward_chunked(
         _ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgamma),
@@ -434,7 +444,7 @@ def lasad_backward_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, d_
             raise ValueError("gradient tensors must share q's shape and one set of strides and dtype")
     need = lasad_backward_gated_workspace_bytes(B, Hh, n, d)
     if workspace is None and need:
-        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     li, lg = _layout(q), _layout(dq)
     _check(load().lasad_backward_gated(
         _ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dlam), _ptr(dk), _ptr(dv),
@@ -480,7 +490,7 @@ def lasad_backward_layer(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, 
         raise ValueError("dweight must be contiguous fp32 [Hh, d]")
     need = lasad_backward_layer_workspace_bytes(q_pre)
     if workspace is None and need:
-        workspace = torch.empty((need,), dtype=torch.uint8, device=q_pre.device)
+        workspace = _scratch(need, q_pre.device, stream)
     li, lo, lg = _layout(q_pre), _layout(d_out), _layout(dq)
     _check(load().lasad_backward_layer(
         _ptr(q_pre), _ptr(z), _ptr(v), _ptr(d_out), _ptr(dq), _ptr(dz), _ptr(dv), _ptr(dweight),
@@ -493,10 +503,10 @@ def lasad_backward_layer(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, 
 def lasad_backward_layer_norm(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Tensor, d_out: torch.Tensor,
                               grid_h: int, grid_w: int, norm_weight: torch.Tensor | None = None, norm_eps: float = 1e-6,
                               start_pos: int = 0, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
-                              d_o: torch.Tensor | None = None, want_dweight: bool = True,
-                              workspace: torch.Tensor | None = None, stream=None):
+                              d_o: torch.Tensor | None = None, d_o_dtype: torch.dtype | None = None,
+                              want_dweight: bool = True, workspace: torch.Tensor | None = None, stream=None):
     """The normalisation's part of lasad_backward_layer alone: returns (d_o, dweight), d_o = dL/d(recurrence
-    output) in the inputs' dtype."""
+    output) in the inputs' dtype (or fp32 on request)."""
     B, n, Hh, d = q_pre.shape
     for t in (z, v):
         if t.shape != q_pre.shape or t.stride() != q_pre.stride() or t.dtype != q_pre.dtype:
@@ -504,17 +514,17 @@ def lasad_backward_layer_norm(q_pre: torch.Tensor, z: torch.Tensor, v: torch.Ten
     if d_out.shape != q_pre.shape or d_out.dtype != q_pre.dtype:
         raise ValueError("d_out must have q_pre's shape and dtype")
     if d_o is None:
-        d_o = torch.empty(q_pre.shape, dtype=q_pre.dtype, device=q_pre.device)
-    if d_o.shape != q_pre.shape or d_o.dtype != q_pre.dtype:
-        raise ValueError("d_o must have q_pre's shape and dtype")
+        d_o = torch.empty(q_pre.shape, dtype=d_o_dtype or q_pre.dtype, device=q_pre.device)
+    if d_o.shape != q_pre.shape:
+        raise ValueError("d_o must have q_pre's shape")
     dweight = torch.empty((Hh, d), dtype=torch.float32, device=q_pre.device) if want_dweight else None
     need = lasad_backward_layer_workspace_bytes(q_pre)
     if workspace is None and need:
-        workspace = torch.empty((need,), dtype=torch.uint8, device=q_pre.device)
+        workspace = _scratch(need, q_pre.device, stream)
     li, lo, ld = _layout(q_pre), _layout(d_out), _layout(d_o)
     _check(load().lasad_backward_layer_norm(
         _ptr(q_pre), _ptr(z), _ptr(v), _ptr(d_out), _ptr(d_o), _ptr(dweight),
-        ctypes.byref(li), ctypes.byref(lo), ctypes.byref(ld), _dtype_code(q_pre),
+        ctypes.byref(li), ctypes.byref(lo), ctypes.byref(ld), _dtype_code(q_pre), _dtype_code(d_o),
         B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale, _ptr(norm_weight), norm_eps,
         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
     return d_o, dweight

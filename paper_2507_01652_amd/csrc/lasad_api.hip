@@ -420,7 +420,7 @@ size_t lasad_backward_layer_workspace_bytes(int B, int n_heads, int n_tokens, in
 }
 
 // d_o_out NULL: the whole backward (gradients dq_pre, dz, dv with grad_layout / grad_dtype);
-// else only the normalisation's part: d_o_out (grad_layout, io_dtype) and dweight.
+// else only the normalisation's part: d_o_out (grad_layout, grad_dtype) and dweight.
 static int backward_layer_common(const void *q_pre, const void *z, const void *v, const void *d_out,
                                  void *dq_pre, void *dz, void *dv, void *d_o_out, float *dweight,
                                  const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
@@ -477,7 +477,7 @@ static int backward_layer_common(const void *q_pre, const void *z, const void *v
     lasad::LayerBackwardArgs a;
     a.q_pre = q_pre; a.z = z; a.v = v; a.d_out = d_out;
     a.dq_pre = dq_pre; a.dz = dz; a.dv = dv; a.dweight = dweight;
-    a.d_o_out = d_o_out; a.d_o_l = *grad_layout;
+    a.d_o_out = d_o_out; a.d_o_l = *grad_layout; a.d_o_f32 = (norm_only && grad_dtype == LASAD_F32) ? 1 : 0;
     a.in = *in_layout; a.dout = *dout_layout; a.grad = *grad_layout;
     a.io_dtype = io_dtype; a.grad_dtype = grad_dtype;
     a.B = B; a.Hh = n_heads; a.d = d; a.grid_w = grid_w;
@@ -509,7 +509,7 @@ int lasad_backward_layer(const void *q_pre, const void *z, const void *v, const 
 int lasad_backward_layer_norm(const void *q_pre, const void *z, const void *v, const void *d_out,
                               void *d_o, float *dweight,
                               const lasad_layout_t *in_layout, const lasad_layout_t *dout_layout,
-                              const lasad_layout_t *d_o_layout, int io_dtype,
+                              const lasad_layout_t *d_o_layout, int io_dtype, int d_o_dtype,
                               int B, int n_heads, int d, int grid_h, int grid_w,
                               int start_pos, int n_tokens, int boundary_mode, float q_scale,
                               const float *norm_weight, float norm_eps,
@@ -517,7 +517,7 @@ int lasad_backward_layer_norm(const void *q_pre, const void *z, const void *v, c
 {
     if (!d_o) return fail(LASAD_ERR_INVALID_ARG, "d_o is NULL");
     return backward_layer_common(q_pre, z, v, d_out, nullptr, nullptr, nullptr, d_o, dweight, in_layout, dout_layout, d_o_layout,
-                                 io_dtype, io_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens, boundary_mode,
+                                 io_dtype, d_o_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens, boundary_mode,
                                  q_scale, norm_weight, norm_eps, workspace, workspace_bytes, hip_stream);
 }
 

@@ -78,7 +78,7 @@ norm_backward_kernel(LayerBackwardArgs a, const float *o32, void *d_o, void *d_o
     }
     if (live) {
         const int64_t i = (int64_t)b * dl.stride_b + (int64_t)t * dl.stride_n + (int64_t)h * dl.stride_h + c4;
-        if (IN_BF16) {
+        if (IN_BF16 && !a.d_o_f32) {
             uint2 w;
             w.x = (uint32_t)float_to_bf16_bits(res[0]) | ((uint32_t)float_to_bf16_bits(res[1]) << 16);
             w.y = (uint32_t)float_to_bf16_bits(res[2]) | ((uint32_t)float_to_bf16_bits(res[3]) << 16);

@@ -138,7 +138,8 @@ struct LayerBackwardArgs {
     const void *q_pre, *z, *v, *d_out;
     void *dq_pre, *dz, *dv;
     void *d_o_out;                       // not NULL: stop after the normalisation's backward and leave the gradient
-    lasad_layout_t d_o_l;                //   that enters the recurrence here (type io_dtype, this layout)
+    lasad_layout_t d_o_l;                //   that enters the recurrence here (this layout; type io_dtype, or fp32
+    int d_o_f32;                         //   if d_o_f32 is set)
     float *dweight;                      // [Hh, d], or NULL
     lasad_layout_t in, dout, grad;
     int io_dtype, grad_dtype;

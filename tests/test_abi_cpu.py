@@ -116,7 +116,7 @@ def _backward_layer(lib, norm_only=False, **kw):
     if norm_only:
         return lib.lasad_backward_layer_norm(vp(a["q"]), vp(a["z"]), vp(a["v"]), vp(a["g"]), vp(a["d_o"]), vp(a["dw"]),
                                              ctypes.byref(a["li"]), ctypes.byref(a["lo"]), ctypes.byref(a["lg"]),
-                                             a["io"], *tail)
+                                             a["io"], a.get("d_o_dtype", a["io"]), *tail)
     return lib.lasad_backward_layer(vp(a["q"]), vp(a["z"]), vp(a["v"]), vp(a["g"]), vp(a["dq"]), vp(a["dz"]), vp(a["dv"]),
                                     vp(a["dw"]), ctypes.byref(a["li"]), ctypes.byref(a["lo"]), ctypes.byref(a["lg"]),
                                     a["io"], a["gd"], *tail)
@@ -140,6 +140,9 @@ def test_backward_layer_norm_rejects_bad_arguments_and_sizes_its_workspace(lib):
     assert _backward_layer(lib, norm_only=True, eps=-1.0) == 1          # no normalisation to differentiate
     assert _backward_layer(lib, norm_only=True, d_o=0x4000) == 1        # aliases d_out
     assert _backward_layer(lib, norm_only=True) == 3                    # workspace too small
+    assert _backward_layer(lib, norm_only=True, d_o_dtype=0) == 3       # fp32 d_o of bf16 inputs is accepted
+    assert _backward_layer(lib, norm_only=True, io=0, d_o_dtype=1) == 2 # bf16 d_o of fp32 inputs is not
+    assert _backward_layer(lib, norm_only=True, d_o_dtype=5) == 1
     lib.lasad_backward_layer_workspace_bytes.restype = ctypes.c_size_t
     lib.lasad_backward_gated_workspace_bytes.restype = ctypes.c_size_t
     size = lambda l, io=1: lib.lasad_backward_layer_workspace_bytes(2, 3, 100, 64, io, ctypes.byref(l))
@@ -155,3 +158,4 @@ def test_backward_layer_norm_rejects_bad_arguments_and_sizes_its_workspace(lib):
     assert abs(size(dense, io=0) - size(dense)) <= 512
     assert lib.lasad_backward_layer_workspace_bytes(0, 3, 100, 64, 1, ctypes.byref(dense)) == 0
     assert lib.lasad_backward_layer_workspace_bytes(2, 3, 100, 64, 1, None) == 0
+

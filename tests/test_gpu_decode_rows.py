@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2507_01652_amd import workloads as wl
-from helpers import TOL, parity_err, rel_err
+from helpers import TOL, rel_err
 
 pytestmark = pytest.mark.gpu
 

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2507_01652_amd import workloads as wl
-from helpers import TOL, parity_err, rel_err, sample_pairs, gather_pairs
+from helpers import TOL, both_outputs, decode_both, rel_err, sample_pairs, gather_pairs
 
 pytestmark = pytest.mark.gpu
 
@@ -44,12 +44,13 @@ def test_forward_layer(lasad, oracle, dtype, H, W, B, Hh, mode, norm):
         ref, s_ref = oracle.gated_layer(q, z, v, W, norm_weight=w, eps=eps, mode=mode, want_state=True)
     dev = lambda x: lasad.to_device(x, dtype)
     s1 = torch.empty((B, Hh, d, d), dtype=torch.float32, device="cuda")
-    for out_dtype in ([torch.bfloat16, torch.float32] if dtype == "bf16" else [torch.float32]):
-        o = lasad.lasad_forward_layer(dev(q), dev(z), dev(v), H, W, norm_weight=None if w is None else torch.from_numpy(w).cuda(),
-                                      norm_eps=eps, boundary_mode=mode, state_out=s1, out_dtype=out_dtype)
-        torch.cuda.synchronize()
-        assert parity_err(o.float().cpu().numpy(), ref, out_dtype == torch.bfloat16) <= TOL[dtype], out_dtype
-        assert rel_err(s1.cpu().numpy(), s_ref) <= TOL[dtype]
+    # fp32 output against the bare tolerance; with bf16 inputs the bf16 output must be its rounding
+    o = both_outputs(lasad.lasad_forward_layer, dtype == "bf16", q_pre=dev(q), z=dev(z), v=dev(v), grid_h=H, grid_w=W,
+                     norm_weight=None if w is None else torch.from_numpy(w).cuda(), norm_eps=eps, boundary_mode=mode,
+                     state_out=s1)
+    torch.cuda.synchronize()
+    assert rel_err(o.cpu().numpy(), ref) <= TOL[dtype]
+    assert rel_err(s1.cpu().numpy(), s_ref) <= TOL[dtype]
 
 
 def test_forward_layer_strong_gates_take_the_serial_route(lasad, oracle):
@@ -65,14 +66,16 @@ def test_forward_layer_strong_gates_take_the_serial_route(lasad, oracle):
     assert rel_err(o.cpu().numpy(), ref) <= TOL["bf16"]
 
 
-def test_forward_layer_bench_shape_sampled(lasad, oracle):
+@pytest.mark.parametrize("name,n_pairs", [("base_prefill_16x16", 16), ("large_prefill_24x24", 16), ("highres_64x64", 4)])
+def test_forward_layer_bench_shape_sampled(lasad, oracle, name, n_pairs):
+    """The shapes bench.py times, full size; the oracle on sampled sequences; bf16 output = rounded fp32 output."""
     import torch
-    w = wl.BASE_PREFILL
+    w = wl.CONFIGS[name]
     q, z, v = _pre_inputs(w.B, w.N, w.Hh, w.d, "bf16", 7)
     dev = lambda x: lasad.to_device(x, "bf16")
-    o = lasad.lasad_forward_layer(dev(q), dev(z), dev(v), w.grid_h, w.grid_w, out_dtype=torch.float32)
+    o = both_outputs(lasad.lasad_forward_layer, True, q_pre=dev(q), z=dev(z), v=dev(v), grid_h=w.grid_h, grid_w=w.grid_w)
     torch.cuda.synchronize()
-    pairs = sample_pairs(w.B, w.Hh, 16, seed=1)
+    pairs = sample_pairs(w.B, w.Hh, n_pairs, seed=1)
     ref = oracle.gated_layer(gather_pairs(q, pairs), gather_pairs(z, pairs), gather_pairs(v, pairs), w.grid_w)
     assert rel_err(gather_pairs(o.cpu().numpy(), pairs), ref) <= TOL["bf16"]
 
@@ -91,8 +94,9 @@ def test_decode_layer_walk(lasad, oracle, d, dtype):
     state = torch.zeros((B, Hh, d, d), dtype=torch.float32, device="cuda")
     worst = 0.0
     for t in range(n):
-        o = lasad.lasad_decode_step_layer(tq[t], tz[t], tv[t], state, H, W, t, norm_weight=tw, norm_eps=1e-5,
-                                          q_scale=1.3, out_dtype=torch.float32)
+        o = decode_both(lambda st, odt: lasad.lasad_decode_step_layer(tq[t], tz[t], tv[t], st, H, W, t, norm_weight=tw,
+                                                                      norm_eps=1e-5, q_scale=1.3, out_dtype=odt),
+                        state, dtype == "bf16")
         worst = max(worst, rel_err(o.cpu().numpy()[:, None], ref[:, t:t + 1]))
     assert worst <= TOL[dtype]
     assert rel_err(state.cpu().numpy(), s_ref) <= TOL[dtype]

@@ -1,11 +1,12 @@
 """GPU parity of the fused layer's backward (lasad_backward_layer: chain rule through the normalisation, the
 vector-decay recurrence with the tied key and the two activations of Algorithm 1) against the oracle's
-gated_layer_backward, element by element on seeded inputs."""
+gated_layer_backward, element by element on seeded inputs: fp32 results against the bare tolerance; results
+stored as bf16 must be those fp32 results rounded, bit for bit (helpers.both_outputs)."""
 import numpy as np
 import pytest
 
 from paper_2507_01652_amd import workloads as wl
-from helpers import TOL, parity_err, rel_err, sample_pairs
+from helpers import TOL, both_outputs, rel_err, sample_pairs
 
 pytestmark = pytest.mark.gpu
 
@@ -36,11 +37,14 @@ def _weight(Hh, d, seed=3):
 
 
 def _call(lasad, dtype, tensors, H, W, w, eps, start=0, mode=0, q_scale=1.0, grad_bf16=False):
-    """lasad_backward_layer on device tensors -> device results."""
+    """lasad_backward_layer on device tensors -> device results with fp32 gradients; grad_bf16 (bf16 inputs) runs
+    the call with bf16 gradients as well: they must be the fp32 gradients rounded, dweight the same."""
     import torch
-    res = lasad.lasad_backward_layer(*tensors, H, W, norm_weight=None if w is None else torch.from_numpy(w).cuda(),
-                                     norm_eps=eps, start_pos=start, boundary_mode=mode, q_scale=q_scale,
-                                     grad_dtype=torch.bfloat16 if grad_bf16 else torch.float32)
+    q_pre, z, v, d_out = tensors
+    res = both_outputs(lasad.lasad_backward_layer, grad_bf16 and dtype == "bf16", dtype_kw="grad_dtype",
+                       q_pre=q_pre, z=z, v=v, d_out=d_out, grid_h=H, grid_w=W,
+                       norm_weight=None if w is None else torch.from_numpy(w).cuda(),
+                       norm_eps=eps, start_pos=start, boundary_mode=mode, q_scale=q_scale)
     torch.cuda.synchronize()
     return res
 
@@ -48,7 +52,24 @@ def _call(lasad, dtype, tensors, H, W, w, eps, start=0, mode=0, q_scale=1.0, gra
 def _run(lasad, dtype, q, z, v, g, H, W, w, eps, start=0, mode=0, q_scale=1.0, grad_bf16=False):
     dev = lambda x: lasad.to_device(x, dtype)
     res = _call(lasad, dtype, (dev(q), dev(z), dev(v), dev(g)), H, W, w, eps, start, mode, q_scale, grad_bf16)
-    return [r.float().cpu().numpy() for r in res]
+    return [r.cpu().numpy() for r in res]
+
+
+def _norm_condition(oracle, q, z, v, g, W, w, eps, okw, d_o_ref):
+    """How much more than the recurrence output o the gradient d_o = rstd gw - o rstd^3 mean_c(gw o) may be off,
+    both relative to their RMS, when o carries an error delta (rstd = (mean_c(o^2) + eps)^(-1/2), gw = d_out w).
+    Differentiating in o and bounding the four terms (|o . delta| <= |o| |delta|, |mean(gw o)| <= |gw| |o| / d,
+    rstd^2 |o|^2 / d <= 1) gives, per token, |delta d_o| <= 6 rstd^2 |gw| |delta| / sqrt(d) in Euclidean norms,
+    so an element of d_o moves by at most 6 rstd^2 |gw|_2 max|delta|.  With fp32 inputs o is only required to be
+    right to TOL x rms(o), which by this bound allows d_o an error of
+        TOL x 6 max_t(rstd_t^2 |gw_t|_2) rms(o) / rms(d_o)
+    of its RMS: that factor (never below 1) is the condition used for the fp32 tolerance of d_o and of the
+    gradients computed from it.  Tokens whose o nearly cancels (large rstd) dominate it."""
+    o = oracle.gated_recurrent(oracle.silu(q), oracle.sigmoid(z), v, W, **okw)
+    gw = g.astype(np.float64) * (1.0 if w is None else w[None, None])
+    rstd2 = 1.0 / (np.mean(o * o, axis=-1) + eps)
+    worst = float(np.max(rstd2 * np.sqrt(np.sum(gw * gw, axis=-1))))
+    return max(1.0, 6.0 * worst * float(np.sqrt(np.mean(o * o))) / float(np.sqrt(np.mean(d_o_ref * d_o_ref))))
 
 
 def _tol(nm, dtype, z):
@@ -60,7 +81,7 @@ def _tol(nm, dtype, z):
 def _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, w, eps, dtype="bf16", start=0, mode=0, q_scale=1.0,
                  grad_bf16=False):
     """The whole call against the oracle, and its two parts as calls of their own:
-      1. lasad_backward_layer_norm: d_o (to the tolerance plus its storage rounding) and dweight;
+      1. lasad_backward_layer_norm: d_o in fp32 (bare tolerance; the bf16 d_o must be its rounding) and dweight;
       2. the recurrence + activations part (the call without a normalisation) on the oracle's d_o, rounded to the
          storage type (an input like any other).
     The whole call keeps d_o as a bf16 pair between the two parts, so it is held against the UNROUNDED oracle."""
@@ -69,27 +90,25 @@ def _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, w, eps, dtype="bf16", 
     okw = dict(start_pos=start, mode=mode, q_scale=q_scale)
     wt = None if w is None else torch.from_numpy(w).cuda()
     d_o_ref, dw_ref = oracle.layer_norm_backward(q, z, v, g, W, norm_weight=w, eps=eps, **okw)
-    d_o, dw = lasad.lasad_backward_layer_norm(*dev_in, H, W, norm_weight=wt, norm_eps=eps, start_pos=start,
-                                              boundary_mode=mode, q_scale=q_scale)
+    d_o, dw = both_outputs(lasad.lasad_backward_layer_norm, dtype == "bf16", dtype_kw="d_o_dtype",
+                           q_pre=dev_in[0], z=dev_in[1], v=dev_in[2], d_out=dev_in[3], grid_h=H, grid_w=W,
+                           norm_weight=wt, norm_eps=eps, start_pos=start, boundary_mode=mode, q_scale=q_scale)
     torch.cuda.synchronize()
-    # d_o depends on the DIRECTION of o_t: a token whose o nearly cancels (a short o_t, hence a large d_o_t) carries
-    # the fp32 rounding of o, relative to that short length, into d_o.  With fp32 inputs the tolerance sits at the
-    # rounding level, so it gets a factor 10 for this (measured 2.4e-5); with bf16 inputs it is far above it.
-    cond = 10 if dtype == "f32" else 1
-    err = parity_err(d_o.float().cpu().numpy(), d_o_ref, dtype == "bf16")
-    assert err <= cond * TOL[dtype], ("d_o", err)
+    cond = _norm_condition(oracle, q, z, v, g, W, w, eps, okw, d_o_ref) if dtype == "f32" else 1.0
+    err = rel_err(d_o.cpu().numpy(), d_o_ref)
+    assert err <= cond * TOL[dtype], ("d_o", err, cond)
     assert rel_err(dw.cpu().numpy(), dw_ref) <= TOL[dtype], "dweight"
     d_o_in = wl.store_round(d_o_ref.astype(np.float32), dtype)
-    got = _call(lasad, dtype, (*dev_in[:3], lasad.to_device(d_o_in, dtype)), H, W, None, -1.0, grad_bf16=grad_bf16, **kw)
+    got = _call(lasad, dtype, (*dev_in[:3], lasad.to_device(d_o_in, dtype)), H, W, None, -1.0, grad_bf16=grad_bf16, **kw)[:3]
     ref = oracle.layer_core_backward(q, z, v, d_o_in, W, **okw)
     for nm, a, r in zip(("dq_pre", "dz", "dv"), got, ref):
-        err = parity_err(a.float().cpu().numpy(), r, grad_bf16)
+        err = rel_err(a.cpu().numpy(), r)
         assert err <= _tol(nm, dtype, z), (nm, err)
     whole = _call(lasad, dtype, dev_in, H, W, w, eps, grad_bf16=grad_bf16, **kw)
     ref = oracle.gated_layer_backward(q, z, v, g, W, norm_weight=w, eps=eps, **okw)
     for nm, a, r in zip(("dq_pre", "dz", "dv"), whole, ref):
-        err = parity_err(a.float().cpu().numpy(), r, grad_bf16)
-        assert err <= cond * _tol(nm, dtype, z), (nm, err)
+        err = rel_err(a.cpu().numpy(), r)
+        assert err <= cond * _tol(nm, dtype, z), (nm, err, cond)
     assert torch.equal(whole[3], dw)
 
 
@@ -102,7 +121,7 @@ def _check(lasad, oracle, B, Hh, H, W, dtype, seed, norm="weighted", start=0, n=
         got = _run(lasad, dtype, q, z, v, g, H, W, None, -1.0, start, mode, q_scale, grad_bf16)
         ref = oracle.layer_core_backward(q, z, v, g, W, start_pos=start, mode=mode, q_scale=q_scale)
         for nm, a, r in zip(("dq_pre", "dz", "dv"), got, ref):
-            assert parity_err(a, r, grad_bf16) <= _tol(nm, dtype, z), (nm, parity_err(a, r, grad_bf16))
+            assert rel_err(a, r) <= _tol(nm, dtype, z), (nm, rel_err(a, r))
         assert not got[3].any()
         return
     dev_in = tuple(lasad.to_device(x, dtype) for x in (q, z, v, g))
@@ -166,8 +185,8 @@ def test_backward_layer_strong_gates_take_the_serial_route(lasad, oracle):
     _check_parts(lasad, oracle, dev_in, q, z, v, g, H, W, None, 1e-5)
 
 
-@pytest.mark.parametrize("name", ["base_prefill_16x16", "large_prefill_24x24"])
-def test_backward_layer_bench_shapes_sampled(lasad, oracle, name):
+@pytest.mark.parametrize("name,n_pairs", [("base_prefill_16x16", 8), ("large_prefill_24x24", 8), ("highres_64x64", 3)])
+def test_backward_layer_bench_shapes_sampled(lasad, oracle, name, n_pairs):
     """The benchmark shapes in the benchmark's launch configuration; the oracle on sampled sequences (dweight sums
     over the batch: compared for one head over sampled batch rows by linearity is not possible, so for the base shape
     it is compared in full for two heads)."""
@@ -176,14 +195,14 @@ def test_backward_layer_bench_shapes_sampled(lasad, oracle, name):
     q, z, v, g = _inputs(w.B, w.N, w.Hh, w.d, "bf16", w.seed + 21)
     wt = _weight(w.Hh, w.d)
     got = _run(lasad, "bf16", q, z, v, g, w.grid_h, w.grid_w, wt, 1e-6, grad_bf16=True)
-    pairs = sample_pairs(w.B, w.Hh, 8, seed=w.seed)
+    pairs = sample_pairs(w.B, w.Hh, n_pairs, seed=w.seed)
     ref = [oracle.gated_layer_backward(q[b:b + 1, :, h:h + 1], z[b:b + 1, :, h:h + 1], v[b:b + 1, :, h:h + 1],
                                        g[b:b + 1, :, h:h + 1], w.grid_w, norm_weight=wt[h:h + 1], eps=1e-6)
            for b, h in pairs]
     for i, nm in enumerate(("dq_pre", "dz", "dv")):
         r = np.concatenate([x[i] for x in ref], axis=0)
         a = np.concatenate([got[i][b:b + 1, :, h:h + 1] for b, h in pairs], axis=0)
-        assert parity_err(a, r, True) <= TOL["bf16"], (nm, parity_err(a, r, True))
+        assert rel_err(a, r) <= TOL["bf16"], (nm, rel_err(a, r))
     if name == "base_prefill_16x16":
         full = oracle.layer_norm_backward(q[:, :, :2], z[:, :, :2], v[:, :, :2], g[:, :, :2], w.grid_w, norm_weight=wt[:2], eps=1e-6)
         assert rel_err(got[3][:2], full[1]) <= TOL["bf16"]

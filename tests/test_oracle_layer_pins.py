@@ -110,20 +110,20 @@ def test_layer_backward_is_blind_to_the_scale_of_v(oracle):
     assert abs(float((dv * v).sum())) <= 1e-10 * float(np.abs(dv * v).sum())
 
 
-def test_layer_backward_storage_hook_is_applied_to_the_recurrence_gradient_only(oracle):
-    """store_d_o = identity changes nothing; store_d_o = 0 leaves only the weight gradient (which does not pass
-    through the recurrence); scaling by 2 doubles the three tensor gradients (they are linear in that gradient)."""
+def test_layer_backward_is_the_chain_of_its_two_parts(oracle):
+    """gated_layer_backward = layer_core_backward after layer_norm_backward; the tensor gradients are linear in
+    the gradient that passes between the two parts, the weight gradient does not depend on it."""
     rng = np.random.default_rng(11)
     q, z, v, g = (rng.standard_normal((1, 6, 2, 4)) for _ in range(4))
     w = rng.uniform(0.5, 1.5, size=(2, 4))
     base = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w)
-    same = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w, store_d_o=lambda x: x)
-    none = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w, store_d_o=lambda x: 0 * x)
-    twice = oracle.gated_layer_backward(q, z, v, g, 3, norm_weight=w, store_d_o=lambda x: 2 * x)
+    d_o, dw = oracle.layer_norm_backward(q, z, v, g, 3, norm_weight=w)
+    once = oracle.layer_core_backward(q, z, v, d_o, 3)
+    twice = oracle.layer_core_backward(q, z, v, 2 * d_o, 3)
     for i in range(3):
-        assert np.array_equal(base[i], same[i]) and not none[i].any()
+        assert np.array_equal(base[i], once[i])
         assert np.allclose(twice[i], 2 * base[i], rtol=1e-12, atol=0)
-    assert np.array_equal(base[3], none[3]) and np.array_equal(base[3], twice[3])
+    assert np.array_equal(base[3], dw)
 
 
 @pytest.mark.parametrize("mode", [0, 1])
