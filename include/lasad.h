@@ -121,6 +121,28 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * lasad_forward_chunked for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and results as lasad_forward_chunked, without the workspace pair: the
+ * per-segment partial states of the segment plan live in an array that is part of the loaded
+ * library (lasad_forward_static_scratch_bytes() = 8 MiB per GPU, held until the process ends;
+ * every size the segment plan can ask for fits, a larger request would be LASAD_ERR_WORKSPACE).
+ * The call allocates nothing and synchronises nothing.  Every segment state that a call reads
+ * is written earlier by the same call, so nothing is cleared between calls; but all calls on
+ * one GPU share the one array: calls that may run at the same time on one GPU (different
+ * streams, different threads) race on it and must use lasad_forward_chunked with workspaces of
+ * their own.  Calls on one stream are ordered and safe.
+ */
+size_t lasad_forward_static_scratch_bytes(void);
+int lasad_forward_chunked_static(const void *q, const void *k, const void *v, void *o,
+                                 const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
+                                 int io_dtype, int out_dtype,
+                                 int B, int n_heads, int d, int grid_h, int grid_w,
+                                 int start_pos, int n_tokens,
+                                 const float *gamma, int boundary_mode, float q_scale,
+                                 const float *state_in, float *state_out, void *hip_stream);
+
+/*
  * Recurrent decode step (Algorithm 1 loop body; Section 3.4 first equation):
  * one token for every (batch, head):  S <- lambda S + k v^T,  o = q_scale * S^T q
  * with lambda = 1 if `pos` is a boundary position, else gamma[h].

@@ -20,6 +20,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "lasad_decay_factors", "lasad_forward_workspace_bytes", "lasad_forward_chunked",
+    "lasad_forward_static_scratch_bytes", "lasad_forward_chunked_static",
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
     "lasad_forward_layer", "lasad_decode_step_layer",
     "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
@@ -61,6 +62,11 @@ def load() -> ctypes.CDLL:
     lib.lasad_forward_chunked.argtypes = [vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                           vp, ci, cf, vp, vp, vp, ctypes.c_size_t, vp]
     lib.lasad_forward_chunked.restype = ci
+    lib.lasad_forward_static_scratch_bytes.argtypes = []
+    lib.lasad_forward_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.lasad_forward_chunked_static.argtypes = [vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                                 vp, ci, cf, vp, vp, vp]
+    lib.lasad_forward_chunked_static.restype = ci
     lib.lasad_decode_step.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, cf, vp, vp]
     lib.lasad_decode_step.restype = ci
     lib.lasad_forward_gated.argtypes = [vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
@@ -197,6 +203,36 @@ def lasad_forward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gam
         _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, start_pos, n,
         _ptr(gamma), boundary_mode, q_scale, _ptr(state_in), _ptr(state_out),
         _ptr(workspace), ws_bytes, _stream(stream)))
+    return out
+
+
+def lasad_forward_static_scratch_bytes() -> int:
+    return int(load().lasad_forward_static_scratch_bytes())
+
+
+def lasad_forward_chunked_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, gamma: torch.Tensor,
+                                 grid_h: int, grid_w: int, out: torch.Tensor, start_pos: int = 0,
+                                 boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                                 state_in: torch.Tensor | None = None, state_out: torch.Tensor | None = None,
+                                 stream=None) -> torch.Tensor:
+    """lasad_forward_chunked over the library's built-in scratch array: nothing is allocated, so the
+    caller passes every buffer, `out` included."""
+    B, n, Hh, d = q.shape
+    if k.shape != q.shape or v.shape != q.shape or k.stride() != q.stride() or v.stride() != q.stride():
+        raise ValueError("q, k, v must share shape and strides")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share a dtype")
+    if out.shape != q.shape:
+        raise ValueError("out has the wrong shape")
+    for s in (state_in, state_out):
+        if s is not None and (s.dtype != torch.float32 or not s.is_contiguous() or tuple(s.shape) != (B, Hh, d, d)):
+            raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
+    assert gamma.dtype == torch.float32 and gamma.is_contiguous() and tuple(gamma.shape) == (Hh,)
+    lq, lo = _layout(q), _layout(out)
+    _check(load().lasad_forward_chunked_static(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(out), ctypes.byref(lq), ctypes.byref(lo),
+        _dtype_code(q), _dtype_code(out), B, Hh, d, grid_h, grid_w, start_pos, n,
+        _ptr(gamma), boundary_mode, q_scale, _ptr(state_in), _ptr(state_out), _stream(stream)))
     return out
 
 

@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "lasad_internal.h"
 
 namespace {
@@ -48,6 +50,39 @@ int check_grid(int grid_h, int grid_w, int mode)
 
 }  // namespace
 
+// Scratch of lasad_forward_chunked_static: the per-segment partial states of the segment plan
+// (at most 512 workgroup slots x one 64 x 64 fp32 state).  One copy per GPU, held until the
+// process ends; its device address is looked up once per device (the array's name is only a
+// host-side handle).
+constexpr size_t kStaticScratchBytes = (size_t)512 * 64 * 64 * sizeof(float);   // 8 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail("hipGetDevice", e);
+    if (dev < 0 || dev >= kMaxDevices) return fail(LASAD_ERR_UNSUPPORTED, "device index %d", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail("hipGetSymbolAddress(scratch)", e);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LASAD_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char *lasad_last_error(void) { return g_err; }
@@ -77,14 +112,15 @@ size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, in
     return 0;   // the fp32 kernel keeps everything in registers and LDS
 }
 
-int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
-                          const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
-                          int io_dtype, int out_dtype,
-                          int B, int n_heads, int d, int grid_h, int grid_w,
-                          int start_pos, int n_tokens,
-                          const float *gamma, int boundary_mode, float q_scale,
-                          const float *state_in, float *state_out,
-                          void *workspace, size_t workspace_bytes, void *hip_stream)
+// static_ws: the workspace is the library's own scratch array (looked up after the arguments have passed)
+static int forward_chunked_impl(const void *q, const void *k, const void *v, void *o,
+                                const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
+                                int io_dtype, int out_dtype,
+                                int B, int n_heads, int d, int grid_h, int grid_w,
+                                int start_pos, int n_tokens,
+                                const float *gamma, int boundary_mode, float q_scale,
+                                const float *state_in, float *state_out,
+                                void *workspace, size_t workspace_bytes, bool static_ws, void *hip_stream)
 {
     if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
     if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
@@ -124,6 +160,13 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
     a.state_in = state_in; a.state_out = state_out;
     a.seg_states = nullptr; a.n_segments = 1; a.seg_chunks = 0;
     a.fused_act = 0; a.norm = 0; a.norm_eps = 0.f; a.norm_w = nullptr;
+    if (static_ws && n_tokens > 0) {
+        if (lasad_forward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype) > kStaticScratchBytes)
+            return fail(LASAD_ERR_WORKSPACE, "the call wants %zu bytes of scratch, the built-in array holds %zu",
+                        lasad_forward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype), kStaticScratchBytes);
+        if (int rc = static_scratch(&workspace)) return rc;
+        workspace_bytes = kStaticScratchBytes;
+    }
     if (workspace) {
         const size_t need = lasad_forward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype);
         if (workspace_bytes < need)
@@ -142,6 +185,35 @@ int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
         e = lasad::launch_forward_generic(a, s);
     if (e != hipSuccess) return hip_fail("lasad_forward_chunked launch", e);
     return LASAD_OK;
+}
+
+int lasad_forward_chunked(const void *q, const void *k, const void *v, void *o,
+                          const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
+                          int io_dtype, int out_dtype,
+                          int B, int n_heads, int d, int grid_h, int grid_w,
+                          int start_pos, int n_tokens,
+                          const float *gamma, int boundary_mode, float q_scale,
+                          const float *state_in, float *state_out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return forward_chunked_impl(q, k, v, o, qkv_layout, o_layout, io_dtype, out_dtype, B, n_heads, d, grid_h, grid_w,
+                                start_pos, n_tokens, gamma, boundary_mode, q_scale, state_in, state_out,
+                                workspace, workspace_bytes, false, hip_stream);
+}
+
+size_t lasad_forward_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int lasad_forward_chunked_static(const void *q, const void *k, const void *v, void *o,
+                                 const lasad_layout_t *qkv_layout, const lasad_layout_t *o_layout,
+                                 int io_dtype, int out_dtype,
+                                 int B, int n_heads, int d, int grid_h, int grid_w,
+                                 int start_pos, int n_tokens,
+                                 const float *gamma, int boundary_mode, float q_scale,
+                                 const float *state_in, float *state_out, void *hip_stream)
+{
+    return forward_chunked_impl(q, k, v, o, qkv_layout, o_layout, io_dtype, out_dtype, B, n_heads, d, grid_h, grid_w,
+                                start_pos, n_tokens, gamma, boundary_mode, q_scale, state_in, state_out,
+                                nullptr, 0, true, hip_stream);
 }
 
 int lasad_decode_step(const void *q, const void *k, const void *v, void *o,

@@ -159,3 +159,19 @@ def test_backward_layer_norm_rejects_bad_arguments_and_sizes_its_workspace(lib):
     assert lib.lasad_backward_layer_workspace_bytes(0, 3, 100, 64, 1, ctypes.byref(dense)) == 0
     assert lib.lasad_backward_layer_workspace_bytes(2, 3, 100, 64, 1, None) == 0
 
+
+def test_static_forward_entry_validates_like_the_workspace_entry(lib):
+    """lasad_forward_chunked_static: same argument checks (nothing is launched: the pointers are fake) and an
+    8 MiB built-in scratch array that covers every size the segment plan asks for."""
+    lib.lasad_forward_static_scratch_bytes.restype = ctypes.c_size_t
+    assert lib.lasad_forward_static_scratch_bytes() == 8 << 20
+    for B, Hh, n in ((4, 24, 4096), (1, 1, 1 << 20), (2, 100, 8192), (255, 1, 2048)):
+        assert lib.lasad_forward_workspace_bytes(B, Hh, n, 64, 1) <= 8 << 20
+    vp = ctypes.c_void_p
+    lay = Layout(64 * 4 * 2, 2 * 64, 64)
+    call = lambda **k: lib.lasad_forward_chunked_static(
+        vp(k.get("q", 0x1000)), vp(0x2000), vp(0x3000), vp(k.get("o", 0x4000)), ctypes.byref(lay), ctypes.byref(lay),
+        1, 1, k.get("B", 1), 2, k.get("d", 64), 2, 2, 0, k.get("n", 4), vp(k.get("gamma", 0x5000)), 0,
+        ctypes.c_float(1.0), None, None, None)
+    assert call(d=48) == 2 and call(B=0) == 1 and call(n=5) == 1 and call(q=None) == 1
+    assert call(o=0x1000) == 1 and call(gamma=None) == 1
