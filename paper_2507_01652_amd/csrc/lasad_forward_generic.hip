@@ -43,7 +43,10 @@ hipError_t launch_d(const ForwardArgs &a, hipStream_t s)
 hipError_t launch_forward_generic(const ForwardArgs &a, hipStream_t s)
 {
     static const bool scan = [] { const char *e = getenv("LASAD_SCAN"); return !(e && e[0] == '0'); }();
-    if (a.d == 64 && scan) return launch_forward_scan(a, s);
+    // the fused activations and the norm exist in the scan kernel only: such calls go there whatever the switch says
+    const bool fused = a.fused_act || a.norm;
+    if (fused && a.d != 64) return hipErrorInvalidValue;
+    if (a.d == 64 && (scan || fused)) return launch_forward_scan(a, s);
     switch (a.d) {
         case 32: return launch_d<32>(a, s);
         case 64: return launch_d<64>(a, s);
