@@ -346,19 +346,25 @@ int lasad_oracle_gated_bruteforce(const double *q, const double *lam, const doub
 
 /* Threads the OpenMP loops above will use (reported by the benchmark). */
 /*
- * Gradients of the sequential form (Section 3.4 recurrence from a zero state) by differentiating
- * it step by step in reverse.  Given d_o[t] = dL/do_t, with
+ * Gradients of the sequential form (Section 3.4 recurrence) by differentiating it step by step in
+ * reverse.  The call covers tokens 1..n of a sequence whose state before token 1 is s_0 (zero if
+ * s0 is NULL) and whose loss may also depend on the state after token n: given d_o[t] = dL/do_t
+ * and d_sn = dL/ds_n (zero if NULL), with
  *     s_t = lambda_t s_{t-1} + k_t v_t^T,        o_t = q_scale * s_t^T q_t,
- * the state gradient g_t = dL/ds_t obeys g_t = q_scale q_t d_o_t^T + lambda_{t+1} g_{t+1}, and
- *     dq_t = q_scale * s_t d_o_t,   dk_t = g_t v_t,   dv_t = g_t^T k_t,   dlambda_t = <g_t, s_{t-1}>.
+ * the state gradient g_t = dL/ds_t obeys g_n = d_sn + q_scale q_n d_o_n^T,
+ * g_t = q_scale q_t d_o_t^T + lambda_{t+1} g_{t+1}, and
+ *     dq_t = q_scale * s_t d_o_t,   dk_t = g_t v_t,   dv_t = g_t^T k_t,   dlambda_t = <g_t, s_{t-1}>,
+ *     d_s0 = lambda_1 g_1          (the gradient for the incoming state; not written if d_s0 is NULL).
  * The forward states s_0 .. s_n are kept (n+1 matrices per sequence).  lam is [Hh][n]; dq, dk, dv
- * are [B][Hh][n][d]; dlam is [B][Hh][n], the gradient with respect to the decay applied at each
- * token of each sequence (the caller sums it over whatever positions share a parameter).
+ * are [B][Hh][n][d]; s0, d_sn, d_s0 are [B][Hh][d][d]; dlam is [B][Hh][n], the gradient with
+ * respect to the decay applied at each token of each sequence (the caller sums it over whatever
+ * positions share a parameter).
  */
-int lasad_oracle_backward(const double *q, const double *k, const double *v,
-                          const double *lam, double q_scale, const double *d_o,
-                          double *dq, double *dk, double *dv, double *dlam,
-                          int B, int n_heads, int n, int d)
+int lasad_oracle_backward_carried(const double *q, const double *k, const double *v,
+                                  const double *lam, double q_scale, const double *d_o,
+                                  const double *s0, const double *d_sn,
+                                  double *dq, double *dk, double *dv, double *dlam, double *d_s0,
+                                  int B, int n_heads, int n, int d)
 {
     if (!q || !k || !v || !lam || !d_o || !dq || !dk || !dv || !dlam || B < 1 || n_heads < 1 || n < 0 || d < 1)
         return 1;
@@ -376,6 +382,8 @@ int lasad_oracle_backward(const double *q, const double *k, const double *v,
             free(S); free(G);
             continue;
         }
+        if (s0) memcpy(S, s0 + (size_t)bh * dd, dd * sizeof(double));       /* s_0 */
+        if (d_sn) memcpy(G, d_sn + (size_t)bh * dd, dd * sizeof(double));    /* dL/ds_n */
         for (int t = 0; t < n; ++t) {
             const double l = lam[(size_t)h * n + t];
             const double *kt = k + ((size_t)bh * n + t) * d;
@@ -420,9 +428,19 @@ int lasad_oracle_backward(const double *q, const double *k, const double *v,
             dlam[(size_t)bh * n + t] = dl;
             for (size_t e = 0; e < dd; ++e) G[e] *= l;
         }
+        if (d_s0) memcpy(d_s0 + (size_t)bh * dd, G, dd * sizeof(double));    /* lambda_1 g_1 (d_sn itself if n = 0) */
         free(S); free(G);
     }
     return status;
+}
+
+/* The same from a zero state, final state unused. */
+int lasad_oracle_backward(const double *q, const double *k, const double *v,
+                          const double *lam, double q_scale, const double *d_o,
+                          double *dq, double *dk, double *dv, double *dlam,
+                          int B, int n_heads, int n, int d)
+{
+    return lasad_oracle_backward_carried(q, k, v, lam, q_scale, d_o, NULL, NULL, dq, dk, dv, dlam, NULL, B, n_heads, n, d);
 }
 
 /*
@@ -447,9 +465,10 @@ int lasad_oracle_dgamma(const double *dlam, int B, int n_heads, int n,
 }
 
 /*
- * Gradients of the vector-decay recurrence (Section 3.4 / Algorithm 1, zero initial state) by
- * differentiating it step by step in reverse, exactly as lasad_oracle_backward does for one decay
- * per token.  With l_t = lambda_t^spatial (1 in every channel at a row boundary, lambda_t elsewhere),
+ * Gradients of the vector-decay recurrence (Section 3.4 / Algorithm 1) by differentiating it step
+ * by step in reverse, exactly as lasad_oracle_backward_carried does for one decay per token: the
+ * state before the first token is s0 (zero if NULL), d_sn = dL/ds_n (zero if NULL) enters the state
+ * gradient at the last token, and d_s0 = diag(l_1) g_1 is returned if d_s0 is not NULL.  With l_t = lambda_t^spatial (1 in every channel at a row boundary, lambda_t elsewhere),
  *     s_t = diag(l_t) s_{t-1} + k_t v_t^T,        o_t = q_scale * s_t^T q_t,
  * the state gradient g_t = dL/ds_t obeys g_t = q_scale q_t d_o_t^T + diag(l_{t+1}) g_{t+1}, and
  *     dq_t = q_scale * s_t d_o_t,   dk_t = g_t v_t,   dv_t = g_t^T k_t,
@@ -461,10 +480,10 @@ int lasad_oracle_dgamma(const double *dlam, int B, int n_heads, int n,
  * (dk must then be non-NULL); with the tied key, dk may be NULL.
  * All tensors [B][Hh][n][d]; the forward states s_0 .. s_n are kept (n+1 matrices per sequence).
  */
-int lasad_oracle_gated_backward(const double *q, const double *lam, const double *k, const double *v,
-                                double q_scale, const double *d_o,
-                                double *dq, double *dlam, double *dk, double *dv,
-                                int B, int n_heads, int n, int d, int grid_w, int start_pos, int mode)
+int lasad_oracle_gated_backward_carried(const double *q, const double *lam, const double *k, const double *v,
+                                        double q_scale, const double *d_o, const double *s0, const double *d_sn,
+                                        double *dq, double *dlam, double *dk, double *dv, double *d_s0,
+                                        int B, int n_heads, int n, int d, int grid_w, int start_pos, int mode)
 {
     if (!q || !lam || !v || !d_o || !dq || !dlam || !dv || (k && !dk)) return 1;
     if (B < 1 || n_heads < 1 || n < 0 || d < 1 || grid_w < 1 || start_pos < 0 || mode < 0 || mode > 2) return 1;
@@ -483,6 +502,8 @@ int lasad_oracle_gated_backward(const double *q, const double *lam, const double
             free(S); free(G); free(kt); free(dkt);
             continue;
         }
+        if (s0) memcpy(S, s0 + (size_t)bh * dd, dd * sizeof(double));       /* s_0 */
+        if (d_sn) memcpy(G, d_sn + (size_t)bh * dd, dd * sizeof(double));    /* dL/ds_n */
         for (int t = 0; t < n; ++t) {
             const size_t off = ((size_t)bh * n + t) * d;
             const int boundary = is_boundary((int64_t)start_pos + 1 + t, grid_w, mode);
@@ -532,9 +553,20 @@ int lasad_oracle_gated_backward(const double *q, const double *lam, const double
                 for (int c = 0; c < d; ++c) G[(size_t)r * d + c] *= ls;
             }
         }
+        if (d_s0) memcpy(d_s0 + (size_t)bh * dd, G, dd * sizeof(double));    /* diag(l_1) g_1 */
         free(S); free(G); free(kt); free(dkt);
     }
     return status;
+}
+
+/* The same from a zero state, final state unused. */
+int lasad_oracle_gated_backward(const double *q, const double *lam, const double *k, const double *v,
+                                double q_scale, const double *d_o,
+                                double *dq, double *dlam, double *dk, double *dv,
+                                int B, int n_heads, int n, int d, int grid_w, int start_pos, int mode)
+{
+    return lasad_oracle_gated_backward_carried(q, lam, k, v, q_scale, d_o, NULL, NULL, dq, dlam, dk, dv, NULL,
+                                               B, n_heads, n, d, grid_w, start_pos, mode);
 }
 
 #ifdef _OPENMP

@@ -66,6 +66,12 @@ def _load():
         lib.lasad_oracle_gated_bruteforce.restype = ci
         lib.lasad_oracle_backward.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp, dp, dp, ci, ci, ci, ci]
         lib.lasad_oracle_backward.restype = ci
+        lib.lasad_oracle_backward_carried.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp, dp, dp, dp, dp, dp,
+                                                      ci, ci, ci, ci]
+        lib.lasad_oracle_backward_carried.restype = ci
+        lib.lasad_oracle_gated_backward_carried.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, dp, dp, dp, dp, dp, dp, dp,
+                                                            ci, ci, ci, ci, ci, ci, ci]
+        lib.lasad_oracle_gated_backward_carried.restype = ci
         lib.lasad_oracle_dgamma.argtypes = [dp, ci, ci, ci, ci, ci, ci, dp]
         lib.lasad_oracle_dgamma.restype = ci
         lib.lasad_oracle_num_threads.argtypes = []
@@ -181,6 +187,37 @@ def backward(q, k, v, lam, d_o, q_scale=1.0):
     return dq, dk, dv, dlam
 
 
+def _state(x, B, Hh, d):
+    if x is None:
+        return None
+    x = _f64c(x)
+    assert x.shape == (B, Hh, d, d)
+    return x
+
+
+def backward_carried(q, k, v, lam, d_o, s0=None, d_state=None, q_scale=1.0):
+    """Gradients of the recurrence for a call that starts from the state s0 [B, Hh, d, d] (None: zero) and whose
+    final state s_n also enters the loss with gradient d_state = dL/ds_n (None: zero).  Other arguments as
+    backward().  Returns dq, dk, dv [B, n, Hh, d], dlam [B, Hh, n] and d_s0 = dL/ds_0 [B, Hh, d, d]."""
+    q, k, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, k, v, d_o))
+    B, n, Hh, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and d_o.shape == q.shape
+    lam = _f64c(lam)
+    assert lam.shape == (Hh, n)
+    s0, d_state = _state(s0, B, Hh, d), _state(d_state, B, Hh, d)
+    qh, kh, vh, gh = (np.ascontiguousarray(x.transpose(0, 2, 1, 3)) for x in (q, k, v, d_o))
+    dqh, dkh, dvh = np.empty_like(qh), np.empty_like(qh), np.empty_like(qh)
+    dlam = np.empty((B, Hh, n), dtype=np.float64)
+    d_s0 = np.empty((B, Hh, d, d), dtype=np.float64)
+    rc = _load().lasad_oracle_backward_carried(_dptr(qh), _dptr(kh), _dptr(vh), _dptr(lam), float(q_scale), _dptr(gh),
+                                               _dptr(s0), _dptr(d_state), _dptr(dqh), _dptr(dkh), _dptr(dvh),
+                                               _dptr(dlam), _dptr(d_s0), B, Hh, n, d)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_backward_carried failed (rc={rc})")
+    dq, dk, dv = (np.ascontiguousarray(x.transpose(0, 2, 1, 3)) for x in (dqh, dkh, dvh))
+    return dq, dk, dv, dlam, d_s0
+
+
 def dgamma(dlam, grid_w, start_pos=0, mode=RESET_LAST_COL):
     """Sum of the per-token decay gradients over the non-boundary positions and the batch: [Hh]."""
     dlam = _f64c(dlam)
@@ -250,6 +287,31 @@ def gated_backward(q, lam, v, d_o, grid_w, k=None, start_pos=0, mode=RESET_LAST_
     if k is None:
         return back(dq), back(dl), back(dv)
     return back(dq), back(dl), back(dv), back(dk)
+
+
+def gated_backward_carried(q, lam, v, d_o, grid_w, k=None, s0=None, d_state=None, start_pos=0, mode=RESET_LAST_COL,
+                           q_scale=1.0):
+    """gated_backward for a call that starts from the state s0 (None: zero) and whose final state enters the loss
+    with gradient d_state (None: zero).  Returns (dq, dlam, dv[, dk], d_s0), d_s0 = dL/ds_0 [B, Hh, d, d]."""
+    q, lam, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, lam, v, d_o))
+    B, n, Hh, d = q.shape
+    assert lam.shape == q.shape and v.shape == q.shape and d_o.shape == q.shape
+    s0, d_state = _state(s0, B, Hh, d), _state(d_state, B, Hh, d)
+    tr = lambda x: np.ascontiguousarray(x.transpose(0, 2, 1, 3))
+    qh, lh, vh, gh = tr(q), tr(lam), tr(v), tr(d_o)
+    kh = None if k is None else tr(np.asarray(k, dtype=np.float64))
+    dq, dl, dv = np.empty_like(qh), np.empty_like(qh), np.empty_like(qh)
+    dk = None if k is None else np.empty_like(qh)
+    d_s0 = np.empty((B, Hh, d, d), dtype=np.float64)
+    rc = _load().lasad_oracle_gated_backward_carried(_dptr(qh), _dptr(lh), _dptr(kh), _dptr(vh), float(q_scale), _dptr(gh),
+                                                     _dptr(s0), _dptr(d_state), _dptr(dq), _dptr(dl), _dptr(dk), _dptr(dv),
+                                                     _dptr(d_s0), B, Hh, n, d, grid_w, start_pos, mode)
+    if rc != 0:
+        raise RuntimeError(f"lasad_oracle_gated_backward_carried failed (rc={rc})")
+    back = lambda x: np.ascontiguousarray(x.transpose(0, 2, 1, 3))
+    if k is None:
+        return back(dq), back(dl), back(dv), d_s0
+    return back(dq), back(dl), back(dv), back(dk), d_s0
 
 
 # ---- Algorithm 1's elementwise steps around the recurrence --------------------------------------
