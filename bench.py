@@ -516,6 +516,28 @@ def measure_copy_peak(torch, timer):
     return 2.0 * n * reps / (ms * 1e-3) / 1e9
 
 
+def measure_stream_3r1w(torch, timer, shape):
+    """The traffic mix of the forward (three bf16 tensors read, one written) as one plain elementwise kernel
+    (torch.addcmul) over tensors of the headline workload's size, cold caches, rotating buffer sets: the rate a
+    streaming kernel without any of the method's structure reaches on this mix."""
+    n_sets = 8
+    bufs = [tuple(torch.ones(shape, dtype=torch.bfloat16, device="cuda") for _ in range(4)) for _ in range(n_sets)]
+    steps = 16
+
+    def run():
+        for i in range(steps):
+            a, b, c, o = bufs[i % n_sets]
+            torch.addcmul(a, b, c, out=o)
+
+    run()
+    ms = min(timer.region(run) for _ in range(3)) / steps
+    nbytes = 4 * bufs[0][0].numel() * 2
+    del bufs
+    return {"value": nbytes / (ms * 1e-3) / 1e9, "unit": "GB/s", "ms_per_step": ms,
+            "what": "torch.addcmul(q, k, v, out=o) on bf16 tensors of the headline workload's size (3 read + 1 written, "
+                    "the forward's algorithmic bytes), eager launches, cold caches"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -551,6 +573,9 @@ def main():
                                       "plain copy kernel reaches on this GPU; roofline.frac stays against the published 8 TB/s"},
     }
     line["roofline"]["frac_of_measured_copy"] = line["roofline"]["achieved"] / copy_gbs
+    w0 = wl.CONFIGS[PREFILL_WORKLOADS[args.workload]]
+    line["hbm_stream_3r1w_measured"] = measure_stream_3r1w(torch, timer, (w0.B, w0.N, w0.Hh, w0.d))
+    line["roofline"]["frac_of_measured_stream_3r1w"] = line["roofline"]["achieved"] / line["hbm_stream_3r1w_measured"]["value"]
     if "cpu_baseline" in pre:
         line["cpu_baseline"] = pre["cpu_baseline"]
     legs = {pre["workload"]: pre}

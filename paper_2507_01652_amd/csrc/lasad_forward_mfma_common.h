@@ -164,6 +164,7 @@ __device__ inline void state_update(f32x16 &accS, const uint16_t *sKh, const uin
 }
 
 // K/V staging loads of one chunk of a token range [0, n): unconditional, index clamped.
+template <bool NT = false>
 __device__ inline void load_kv(uint4 (&rk)[2], uint4 (&rv)[2], const uint16_t *gk, const uint16_t *gv,
                                int t0, int n, int64_t stride_n, int tid)
 {
@@ -171,8 +172,8 @@ __device__ inline void load_kv(uint4 (&rk)[2], uint4 (&rv)[2], const uint16_t *g
     for (int it = 0; it < 2; ++it) {
         const int tok = min(t0 + (tid >> 3) + 32 * it, n - 1);
         const int64_t off = (int64_t)tok * stride_n + (tid & 7) * 8;
-        rk[it] = *(const uint4 *)(gk + off);
-        rv[it] = *(const uint4 *)(gv + off);
+        rk[it] = gload16<NT>(gk + off);
+        rv[it] = gload16<NT>(gv + off);
     }
 }
 

@@ -55,6 +55,9 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         a.in = m.in[pass]; a.out = m.out[pass]; a.start_pos = m.start_pos[pass];
     }
 
+    // q, k, v and o rows are touched once by a forward call: non-temporal.  The passes of a backward launch read
+    // each tensor two or three times and share it through the L2: ordinary loads there.
+    constexpr bool NT = !DOT;
     constexpr int kLdsHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;
     __shared__ __attribute__((aligned(16))) uint16_t smem[kLdsHalfs];
     __shared__ __attribute__((aligned(16))) float tabC[C];
@@ -101,7 +104,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
     if (state_wave) {
         // ===================================== state waves =====================================
         uint4 rk[2], rv[2];
-        load_kv(rk, rv, gk, gv, 0, n, a.in.stride_n, st);
+        load_kv<NT>(rk, rv, gk, gv, 0, n, a.in.stride_n, st);
 
         f32x16 accS;                   // S[dk = wa*32 + 8*(r/4) + 4*g + r%4][dv = wc*32 + l32]
         if (a.state_in) {
@@ -152,7 +155,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             WPROF(1);
             __syncthreads();                              // (A) tiles, c_j table and S^T visible
             WPROF(2);
-            if (chunk + 1 < n_chunks) load_kv(rk, rv, gk, gv, t0 + C, n, a.in.stride_n, st);
+            if (chunk + 1 < n_chunks) load_kv<NT>(rk, rv, gk, gv, t0 + C, n, a.in.stride_n, st);
             Frag fv[4];
             load_v_frags(fv, sV, wc, lane);
             state_update(accS, sKh, sKl, fv, wa, lane);
@@ -185,7 +188,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         const int qtok = min(chunk * C + (wa ^ (chunk & 1)) * 32 + l32, n - 1);
         const uint16_t *p = gq + (int64_t)qtok * a.in.stride_n + 8 * g;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);
+        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);    // (a row in four pieces: they meet in the cache)
     };
     auto take_q = [&](int chunk) {                        // prefetched Q fragments -> fq (tail rows zero)
         const bool live = chunk * C + (wa ^ (chunk & 1)) * 32 + l32 < n;
@@ -278,8 +281,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             float *go = (float *)a.o + o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)
-                *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
-                                                       accO[4 * qd + 2], accO[4 * qd + 3]);
+                gstore16<NT>(go + 8 * qd, accO[4 * qd + 0], accO[4 * qd + 1], accO[4 * qd + 2], accO[4 * qd + 3]);
         }
         WPROF(4);
         __syncthreads();                                  // (B)
@@ -290,8 +292,8 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             for (int it = 0; it < 2; ++it) {
                 const int row = (st >> 3) + 32 * it;
                 if (row < nt)
-                    *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
-                        *(const uint4 *)&sO[row * RS + (st & 7) * 8];
+                    gstore16<NT>(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8,
+                                 *(const uint4 *)&sO[row * RS + (st & 7) * 8]);
             }
         }
     }

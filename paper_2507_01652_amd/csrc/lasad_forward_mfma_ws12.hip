@@ -33,6 +33,10 @@ using namespace fwd;
 constexpr int kWs12Threads = 768;     // SPLIT 1: 4 output + 4 state + 4 loader waves
 constexpr int kWs10Threads = 640;     // SPLIT 2: 4 output + 2 state + 4 loader waves
 constexpr int PS = 36;                // row stride (floats) of an fp32 partial output tile [token][32 channels]
+#ifndef LASAD_WS12_PF
+#define LASAD_WS12_PF 1
+#endif
+constexpr int kPf = LASAD_WS12_PF;    // chunks between the global loads of K / V rows and their staging
 
 #ifdef LASAD_PROFILE
 // Development aid: cycle stamps of workgroup 0, waves 0 (output), 4 (state), 8 (loader), 8 slots each.
@@ -66,6 +70,10 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         a.in = m.in[y]; a.out = m.out[y]; a.start_pos = m.start_pos[y];
     }
 
+    // rows touched once per call: non-temporal.  Split workgroups share Q and K through the L2 and the passes of a
+    // backward launch read every tensor two or three times: ordinary loads there.
+    constexpr bool NT = !DOT && SPLIT == 1;
+    constexpr bool NTO = !DOT;                          // output rows
     constexpr int SROWS = SPLIT == 1 ? D : D / 2;       // rows (value channels) of the S^T tiles
     constexpr int oV = C * RS, oKh = oV + C * VS, oKl = oKh + C * VS, oSh = oKl + C * VS;
     constexpr int oSl = oSh + SROWS * RS, oO = oSl + SROWS * RS;
@@ -140,8 +148,8 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
             for (int it = 0; it < 2; ++it) {
                 const int row = (st >> 3) + 32 * it;
                 if (row < nt)
-                    *(uint4 *)(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8) =
-                        *(const uint4 *)&bO[row * RS + (st & 7) * 8];
+                    gstore16<NTO>(go + (int64_t)(t0 + row) * a.out.stride_n + (st & 7) * 8,
+                                  *(const uint4 *)&bO[row * RS + (st & 7) * 8]);
             }
         } else {                                          // sum of the two fp32 partial tiles of this channel half
             const float *x = sPart(chunk & 1, 0), *y = sPart(chunk & 1, 1);
@@ -154,40 +162,50 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
                     uint4 w;
                     w.x = pack2(x0.x + y0.x, x0.y + y0.y); w.y = pack2(x0.z + y0.z, x0.w + y0.w);
                     w.z = pack2(x1.x + y1.x, x1.y + y1.y); w.w = pack2(x1.z + y1.z, x1.w + y1.w);
-                    *(uint4 *)((uint16_t *)a.o + oi) = w;
+                    gstore16<NTO>((uint16_t *)a.o + oi, w);
                 } else {
-                    *(float4 *)((float *)a.o + oi) = make_float4(x0.x + y0.x, x0.y + y0.y, x0.z + y0.z, x0.w + y0.w);
-                    *(float4 *)((float *)a.o + oi + 4) = make_float4(x1.x + y1.x, x1.y + y1.y, x1.z + y1.z, x1.w + y1.w);
+                    gstore16<NTO>((float *)a.o + oi, x0.x + y0.x, x0.y + y0.y, x0.z + y0.z, x0.w + y0.w);
+                    gstore16<NTO>((float *)a.o + oi + 4, x1.x + y1.x, x1.y + y1.y, x1.z + y1.z, x1.w + y1.w);
                 }
             }
         }
     };
     if (group == 2) {
         // ===================================== loader waves =====================================
-        uint4 rk[2], rv[2];
+        // K and V rows travel through one of kPf register sets; the set of chunk c is loaded kPf chunks
+        // before its tiles are written (the loads of kPf - 1 chunks are in flight while one is staged)
+        uint4 rk[kPf][2], rv[kPf][2];
         StagedKeys sk;
         ChunkPos pos;
         pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
-        load_kv(rk, rv, gk, gv, 0, n, a.in.stride_n, st);
-        prepare_keys(sk, rk, rv, st, min(C, n), pos, lg, sc);
+#pragma unroll
+        for (int u = 0; u < kPf; ++u)
+            if (u == 0 || u < n_chunks) load_kv<NT>(rk[u], rv[u], gk, gv, u * C, n, a.in.stride_n, st);
+        prepare_keys(sk, rk[0], rv[0], st, min(C, n), pos, lg, sc);
         pos.advance();
-        write_tiles<true>(sK(0), sV(0), sKh(0), sKl(0), tabC2[0], rk, rv, sk, st);
-        if (n_chunks > 1) load_kv(rk, rv, gk, gv, C, n, a.in.stride_n, st);
+        write_tiles<true>(sK(0), sV(0), sKh(0), sKl(0), tabC2[0], rk[0], rv[0], sk, st);
+        if (kPf < n_chunks) load_kv<NT>(rk[0], rv[0], gk, gv, kPf * C, n, a.in.stride_n, st);
         __syncthreads();
-        for (int chunk = 0; chunk < n_chunks; ++chunk) {
-            WPROF(0);
-            if ((OUT_BF16 || SPLIT == 2) && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
-            if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
-                const int p = (chunk + 1) & 1;
-                prepare_keys(sk, rk, rv, st, min(C, n - (chunk + 1) * C), pos, lg, sc);
-                pos.advance();
-                WPROF(1);
-                write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk, rv, sk, st);
-                if (chunk + 2 < n_chunks) load_kv(rk, rv, gk, gv, (chunk + 2) * C, n, a.in.stride_n, st);
+        for (int c0 = 0; c0 < n_chunks; c0 += kPf) {
+#pragma unroll
+            for (int u = 0; u < kPf; ++u) {
+                const int chunk = c0 + u;
+                if (chunk >= n_chunks) break;
+                const int r = (u + 1) % kPf;              // register set of chunk + 1
+                WPROF(0);
+                if ((OUT_BF16 || SPLIT == 2) && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
+                if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
+                    const int p = (chunk + 1) & 1;
+                    prepare_keys(sk, rk[r], rv[r], st, min(C, n - (chunk + 1) * C), pos, lg, sc);
+                    pos.advance();
+                    WPROF(1);
+                    write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk[r], rv[r], sk, st);
+                    if (chunk + 1 + kPf < n_chunks) load_kv<NT>(rk[r], rv[r], gk, gv, (chunk + 1 + kPf) * C, n, a.in.stride_n, st);
+                }
+                WPROF(2);
+                __syncthreads();
+                WPROF(3);
             }
-            WPROF(2);
-            __syncthreads();
-            WPROF(3);
         }
         if (OUT_BF16 || SPLIT == 2) store_tile(n_chunks - 1);
         if (first_of_group) WPROF_MARK(23);
@@ -258,19 +276,21 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     }
 
     // ========================================= output waves =========================================
-    Frag fqn[4], fq[4];
-    auto prefetch_q = [&](int chunk) {
+    // Q fragments go through one of two register sets, loaded two chunks ahead (chunk c uses set c & 1)
+    Frag fqn[2][4], fq[4];
+    auto prefetch_q = [&](Frag (&dst)[4], int chunk) {
         const int qtok = min(chunk * C + (wa ^ (chunk & 1)) * 32 + l32, n - 1);
         const uint16_t *p = gq + (int64_t)qtok * a.in.stride_n + 8 * g;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) fqn[s].u = *(const uint4 *)(p + 16 * s);
+        for (int s = 0; s < 4; ++s) dst[s].u = *(const uint4 *)(p + 16 * s);    // (a row in four pieces: they meet in the cache)
     };
-    auto take_q = [&](int chunk) {                        // prefetched Q fragments -> fq (tail rows zero)
+    auto take_q = [&](const Frag (&src)[4], int chunk) {  // prefetched Q fragments -> fq (tail rows zero)
         const bool live = chunk * C + (wa ^ (chunk & 1)) * 32 + l32 < n;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
+        for (int s = 0; s < 4; ++s) fq[s].u = live ? src[s].u : make_uint4(0, 0, 0, 0);
     };
-    prefetch_q(0);
+    prefetch_q(fqn[0], 0);
+    if (n_chunks > 1) prefetch_q(fqn[1], 1);
     GradDot gd;
     if (DOT) gd.init(a, m, blockIdx.y, in_base);
 
@@ -278,17 +298,20 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     const int cq = l32 - 4 * g;
 
     __syncthreads();
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+    for (int c0 = 0; c0 < n_chunks; c0 += 2) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {                         // p = chunk & 1: buffer set and Q register set
+        const int chunk = c0 + p;
+        if (chunk >= n_chunks) break;
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
-        const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
-        const int p = chunk & 1;
+        const int qa = wa ^ p;                            // query half of this wave in this chunk
         const uint16_t *bK = sK(p), *bV = sV(p), *bSh = sSh(p), *bSl = sSl(p);
         uint16_t *bO = sO(p);
         const float *bC = tabC2[p];
         WPROF(0);
-        take_q(chunk);
-        if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
+        take_q(fqn[p], chunk);
+        if (chunk + 2 < n_chunks) prefetch_q(fqn[p], chunk + 2);
         WPROF(1);
         const int i_row = qa * 32 + l32;
         if (DOT) gd.fetch(min(t0 + i_row, n - 1), wc * 32 + 4 * g);
@@ -383,12 +406,12 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
             float *go = (float *)a.o + o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)
-                *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
-                                                       accO[4 * qd + 2], accO[4 * qd + 3]);
+                gstore16<NTO>(go + 8 * qd, accO[4 * qd + 0], accO[4 * qd + 1], accO[4 * qd + 2], accO[4 * qd + 3]);
         }
         WPROF(4);
         __syncthreads();
         WPROF(5);
+    }
     }
     // slots: SPLIT 1 waves 0-3 (4-7 zero); SPLIT 2 channel half * 4 + wave
     if (!DOT) return;

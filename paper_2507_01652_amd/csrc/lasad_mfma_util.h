@@ -15,6 +15,41 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((__vector_size__(4 * sizeof(short))));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+// 16-byte global loads and stores.  NT: with the non-temporal hint, for rows that a call touches once
+// (q, k, v in, o out): they stream through the caches without displacing what is reused.
+template <bool NT>
+__device__ inline uint4 gload16(const void *p)
+{
+    if (NT) {
+        const u32x4 r = __builtin_nontemporal_load((const u32x4 *)p);
+        return make_uint4(r.x, r.y, r.z, r.w);
+    }
+    return *(const uint4 *)p;
+}
+template <bool NT>
+__device__ inline void gstore16(void *p, uint4 v)
+{
+    if (NT) {
+        const u32x4 r = {v.x, v.y, v.z, v.w};
+        __builtin_nontemporal_store(r, (u32x4 *)p);
+    } else {
+        *(uint4 *)p = v;
+    }
+}
+template <bool NT>
+__device__ inline void gstore16(float *p, float x, float y, float z, float w)
+{
+    if (NT) {
+        const f32x4v r = {x, y, z, w};
+        __builtin_nontemporal_store(r, (f32x4v *)p);
+    } else {
+        *(float4 *)p = make_float4(x, y, z, w);
+    }
+}
+
 struct Frag {              // 8 bf16 = one lane's share of a 32x16 MFMA operand
     union { bf16x8 v; uint4 u; uint2 h[2]; };
 };
