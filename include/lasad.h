@@ -283,6 +283,31 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * lasad_backward_chunked through carried states: the call covers tokens start_pos+1 .. start_pos+n_tokens of
+ * sequences whose state before the first token is state_in, and the loss may also depend on the state after
+ * the last token (the Section 3.4 recurrence differentiated with s_0 given; what one part of a sequence split
+ * over several calls, or over several GPUs, hands to its neighbours).
+ *   state_in     [B, n_heads, d, d] fp32 as in lasad_forward_chunked, or NULL (zeros).
+ *   d_state_out  [B, n_heads, d, d] fp32: dL/d(final state of the forward call), or NULL (zeros).
+ *   d_state_in   [B, n_heads, d, d] fp32, overwritten with dL/d(state_in), or NULL; must not alias the other two.
+ * dq, dk, dv then include the terms through state_in and d_state_out, and dgamma includes the dependence of
+ * the final state on the decay.  Two chained calls over a split sequence (the second call's d_state_in given
+ * to the first as d_state_out) reproduce one call over the whole up to rounding.  With n_tokens = 0 dgamma is
+ * zero and d_state_in = d_state_out.  Workspace: lasad_backward_carried_workspace_bytes(...) bytes.
+ * Everything else as in lasad_backward_chunked.
+ */
+size_t lasad_backward_carried_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype);
+int lasad_backward_chunked_carried(const void *q, const void *k, const void *v, const void *d_o,
+                                   const float *state_in, const float *d_state_out,
+                                   void *dq, void *dk, void *dv, float *dgamma, float *d_state_in,
+                                   const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                                   int io_dtype, int grad_dtype,
+                                   int B, int n_heads, int d, int grid_h, int grid_w,
+                                   int start_pos, int n_tokens,
+                                   const float *gamma, int boundary_mode, float q_scale,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Backward pass of lasad_forward_gated (vector decay, Section 3.4 / Algorithm 1) for a call that
  * starts from a zero state and whose final state is not used: given d_o = dL/do, with
  * l_t = lambda_t^spatial (1 at a row boundary) and D[i][j][c] = prod_{s=j+1..i} l_s[c],

@@ -24,6 +24,7 @@ EXPORTS = (
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
     "lasad_forward_layer", "lasad_decode_step_layer",
     "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
+    "lasad_backward_carried_workspace_bytes", "lasad_backward_chunked_carried",
     "lasad_backward_gated_workspace_bytes", "lasad_backward_gated",
     "lasad_backward_layer_workspace_bytes", "lasad_backward_layer", "lasad_backward_layer_norm",
     "lasad_last_error", "lasad_version",
@@ -87,6 +88,11 @@ def load() -> ctypes.CDLL:
     lib.lasad_backward_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                            vp, ci, cf, vp, ctypes.c_size_t, vp]
     lib.lasad_backward_chunked.restype = ci
+    lib.lasad_backward_carried_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.lasad_backward_carried_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_chunked_carried.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci,
+                                                   ci, ci, vp, ci, cf, vp, ctypes.c_size_t, vp]
+    lib.lasad_backward_chunked_carried.restype = ci
     lib.lasad_backward_gated_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.lasad_backward_gated_workspace_bytes.restype = ctypes.c_size_t
     lib.lasad_backward_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
@@ -450,6 +456,51 @@ def lasad_backward_chunked(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_
         B, Hh, d, grid_h, grid_w, start_pos, n, _ptr(gamma), boundary_mode, q_scale,
         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
     return dq, dk, dv, dgamma
+
+
+def lasad_backward_carried_workspace_bytes(B: int, n_heads: int, n_tokens: int, d: int, io_dtype: int) -> int:
+    return int(load().lasad_backward_carried_workspace_bytes(B, n_heads, n_tokens, d, io_dtype))
+
+
+def lasad_backward_chunked_carried(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
+                                   gamma: torch.Tensor, grid_h: int, grid_w: int,
+                                   state_in: torch.Tensor | None = None, d_state_out: torch.Tensor | None = None,
+                                   start_pos: int = 0, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                                   grads: tuple | None = None, grad_dtype: torch.dtype | None = None,
+                                   dgamma: torch.Tensor | None = None, d_state_in: torch.Tensor | None = None,
+                                   workspace: torch.Tensor | None = None, stream=None):
+    """lasad_backward_chunked for a call that starts from state_in and whose final state enters the loss with
+    gradient d_state_out (fp32 [B, Hh, d, d] each, or None).  Returns (dq, dk, dv, dgamma, d_state_in)."""
+    B, n, Hh, d = q.shape
+    for t in (k, v, d_o):
+        if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
+            raise ValueError("q, k, v, d_o must share shape, strides and dtype")
+    if grads is None:
+        grads = tuple(torch.empty_like(q, dtype=grad_dtype or q.dtype) for _ in range(3))
+    dq, dk, dv = grads
+    for t in (dk, dv):
+        if t.shape != q.shape or t.stride() != dq.stride() or t.dtype != dq.dtype:
+            raise ValueError("dq, dk, dv must share shape, strides and dtype")
+    for st in (state_in, d_state_out, d_state_in):
+        if st is not None and (st.dtype != torch.float32 or not st.is_contiguous() or tuple(st.shape) != (B, Hh, d, d)):
+            raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
+    if gamma.dtype != torch.float32 or gamma.numel() != Hh or not gamma.is_contiguous():
+        raise ValueError("gamma must be contiguous fp32 [Hh]")
+    if dgamma is None:
+        dgamma = torch.empty((Hh,), dtype=torch.float32, device=q.device)
+    if d_state_in is None:
+        d_state_in = torch.empty((B, Hh, d, d), dtype=torch.float32, device=q.device)
+    need = lasad_backward_carried_workspace_bytes(B, Hh, n, d, _dtype_code(q))
+    if workspace is None and need:
+        workspace = _scratch(need, q.device, stream)
+    li, lg = _layout(q), _layout(dq)
+    _check(load().lasad_backward_chunked_carried(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(state_in), _ptr(d_state_out),
+        _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgamma), _ptr(d_state_in),
+        ctypes.byref(li), ctypes.byref(lg), _dtype_code(q), _dtype_code(dq),
+        B, Hh, d, grid_h, grid_w, start_pos, n, _ptr(gamma), boundary_mode, q_scale,
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+    return dq, dk, dv, dgamma, d_state_in
 
 
 def lasad_backward_gated_workspace_bytes(B: int, n_heads: int, n_tokens: int, d: int) -> int:

@@ -346,7 +346,15 @@ size_t lasad_backward_workspace_bytes(int B, int n_heads, int n_tokens, int d, i
     return lasad::backward_workspace_bytes((int64_t)B * n_heads, n_tokens, d, force_generic() ? LASAD_F32 : io_dtype);
 }
 
-int lasad_backward_chunked(const void *q, const void *k, const void *v, const void *d_o,
+size_t lasad_backward_carried_workspace_bytes(int B, int n_heads, int n_tokens, int d, int io_dtype)
+{
+    if (B < 1 || n_heads < 1 || n_tokens < 1 || d < 1) return 0;
+    return lasad_backward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype) +
+           lasad::backward_carried_extra_bytes((int64_t)B * n_heads, d);
+}
+
+static int backward_chunked_impl(const void *q, const void *k, const void *v, const void *d_o,
+                           const float *state_in, const float *d_state_out, float *d_state_in, bool carried,
                            void *dq, void *dk, void *dv, float *dgamma,
                            const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
                            int io_dtype, int grad_dtype,
@@ -379,6 +387,12 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
     if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) ||
         !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(workspace, 256))
         return fail(LASAD_ERR_INVALID_ARG, "tensors must be 16-byte aligned, the workspace 256-byte aligned");
+    if (!aligned(state_in, 16) || !aligned(d_state_out, 16) || !aligned(d_state_in, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "the states must be 16-byte aligned");
+    if (d_state_in && (d_state_in == state_in || d_state_in == d_state_out))
+        return fail(LASAD_ERR_INVALID_ARG, "d_state_in aliases an input state");
+    if (d_state_out && !(q_scale != 0.f))
+        return fail(LASAD_ERR_UNSUPPORTED, "q_scale = 0 with a gradient of the final state");
     const void *ins[4] = {q, k, v, d_o};
     void *outs[3] = {dq, dk, dv};
     for (int i = 0; n_tokens > 0 && i < 3; ++i) {
@@ -388,12 +402,15 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
             if (outs[i] == outs[j]) return fail(LASAD_ERR_INVALID_ARG, "two gradient buffers alias");
     }
     hipStream_t s = (hipStream_t)hip_stream;
-    if (n_tokens == 0) {
+    if (n_tokens == 0) {                                  // no token: the state passes through, so does its gradient
         hipError_t e = lasad::launch_zero_f32(dgamma, n_heads, s);
+        if (e == hipSuccess && d_state_in)
+            e = lasad::launch_copy_state(d_state_out, d_state_in, (int64_t)B * n_heads * d * d, s);
         if (e != hipSuccess) return hip_fail("lasad_backward_chunked", e);
         return LASAD_OK;
     }
-    const size_t need = lasad_backward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype);
+    const size_t need = carried ? lasad_backward_carried_workspace_bytes(B, n_heads, n_tokens, d, io_dtype)
+                                : lasad_backward_workspace_bytes(B, n_heads, n_tokens, d, io_dtype);
     if (!workspace || workspace_bytes < need)
         return fail(LASAD_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
 
@@ -405,10 +422,40 @@ int lasad_backward_chunked(const void *q, const void *k, const void *v, const vo
     a.start_pos = start_pos; a.n_tokens = n_tokens;
     a.gamma = gamma; a.mode = boundary_mode; a.q_scale = q_scale;
     a.workspace = workspace; a.dq32 = a.dk32 = a.seq_sums = nullptr;
+    a.state_in = state_in; a.d_state_out = d_state_out; a.d_state_in = d_state_in;
     const bool use_mfma = io_dtype == LASAD_BF16 && d == 64 && !force_generic();
     hipError_t e = lasad::launch_backward(a, use_mfma, s);
     if (e != hipSuccess) return hip_fail("lasad_backward_chunked launch", e);
     return LASAD_OK;
+}
+
+int lasad_backward_chunked(const void *q, const void *k, const void *v, const void *d_o,
+                           void *dq, void *dk, void *dv, float *dgamma,
+                           const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                           int io_dtype, int grad_dtype,
+                           int B, int n_heads, int d, int grid_h, int grid_w,
+                           int start_pos, int n_tokens,
+                           const float *gamma, int boundary_mode, float q_scale,
+                           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return backward_chunked_impl(q, k, v, d_o, nullptr, nullptr, nullptr, false, dq, dk, dv, dgamma, in_layout, grad_layout,
+                                 io_dtype, grad_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens, gamma,
+                                 boundary_mode, q_scale, workspace, workspace_bytes, hip_stream);
+}
+
+int lasad_backward_chunked_carried(const void *q, const void *k, const void *v, const void *d_o,
+                                   const float *state_in, const float *d_state_out,
+                                   void *dq, void *dk, void *dv, float *dgamma, float *d_state_in,
+                                   const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                                   int io_dtype, int grad_dtype,
+                                   int B, int n_heads, int d, int grid_h, int grid_w,
+                                   int start_pos, int n_tokens,
+                                   const float *gamma, int boundary_mode, float q_scale,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return backward_chunked_impl(q, k, v, d_o, state_in, d_state_out, d_state_in, true, dq, dk, dv, dgamma, in_layout,
+                                 grad_layout, io_dtype, grad_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens,
+                                 gamma, boundary_mode, q_scale, workspace, workspace_bytes, hip_stream);
 }
 
 size_t lasad_backward_gated_workspace_bytes(int B, int n_heads, int n_tokens, int d)

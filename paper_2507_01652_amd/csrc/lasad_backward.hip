@@ -35,6 +35,16 @@
 // are produced in fp32 into the workspace, a finishing kernel (one workgroup per 64 tokens of a
 // sequence) forms its part of the sum above (fp32, fixed order) and stores dq, dk in the caller's
 // type and layout, and a last small kernel (one wave per head) adds the partial sums.
+//
+// Carried states.  When the call starts from a state s_0 and the loss also depends on the final state s_n
+// (H = dL/ds_n given), the three passes keep their form: the dq pass is the forward recurrence on S^T, so it
+// starts from s_0^T (and ends with s_n^T); the reversed passes run the recurrence of the state gradient
+// g_t = lambda_{t+1} g_{t+1} + q_scale q_t d_o_t^T, g_n = H + q_scale q_n d_o_n^T, so they start from H (dv pass)
+// and H^T (dk pass) with NO decay at their first step; the dv pass ends with g_1, and dL/ds_0 = lambda_1 g_1.
+// The decay gradient gains one term: L depends on the cumulative decays also through s_n, which adds
+// E_n <H, s_n> to the sum above (E_n: non-boundary tokens of the call).  A preparation kernel makes the
+// transposed copies (H divided by q_scale: the kernels multiply their outputs by it, and g_t carries it only on
+// the q d_o^T part), a finishing kernel forms dL/ds_0 and <H, s_n> per sequence.
 #include "lasad_internal.h"
 
 namespace lasad {
@@ -110,7 +120,7 @@ backward_finish_kernel(BackwardArgs a)
 // dgamma[h] = (1 / gamma[h]) * sum over the batch and the token blocks of the partial sums of head h.
 // One wave per head: lane l adds entries l, l + 64, ... in order, then a butterfly over the lanes.
 __global__ void __launch_bounds__(64)
-backward_dgamma_kernel(const float *sums, const float *gamma, float *dgamma, int B, int Hh, int nblk)
+backward_dgamma_kernel(const float *sums, const float *extra, const float *gamma, float *dgamma, int B, int Hh, int nblk)
 {
     const int h = blockIdx.x;
     float acc = 0.f;
@@ -118,6 +128,8 @@ backward_dgamma_kernel(const float *sums, const float *gamma, float *dgamma, int
         const int b = i / nblk, blk = i - b * nblk;
         acc += sums[((int64_t)b * Hh + h) * nblk + blk];
     }
+    if (extra)                                            // E_n <dL/ds_n, s_n> of every sequence of this head
+        for (int b = threadIdx.x; b < B; b += 64) acc += extra[(int64_t)b * Hh + h];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
     if (threadIdx.x == 0) dgamma[h] = acc / gamma[h];     // gamma = 0: the formula does not apply (inf or NaN)
@@ -125,7 +137,7 @@ backward_dgamma_kernel(const float *sums, const float *gamma, float *dgamma, int
 
 // The same from the sums the forward kernels left: [pass (3)][B][Hh][kDotSlots]; pass 1 (dv) has none.
 __global__ void __launch_bounds__(256)
-backward_dgamma_slots_kernel(const float *sums, const float *gamma, float *dgamma, int B, int Hh)
+backward_dgamma_slots_kernel(const float *sums, const float *extra, const float *gamma, float *dgamma, int B, int Hh)
 {
     __shared__ float red[4];
     const int h = blockIdx.x;
@@ -135,11 +147,66 @@ backward_dgamma_slots_kernel(const float *sums, const float *gamma, float *dgamm
         const int b = r / kDotSlots, slot = r - b * kDotSlots;
         acc += sums[(((int64_t)pass * B + b) * Hh + h) * kDotSlots + slot];
     }
+    if (extra)
+        for (int b = threadIdx.x; b < B; b += 256) acc += extra[(int64_t)b * Hh + h];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) dgamma[h] = ((red[0] + red[1]) + (red[2] + red[3])) / gamma[h];
+}
+
+// Per sequence: s0T = s_0^T; hS = H / q_scale and hT = H^T / q_scale (either source may be NULL).  The kernels
+// multiply every output by q_scale, the state gradient g_t = H-part + q_scale (q d_o^T)-part carries q_scale only on
+// its second part: the reversed passes therefore run on g_t / q_scale.
+__global__ void __launch_bounds__(256)
+carried_prep_kernel(const float *s0, float *s0T, const float *H, float *hS, float *hT, float inv_q_scale, int d)
+{
+    const int64_t off = (int64_t)blockIdx.x * d * d;
+    for (int e = threadIdx.x; e < d * d; e += 256) {
+        const int i = e / d, j = e - i * d;
+        if (s0) s0T[off + (int64_t)j * d + i] = s0[off + e];
+        if (H) {
+            const float x = H[off + e] * inv_q_scale;
+            hS[off + e] = x;
+            hT[off + (int64_t)j * d + i] = x;
+        }
+    }
+}
+
+// One workgroup per sequence: dL/ds_0 = lambda_1 g_1 (g_1 / q_scale: final state of the reversed dv pass) and
+// extra[bh] = E_n <H, s_n> with s_n^T the final state of the dq pass.  Fixed summation order.
+__global__ void __launch_bounds__(256)
+carried_finish_kernel(BackwardArgs a, const float *g1, const float *snT, float *extra)
+{
+    __shared__ float red[4];
+    const int bh = blockIdx.x, h = bh % a.Hh, d = a.d;
+    const int64_t off = (int64_t)bh * d * d;
+    const float lam1 = is_boundary(a.start_pos + 1, a.grid_w, a.mode) ? 1.0f : a.gamma[h];
+    float acc = 0.f;
+    for (int e = threadIdx.x; e < d * d; e += 256) {
+        if (a.d_state_in) a.d_state_in[off + e] = (lam1 * a.q_scale) * g1[off + e];
+        if (extra) {
+            const int i = e / d, j = e - i * d;
+            acc = fmaf(a.d_state_out[off + e], snT[off + (int64_t)j * d + i], acc);
+        }
+    }
+    if (!extra) return;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) acc += __shfl_xor(acc, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int en = cum_exp(a.start_pos + a.n_tokens, a.grid_w, a.mode) - cum_exp(a.start_pos, a.grid_w, a.mode);
+        extra[bh] = (float)en * ((red[0] + red[1]) + (red[2] + red[3]));
+    }
+}
+
+// dst = src (d_state_in of a call without tokens)
+__global__ void copy_f32_kernel(const float *src, float *dst, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src ? src[i] : 0.f;
 }
 
 }  // namespace
@@ -169,6 +236,19 @@ static size_t sums_bytes(int64_t n_seq, int n_tokens)
     return ((size_t)n_seq * per_seq * sizeof(float) + 255) / 256 * 256;
 }
 
+size_t backward_carried_extra_bytes(int64_t n_seq, int d)
+{
+    // s_0^T, H / q_scale, its transpose, s_n^T (dq pass), g_1 / q_scale (dv pass), one sum per sequence
+    return 5 * (size_t)n_seq * d * d * sizeof(float) + (((size_t)n_seq * sizeof(float) + 255) / 256 * 256);
+}
+
+hipError_t launch_copy_state(const float *src, float *dst, int64_t n, hipStream_t s)
+{
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, src, dst, n);
+    return hipGetLastError();
+}
+
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype)
 {
     const size_t grads = 2 * (size_t)n_seq * n_tokens * d * sizeof(float);
@@ -192,6 +272,32 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     b.seq_sums = (float *)(ws + 2 * one);
     float *fwd_ws = (float *)(ws + 2 * one + sums_bytes(n_seq, n));
     const bool has_fwd_ws = use_mfma && forward_mfma_workspace_bytes(n_seq, n) > 0;
+    // carried states: transposed copies and the passes' final states follow the forward kernels' workspace
+    const bool carried = b.state_in || b.d_state_out || b.d_state_in;
+    const size_t mat = (size_t)n_seq * b.d * b.d;
+    float *cw = (float *)((char *)fwd_ws + (use_mfma ? forward_mfma_workspace_bytes(n_seq, n) : 0));
+    float *s0T = cw, *hS = cw + mat, *hT = cw + 2 * mat, *snT = cw + 3 * mat, *g1 = cw + 4 * mat, *extra = cw + 5 * mat;
+    const float *st_in[3] = {nullptr, nullptr, nullptr};      // per pass (dq, dv, dk)
+    float *st_out[3] = {nullptr, nullptr, nullptr};
+    if (carried) {
+        if (b.state_in || b.d_state_out) {
+            hipLaunchKernelGGL(carried_prep_kernel, dim3((unsigned)n_seq), dim3(256), 0, s,
+                               b.state_in, s0T, b.d_state_out, hS, hT, 1.0f / b.q_scale, b.d);
+            hipError_t e0 = hipGetLastError();
+            if (e0 != hipSuccess) return e0;
+        }
+        st_in[0] = b.state_in ? s0T : nullptr;
+        st_out[0] = b.d_state_out ? snT : nullptr;            // s_n^T, for the decay gradient only
+        st_in[1] = b.d_state_out ? hS : nullptr;
+        st_out[1] = b.d_state_in ? g1 : nullptr;
+        st_in[2] = b.d_state_out ? hT : nullptr;
+    }
+    const float *extra_sum = (carried && b.d_state_out) ? extra : nullptr;
+    auto finish_carried = [&]() -> hipError_t {
+        if (!carried || (!b.d_state_in && !extra_sum)) return hipSuccess;
+        hipLaunchKernelGGL(carried_finish_kernel, dim3((unsigned)n_seq), dim3(256), 0, s, b, g1, snT, (float *)extra_sum);
+        return hipGetLastError();
+    };
     // The three passes are independent: one launch runs them side by side when that alone fills
     // the chip or when a pass would not be cut into segments anyway.  The passes then store dq, dv
     // and dk in the caller's type themselves and take the decay-gradient sums from their fp32
@@ -235,18 +341,25 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
         m.x[2] = last_token(b.k, b.in, n, elt); m.x_sign[2] = -1.f; m.x_rev[2] = 1;
         m.x_start_pos = b.start_pos;
         m.x_sums = b.seq_sums;
+        for (int y = 0; y < 3; ++y) {
+            m.state_in[y] = st_in[y]; m.state_out[y] = st_out[y];
+            m.first_decay_off[y] = y > 0;                 // the reversed passes take their incoming state undecayed
+        }
         f.q = m.q[0]; f.k = m.k[0]; f.v = m.v[0]; f.o = m.o[0];
         f.in = m.in[0]; f.out = m.out[0]; f.out_dtype = b.grad_dtype; f.start_pos = b.start_pos;
         f.seg_states = nullptr; f.seg_chunks = (n + 63) / 64;
         e = launch_forward_mfma_multi(f, m, s);
         if (e != hipSuccess) return e;
+        e = finish_carried();
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(backward_dgamma_slots_kernel, dim3((unsigned)b.Hh), dim3(256), 0, s,
-                           b.seq_sums, b.gamma, b.dgamma, b.B, b.Hh);
+                           b.seq_sums, extra_sum, b.gamma, b.dgamma, b.B, b.Hh);
         return hipGetLastError();
     } else {
         // dq (fp32, workspace): forward order, (q, k, v) := (d_o, v, k)
         f.q = b.d_o; f.k = b.v; f.v = b.k; f.o = b.dq32;
         f.in = b.in; f.out = wl; f.out_dtype = LASAD_F32; f.start_pos = b.start_pos;
+        f.state_in = st_in[0]; f.state_out = st_out[0]; f.first_decay_off = 0;
         e = run(f);
         if (e != hipSuccess) return e;
 
@@ -255,6 +368,7 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
         f.o = (void *)last_token(b.dv, b.grad, n, gelt);
         f.in = in_rev; f.out = grad_rev; f.out_dtype = b.grad_dtype;
         f.start_pos = rev_start;
+        f.state_in = st_in[1]; f.state_out = st_out[1]; f.first_decay_off = 1;
         e = run(f);
         if (e != hipSuccess) return e;
 
@@ -262,6 +376,7 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
         f.q = last_token(b.v, b.in, n, elt); f.k = last_token(b.d_o, b.in, n, elt); f.v = last_token(b.q, b.in, n, elt);
         f.o = (void *)last_token(b.dk32, wl, n, 4);
         f.out = wl_rev; f.out_dtype = LASAD_F32;
+        f.state_in = st_in[2]; f.state_out = st_out[2]; f.first_decay_off = 1;
         e = run(f);
         if (e != hipSuccess) return e;
     }
@@ -276,8 +391,10 @@ hipError_t launch_backward(const BackwardArgs &b_in, bool use_mfma, hipStream_t 
     else hipLaunchKernelGGL((backward_finish_kernel<0, 0>), grid, block, 0, s, b);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    e = finish_carried();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(backward_dgamma_kernel, dim3((unsigned)b.Hh), dim3(64), 0, s,
-                       b.seq_sums, b.gamma, b.dgamma, b.B, b.Hh, nblk);
+                       b.seq_sums, extra_sum, b.gamma, b.dgamma, b.B, b.Hh, nblk);
     return hipGetLastError();
 }
 

@@ -220,9 +220,10 @@ forward_mfma_kernel(ForwardArgs a)
     bool have_state = a.state_in != nullptr;
     if (have_state) {
         const float *s0 = a.state_in + (int64_t)bh * D * D;
+        const float s_in = incoming_state_scale(a, gamma);
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            accS[r] = s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
+            accS[r] = s_in * s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
     } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) accS[r] = 0.f;

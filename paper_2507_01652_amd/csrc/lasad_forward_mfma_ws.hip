@@ -53,6 +53,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         if (wg >= a.B * a.Hh) return;  // (n_segments is 1 here; the last group may be partly empty)
         a.q = m.q[pass]; a.k = m.k[pass]; a.v = m.v[pass]; a.o = m.o[pass];
         a.in = m.in[pass]; a.out = m.out[pass]; a.start_pos = m.start_pos[pass];
+        a.state_in = m.state_in[pass]; a.state_out = m.state_out[pass]; a.first_decay_off = m.first_decay_off[pass];
     }
 
     // q, k, v and o rows are touched once by a forward call: non-temporal.  The passes of a backward launch read
@@ -109,9 +110,10 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         f32x16 accS;                   // S[dk = wa*32 + 8*(r/4) + 4*g + r%4][dv = wc*32 + l32]
         if (a.state_in) {
             const float *s0 = a.state_in + (int64_t)bh * D * D;
+            const float s_in = incoming_state_scale(a, a.gamma[h]);
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                accS[r] = s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
+                accS[r] = s_in * s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
         } else {
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] = 0.f;

@@ -68,6 +68,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         const int y = blockIdx.y;
         a.q = m.q[y]; a.k = m.k[y]; a.v = m.v[y]; a.o = m.o[y];
         a.in = m.in[y]; a.out = m.out[y]; a.start_pos = m.start_pos[y];
+        a.state_in = m.state_in[y]; a.state_out = m.state_out[y]; a.first_decay_off = m.first_decay_off[y];
     }
 
     // rows touched once per call: non-temporal.  Split workgroups share Q and K through the L2 and the passes of a
@@ -217,9 +218,10 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         f32x16 accS;                   // S[dk = wa*32 + 8*(r/4) + 4*g + r%4][dv = wc*32 + l32]
         if (a.state_in) {
             const float *s0 = a.state_in + (int64_t)bh * D * D;
+            const float s_in = incoming_state_scale(a, a.gamma[h]);
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                accS[r] = s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
+                accS[r] = s_in * s0[(wa * 32 + 8 * (r / 4) + 4 * g + (r % 4)) * D + wc * 32 + l32];
         } else {
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] = 0.f;

@@ -37,6 +37,10 @@ struct ForwardArgs {
     // column passes of the layer backward only: low-order bf16 parts of the tensors in the q and v fields
     // (the operand is hi + lo; same layout), or NULL
     const void *q_lo = nullptr, *v_lo = nullptr;
+    // 1: the decay of the call's first token is NOT applied to the incoming state (the state then enters
+    // the first token's update as it is).  Used by the reversed passes of a backward call whose loss also
+    // depends on the forward's final state: its gradient joins the state gradient of the last token undecayed.
+    int first_decay_off = 0;
 };
 
 // Up to three independent forward passes in one launch of the wave-specialised kernels
@@ -61,6 +65,10 @@ struct MultiPass {
     int x_rev[3];
     int x_start_pos;             // start column of the call (not of the reversed passes)
     float *x_sums;
+    // per-pass incoming / final states ([B, Hh, d, d] fp32 or NULL) and first_decay_off, as in ForwardArgs
+    const float *state_in[3] = {nullptr, nullptr, nullptr};
+    float *state_out[3] = {nullptr, nullptr, nullptr};
+    int first_decay_off[3] = {0, 0, 0};
 };
 
 struct DecodeArgs {
@@ -98,6 +106,10 @@ struct BackwardArgs {
     void *workspace;
     // carved out of the workspace by the launcher
     float *dq32, *dk32, *seq_sums;
+    // gradients through a carried state (all [B, Hh, d, d] fp32, each may be NULL): the state before the call's
+    // first token, dL/d(final state), and the output dL/d(state_in)
+    const float *state_in = nullptr, *d_state_out = nullptr;
+    float *d_state_in = nullptr;
 };
 
 // Arguments of one decode step from a key / value cache, already validated.
@@ -180,7 +192,10 @@ hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 // use_mfma, else the generic / scan kernels) plus two small finishing kernels.
 hipError_t launch_backward(const BackwardArgs &a, bool use_mfma, hipStream_t s);
 hipError_t launch_zero_f32(float *p, int n, hipStream_t s);
+hipError_t launch_copy_state(const float *src, float *dst, int64_t n, hipStream_t s);   // dst = src (zeros if src is NULL)
 size_t backward_workspace_bytes(int64_t n_seq, int n_tokens, int d, int io_dtype);
+// extra workspace of a backward call with carried states (transposed copies, the passes' final states, one sum per sequence)
+size_t backward_carried_extra_bytes(int64_t n_seq, int d);
 
 // ---- host helpers of the backward passes ---------------------------------------
 
@@ -213,6 +228,14 @@ __host__ __device__ inline bool is_boundary(int t, int grid_w, int mode)
     if (mode == LASAD_RESET_LAST_COL) return (t % grid_w) == 0;
     if (mode == LASAD_RESET_FIRST_COL) return ((t - 1) % grid_w) == 0;
     return false;
+}
+
+// factor for an incoming state whose first decay is switched off (ForwardArgs::first_decay_off): the kernels of the
+// separable form apply the first token's decay to everything that was there before it, so the state is pre-divided
+__device__ inline float incoming_state_scale(const ForwardArgs &a, float gamma)
+{
+    if (a.first_decay_off && !is_boundary(a.start_pos + 1, a.grid_w, a.mode)) return 1.0f / gamma;
+    return 1.0f;
 }
 
 // E(t): number of non-boundary positions among 1..t (t >= 0), closed form.

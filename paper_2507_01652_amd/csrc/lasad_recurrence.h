@@ -98,7 +98,7 @@ __device__ void recurrence_sequence(const ForwardArgs &a, int bh, float *smem, H
         __syncthreads();
         for (int tt = 0; tt < nt; ++tt) {
             const int t = a.start_pos + t0 + tt + 1;   // 1-indexed raster position
-            const float lam = is_boundary(t, a.grid_w, a.mode) ? 1.0f : gamma;
+            const float lam = (is_boundary(t, a.grid_w, a.mode) || (a.first_decay_off && t0 + tt == 0)) ? 1.0f : gamma;
             const float vj = sv[tt][j];
             float part = 0.f;
 #pragma unroll

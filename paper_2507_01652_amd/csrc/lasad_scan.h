@@ -313,7 +313,8 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds, 
             const float vj = st[(PV * kT + tt) * kD + j0 + j];
             float lo;
             if (KIND == SCALAR)
-                lo = (t0 + tt >= a.n_tokens || is_boundary(a.start_pos + t0 + tt + 1, a.grid_w, a.mode)) ? 1.0f : gamma;
+                lo = (t0 + tt >= a.n_tokens || is_boundary(a.start_pos + t0 + tt + 1, a.grid_w, a.mode) ||
+                      (a.first_decay_off && t0 + tt == 0)) ? 1.0f : gamma;
             else if (KIND == ROLES_COL) lo = st[(PL * kT + tt) * kD + j0 + j];
             else lo = st[(PL * kT + tt) * kD + cop];
             float o[4];

@@ -175,3 +175,34 @@ def test_static_forward_entry_validates_like_the_workspace_entry(lib):
         ctypes.c_float(1.0), None, None, None)
     assert call(d=48) == 2 and call(B=0) == 1 and call(n=5) == 1 and call(q=None) == 1
     assert call(o=0x1000) == 1 and call(gamma=None) == 1
+
+
+def test_backward_carried_entry_validates_and_sizes_its_workspace(lib):
+    """lasad_backward_chunked_carried: the zero-state call's checks plus those of the three states (nothing is
+    launched: the pointers are fake); its workspace is the zero-state call's plus five d x d matrices and one sum
+    per sequence."""
+    lib.lasad_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_carried_workspace_bytes.restype = ctypes.c_size_t
+    base = lib.lasad_backward_workspace_bytes(2, 3, 100, 64, 1)
+    carried = lib.lasad_backward_carried_workspace_bytes(2, 3, 100, 64, 1)
+    assert 5 * 6 * 64 * 64 * 4 <= carried - base <= 5 * 6 * 64 * 64 * 4 + 512
+    assert lib.lasad_backward_carried_workspace_bytes(0, 3, 100, 64, 1) == 0
+    vp, cf = ctypes.c_void_p, ctypes.c_float
+    dense = Layout(4 * 2 * 64, 2 * 64, 64)
+
+    def call(**k):
+        a = dict(q=0x1000, s0=0x20000, h=0x30000, ds0=0x40000, dq=0x5000, io=1, gd=1, d=64, n=4, qs=1.0, ws=0x100000, ws_bytes=0)
+        a.update(k)
+        return lib.lasad_backward_chunked_carried(
+            vp(a["q"]), vp(0x2000), vp(0x3000), vp(0x4000), vp(a["s0"]), vp(a["h"]),
+            vp(a["dq"]), vp(0x6000), vp(0x7000), vp(0x8000), vp(a["ds0"]),
+            ctypes.byref(dense), ctypes.byref(dense), a["io"], a["gd"], 1, 2, a["d"], 2, 2, 0, a["n"],
+            vp(0x9000), 0, cf(a["qs"]), vp(a["ws"]), ctypes.c_size_t(a["ws_bytes"]), None)
+
+    assert call() == 3                                     # workspace too small
+    assert call(s0=None, h=None, ds0=None) == 3            # every state is optional
+    assert call(q=None) == 1 and call(d=48) == 2 and call(n=5) == 1 and call(io=0, gd=1) == 2
+    assert call(s0=0x20004) == 1 and call(h=0x30008) == 1 and call(ds0=0x4000c) == 1      # misaligned states
+    assert call(ds0=0x20000) == 1 and call(ds0=0x30000) == 1                               # d_state_in aliases an input
+    assert call(qs=0.0) == 2 and call(qs=0.0, h=None) == 3                                  # q_scale 0 needs no final-state gradient
+    assert len(lib.lasad_last_error()) > 0
