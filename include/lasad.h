@@ -30,6 +30,16 @@
  *    host before anything is launched; nothing is launched on error.  A
  *    human-readable reason is available from lasad_last_error().
  *  - gfx950 only.  There is no CPU path.
+ *
+ * Environment variables (test hooks, read once per process at the first call that needs them; none
+ * changes a result beyond rounding, each forces a kernel the launcher would otherwise pick by size):
+ *   LASAD_WS=0|8|12        scalar-decay forward, full pass: four-, eight- or twelve-wave workgroups
+ *   LASAD_SPLIT=1|2        twelve-wave kernel: whole sequences | two workgroups per sequence
+ *   LASAD_WS_MULTI=8|12    merged backward launch: eight- or twelve-wave workgroups
+ *   LASAD_GATED_WS=0|1     vector-decay forward: four- or twelve-wave workgroups
+ *   LASAD_GATED_BWD=walk   vector-decay backward: fp32 token-serial walks instead of the chunked passes
+ *   LASAD_SCAN=0           fp32 head dim 64: the generic recurrence kernel instead of the scan kernel
+ *   LASAD_FORCE_GENERIC=1  bf16 head dim 64: the fp32 kernels instead of the matrix-core kernels
  */
 #ifndef LASAD_H
 #define LASAD_H

@@ -27,13 +27,6 @@ namespace {
 using namespace gated;
 
 
-#ifdef LASAD_PROFILE
-__device__ long long g_prof_gws[24 * 64];
-#define GPROF(slot) do { if (blockIdx.x == 0 && lane == 0 && chunk < 64 && (wave & 3) == 0) \
-    g_prof_gws[chunk * 24 + 8 * (wave >> 2) + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define GPROF(slot) do { } while (0)
-#endif
 
 }  // namespace
 }  // namespace lasad
@@ -67,12 +60,6 @@ forward_gated_ws_kernel(ForwardArgs a)
 
 }  // namespace
 
-#ifdef LASAD_PROFILE
-extern "C" int lasad_debug_read_profile_gws(long long *host_out, int n)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof_gws), sizeof(long long) * n);
-}
-#endif
 
 hipError_t launch_forward_gated_ws(const ForwardArgs &a, hipStream_t s)
 {

@@ -64,24 +64,6 @@ namespace lasad {
 
 namespace {
 
-#ifdef LASAD_PROFILE
-// Development aid: cycle stamps of workgroup 0 / wave 0 at phase boundaries of each chunk.
-__device__ long long g_prof[16 * 64];
-#define PROF(slot) do { if (blockIdx.x == 0 && tid == 0 && chunk < 64) g_prof[chunk * 16 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define PROF(slot) do { } while (0)
-#endif
-
-// Schedule switches of the full-pass kernel (chosen by measurement on the large-prefill shape).
-#ifndef OPT_DIRECT_O
-#define OPT_DIRECT_O 0        // 1: store the output tile from registers; 0: through LDS, 16-byte rows
-#endif
-#ifndef OPT_EARLY_PUBLISH
-#define OPT_EARLY_PUBLISH 0   // 1: publish S^T mid-chunk into a second LDS buffer; 0: after barrier B
-#endif
-#ifndef OPT_EARLY_PREP
-#define OPT_EARLY_PREP 1      // 1: scale/split the next chunk's keys before barrier B; 0: after it
-#endif
 
 using namespace fwd;
 
@@ -154,16 +136,17 @@ segment_state_kernel(ForwardArgs a)
 //   issue the global loads of the next chunk (K, V pieces, Q fragments)
 //   scores K Q^T, Q S, state update K~^T V        (MFMA chains, operands from LDS)
 //   decay + causal mask, hi/lo split, P V          (VALU, then MFMA)
-//   scale and publish the new S^T (other LDS buffer), scale and store O straight from registers
+//   scale the state and the output tile (bf16 tile into LDS; fp32 rows straight to memory)
 //   scale/split the next chunk's keys in registers (its loads have landed by now)  | barrier B
+//   16-byte stores of the bf16 tile, bf16 hi/lo copy of the new S^T for the next chunk
 // ------------------------------------------------------------------------------------------
 template <int OUT_BF16>
 __global__ void __launch_bounds__(kThreads, 2)
 forward_mfma_kernel(ForwardArgs a)
 {
-    // LDS: K tile (16-byte reads), V and decayed-K hi/lo tiles (transpose reads), two buffers of
-    // S^T hi/lo, the table of c_j.  The fp32-recurrence fallback reuses the block.
-    constexpr int kLdsHalfs = C * RS + 3 * C * VS + (OPT_EARLY_PUBLISH ? 4 : 2) * D * RS + (OPT_DIRECT_O ? 0 : C * RS);
+    // LDS: K tile (16-byte reads), V and decayed-K hi/lo tiles (transpose reads), S^T hi/lo, the
+    // bf16 output tile, the table of c_j.  The fp32-recurrence fallback reuses the block.
+    constexpr int kLdsHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;
     __shared__ __attribute__((aligned(16))) uint16_t smem[kLdsHalfs];
     __shared__ __attribute__((aligned(16))) float tabC[C];
     static_assert(kLdsHalfs * 2 >= recurrence_lds_floats<D>() * 4, "fallback needs the LDS block");
@@ -171,10 +154,8 @@ forward_mfma_kernel(ForwardArgs a)
     uint16_t *sV = sK + C * RS;
     uint16_t *sKh = sV + C * VS;
     uint16_t *sKl = sKh + C * VS;
-    uint16_t *sS = sKl + C * VS;       // S^T [buffer][hi, lo][dv][dk]
-#if !OPT_DIRECT_O
-    uint16_t *sO = sS + (OPT_EARLY_PUBLISH ? 4 : 2) * D * RS;   // bf16 output tile [token][dv]
-#endif
+    uint16_t *sS = sKl + C * VS;       // S^T [hi, lo][dv][dk]
+    uint16_t *sO = sS + 2 * D * RS;   // bf16 output tile [token][dv]
 
     const int G = a.n_segments;
     const int bh = blockIdx.x / G, seg = blockIdx.x - bh * G;
@@ -274,33 +255,18 @@ forward_mfma_kernel(ForwardArgs a)
 #pragma unroll
         for (int s = 0; s < 4; ++s) fq[s].u = live ? fqn[s].u : make_uint4(0, 0, 0, 0);
     };
-#if OPT_EARLY_PREP
     prepare_keys(st, rk, rv, tid, min(C, n), pos, lg, sc);
     pos.advance();
     take_q(0);
-#endif
 
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
-#if OPT_EARLY_PUBLISH
-        const int cur = chunk & 1;                        // S^T buffer read by this chunk
-#else
-        const int cur = 0;
-#endif
-        const uint16_t *sSh = sS + cur * 2 * D * RS, *sSl = sSh + D * RS;
+        const uint16_t *sSh = sS, *sSl = sSh + D * RS;
 
-        PROF(0);
-#if !OPT_EARLY_PREP
-        prepare_keys(st, rk, rv, tid, nt, pos, lg, sc);
-        pos.advance();
-        take_q(chunk);
-#endif
         write_tiles<true>(sK, sV, sKh, sKl, tabC, rk, rv, st, tid);
-        PROF(1);
-        __syncthreads();                                  // (A) tiles, c_j table and S^T[cur] visible
-        PROF(2);
+        __syncthreads();                                  // (A) tiles, c_j table and S^T visible
         if (chunk + 1 < n_chunks) prefetch(chunk + 1);
 
         const int i_row = qa * 32 + l32;                  // this lane's query (column of the transposed tiles)
@@ -315,7 +281,6 @@ forward_mfma_kernel(ForwardArgs a)
             fk.u = *(const uint4 *)&sK[l32 * RS + 16 * s + 8 * g];
             acc0 = mfma(fk, fq[s], acc0);
         }
-        PROF(8);
         // ---- O^T[n][i] += sum_dk S^T[n][dk] Q[i][dk]  (independent of the scores) ----
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -325,7 +290,6 @@ forward_mfma_kernel(ForwardArgs a)
             fs.u = *(const uint4 *)&sSl[(wc * 32 + l32) * RS + 16 * s + 8 * g];
             accO = mfma(fs, fq[s], accO);
         }
-        PROF(9);
         // ---- scores of key block 1 (all masked for the lower query half) ----
         if (qa == 1) {
 #pragma unroll
@@ -335,23 +299,11 @@ forward_mfma_kernel(ForwardArgs a)
                 acc1 = mfma(fk, fq[s], acc1);
             }
         }
-        PROF(10);
         // ---- state update (independent of the scores) ----
         Frag fv[4];
         load_v_frags(fv, sV, wc, lane);
-        PROF(11);
         state_update(accS, sKh, sKl, fv, wa, lane);
-#if OPT_EARLY_PUBLISH
-        {
-            const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) accS[r] *= r_end;
-            have_state = true;
-            if (chunk + 1 < n_chunks) publish_state(cur ^ 1);   // read after the next barrier (A)
-        }
-#endif
 
-        PROF(3);
         // ---- decay + causal mask on the fp32 scores, split to bf16 hi + lo, then P V ----
         // slot e of quad qd of key block jb is key j = jb*32 + 8*qd + 4*g + e; it lands in the
         // fragment of k-step s = 2*jb + qd/2, half qd%2.
@@ -377,14 +329,12 @@ forward_mfma_kernel(ForwardArgs a)
         {
             Frag ph[2], pl[2];
             mask_split(acc0, 0, qa == 0, ph, pl);
-            PROF(12);
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 accO = mfma(fv[s], ph[s], accO);
                 accO = mfma(fv[s], pl[s], accO);
             }
         }
-        PROF(13);
         if (qa == 1) {
             Frag ph[2], pl[2];
             mask_split(acc1, 1, true, ph, pl);
@@ -395,41 +345,17 @@ forward_mfma_kernel(ForwardArgs a)
             }
         }
 
-        PROF(4);
         // ---- row factors ----
         {
             const float osc = a.q_scale * __builtin_amdgcn_rcpf(tabC[i_row]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) accO[r] *= osc;
-#if !OPT_EARLY_PUBLISH
             const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] *= r_end;
             have_state = true;
-#endif
         }
         // ---- the output tile: a lane owns four consecutive value channels of its query per quad ----
-#if OPT_DIRECT_O
-        if (i_row < nt) {
-            const int64_t off = o_base + (int64_t)(t0 + i_row) * a.out.stride_n + wc * 32 + 4 * g;
-            if (OUT_BF16) {
-                uint16_t *go = (uint16_t *)a.o + off;
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    uint2 w2;
-                    w2.x = pack2(accO[4 * qd + 0], accO[4 * qd + 1]);
-                    w2.y = pack2(accO[4 * qd + 2], accO[4 * qd + 3]);
-                    *(uint2 *)(go + 8 * qd) = w2;
-                }
-            } else {
-                float *go = (float *)a.o + off;
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd)
-                    *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
-                                                           accO[4 * qd + 2], accO[4 * qd + 3]);
-            }
-        }
-#else
         if (OUT_BF16) {                                   // via LDS for 16-byte coalesced stores
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -445,20 +371,13 @@ forward_mfma_kernel(ForwardArgs a)
                 *(float4 *)(go + 8 * qd) = make_float4(accO[4 * qd + 0], accO[4 * qd + 1],
                                                        accO[4 * qd + 2], accO[4 * qd + 3]);
         }
-#endif
-        PROF(5);
-#if OPT_EARLY_PREP
         // ---- the next chunk's keys (scaled and split) and Q fragments, in registers ----
         if (chunk + 1 < n_chunks) {
             prepare_keys(st, rk, rv, tid, min(C, n - t0 - C), pos, lg, sc);
             pos.advance();
             take_q(chunk + 1);
         }
-#endif
-        PROF(6);
-        __syncthreads();                                  // (B) all reads of the tiles and of S^T[cur] finished
-        PROF(7);
-#if !OPT_DIRECT_O
+        __syncthreads();                                  // (B) all reads of the tiles and of S^T finished
         if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
             uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
@@ -469,10 +388,7 @@ forward_mfma_kernel(ForwardArgs a)
                         *(const uint4 *)&sO[row * RS + (tid & 7) * 8];
             }
         }
-#endif
-#if !OPT_EARLY_PUBLISH
         if (chunk + 1 < n_chunks) publish_state(0);       // read after the next barrier (A)
-#endif
     }
 
     if (a.state_out && seg == G - 1) {
@@ -536,11 +452,5 @@ hipError_t launch_forward_mfma(const ForwardArgs &a_in, hipStream_t s)
     return hipGetLastError();
 }
 
-#ifdef LASAD_PROFILE
-extern "C" int lasad_debug_read_profile(long long *host_out, int n)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof), sizeof(long long) * n);
-}
-#endif
 
 }  // namespace lasad

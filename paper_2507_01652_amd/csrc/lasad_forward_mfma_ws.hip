@@ -27,15 +27,6 @@ using namespace fwd;
 
 constexpr int kWsThreads = 512;
 
-#ifdef LASAD_PROFILE
-// Development aid: cycle stamps of workgroup 0 at phase boundaries of each chunk, for output
-// wave 0 (slots 0-7), output wave 2 (8-15) and state wave 4 (slots 16-23).
-__device__ long long g_prof_ws[24 * 64];
-#define WPROF(slot) do { if (blockIdx.x == 0 && lane == 0 && chunk < 64 && (wave == 0 || wave == 2 || wave == 4)) \
-    g_prof_ws[chunk * 24 + (wave == 4 ? 16 : wave == 2 ? 8 : 0) + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define WPROF(slot) do { } while (0)
-#endif
 
 // DOT: the variant for passes of the backward that also take the decay-gradient sums (MultiPass::x)
 template <int OUT_BF16, int DOT>
@@ -152,11 +143,8 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int t0 = chunk * C;
             const int nt = min(C, n - t0);
-            WPROF(0);
             write_tiles<true>(sK, sV, sKh, sKl, tabC, rk, rv, sk, st);
-            WPROF(1);
             __syncthreads();                              // (A) tiles, c_j table and S^T visible
-            WPROF(2);
             if (chunk + 1 < n_chunks) load_kv<NT>(rk, rv, gk, gv, t0 + C, n, a.in.stride_n, st);
             Frag fv[4];
             load_v_frags(fv, sV, wc, lane);
@@ -164,16 +152,12 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             const float r_end = __builtin_amdgcn_rcpf(tabC[nt - 1]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] *= r_end;
-            WPROF(3);
             if (chunk + 1 < n_chunks) {
                 prepare_keys(sk, rk, rv, st, min(C, n - t0 - C), pos, lg, sc);
                 pos.advance();
             }
-            WPROF(4);
             __syncthreads();                              // (B) all reads of the tiles and of S^T finished
-            WPROF(5);
             if (chunk + 1 < n_chunks) publish_state();    // read after the next barrier (A)
-            WPROF(6);
         }
         if (a.state_out && seg == G - 1) {
             float *s1 = a.state_out + (int64_t)bh * D * D;
@@ -208,10 +192,8 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
         const int t0 = chunk * C;
         const int nt = min(C, n - t0);
         const int qa = wa ^ (chunk & 1);                  // query half of this wave in this chunk
-        WPROF(0);
         take_q(chunk);
         __syncthreads();                                  // (A)
-        WPROF(1);
         if (chunk + 1 < n_chunks) prefetch_q(chunk + 1);
         const int i_row = qa * 32 + l32;
 
@@ -242,7 +224,6 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
                 acc1 = mfma(fk, fq[s], acc1);
             }
         }
-        WPROF(2);
         if (DOT) gd.fetch(min(t0 + i_row, n - 1), wc * 32 + 4 * g);     // (here the Q fragments' registers are free)
         Frag fv[4];
         load_v_frags(fv, sV, wc, lane);
@@ -265,7 +246,6 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
                 accO = mfma(fv[2 + s], pl[s], accO);
             }
         }
-        WPROF(3);
         // ---- row factor r_i = 1 / c_i and the output tile ----
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(tabC[i_row]);
 #pragma unroll
@@ -285,9 +265,7 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
             for (int qd = 0; qd < 4; ++qd)
                 gstore16<NT>(go + 8 * qd, accO[4 * qd + 0], accO[4 * qd + 1], accO[4 * qd + 2], accO[4 * qd + 3]);
         }
-        WPROF(4);
         __syncthreads();                                  // (B)
-        WPROF(5);
         if (OUT_BF16) {                                   // coalesced 16-byte stores of the bf16 tile
             uint16_t *go = (uint16_t *)a.o + o_base;
 #pragma unroll
@@ -304,12 +282,6 @@ forward_mfma_ws_kernel(ForwardArgs a, MultiPass m)
 
 }  // namespace
 
-#ifdef LASAD_PROFILE
-extern "C" int lasad_debug_read_profile_ws(long long *host_out, int n)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof_ws), sizeof(long long) * n);
-}
-#endif
 
 static hipError_t launch_ws8(const ForwardArgs &a, const MultiPass &m, hipStream_t s);
 

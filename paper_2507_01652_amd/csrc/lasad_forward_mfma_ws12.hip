@@ -38,20 +38,6 @@ constexpr int PS = 36;                // row stride (floats) of an fp32 partial 
 #endif
 constexpr int kPf = LASAD_WS12_PF;    // chunks between the global loads of K / V rows and their staging
 
-#ifdef LASAD_PROFILE
-// Development aid: cycle stamps of workgroup 0, waves 0 (output), 4 (state), 8 (loader), 8 slots each.
-__device__ long long g_prof_ws12[24 * 64];
-#define WPROF(slot) do { if (blockIdx.x == 0 && lane == 0 && chunk < 64 && first_of_group) \
-    g_prof_ws12[chunk * 24 + 8 * group + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define WPROF(slot) do { } while (0)
-#endif
-#ifdef LASAD_PROFILE
-// kernel entry (slot 7 of chunk 0) and the loader waves' last store (slot 23 of chunk 0) of workgroup 0
-#define WPROF_MARK(idx) do { if (blockIdx.x == 0 && (threadIdx.x & 63) == 0) g_prof_ws12[idx] = __builtin_readcyclecounter(); } while (0)
-#else
-#define WPROF_MARK(idx) do { } while (0)
-#endif
 constexpr int kSetHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;   // one set of tiles
 
 __device__ inline int l32_of(int tid) { return tid & 31; }
@@ -93,7 +79,6 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     auto sO = [&](int p) { return smem + p * kSetHalfs + oO; };
     auto sPart = [&](int p, int part) { return (float *)(smem + p * kSetHalfs + oO) + part * C * PS; };
 
-    if (threadIdx.x == 0) WPROF_MARK(7);
     const int G = a.n_segments;
     // SPLIT 2: the two workgroups of a sequence (half = value-channel half) are 8 workgroup ids apart,
     // so they start together on the same XCD (ids go round the 8 XCDs) and what both read, Q and
@@ -123,8 +108,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     const int wc = SPLIT == 1 ? wave & 1 : half;                 // value-channel half
     const int part = wave >> 1;                                  // SPLIT 2 output waves: 0 off-diagonal, 1 diagonal
     const int srow = SPLIT == 1 ? wc * 32 + l32_of(tid) : l32_of(tid);   // this lane's row of the S^T tiles
-    const bool first_of_group = SPLIT == 1 ? (wave & 3) == 0 : (wave == 0 || wave == 4 || wave == 6);
-    (void)first_of_group; (void)part;
+    (void)part;
     const int l32 = lane & 31, g = lane >> 5;
     const int st = SPLIT == 1 ? tid & 255 : tid - 384;   // thread index inside the loader group
 
@@ -193,23 +177,18 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
                 const int chunk = c0 + u;
                 if (chunk >= n_chunks) break;
                 const int r = (u + 1) % kPf;              // register set of chunk + 1
-                WPROF(0);
                 if ((OUT_BF16 || SPLIT == 2) && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
                 if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
                     const int p = (chunk + 1) & 1;
                     prepare_keys(sk, rk[r], rv[r], st, min(C, n - (chunk + 1) * C), pos, lg, sc);
                     pos.advance();
-                    WPROF(1);
                     write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk[r], rv[r], sk, st);
                     if (chunk + 1 + kPf < n_chunks) load_kv<NT>(rk[r], rv[r], gk, gv, (chunk + 1 + kPf) * C, n, a.in.stride_n, st);
                 }
-                WPROF(2);
                 __syncthreads();
-                WPROF(3);
             }
         }
         if (OUT_BF16 || SPLIT == 2) store_tile(n_chunks - 1);
-        if (first_of_group) WPROF_MARK(23);
         return;
     }
 
@@ -255,18 +234,14 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int p = chunk & 1;
             const int nt = min(C, n - chunk * C);
-            WPROF(0);
             Frag fv[4];
             load_v_frags(fv, sV(p), wc, lane);
             state_update(accS, sKh(p), sKl(p), fv, wa, lane);
             const float r_end = __builtin_amdgcn_rcpf(tabC2[p][nt - 1]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) accS[r] *= r_end;
-            WPROF(1);
             if (chunk + 1 < n_chunks) publish_state(p ^ 1);   // the state chunk + 1 starts from
-            WPROF(2);
             __syncthreads();
-            WPROF(3);
         }
         if (a.state_out && seg == G - 1) {
             float *s1 = a.state_out + (int64_t)bh * D * D;
@@ -311,10 +286,8 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
         const uint16_t *bK = sK(p), *bV = sV(p), *bSh = sSh(p), *bSl = sSl(p);
         uint16_t *bO = sO(p);
         const float *bC = tabC2[p];
-        WPROF(0);
         take_q(fqn[p], chunk);
         if (chunk + 2 < n_chunks) prefetch_q(fqn[p], chunk + 2);
-        WPROF(1);
         const int i_row = qa * 32 + l32;
         if (DOT) gd.fetch(min(t0 + i_row, n - 1), wc * 32 + 4 * g);
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -369,22 +342,18 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
             accO = inter(accO, bSl);
             f32x16 acc1 = zero16;
             if (qa == 1) acc1 = scores(1);
-            WPROF(2);
             accO = intra(accO, acc0, 0, qa == 0);
             if (qa == 1) accO = intra(accO, acc1, 1, true);
         } else if (part == 1) {                           // diagonal block of this query half, low part of Q S
             const f32x16 accd = scores(qa);
             accO = inter(accO, bSl);
-            WPROF(2);
             accO = intra(accO, accd, qa, true);
         } else {                                          // off-diagonal block (upper query half), high part of Q S
             f32x16 acc0 = zero16;
             if (qa == 1) acc0 = scores(0);
             accO = inter(accO, bSh);
-            WPROF(2);
             if (qa == 1) accO = intra(accO, acc0, 0, false);
         }
-        WPROF(3);
         // ---- row factor r_i = 1 / c_i and the output tile ----
         const float osc = a.q_scale * __builtin_amdgcn_rcpf(bC[i_row]);
 #pragma unroll
@@ -410,9 +379,7 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
             for (int qd = 0; qd < 4; ++qd)
                 gstore16<NTO>(go + 8 * qd, accO[4 * qd + 0], accO[4 * qd + 1], accO[4 * qd + 2], accO[4 * qd + 3]);
         }
-        WPROF(4);
         __syncthreads();
-        WPROF(5);
     }
     }
     // slots: SPLIT 1 waves 0-3 (4-7 zero); SPLIT 2 channel half * 4 + wave
@@ -423,12 +390,6 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
 
 }  // namespace
 
-#ifdef LASAD_PROFILE
-extern "C" int lasad_debug_read_profile_ws12(long long *host_out, int n)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_prof_ws12), sizeof(long long) * n);
-}
-#endif
 
 hipError_t launch_ws12_passes(const ForwardArgs &a, const MultiPass &m, hipStream_t s);
 

@@ -21,10 +21,6 @@
 #include "lasad_forward_gated_common.h"
 #include "lasad_scan.h"
 
-#ifndef GPROF
-#define GPROF(slot) do { } while (0)
-#endif
-
 namespace lasad {
 namespace gated {
 
@@ -119,23 +115,17 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
         if (n_chunks > 1) stg.fetch(gq, gl, gk, gv, 1, n, a.in.stride_n, l32, pcol);
         if (barrier_flag(stg.trip)) return;           // (output waves run the fallback)
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
-            GPROF(0);
             if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
                 const int p = (chunk + 1) & 1;
                 stg.prepare_begin(a, chunk + 1, n, lane);
-                GPROF(1);
                 // the fetched registers are free again: the loads of chunk + 2 fly during the rest of this chunk
                 if (chunk + 2 < n_chunks) stg.fetch(gq, gl, gk, gv, chunk + 2, n, a.in.stride_n, l32, pcol);
-                GPROF(2);
                 stg.prepare_end(a, lane, pcol, sTot[p], sc);
-                GPROF(3);
                 stg.write(sQh(p), sQl(p), sKh(p), sKl(p), sV(p), l32, pcol);
             }
             // the output tile last: the wait for the next loads must not include these stores
             if (OUT_BF16 && chunk > NORM) store_tile(chunk - 1 - NORM);
-            GPROF(4);
             if (barrier_flag(stg.trip)) return;
-            GPROF(5);
         }
         if (OUT_BF16) {
             if (NORM) {
@@ -199,7 +189,6 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
         if (barrier_flag(false)) return;
         for (int chunk = 0; chunk < n_chunks; ++chunk) {
             const int p = chunk & 1;
-            GPROF(0);
             const uint16_t *bKh = sKh(p), *bKl = sKl(p), *bV = sV(p), *bVl = sVl(p);
             // ---- S[dk][dv] += sum_j K~[j][dk] V[j][dv], then row dk times A_end[dk] ----
             const int trow = (lane & 15) >> 2;
@@ -230,15 +219,12 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 accS[4 * qd + 0] *= t4.x; accS[4 * qd + 1] *= t4.y;
                 accS[4 * qd + 2] *= t4.z; accS[4 * qd + 3] *= t4.w;
             }
-            GPROF(1);
             if (chunk + 1 < n_chunks) {
                 publish_state(p ^ 1);                         // the state chunk + 1 starts from
                 write_v(chunk + 1);
                 if (chunk + 2 < n_chunks) load_v(chunk + 2);
             }
-            GPROF(2);
             if (barrier_flag(false)) return;
-            GPROF(3);
         }
         if (a.state_out) {
             float *s1 = a.state_out + (int64_t)bh * D * D;
@@ -372,7 +358,6 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 return acc;
             };
 
-            GPROF(0);
             const f32x16 acc0 = scores(0);
             // ---- O^T[n][i] += sum_dk S^T[n][dk] Q~[i][dk] ----
     #pragma unroll
@@ -386,7 +371,6 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
             }
             f32x16 acc1 = zero16;
             if (qa == 1) acc1 = scores(1);
-            GPROF(1);
             accO = intra(accO, acc0, 0, qa == 0);
             if (qa == 1) accO = intra(accO, acc1, 1, true);
         } else {
@@ -490,9 +474,7 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
         } else {
             put_tile(accO, chunk);
         }
-        GPROF(2);
         if (barrier_flag(false)) { fallback(); return; }
-        GPROF(3);
     }
     if (NORM) {
         finish_tile(n_chunks - 1);
