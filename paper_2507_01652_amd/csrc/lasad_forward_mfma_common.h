@@ -13,8 +13,14 @@ namespace fwd {
 constexpr int C = 64;      // chunk length (tokens)
 constexpr int D = 64;      // head dim
 constexpr int kThreads = 256;
-constexpr int RS = 72;     // LDS row stride (elements) of tiles read 16 bytes at a time: 144 B
-constexpr int VS = 80;     // LDS row stride of the V tile (transpose reads only): 160 B
+#ifndef LASAD_RS
+#define LASAD_RS 72
+#endif
+#ifndef LASAD_VS
+#define LASAD_VS 80
+#endif
+constexpr int RS = LASAD_RS;     // LDS row stride (elements) of tiles read 16 bytes at a time: 144 B
+constexpr int VS = LASAD_VS;     // LDS row stride of the V tile (transpose reads only): 160 B
 
 
 // number of boundary positions among x small offsets: floor(x / W), 0 <= x < W + 128

@@ -32,7 +32,7 @@ using namespace fwd;
 
 constexpr int kWs12Threads = 768;     // SPLIT 1: 4 output + 4 state + 4 loader waves
 constexpr int kWs10Threads = 640;     // SPLIT 2: 4 output + 2 state + 4 loader waves
-constexpr int PS = 36;                // row stride (floats) of an fp32 partial output tile [token][32 channels]
+constexpr int PS = RS / 2;            // row stride (floats) of an fp32 partial output tile [token][32 channels]
 #ifndef LASAD_WS12_PF
 #define LASAD_WS12_PF 1
 #endif
