@@ -348,6 +348,24 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * lasad_backward_gated through carried states (see lasad_backward_chunked_carried): state_in is the state
+ * before the call's first token, d_state_out = dL/d(final state), d_state_in receives dL/d(state_in) =
+ * diag(l_1) g_1; each may be NULL.  dq, dlam, dk, dv include the terms through both states; in particular
+ * the decay of the first token now has a gradient (it multiplies state_in), and every decay of the call
+ * gains the products that end in the final state.  Head dim 64.  Workspace:
+ * lasad_backward_gated_carried_workspace_bytes(...) bytes.  Everything else as in lasad_backward_gated.
+ */
+size_t lasad_backward_gated_carried_workspace_bytes(int B, int n_heads, int n_tokens, int d);
+int lasad_backward_gated_carried(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+                                 const float *state_in, const float *d_state_out,
+                                 void *dq, void *dlam, void *dk, void *dv, float *d_state_in,
+                                 const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                                 int io_dtype, int grad_dtype,
+                                 int B, int n_heads, int d, int grid_h, int grid_w,
+                                 int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Backward pass of lasad_forward_layer (Algorithm 1 between its two Linear maps; Norm as read
  * there: root mean square over the d channels of a head, times norm_weight) for a call that starts
  * from a zero state and whose final state is not used.  Given d_out = dL/d(layer output), the chain

@@ -26,6 +26,7 @@ EXPORTS = (
     "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_backward_carried_workspace_bytes", "lasad_backward_chunked_carried",
     "lasad_backward_gated_workspace_bytes", "lasad_backward_gated",
+    "lasad_backward_gated_carried_workspace_bytes", "lasad_backward_gated_carried",
     "lasad_backward_layer_workspace_bytes", "lasad_backward_layer", "lasad_backward_layer_norm",
     "lasad_last_error", "lasad_version",
 )
@@ -98,6 +99,11 @@ def load() -> ctypes.CDLL:
     lib.lasad_backward_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                          ctypes.c_float, vp, ctypes.c_size_t, vp]
     lib.lasad_backward_gated.restype = ci
+    lib.lasad_backward_gated_carried_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.lasad_backward_gated_carried_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_gated_carried.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci,
+                                                 ci, ci, ci, ci, ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.lasad_backward_gated_carried.restype = ci
     lib.lasad_backward_layer_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, lp]
     lib.lasad_backward_layer_workspace_bytes.restype = ctypes.c_size_t
     lib.lasad_backward_layer.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci,
@@ -148,6 +154,8 @@ def _scratch(nbytes: int, device, stream) -> torch.Tensor:
 
 def _layout(t: torch.Tensor) -> Layout:
     """Strides of a logical [B, n, Hh, d] tensor (any permutation with unit d stride)."""
+    if t.dim() == 4 and t.numel() == 0:          # no element is addressed: dense strides stand in for whatever torch reports
+        return Layout(t.shape[1] * t.shape[2] * t.shape[3], t.shape[2] * t.shape[3], t.shape[3])
     if t.dim() != 4 or (t.shape[3] > 1 and t.stride(3) != 1):
         raise ValueError("expected a [B, n_tokens, Hh, d] tensor with unit stride along d")
     return Layout(t.stride(0), t.stride(1), t.stride(2))
@@ -539,6 +547,50 @@ def lasad_backward_gated(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, d_
         B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale,
         _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
     return (dq, dlam, dv) if k is None else (dq, dlam, dv, dk)
+
+
+def lasad_backward_gated_carried_workspace_bytes(B: int, n_heads: int, n_tokens: int, d: int) -> int:
+    return int(load().lasad_backward_gated_carried_workspace_bytes(B, n_heads, n_tokens, d))
+
+
+def lasad_backward_gated_carried(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
+                                 grid_h: int, grid_w: int, k: torch.Tensor | None = None,
+                                 state_in: torch.Tensor | None = None, d_state_out: torch.Tensor | None = None,
+                                 start_pos: int = 0, boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                                 grads: tuple | None = None, grad_dtype: torch.dtype | None = None,
+                                 d_state_in: torch.Tensor | None = None,
+                                 workspace: torch.Tensor | None = None, stream=None):
+    """lasad_backward_gated for a call that starts from state_in and whose final state enters the loss with gradient
+    d_state_out (fp32 [B, Hh, d, d] each, or None).  Returns (dq, dlam, dv[, dk], d_state_in)."""
+    B, n, Hh, d = q.shape
+    for t in (lam, v, d_o) + (() if k is None else (k,)):
+        if t.shape != q.shape or t.stride() != q.stride() or t.dtype != q.dtype:
+            raise ValueError("q, lam, k, v, d_o must share shape, strides and dtype")
+    if grads is None:
+        grads = tuple(torch.empty_like(q, dtype=grad_dtype or q.dtype) for _ in range(3 if k is None else 4))
+    if len(grads) != (3 if k is None else 4):
+        raise ValueError("grads must hold dq, dlam, dv (and dk with an own key)")
+    dq, dlam, dv = grads[:3]
+    dk = None if k is None else grads[3]
+    for t in grads:
+        if t.shape != q.shape or t.stride() != dq.stride() or t.dtype != dq.dtype:
+            raise ValueError("gradient tensors must share q's shape and one set of strides and dtype")
+    for st in (state_in, d_state_out, d_state_in):
+        if st is not None and (st.dtype != torch.float32 or not st.is_contiguous() or tuple(st.shape) != (B, Hh, d, d)):
+            raise ValueError("states must be contiguous fp32 [B, Hh, d, d]")
+    if d_state_in is None:
+        d_state_in = torch.empty((B, Hh, d, d), dtype=torch.float32, device=q.device)
+    need = lasad_backward_gated_carried_workspace_bytes(B, Hh, n, d)
+    if workspace is None and need:
+        workspace = _scratch(need, q.device, stream)
+    li, lg = _layout(q), _layout(dq)
+    _check(load().lasad_backward_gated_carried(
+        _ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(d_o), _ptr(state_in), _ptr(d_state_out),
+        _ptr(dq), _ptr(dlam), _ptr(dk), _ptr(dv), _ptr(d_state_in),
+        ctypes.byref(li), ctypes.byref(lg), _dtype_code(q), _dtype_code(dq),
+        B, Hh, d, grid_h, grid_w, start_pos, n, boundary_mode, q_scale,
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)))
+    return ((dq, dlam, dv) if k is None else (dq, dlam, dv, dk)) + (d_state_in,)
 
 
 def lasad_backward_layer_workspace_bytes(q_pre: torch.Tensor) -> int:

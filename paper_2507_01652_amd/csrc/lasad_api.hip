@@ -464,7 +464,15 @@ size_t lasad_backward_gated_workspace_bytes(int B, int n_heads, int n_tokens, in
     return lasad::backward_gated_workspace_bytes((int64_t)B * n_heads, n_tokens, d);
 }
 
-int lasad_backward_gated(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+size_t lasad_backward_gated_carried_workspace_bytes(int B, int n_heads, int n_tokens, int d)
+{
+    if (B < 1 || n_heads < 1 || n_tokens < 1 || d < 1) return 0;
+    return lasad_backward_gated_workspace_bytes(B, n_heads, n_tokens, d) +
+           lasad::backward_gated_carried_extra_bytes((int64_t)B * n_heads, d);
+}
+
+static int backward_gated_impl(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+                         const float *state_in, const float *d_state_out, float *d_state_in, bool carried,
                          void *dq, void *dlam, void *dk, void *dv,
                          const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
                          int io_dtype, int grad_dtype,
@@ -496,6 +504,12 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
     if (!aligned(q, 16) || !aligned(lam, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(d_o, 16) ||
         !aligned(dq, 16) || !aligned(dlam, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(workspace, 256))
         return fail(LASAD_ERR_INVALID_ARG, "tensors must be 16-byte aligned, the workspace 256-byte aligned");
+    if (!aligned(state_in, 16) || !aligned(d_state_out, 16) || !aligned(d_state_in, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "the states must be 16-byte aligned");
+    if (d_state_in && (d_state_in == state_in || d_state_in == d_state_out))
+        return fail(LASAD_ERR_INVALID_ARG, "d_state_in aliases an input state");
+    if (d_state_out && !(q_scale != 0.f))
+        return fail(LASAD_ERR_UNSUPPORTED, "q_scale = 0 with a gradient of the final state");
     const void *ins[5] = {q, lam, k, v, d_o};
     void *outs[4] = {dq, dlam, dk, dv};
     for (int i = 0; n_tokens > 0 && i < 4; ++i) {
@@ -505,8 +519,15 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
         for (int j = i + 1; j < 4; ++j)
             if (outs[i] == outs[j]) return fail(LASAD_ERR_INVALID_ARG, "two gradient buffers alias");
     }
-    if (n_tokens == 0) return LASAD_OK;
-    const size_t need = lasad_backward_gated_workspace_bytes(B, n_heads, n_tokens, d);
+    if (n_tokens == 0) {                                  // no token: the state passes through, so does its gradient
+        if (d_state_in) {
+            hipError_t e0 = lasad::launch_copy_state(d_state_out, d_state_in, (int64_t)B * n_heads * d * d, (hipStream_t)hip_stream);
+            if (e0 != hipSuccess) return hip_fail("lasad_backward_gated", e0);
+        }
+        return LASAD_OK;
+    }
+    const size_t need = carried ? lasad_backward_gated_carried_workspace_bytes(B, n_heads, n_tokens, d)
+                                : lasad_backward_gated_workspace_bytes(B, n_heads, n_tokens, d);
     if (!workspace || workspace_bytes < need)
         return fail(LASAD_ERR_WORKSPACE, "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
 
@@ -520,9 +541,37 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
     a.mode = boundary_mode; a.q_scale = q_scale;
     a.workspace = workspace;
     a.fused_act = 0; a.d_o_lo = nullptr;
+    a.state_in = state_in; a.d_state_out = d_state_out; a.d_state_in = d_state_in;
     hipError_t e = lasad::launch_backward_gated(a, (hipStream_t)hip_stream);
     if (e != hipSuccess) return hip_fail("lasad_backward_gated launch", e);
     return LASAD_OK;
+}
+
+int lasad_backward_gated(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+                         void *dq, void *dlam, void *dk, void *dv,
+                         const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                         int io_dtype, int grad_dtype,
+                         int B, int n_heads, int d, int grid_h, int grid_w,
+                         int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return backward_gated_impl(q, lam, k, v, d_o, nullptr, nullptr, nullptr, false, dq, dlam, dk, dv, in_layout, grad_layout,
+                               io_dtype, grad_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens, boundary_mode,
+                               q_scale, workspace, workspace_bytes, hip_stream);
+}
+
+int lasad_backward_gated_carried(const void *q, const void *lam, const void *k, const void *v, const void *d_o,
+                                 const float *state_in, const float *d_state_out,
+                                 void *dq, void *dlam, void *dk, void *dv, float *d_state_in,
+                                 const lasad_layout_t *in_layout, const lasad_layout_t *grad_layout,
+                                 int io_dtype, int grad_dtype,
+                                 int B, int n_heads, int d, int grid_h, int grid_w,
+                                 int start_pos, int n_tokens, int boundary_mode, float q_scale,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return backward_gated_impl(q, lam, k, v, d_o, state_in, d_state_out, d_state_in, true, dq, dlam, dk, dv, in_layout,
+                               grad_layout, io_dtype, grad_dtype, B, n_heads, d, grid_h, grid_w, start_pos, n_tokens,
+                               boundary_mode, q_scale, workspace, workspace_bytes, hip_stream);
 }
 
 static bool bad_strides(const lasad_layout_t *l, int vec)

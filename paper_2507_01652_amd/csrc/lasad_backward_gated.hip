@@ -52,6 +52,8 @@ struct WalkArgs {
     void *o[3];
     lasad_layout_t in[3], out[3];
     int start_pos[3];
+    const float *state_in[3];      // per pass, [B, Hh, d, d] in the layout [decayed channel][other index], or NULL
+    float *state_out[3];
 };
 
 template <int IN_BF16, int OUT_BF16, int NJ>
@@ -64,6 +66,7 @@ backward_gated_walk_kernel(WalkArgs w)
     const int bh = blockIdx.x / JS, j0 = (blockIdx.x - bh * JS) * NJ;
     ForwardArgs a = w.common;
     a.o = w.o[pass]; a.in = w.in[pass]; a.out = w.out[pass]; a.start_pos = w.start_pos[pass];
+    a.state_in = w.state_in[pass]; a.state_out = w.state_out[pass];
     if (pass == 1) scan_sequence<IN_BF16, OUT_BF16, ROLES_ROW, NJ>(a, bh, j0, lds, &w.roles[1]);
     else scan_sequence<IN_BF16, 0, ROLES_COL, NJ>(a, bh, j0, lds, &w.roles[pass]);     // fp32 into the workspace
 }
@@ -85,8 +88,10 @@ constexpr int kFinBlock = 64;          // tokens per step of the finishing kerne
 template <int IN_BF16, int OUT_BF16, int TOTALS, int CH>
 __global__ void __launch_bounds__(16 * CH)
 backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float *dk32,
-                             float *seg_totals, int n_seg, int seg_blocks)
+                             float *seg_totals, int n_seg, int seg_blocks, const float *sink)
 {
+    // sink [sequence][d] (or NULL): per key channel, sum_n H[c][n] s_n[c][n] for H = dL/d(final state): the products of
+    // decays that end in the final state pass through EVERY step of the call, so every suffix sum starts from it
     constexpr int LPR = CH / 4;            // threads per token
     __shared__ __attribute__((aligned(16))) float sR[kFinBlock][CH + 4];
     __shared__ __attribute__((aligned(16))) float sQtr[4][CH];
@@ -162,7 +167,7 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         return;
     }
     if (tid < CH) {
-        float carry = 0.f;
+        float carry = sink ? sink[(int64_t)bh * kD + ch0 + tid] : 0.f;
         for (int s2 = n_seg - 1; s2 > seg; --s2) carry += totals[s2 * kD + tid];
         sCarry[tid] = carry;
     }
@@ -191,7 +196,8 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         {
             f4 suffix = *(const f4 *)&sR[row][c4l] + *(const f4 *)&sCarry[c4l];
             for (int q2 = 3; q2 > (row >> 4); --q2) suffix += *(const f4 *)&sQtr[q2][c4l];
-            const bool no_decay = t == 0 || is_boundary(a.start_pos + t + 1, a.grid_w, a.mode);
+            // (from a zero state the first token's decay multiplies nothing)
+            const bool no_decay = (t == 0 && !a.state_in) || is_boundary(a.start_pos + t + 1, a.grid_w, a.mode);
             f4 dl = suffix / cur.lam;
             if (no_decay) dl = f4{0.f, 0.f, 0.f, 0.f};
             if (!a.k) dl -= cur.dk;
@@ -212,6 +218,42 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
     }
 }
 
+// hS = H / q_scale for the reversed passes (the kernels multiply their outputs by q_scale; the state gradient carries it
+// only on its q d_o^T part).
+__global__ void __launch_bounds__(256)
+gated_carried_prep_kernel(const float *H, float *hS, float inv_q_scale, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) hS[i] = H[i] * inv_q_scale;
+}
+
+// One workgroup per sequence: dL/ds_0 = diag(l_1) g_1 (g_1 / q_scale: final state of the reversed dv pass; l_1: the decay
+// applied at the call's first token) and sink[bh][c] = sum_n H[c][n] s_n[c][n] (s_n: final state of the dq pass).
+template <int IN_BF16>
+__global__ void __launch_bounds__(256)
+gated_carried_finish_kernel(GatedBackwardArgs a, const float *g1, const float *sn, float *sink)
+{
+    const int bh = blockIdx.x, b = bh / a.Hh, h = bh - b * a.Hh;
+    const int64_t off = (int64_t)bh * kD * kD;
+    const int c = threadIdx.x >> 2, part = threadIdx.x & 3;          // four threads per key channel, 16 columns each
+    float l1 = 1.0f;
+    if (!is_boundary(a.start_pos + 1, a.grid_w, a.mode)) {
+        const int64_t i = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + c;
+        l1 = IN_BF16 ? bf16_bits_to_float(((const uint16_t *)a.lam)[i]) : ((const float *)a.lam)[i];
+        if (a.fused_act) l1 = sigmoid_f32(l1);
+    }
+    float acc = 0.f;
+    for (int n = part * 16; n < part * 16 + 16; ++n) {
+        if (a.d_state_in) a.d_state_in[off + c * kD + n] = (l1 * a.q_scale) * g1[off + c * kD + n];
+        if (sink) acc = fmaf(a.d_state_out[off + c * kD + n], sn[off + c * kD + n], acc);
+    }
+    if (sink) {
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        if (part == 0) sink[(int64_t)bh * kD + c] = acc;
+    }
+}
+
 template <int IN_BF16, int OUT_BF16>
 void launch_walks(const WalkArgs &w, int64_t n_seq, hipStream_t s)
 {
@@ -223,6 +265,12 @@ void launch_walks(const WalkArgs &w, int64_t n_seq, hipStream_t s)
 }
 
 }  // namespace
+
+size_t backward_gated_carried_extra_bytes(int64_t n_seq, int d)
+{
+    // H / q_scale, s_n (dq pass), g_1 / q_scale (dv pass), one sum per sequence and key channel
+    return 3 * (size_t)n_seq * d * d * sizeof(float) + (size_t)n_seq * d * sizeof(float);
+}
 
 size_t backward_gated_workspace_bytes(int64_t n_seq, int n_tokens, int d)
 {
@@ -250,7 +298,25 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     const void *k_l = last_token(b.k, b.in, n, elt), *v_l = last_token(b.v, b.in, n, elt);
     const void *g_l = last_token(b.d_o, b.in, n, elt);
 
+    // carried states: the dq pass runs the forward recurrence itself (state [dk][dv], starts from state_in, ends with
+    // s_n); the reversed passes run the recurrence of the state gradient from H / q_scale (no decay at their first
+    // step: the shifted decay of step 0 is neutral); the dv pass ends with g_1 / q_scale
+    const bool carried = b.state_in || b.d_state_out || b.d_state_in;
+    const size_t mat = (size_t)n_seq * b.d * b.d;
+    float *cw = dk32 + (size_t)n_seq * n * b.d + (size_t)n_seq * 8 * b.d;      // after the gradients and the segment totals
+    float *hS = cw, *sn = cw + mat, *g1 = cw + 2 * mat, *sink_buf = cw + 3 * mat;
+    const float *sink = (carried && b.d_state_out) ? sink_buf : nullptr;
+    if (carried && b.d_state_out) {
+        hipLaunchKernelGGL(gated_carried_prep_kernel, dim3((unsigned)((mat + 255) / 256)), dim3(256), 0, s,
+                           b.d_state_out, hS, 1.0f / b.q_scale, (int64_t)mat);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
+    const float *st_in[3] = {b.state_in, b.d_state_out ? hS : nullptr, b.d_state_out ? hS : nullptr};
+    float *st_out[3] = {b.d_state_out ? sn : nullptr, b.d_state_in ? g1 : nullptr, nullptr};
+
     WalkArgs w;
+    for (int y = 0; y < 3; ++y) { w.state_in[y] = st_in[y]; w.state_out[y] = st_out[y]; }
     ForwardArgs &f = w.common;
     f.q = f.k = f.v = f.lam = nullptr; f.o = nullptr;
     if (b.fused_act && b.k) return hipErrorInvalidValue;
@@ -291,6 +357,7 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
         p[2] = p[1];
         p[2].q = v_l; p[2].o = w.o[2]; p[2].out = wl_rev; p[2].out_dtype = LASAD_F32;                  // dk
         p[2].v_lo = gl_l;
+        for (int y = 0; y < 3; ++y) { p[y].state_in = st_in[y]; p[y].state_out = st_out[y]; }
         e = launch_backward_gated_passes(p, w.roles, b.k == nullptr, s);
         if (e != hipSuccess) return e;
     } else {
@@ -302,6 +369,12 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
         if (e != hipSuccess) return e;
     }
 
+    if (carried && (b.d_state_in || sink)) {
+        if (in16) hipLaunchKernelGGL((gated_carried_finish_kernel<1>), dim3((unsigned)n_seq), dim3(256), 0, s, b, g1, sn, (float *)sink);
+        else hipLaunchKernelGGL((gated_carried_finish_kernel<0>), dim3((unsigned)n_seq), dim3(256), 0, s, b, g1, sn, (float *)sink);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     // finishing kernel: one workgroup per sequence, or several segments per sequence when there are
     // few long ones (then a first launch for the segment totals)
     const int nblk = (n + kFinBlock - 1) / kFinBlock;
@@ -319,8 +392,8 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     const bool narrow = n_seq * n_seg < 256;      // (at 480 workgroups the narrow rows already cost more than they gain)
     const dim3 grid((unsigned)n_seq, (unsigned)n_seg, narrow ? 4 : 1), block(narrow ? 256 : 1024);
 #define LASAD_FIN_LAUNCH(I, O, T) do { \
-        if (narrow) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 16>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks); \
-        else hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 64>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks); \
+        if (narrow) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 16>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks, sink); \
+        else hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 64>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks, sink); \
     } while (0)
     if (n_seg > 1) {
         if (in16) LASAD_FIN_LAUNCH(1, 0, 1); else LASAD_FIN_LAUNCH(0, 0, 1);

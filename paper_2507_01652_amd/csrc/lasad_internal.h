@@ -142,6 +142,10 @@ struct GatedBackwardArgs {
     const void *d_o_lo;                  // fused_act with bf16 inputs: low-order bf16 part of d_o (d_o is hi + lo), else NULL
     int fused_act;                       // 1: q and lam hold Algorithm 1's pre-activation query and gate logits
                                          // (tied key only); dq and dlam are then the gradients of THOSE tensors
+    // gradients through a carried state ([B, Hh, d, d] fp32, each may be NULL): the state before the call's first
+    // token, dL/d(final state), and the output dL/d(state_in)
+    const float *state_in = nullptr, *d_state_out = nullptr;
+    float *d_state_in = nullptr;
 };
 hipError_t launch_backward_gated(const GatedBackwardArgs &a, hipStream_t s);
 
@@ -167,6 +171,8 @@ struct LayerBackwardArgs {
 hipError_t launch_backward_layer(const LayerBackwardArgs &a, bool use_mfma, hipStream_t s);
 size_t backward_layer_workspace_bytes(int B, int Hh, int n_tokens, int d, int io_dtype, const lasad_layout_t &in);
 size_t backward_gated_workspace_bytes(int64_t n_seq, int n_tokens, int d);
+// extra workspace of lasad_backward_gated with carried states
+size_t backward_gated_carried_extra_bytes(int64_t n_seq, int d);
 
 hipError_t launch_decay_factors(const float *gamma, int Hh, int grid_w, int start_pos, int n,
                                 int mode, float *lambda_out, int32_t *cum_out, hipStream_t s);

@@ -266,11 +266,21 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds, 
     const int cop = cg * R + (tid % 16) % R;      // key channel whose operands this lane carries
     const float gamma = KIND == SCALAR ? a.gamma[h] : 1.0f;
 
+    // The walk's state is [update row operand][update column operand].  A column-decay walk (ROLES_COL) is the
+    // transposed form of a pass whose state is [decayed channel][other index]: in memory its incoming and final
+    // states keep THAT layout (the one of the chunked column pass it stands in for), so they are read and
+    // written transposed here.
     float S[R];
     if (a.state_in) {
-        const float *s0 = a.state_in + (int64_t)bh * kD * kD + j0 + j;
+        if (KIND == ROLES_COL) {
+            const float *s0 = a.state_in + (int64_t)bh * kD * kD + (int64_t)(j0 + j) * kD;
 #pragma unroll
-        for (int r = 0; r < R; ++r) S[r] = s0[(cg * R + r) * kD];
+            for (int r = 0; r < R; ++r) S[r] = s0[cg * R + r];
+        } else {
+            const float *s0 = a.state_in + (int64_t)bh * kD * kD + j0 + j;
+#pragma unroll
+            for (int r = 0; r < R; ++r) S[r] = s0[(cg * R + r) * kD];
+        }
     } else {
 #pragma unroll
         for (int r = 0; r < R; ++r) S[r] = 0.f;
@@ -358,9 +368,15 @@ __device__ void scan_sequence(const ForwardArgs &a, int bh, int j0, float *lds, 
     }
 
     if (a.state_out) {
-        float *s1 = a.state_out + (int64_t)bh * kD * kD + j0 + j;
+        if (KIND == ROLES_COL) {
+            float *s1 = a.state_out + (int64_t)bh * kD * kD + (int64_t)(j0 + j) * kD;
 #pragma unroll
-        for (int r = 0; r < R; ++r) s1[(cg * R + r) * kD] = S[r];
+            for (int r = 0; r < R; ++r) s1[cg * R + r] = S[r];
+        } else {
+            float *s1 = a.state_out + (int64_t)bh * kD * kD + j0 + j;
+#pragma unroll
+            for (int r = 0; r < R; ++r) s1[(cg * R + r) * kD] = S[r];
+        }
     }
 }
 

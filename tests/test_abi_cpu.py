@@ -206,3 +206,25 @@ def test_backward_carried_entry_validates_and_sizes_its_workspace(lib):
     assert call(ds0=0x20000) == 1 and call(ds0=0x30000) == 1                               # d_state_in aliases an input
     assert call(qs=0.0) == 2 and call(qs=0.0, h=None) == 3                                  # q_scale 0 needs no final-state gradient
     assert len(lib.lasad_last_error()) > 0
+
+
+def test_backward_gated_carried_entry_validates_and_sizes_its_workspace(lib):
+    lib.lasad_backward_gated_workspace_bytes.restype = ctypes.c_size_t
+    lib.lasad_backward_gated_carried_workspace_bytes.restype = ctypes.c_size_t
+    extra = lib.lasad_backward_gated_carried_workspace_bytes(2, 3, 100, 64) - lib.lasad_backward_gated_workspace_bytes(2, 3, 100, 64)
+    assert extra == 3 * 6 * 64 * 64 * 4 + 6 * 64 * 4
+    vp, cf = ctypes.c_void_p, ctypes.c_float
+    dense = Layout(4 * 2 * 64, 2 * 64, 64)
+
+    def call(**k):
+        a = dict(q=0x1000, s0=0x20000, h=0x30000, ds0=0x40000, d=64, n=4, qs=1.0, kk=None, dk=None)
+        a.update(k)
+        return lib.lasad_backward_gated_carried(
+            vp(a["q"]), vp(0x2000), vp(a["kk"]), vp(0x3000), vp(0x4000), vp(a["s0"]), vp(a["h"]),
+            vp(0x5000), vp(0x6000), vp(a["dk"]), vp(0x7000), vp(a["ds0"]),
+            ctypes.byref(dense), ctypes.byref(dense), 1, 1, 1, 2, a["d"], 2, 2, 0, a["n"], 0, cf(a["qs"]),
+            vp(0x100000), ctypes.c_size_t(0), None)
+
+    assert call() == 3 and call(s0=None, h=None, ds0=None) == 3
+    assert call(q=None) == 1 and call(d=32) == 2 and call(n=5) == 1 and call(kk=0x8000) == 1     # dk must come with k
+    assert call(s0=0x20004) == 1 and call(ds0=0x30000) == 1 and call(qs=0.0) == 2
