@@ -500,6 +500,34 @@ def bench_gated(args, timer, torch, lasad, wl):
             "workload": wd.name + " (q, gate, v; k = 1 - gate)", "value": 1.0 / dur_s, "unit": "steps/s",
             "ms_per_step": d_ms, "steps_timed": n_steps, "eager_ms_per_step": d_eager,
             "roofline": hbm_roofline("lasad_decode_step_gated", bytes_dec, dur_s, measured_traffic("gated_decode", wd.name))}
+        # the first positions from gate / value caches (tied key: two rows per cached token, as for the scalar decay)
+        switch = min(2 * wd.d, wd.steps)
+        cap = switch + 8                   # (not a power-of-two distance between the sequences' caches: see bench_decode)
+        lcs = [torch.zeros((wd.B, wd.Hh, cap, wd.d), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+        vcs = [torch.zeros_like(lcs[0]) for _ in range(L)]
+        fwd_out = torch.empty((wd.B, switch, wd.Hh, wd.d), dtype=torch.bfloat16, device="cuda")
+        as_seq = lambda c: c.permute(0, 2, 1, 3)
+
+        def dhybrid(nsteps, first=0):
+            for i in range(first, first + nsteps):
+                t, l = i % wd.steps, i % L
+                if t < switch:
+                    lasad.lasad_decode_step_gated_cached(tq[t], tl[t], tv[t], lcs[l], vcs[l], wd.grid_h, wd.grid_w, t, out=outs[l])
+                else:
+                    if t == switch:
+                        # (only state_out is wanted: the query operand is a stand-in with the caches' layout)
+                        lasad.lasad_forward_gated(as_seq(lcs[l][:, :, :switch]), as_seq(lcs[l][:, :, :switch]),
+                                                  as_seq(vcs[l][:, :, :switch]), wd.grid_h, wd.grid_w,
+                                                  state_out=states[l], out=fwd_out)
+                    lasad.lasad_decode_step_gated(tq[t], tl[t], tv[t], states[l], wd.grid_h, wd.grid_w, t, out=outs[l])
+
+        h_ms, _, _ = timer.steps(dhybrid, n_steps, wd.steps)
+        res["decode"]["cache_then_state"] = {
+            "what": f"positions 0..{switch - 1} from gate / value caches (lasad_decode_step_gated_cached), the state built from "
+                    "the caches by one lasad_forward_gated call per walk, lasad_decode_step_gated afterwards",
+            "ms_per_step": h_ms, "value": 1.0 / (h_ms * 1e-3), "unit": "steps/s",
+            "speedup_vs_state_form": d_ms / h_ms}
+        del lcs, vcs, fwd_out
     return res
 
 

@@ -189,6 +189,26 @@ int lasad_decode_step_cached(const void *q, const void *k, const void *v, void *
                              void *hip_stream);
 
 /*
+ * lasad_decode_step_cached for the vector decay (Section 3.4 as written; Algorithm 1): the recurrence of
+ * lasad_decode_step_gated unrolled from a zero state at position 0,
+ *     o = q_scale sum_{j<=pos} [ sum_c q[c] (l_{j+1}[c] .. l_pos[c]) k_j[c] ] v_j,   l_s = 1 at a boundary position,
+ * from caches of the gate rows and of v (and of k with an own key).  With the tied key (k, k_cache NULL:
+ * k_j = 1 - lambda_j from the cached base gate) a cached token is two rows, as for the scalar decay, so the
+ * form moves fewer bytes than the state for the same first positions.  This step's rows are appended (row pos).
+ *   q, lam, k, v                 [B, n_heads, d] contiguous, io_dtype; o same shape, out_dtype.
+ *   lam_cache, k_cache, v_cache  [B, n_heads, cache_tokens, d] contiguous, io_dtype, owned by the caller; rows
+ *                                0 .. pos-1 must hold the earlier steps' rows; pos < cache_tokens.
+ *   d                            32, 64 or 128.
+ * To continue with lasad_decode_step_gated, build the state once with lasad_forward_gated over the cached rows
+ * (state_out).
+ */
+int lasad_decode_step_gated_cached(const void *q, const void *lam, const void *k, const void *v, void *o,
+                                   void *lam_cache, void *k_cache, void *v_cache, int cache_tokens,
+                                   int io_dtype, int out_dtype, int B, int n_heads, int d,
+                                   int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                                   void *hip_stream);
+
+/*
  * Vector, data-dependent decay: the recurrence exactly as Section 3.4 / Algorithm 1 write it.
  * Every token carries a decay vector lambda_t in [0, 1]^d over the key channels,
  *     s_t = diag(lambda_t^spatial) s_{t-1} + k_t v_t^T,   o_t^T = q_scale * q_t^T s_t,

@@ -23,7 +23,8 @@ EXPORTS = (
     "lasad_forward_static_scratch_bytes", "lasad_forward_chunked_static",
     "lasad_decode_step", "lasad_forward_gated", "lasad_decode_step_gated",
     "lasad_forward_layer", "lasad_decode_step_layer",
-    "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_backward_workspace_bytes", "lasad_backward_chunked",
+    "lasad_decode_step_rows", "lasad_decode_step_cached", "lasad_decode_step_gated_cached",
+    "lasad_backward_workspace_bytes", "lasad_backward_chunked",
     "lasad_backward_carried_workspace_bytes", "lasad_backward_chunked_carried",
     "lasad_backward_gated_workspace_bytes", "lasad_backward_gated",
     "lasad_backward_gated_carried_workspace_bytes", "lasad_backward_gated_carried",
@@ -84,6 +85,8 @@ def load() -> ctypes.CDLL:
     lib.lasad_decode_step_rows.restype = ci
     lib.lasad_decode_step_cached.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp, ci, cf, vp]
     lib.lasad_decode_step_cached.restype = ci
+    lib.lasad_decode_step_gated_cached.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp]
+    lib.lasad_decode_step_gated_cached.restype = ci
     lib.lasad_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.lasad_backward_workspace_bytes.restype = ctypes.c_size_t
     lib.lasad_backward_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, lp, lp, ci, ci, ci, ci, ci, ci, ci, ci, ci,
@@ -298,6 +301,37 @@ def lasad_decode_step_cached(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, 
     _check(load().lasad_decode_step_cached(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(k_cache), _ptr(v_cache),
                                            k_cache.shape[2], _dtype_code(q), _dtype_code(out), B, Hh, d,
                                            grid_h, grid_w, pos, _ptr(gamma), boundary_mode, q_scale, _stream(stream)))
+    return out
+
+
+def lasad_decode_step_gated_cached(q: torch.Tensor, lam: torch.Tensor, v: torch.Tensor,
+                                   lam_cache: torch.Tensor, v_cache: torch.Tensor, grid_h: int, grid_w: int, pos: int,
+                                   k: torch.Tensor | None = None, k_cache: torch.Tensor | None = None,
+                                   boundary_mode: int = RESET_LAST_COL, q_scale: float = 1.0,
+                                   out: torch.Tensor | None = None, out_dtype: torch.dtype | None = None,
+                                   stream=None) -> torch.Tensor:
+    """The vector-decay decode step at position `pos` from caches of the gate rows and of v (and of k with an own
+    key; contiguous [B, Hh, T, d] of q's dtype, rows 0..pos-1 filled by the earlier steps; this step's rows are
+    appended as row pos).  Returns o."""
+    B, Hh, d = q.shape
+    if (k is None) != (k_cache is None):
+        raise ValueError("k and k_cache go together")
+    for t in (q, lam, v) + (() if k is None else (k,)):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("q, lam, k, v must be contiguous [B, Hh, d] of one dtype")
+    for t in (lam_cache, v_cache) + (() if k_cache is None else (k_cache,)):
+        if t.dim() != 4 or tuple(t.shape[:2]) != (B, Hh) or t.shape[3] != d or t.dtype != q.dtype or not t.is_contiguous():
+            raise ValueError("caches must be contiguous [B, Hh, T, d] of q's dtype")
+        if t.shape != lam_cache.shape:
+            raise ValueError("the caches differ in shape")
+    if out is None:
+        out = torch.empty_like(q, dtype=out_dtype or q.dtype)
+    elif out.shape != q.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, Hh, d]")
+    _check(load().lasad_decode_step_gated_cached(_ptr(q), _ptr(lam), _ptr(k), _ptr(v), _ptr(out),
+                                                 _ptr(lam_cache), _ptr(k_cache), _ptr(v_cache), lam_cache.shape[2],
+                                                 _dtype_code(q), _dtype_code(out), B, Hh, d,
+                                                 grid_h, grid_w, pos, boundary_mode, q_scale, _stream(stream)))
     return out
 
 

@@ -283,6 +283,44 @@ int lasad_decode_step_cached(const void *q, const void *k, const void *v, void *
     return LASAD_OK;
 }
 
+int lasad_decode_step_gated_cached(const void *q, const void *lam, const void *k, const void *v, void *o,
+                                   void *lam_cache, void *k_cache, void *v_cache, int cache_tokens,
+                                   int io_dtype, int out_dtype, int B, int n_heads, int d,
+                                   int grid_h, int grid_w, int pos, int boundary_mode, float q_scale,
+                                   void *hip_stream)
+{
+    if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
+    if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
+    if ((int64_t)B * n_heads > 0x7fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
+    if (pos < 0 || (int64_t)pos >= (int64_t)grid_h * grid_w)
+        return fail(LASAD_ERR_INVALID_ARG, "pos %d is outside the %d x %d grid", pos, grid_h, grid_w);
+    if (cache_tokens < 1 || pos >= cache_tokens)
+        return fail(LASAD_ERR_INVALID_ARG, "pos %d does not fit a cache of %d tokens", pos, cache_tokens);
+    if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);
+    if (out_dtype != LASAD_F32 && out_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "out_dtype %d", out_dtype);
+    if (io_dtype == LASAD_F32 && out_dtype == LASAD_BF16) return fail(LASAD_ERR_UNSUPPORTED, "fp32 inputs with bf16 output");
+    if (!q || !lam || !v || !o || !lam_cache || !v_cache) return fail(LASAD_ERR_INVALID_ARG, "a required pointer is NULL");
+    if ((k == nullptr) != (k_cache == nullptr))
+        return fail(LASAD_ERR_INVALID_ARG, "k and k_cache must be given together (own key) or both be NULL (tied key)");
+    if (!aligned(q, 16) || !aligned(lam, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) ||
+        !aligned(lam_cache, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16))
+        return fail(LASAD_ERR_INVALID_ARG, "q, lam, k, v, o and the caches must be 16-byte aligned");
+    if (o == q || o == lam || o == v || (k && o == k) || lam_cache == v_cache || (k_cache && (k_cache == v_cache || k_cache == lam_cache)))
+        return fail(LASAD_ERR_INVALID_ARG, "buffers alias");
+
+    lasad::CachedDecodeArgs a;
+    a.q = q; a.lam = lam; a.k = k; a.v = v; a.o = o;
+    a.lam_cache = lam_cache; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.io_dtype = io_dtype; a.out_dtype = out_dtype;
+    a.B = B; a.Hh = n_heads; a.d = d; a.cache_tokens = cache_tokens;
+    a.grid_w = grid_w; a.pos = pos;
+    a.gamma = nullptr; a.mode = boundary_mode; a.q_scale = q_scale;
+    hipError_t e = lasad::launch_decode_cached(a, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return hip_fail("lasad_decode_step_gated_cached launch", e);
+    return LASAD_OK;
+}
+
 static int forward_gated_common(const void *q, const void *lam, const void *k, const void *v, void *o,
                                 const lasad_layout_t *in_layout, const lasad_layout_t *o_layout,
                                 int io_dtype, int out_dtype,

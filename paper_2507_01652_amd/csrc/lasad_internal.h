@@ -115,6 +115,8 @@ struct BackwardArgs {
 // Arguments of one decode step from a key / value cache, already validated.
 struct CachedDecodeArgs {
     const void *q, *k, *v;       // [B, Hh, d]
+    const void *lam = nullptr;   // vector decay: this step's gate row (then gamma is unused, and k may be NULL: tied key)
+    void *lam_cache = nullptr;   // vector decay: the gate rows, like the other caches
     void *o;
     void *k_cache, *v_cache;     // [B, Hh, cache_tokens, d], type io_dtype; row pos is written, rows 0..pos-1 read
     int io_dtype, out_dtype;

@@ -104,6 +104,27 @@ def test_decode_and_decay_reject_bad_arguments(lib):
     assert dk(Hh=0) == 1 and dk(gamma=None) == 1
 
 
+def test_gated_cached_decode_rejects_bad_arguments(lib):
+    """Every check comes before the launch, so the error paths run without a GPU."""
+    vp, cf = ctypes.c_void_p, ctypes.c_float
+    lib.lasad_decode_step_gated_cached.argtypes = [vp] * 8 + [ctypes.c_int] * 10 + [cf, vp]
+    lib.lasad_decode_step_gated_cached.restype = ctypes.c_int
+    def dec(**k):
+        return lib.lasad_decode_step_gated_cached(
+            vp(k.get("q", 0x1000)), vp(k.get("lam", 0x2000)), vp(k.get("k", None)), vp(0x3000), vp(k.get("o", 0x4000)),
+            vp(k.get("lc", 0x10000)), vp(k.get("kc", None)), vp(k.get("vc", 0x20000)), k.get("T", 16),
+            k.get("io", 1), k.get("out", 1), k.get("B", 2), 2, k.get("d", 64), 4, 4, k.get("pos", 0), k.get("mode", 0),
+            cf(1.0), None)
+    assert dec(d=40) == 2 and dec(io=0, out=1) == 2
+    assert dec(pos=16) == 1 and dec(pos=-1) == 1 and dec(pos=8, T=8) == 1 and dec(T=0) == 1
+    assert dec(q=None) == 1 and dec(lam=None) == 1 and dec(lc=None) == 1 and dec(vc=None) == 1
+    assert dec(k=0x5000) == 1 and dec(kc=0x30000) == 1            # own key and its cache go together
+    assert dec(mode=7) == 1 and dec(B=0) == 1
+    assert dec(o=0x1000) == 1 and dec(lc=0x20000) == 1 and dec(k=0x5000, kc=0x20000) == 1
+    assert dec(lam=0x2004) == 1 and dec(vc=0x20008) == 1
+    assert b"alias" in lib.lasad_last_error() or b"aligned" in lib.lasad_last_error()
+
+
 def _backward_layer(lib, norm_only=False, **kw):
     dense = Layout(4 * 2 * 64, 2 * 64, 64)
     a = dict(q=0x1000, z=0x2000, v=0x3000, g=0x4000, dq=0x5000, dz=0x6000, dv=0x7000, dw=0x8000, d_o=0x5000,
