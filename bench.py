@@ -85,6 +85,8 @@ def parse(argv=None):
     p.add_argument("--no-backward", action="store_true", help="skip the backward-pass legs")
     p.add_argument("--no-gated", action="store_true",
                    help="skip the vector-decay (per-channel gate) forward, backward and decode legs")
+    p.add_argument("--no-small-gamma", action="store_true",
+                   help="skip the leg that times the headline shape with every head's decay below the chunked form's range")
     p.add_argument("--no-graph", action="store_true", help="time eager launches only")
     p.add_argument("--layout", default="bnhd", choices=["bnhd", "bhnd"],
                    help="memory order of q, k, v, o: [B, N, Hh, d] (default) or [B, Hh, N, d]")
@@ -200,6 +202,28 @@ def bench_prefill(args, timer, torch, lasad, wl, name):
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_prefill(w, (q, k, v, gam))
     return res
+
+
+def bench_small_gamma(args, timer, torch, lasad, wl, name, headline_ms):
+    """What a head costs whose decay is outside the range of the chunked form (gamma <= 0.5: the separable in-chunk
+    factors would overflow, so the workgroup of such a head walks its sequence with the fp32 recurrence inside the
+    same launch).  No paper-shaped workload has such heads; the leg exists so that the cost is on record: every
+    head of the headline shape gets gamma = 0.4 here."""
+    w = wl.CONFIGS[PREFILL_WORKLOADS[name]]
+    q, k, v, _ = wl.prefill_inputs(w, layout=args.layout)
+    tq, tk, tv = (lasad.to_device(x, w.dtype) for x in (q, k, v))
+    tg = torch.full((w.Hh,), 0.4, dtype=torch.float32, device="cuda")
+    o = torch.empty_like(tq)
+
+    def run(nsteps, first=0):
+        for _ in range(nsteps):
+            lasad.lasad_forward_chunked(tq, tk, tv, tg, w.grid_h, w.grid_w, out=o, use_workspace=False)
+
+    for _ in range(2):
+        run(1)
+    ms = timer.region(lambda: run(4)) / 4
+    return {"workload": w.name, "gamma": 0.4, "ms_per_step": ms, "slowdown_vs_headline": ms / headline_ms,
+            "what": "every head on the fp32 token-serial recurrence (decay outside the chunked form's range); eager launches"}
 
 
 def cpu_baseline_prefill(w, inputs, budget_s=20.0):
@@ -622,6 +646,8 @@ def main():
     if "large_prefill_24x24" in per and "highres_64x64" in per:
         line["linear_in_n"]["highres_over_large"] = (per["highres_64x64"]["ns_per_token_head"] /
                                                      per["large_prefill_24x24"]["ns_per_token_head"])
+    if not args.no_small_gamma:
+        line["small_gamma_fallback"] = bench_small_gamma(args, timer, torch, lasad, wl, args.workload, pre["ms_per_step"])
     if args.decode_walks > 0:
         line["decode"] = bench_decode(args, timer, torch, lasad, wl)
         line["decode"]["roofline"]["frac_of_measured_copy"] = line["decode"]["roofline"]["achieved"] / copy_gbs
