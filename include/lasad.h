@@ -109,7 +109,9 @@ size_t lasad_forward_workspace_bytes(int B, int n_heads, int n_tokens, int d, in
  *   io_dtype  LASAD_F32 (then out_dtype must be LASAD_F32) or LASAD_BF16 (out_dtype
  *             LASAD_BF16 or LASAD_F32).  Accumulation is fp32 in every case.
  *   d         32, 64 or 128 (generic kernel); bf16 with d = 64 takes the MFMA kernel.
- *   gamma     [n_heads] fp32, each in [0, 1].
+ *   gamma     [n_heads] fp32, each in [0, 1].  The matrix-core kernel factorises the in-chunk decay, which needs
+ *             gamma > 0.5; a head with a smaller decay is walked token by token in fp32 inside the same launch
+ *             (same results, about six times the time for that head's sequences).
  *   state_in  [B, n_heads, d, d] fp32, S[i][j] = sum_t (decay) k_t[i] v_t[j] (dv
  *             contiguous), the state after position start_pos; NULL means zeros.
  *   state_out [B, n_heads, d, d] fp32 or NULL; may equal state_in.
