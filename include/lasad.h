@@ -351,7 +351,8 @@ int lasad_backward_chunked_carried(const void *q, const void *k, const void *v, 
  * first token, whose decay multiplies the zero state), and, with the tied key (k NULL,
  * k_t = 1 - lambda_t), through the key as well (- dk_t).
  *   q, lam, k, v, d_o   [B, n_tokens, n_heads, d] views sharing in_layout and io_dtype (device);
- *                       k NULL: tied key.  Head dim 64 only (LASAD_ERR_UNSUPPORTED otherwise).
+ *                       k NULL: tied key.  Head dim 32, 64 or 128 (64 with bf16 inputs: the matrix-core passes;
+ *                       otherwise fp32 token-serial walks).
  *   dq, dlam, dk, dv    same logical shape, grad_layout, grad_dtype (fp32, or bf16 with bf16
  *                       inputs); overwritten; dk must be given exactly when k is; no aliasing.
  *   lambda must be > 0 wherever it is applied (dlam comes from d/dlog lambda; a zero decay gives
@@ -374,7 +375,7 @@ int lasad_backward_gated(const void *q, const void *lam, const void *k, const vo
  * before the call's first token, d_state_out = dL/d(final state), d_state_in receives dL/d(state_in) =
  * diag(l_1) g_1; each may be NULL.  dq, dlam, dk, dv include the terms through both states; in particular
  * the decay of the first token now has a gradient (it multiplies state_in), and every decay of the call
- * gains the products that end in the final state.  Head dim 64.  Workspace:
+ * gains the products that end in the final state.  Workspace:
  * lasad_backward_gated_carried_workspace_bytes(...) bytes.  Everything else as in lasad_backward_gated.
  */
 size_t lasad_backward_gated_carried_workspace_bytes(int B, int n_heads, int n_tokens, int d);

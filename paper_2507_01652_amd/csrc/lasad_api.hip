@@ -521,7 +521,7 @@ static int backward_gated_impl(const void *q, const void *lam, const void *k, co
     if (int rc = check_grid(grid_h, grid_w, boundary_mode)) return rc;
     if (B < 1 || n_heads < 1) return fail(LASAD_ERR_INVALID_ARG, "B = %d, n_heads = %d", B, n_heads);
     if ((int64_t)B * n_heads > 0x3fffffff) return fail(LASAD_ERR_INVALID_ARG, "B * n_heads overflows the launch grid");
-    if (d != 64) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (the vector-decay backward supports 64)", d);
+    if (!supported_d(d)) return fail(LASAD_ERR_UNSUPPORTED, "head dim %d (supported: 32, 64, 128)", d);
     if (start_pos < 0 || n_tokens < 0 || (int64_t)start_pos + n_tokens > (int64_t)grid_h * grid_w)
         return fail(LASAD_ERR_INVALID_ARG, "positions %d+1..%d+%d leave the %d x %d grid", start_pos, start_pos, n_tokens, grid_h, grid_w);
     if (io_dtype != LASAD_F32 && io_dtype != LASAD_BF16) return fail(LASAD_ERR_INVALID_ARG, "io_dtype %d", io_dtype);

@@ -36,6 +36,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include "lasad_recurrence.h"
 #include "lasad_scan.h"
 
 namespace lasad {
@@ -71,6 +72,105 @@ backward_gated_walk_kernel(WalkArgs w)
     else scan_sequence<IN_BF16, 0, ROLES_COL, NJ>(a, bh, j0, lds, &w.roles[pass]);     // fp32 into the workspace
 }
 
+// The same walks for the other head dims (32, 128): the plain fp32 recurrence of lasad_recurrence.h with the
+// tensors in the roles of ScanRoles (shift and 1 - x; no activations: the fused layer is a head-dim-64 path).
+// Thread (g, j) owns column j and rows g R .. g R + R - 1 of the walk's state [update row operand][update column
+// operand]; COL: the decay is per column, and the state's memory layout is [decayed channel][other index], as in
+// scan_sequence.  smem: (4 + G) x kRecT x D floats.
+template <int D>
+constexpr int roles_lds_floats() { return (4 + kRecThreads / D) * kRecT * D; }
+
+template <int D, int IN_BF16, int OUT_BF16, int COL>
+__device__ void recurrence_roles(const ForwardArgs &a, const ScanRoles &ro, int bh, float *smem)
+{
+    constexpr int G = kRecThreads / D;
+    constexpr int R = D / G;
+    float (*pl)[kRecT][D] = (float (*)[kRecT][D])smem;               // planes PQ, PK, PV, PL
+    float (*red)[G][D] = (float (*)[G][D])(smem + 4 * kRecT * D);
+    const int b = bh / a.Hh, h = bh - b * a.Hh;
+    const int tid = threadIdx.x;
+    const int j = tid % D, g = tid / D;
+
+    float S[R];
+    if (a.state_in) {
+        const float *s0 = a.state_in + (int64_t)bh * D * D;
+#pragma unroll
+        for (int r = 0; r < R; ++r) S[r] = COL ? s0[(int64_t)j * D + g * R + r] : s0[(int64_t)(g * R + r) * D + j];
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) S[r] = 0.f;
+    }
+    const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h;
+    const int64_t out_base = (int64_t)b * a.out.stride_b + (int64_t)h * a.out.stride_h;
+
+    for (int t0 = 0; t0 < a.n_tokens; t0 += kRecT) {
+        const int nt = min(kRecT, a.n_tokens - t0);
+        for (int e = tid; e < 4 * kRecT * D; e += kRecThreads) {
+            const int p = e / (kRecT * D), w = e - p * (kRecT * D);
+            const int tt = w / D, c = w - tt * D;
+            float x = p == PL ? 1.0f : 0.0f;                         // rows past the end (never walked)
+            if (tt < nt) {
+                const int t = t0 + tt + ro.shift[p];                  // the plane of token m holds the tensor's token m + shift
+                const bool before = t < 0;                            // a shifted read before the first token is neutral
+                if (!before) {
+                    x = rec_load<IN_BF16>(ro.ptr[p], in_base + (int64_t)t * a.in.stride_n + c);
+                    if (ro.one_minus[p]) x = 1.0f - x;
+                }
+                if (p == PL) {
+                    if (before || is_boundary(a.start_pos + t0 + tt + 1, a.grid_w, a.mode)) x = 1.0f;
+                } else if (before) {
+                    x = 0.0f;
+                }
+                if (p == PQ) x *= a.q_scale;
+            }
+            pl[p][tt][c] = x;
+        }
+        __syncthreads();
+        for (int tt = 0; tt < nt; ++tt) {
+            const float vj = pl[PV][tt][j];
+            const float lj = pl[PL][tt][j];
+            float part = 0.f;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float lr = COL ? lj : pl[PL][tt][g * R + r];
+                S[r] = fmaf(lr, S[r], pl[PK][tt][g * R + r] * vj);
+                part = fmaf(pl[PQ][tt][g * R + r], S[r], part);
+            }
+            red[tt][g][j] = part;
+        }
+        __syncthreads();
+        for (int e = tid; e < nt * D; e += kRecThreads) {
+            const int tt = e / D, c = e - tt * D;
+            float acc = 0.f;
+#pragma unroll
+            for (int gg = 0; gg < G; ++gg) acc += red[tt][gg][c];
+            rec_store<OUT_BF16>(a.o, out_base + (int64_t)(t0 + tt) * a.out.stride_n + c, acc);
+        }
+        // (the next round's staging writes the planes, not red; its first barrier orders them against these reads)
+    }
+    if (a.state_out) {
+        float *s1 = a.state_out + (int64_t)bh * D * D;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (COL) s1[(int64_t)j * D + g * R + r] = S[r];
+            else s1[(int64_t)(g * R + r) * D + j] = S[r];
+        }
+    }
+}
+
+template <int D, int IN_BF16, int OUT_BF16>
+__global__ void __launch_bounds__(kRecThreads)
+backward_gated_generic_walk_kernel(WalkArgs w)
+{
+    __shared__ __attribute__((aligned(16))) float lds[roles_lds_floats<D>()];
+    const int pass = blockIdx.y;
+    ForwardArgs a = w.common;
+    a.o = w.o[pass]; a.in = w.in[pass]; a.out = w.out[pass]; a.start_pos = w.start_pos[pass];
+    a.state_in = w.state_in[pass]; a.state_out = w.state_out[pass];
+    if (pass == 1) recurrence_roles<D, IN_BF16, OUT_BF16, 0>(a, w.roles[1], blockIdx.x, lds);
+    else recurrence_roles<D, IN_BF16, 0, 1>(a, w.roles[pass], blockIdx.x, lds);     // fp32 into the workspace
+}
+
 constexpr int kFinBlock = 64;          // tokens per step of the finishing kernel
 
 // One workgroup per sequence walks it in blocks of 64 tokens from the last block to the first,
@@ -104,8 +204,8 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
     const int nblk = (n + kFinBlock - 1) / kFinBlock;
     const int64_t in_base = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + c4;
     const int64_t g_base = (int64_t)b * a.grad.stride_b + (int64_t)h * a.grad.stride_h + c4;
-    const int64_t w_base = ((int64_t)b * n * a.Hh + h) * kD + c4;        // workspace: [B][n][Hh][d] fp32
-    const int64_t w_stride_n = (int64_t)a.Hh * kD;
+    const int64_t w_base = ((int64_t)b * n * a.Hh + h) * a.d + c4;       // workspace: [B][n][Hh][d] fp32
+    const int64_t w_stride_n = (int64_t)a.Hh * a.d;
 
     struct Item { f4 q, k, lam, dq, dk, dact; };     // dact: d(activation)/d(input) of q, fused activations only
     auto in4 = [&](const void *p, int t) {
@@ -149,7 +249,7 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
 
     const int seg = blockIdx.y;
     const int blk_lo = seg * seg_blocks, blk_hi = min(blk_lo + seg_blocks, nblk) - 1;     // this workgroup's blocks
-    float *totals = seg_totals + ((int64_t)bh * n_seg) * kD + ch0;
+    float *totals = seg_totals + ((int64_t)bh * n_seg) * a.d + ch0;
     if (TOTALS) {
         f4 sum = f4{0.f, 0.f, 0.f, 0.f};
         for (int blk = blk_hi; blk >= blk_lo; --blk) {
@@ -162,13 +262,13 @@ backward_gated_finish_kernel(GatedBackwardArgs a, const float *dq32, const float
         if (tid < CH) {
             float acc = 0.f;
             for (int r2 = kFinBlock - 1; r2 >= 0; --r2) acc += sR[r2][tid];
-            totals[seg * kD + tid] = acc;
+            totals[seg * a.d + tid] = acc;
         }
         return;
     }
     if (tid < CH) {
-        float carry = sink ? sink[(int64_t)bh * kD + ch0 + tid] : 0.f;
-        for (int s2 = n_seg - 1; s2 > seg; --s2) carry += totals[s2 * kD + tid];
+        float carry = sink ? sink[(int64_t)bh * a.d + ch0 + tid] : 0.f;
+        for (int s2 = n_seg - 1; s2 > seg; --s2) carry += totals[s2 * a.d + tid];
         sCarry[tid] = carry;
     }
     Item cur;
@@ -254,6 +354,28 @@ gated_carried_finish_kernel(GatedBackwardArgs a, const float *g1, const float *s
     }
 }
 
+// The same for the other head dims: thread c < d takes key channel c.
+template <int IN_BF16>
+__global__ void __launch_bounds__(128)
+gated_carried_finish_generic_kernel(GatedBackwardArgs a, const float *g1, const float *sn, float *sink)
+{
+    const int bh = blockIdx.x, b = bh / a.Hh, h = bh - b * a.Hh;
+    const int d = a.d, c = threadIdx.x;
+    if (c >= d) return;
+    const int64_t off = (int64_t)bh * d * d + (int64_t)c * d;
+    float l1 = 1.0f;
+    if (!is_boundary(a.start_pos + 1, a.grid_w, a.mode)) {
+        const int64_t i = (int64_t)b * a.in.stride_b + (int64_t)h * a.in.stride_h + c;
+        l1 = IN_BF16 ? bf16_bits_to_float(((const uint16_t *)a.lam)[i]) : ((const float *)a.lam)[i];
+    }
+    float acc = 0.f;
+    for (int n = 0; n < d; ++n) {
+        if (a.d_state_in) a.d_state_in[off + n] = (l1 * a.q_scale) * g1[off + n];
+        if (sink) acc = fmaf(a.d_state_out[off + n], sn[off + n], acc);
+    }
+    if (sink) sink[(int64_t)bh * d + c] = acc;
+}
+
 template <int IN_BF16, int OUT_BF16>
 void launch_walks(const WalkArgs &w, int64_t n_seq, hipStream_t s)
 {
@@ -280,7 +402,8 @@ size_t backward_gated_workspace_bytes(int64_t n_seq, int n_tokens, int d)
 
 hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
 {
-    if (b.d != kD || b.n_tokens < 1) return hipErrorInvalidValue;
+    if ((b.d != 32 && b.d != 64 && b.d != 128) || b.n_tokens < 1) return hipErrorInvalidValue;
+    if (b.d != kD && (b.fused_act || b.d_o_lo)) return hipErrorInvalidValue;     // the fused layer is a head-dim-64 path
     const int64_t n_seq = (int64_t)b.B * b.Hh;
     if (n_seq * 2 > 0x7fffffff) return hipErrorInvalidValue;
     const int n = b.n_tokens;
@@ -346,7 +469,20 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     const bool in16 = b.io_dtype == LASAD_BF16, out16 = b.grad_dtype == LASAD_BF16;
     static const bool force_walk = [] { const char *e = getenv("LASAD_GATED_BWD"); return e && !strcmp(e, "walk"); }();
     hipError_t e;
-    if (in16 && !force_walk) {
+    if (b.d != kD) {
+        // other head dims: the plain fp32 recurrence with the tensors in their roles, one workgroup per sequence and pass
+        const dim3 grid((unsigned)n_seq, 3), block(kRecThreads);
+#define LASAD_GEN_WALK(D) do { \
+            if (in16 && out16) hipLaunchKernelGGL((backward_gated_generic_walk_kernel<D, 1, 1>), grid, block, 0, s, w); \
+            else if (in16) hipLaunchKernelGGL((backward_gated_generic_walk_kernel<D, 1, 0>), grid, block, 0, s, w); \
+            else if (!out16) hipLaunchKernelGGL((backward_gated_generic_walk_kernel<D, 0, 0>), grid, block, 0, s, w); \
+            else return hipErrorInvalidValue; \
+        } while (0)
+        if (b.d == 32) LASAD_GEN_WALK(32); else LASAD_GEN_WALK(128);
+#undef LASAD_GEN_WALK
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else if (in16 && !force_walk) {
         // matrix-core passes: the pass's operands in the forward's fields
         ForwardArgs p[3] = {f, f, f};
         p[0].q = b.d_o; p[0].lam = b.lam; p[0].k = b.k; p[0].v = b.v; p[0].o = dq32;                  // dq
@@ -370,7 +506,10 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     }
 
     if (carried && (b.d_state_in || sink)) {
-        if (in16) hipLaunchKernelGGL((gated_carried_finish_kernel<1>), dim3((unsigned)n_seq), dim3(256), 0, s, b, g1, sn, (float *)sink);
+        if (b.d != kD) {
+            if (in16) hipLaunchKernelGGL((gated_carried_finish_generic_kernel<1>), dim3((unsigned)n_seq), dim3(128), 0, s, b, g1, sn, (float *)sink);
+            else hipLaunchKernelGGL((gated_carried_finish_generic_kernel<0>), dim3((unsigned)n_seq), dim3(128), 0, s, b, g1, sn, (float *)sink);
+        } else if (in16) hipLaunchKernelGGL((gated_carried_finish_kernel<1>), dim3((unsigned)n_seq), dim3(256), 0, s, b, g1, sn, (float *)sink);
         else hipLaunchKernelGGL((gated_carried_finish_kernel<0>), dim3((unsigned)n_seq), dim3(256), 0, s, b, g1, sn, (float *)sink);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -389,10 +528,12 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
     n_seg = (nblk + seg_blocks - 1) / seg_blocks;
     float *seg_totals = dk32 + (size_t)n_seq * n * b.d;          // after the two gradient tensors
     // few workgroups: 16 channels per workgroup (four workgroups of 256 threads per sequence and segment)
-    const bool narrow = n_seq * n_seg < 256;      // (at 480 workgroups the narrow rows already cost more than they gain)
-    const dim3 grid((unsigned)n_seq, (unsigned)n_seg, narrow ? 4 : 1), block(narrow ? 256 : 1024);
+    const bool narrow = b.d == kD && n_seq * n_seg < 256;      // (at 480 workgroups the narrow rows already cost more than they gain)
+    // head dim 32: one workgroup of 32 channels; 128: two of 64; 64: one of 64 or four of 16
+    const dim3 grid((unsigned)n_seq, (unsigned)n_seg, narrow ? 4 : b.d == 128 ? 2 : 1), block(narrow ? 256 : b.d == 32 ? 512 : 1024);
 #define LASAD_FIN_LAUNCH(I, O, T) do { \
-        if (narrow) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 16>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks, sink); \
+        if (b.d == 32) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 32>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks, sink); \
+        else if (narrow) hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 16>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks, sink); \
         else hipLaunchKernelGGL((backward_gated_finish_kernel<I, O, T, 64>), grid, block, 0, s, b, dq32, dk32, seg_totals, n_seg, seg_blocks, sink); \
     } while (0)
     if (n_seg > 1) {

@@ -247,5 +247,5 @@ def test_backward_gated_carried_entry_validates_and_sizes_its_workspace(lib):
             vp(0x100000), ctypes.c_size_t(0), None)
 
     assert call() == 3 and call(s0=None, h=None, ds0=None) == 3
-    assert call(q=None) == 1 and call(d=32) == 2 and call(n=5) == 1 and call(kk=0x8000) == 1     # dk must come with k
+    assert call(q=None) == 1 and call(d=48) == 2 and call(n=5) == 1 and call(kk=0x8000) == 1     # dk must come with k
     assert call(s0=0x20004) == 1 and call(ds0=0x30000) == 1 and call(qs=0.0) == 2

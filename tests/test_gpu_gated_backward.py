@@ -46,9 +46,9 @@ def _run(lasad, dtype, q, lam, v, g, k, H, W, start=0, mode=0, q_scale=1.0, grad
 
 
 def _check(lasad, oracle, B, Hh, H, W, dtype, seed, own_key, start=0, n=None, mode=0, q_scale=1.0, grad_bf16=False,
-           layout="bnhd"):
+           layout="bnhd", d=64):
     n = H * W - start if n is None else n
-    q, lam, v, g, k = _inputs(B, n, Hh, 64, dtype, seed, own_key, layout)
+    q, lam, v, g, k = _inputs(B, n, Hh, d, dtype, seed, own_key, layout)
     got = _run(lasad, dtype, q, lam, v, g, k, H, W, start, mode, q_scale, grad_bf16)
     ref = oracle.gated_backward(q, lam, v, g, W, k=k, start_pos=start, mode=mode, q_scale=q_scale)
     names = ("dq", "dlam", "dv", "dk")
@@ -78,6 +78,19 @@ CASES = [
 def test_backward_gated_shapes(lasad, oracle, case, mode, own_key):
     name, B, Hh, H, W, dtype = case
     _check(lasad, oracle, B, Hh, H, W, dtype, zlib.crc32(name.encode()) % 10000 + mode, own_key, mode=mode, q_scale=0.5)
+
+
+@pytest.mark.parametrize("d", [32, 128])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("own_key", [False, True], ids=["tied_key", "own_key"])
+def test_backward_gated_other_head_dims(lasad, oracle, d, dtype, own_key):
+    """Head dims 32 and 128: fp32 token-serial walks with the tensors in their roles; whole grids, a mid-row range,
+    the three rules, both layouts, bf16 gradients as the rounding of the fp32 ones."""
+    for mode in (0, 1, 2):
+        _check(lasad, oracle, 2, 3, 5, 7, dtype, 900 + d + mode, own_key, mode=mode, q_scale=0.5, d=d, grad_bf16=True)
+    _check(lasad, oracle, 2, 2, 9, 17, dtype, 950 + d, own_key, start=22, n=101, d=d, layout="bhnd")
+    _check(lasad, oracle, 1, 2, 1, 1, dtype, 960 + d, own_key, d=d)
+    _check(lasad, oracle, 1, 1, 40, 16, dtype, 970 + d, own_key, d=d, grad_bf16=True)      # several finishing segments
 
 
 @pytest.mark.parametrize("mode", [0, 1])
@@ -144,9 +157,9 @@ def test_backward_gated_deterministic(lasad):
 
 def test_backward_gated_rejects_bad_arguments(lasad):
     import torch
-    q = torch.zeros((1, 8, 2, 32), dtype=torch.bfloat16, device="cuda")
+    q = torch.zeros((1, 8, 2, 48), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(Exception):
-        lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 4)          # head dim 32
+        lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 4)          # head dim 48
     q = torch.zeros((1, 8, 2, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(Exception):
         lasad.lasad_backward_gated(q, q.clone(), q.clone(), q.clone(), 2, 3)          # 8 tokens on a 2 x 3 grid

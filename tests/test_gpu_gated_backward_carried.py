@@ -20,25 +20,25 @@ def lasad():
     return binding
 
 
-def _inputs(B, n, Hh, dtype, seed, own_key, layout="bnhd"):
+def _inputs(B, n, Hh, dtype, seed, own_key, layout="bnhd", d=64):
     rng = np.random.default_rng(seed)
-    shape = (B, n, Hh, 64)
-    q, v, g = (wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(8.0), dtype) for _ in range(3))
+    shape = (B, n, Hh, d)
+    q, v, g = (wl.store_round(rng.standard_normal(shape, dtype=np.float32) / np.float32(np.sqrt(d)), dtype) for _ in range(3))
     lam = wl.gate_inputs(shape, dtype, seed + 1)
     k = wl.store_round(rng.uniform(0.0, 1.0, size=shape).astype(np.float32), dtype) if own_key else None
     out = [q, lam, v, g, k]
     if layout == "bhnd":
         out = [None if x is None else np.ascontiguousarray(x.transpose(0, 2, 1, 3)).transpose(0, 2, 1, 3) for x in out]
-    s0 = (rng.standard_normal((B, Hh, 64, 64)) * 0.5).astype(np.float32)
-    h = (rng.standard_normal((B, Hh, 64, 64)) * 0.125).astype(np.float32)
+    s0 = (rng.standard_normal((B, Hh, d, d)) * 0.5).astype(np.float32)
+    h = (rng.standard_normal((B, Hh, d, d)) * 0.125).astype(np.float32)
     return out + [s0, h]
 
 
 def _check(lasad, oracle, B, Hh, H, W, dtype, seed, own_key, start=0, n=None, mode=0, q_scale=1.0, grad_bf16=False,
-           layout="bnhd", with_s0=True, with_h=True):
+           layout="bnhd", with_s0=True, with_h=True, d=64):
     import torch
     n = H * W - start if n is None else n
-    q, lam, v, g, k, s0, h = _inputs(B, n, Hh, dtype, seed, own_key, layout)
+    q, lam, v, g, k, s0, h = _inputs(B, n, Hh, dtype, seed, own_key, layout, d)
     s0 = s0 if with_s0 else None
     h = h if with_h else None
     dev = lambda x: None if x is None else lasad.to_device(x, dtype)
@@ -67,6 +67,17 @@ CASES = [
     ("bf16_single_row", 1, 2, 1, 70, "bf16"),
     ("bf16_single_token", 1, 2, 1, 1, "bf16"),
 ]
+
+
+@pytest.mark.parametrize("d", [32, 128])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("own_key", [False, True], ids=["tied_key", "own_key"])
+def test_backward_gated_carried_other_head_dims(lasad, oracle, d, dtype, own_key):
+    for mode in (0, 1, 2):
+        _check(lasad, oracle, 2, 2, 5, 7, dtype, 700 + d + mode, own_key, mode=mode, q_scale=0.5, d=d, grad_bf16=True)
+    _check(lasad, oracle, 1, 2, 9, 17, dtype, 750 + d, own_key, start=22, n=101, d=d, layout="bhnd")
+    _check(lasad, oracle, 1, 2, 6, 5, dtype, 760 + d, own_key, d=d, with_s0=False)
+    _check(lasad, oracle, 1, 2, 6, 5, dtype, 770 + d, own_key, d=d, with_h=False)
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
