@@ -491,6 +491,7 @@ hipError_t launch_backward_gated(const GatedBackwardArgs &b, hipStream_t s)
         p[1].q = b.k ? k_l : lam_l; p[1].lam = lam_l; p[1].k = q_l; p[1].v = g_l; p[1].o = w.o[1];     // dv
         p[1].in = in_rev; p[1].out = grad_rev; p[1].out_dtype = b.grad_dtype; p[1].start_pos = rev_start;
         p[2] = p[1];
+        p[1].v_lo = gl_l;
         p[2].q = v_l; p[2].o = w.o[2]; p[2].out = wl_rev; p[2].out_dtype = LASAD_F32;                  // dk
         p[2].v_lo = gl_l;
         for (int y = 0; y < 3; ++y) { p[y].state_in = st_in[y]; p[y].state_out = st_out[y]; }

@@ -57,10 +57,11 @@ struct PassSet {
 // the 8 XCDs) and share what they both read through its L2 (dv and dk walk the same q, d_o and
 // lambda rows in the same order).  TIED: the key is 1 - lambda.  FUSED (with TIED): the layer's
 // backward: the q and lambda tensors hold Algorithm 1's pre-activation query and gate logits, and
-// d_o comes as a bf16 pair hi + lo, both parts used where it is an operand of a column pass (x of
-// the dq pass, y of the dk pass: one more MFMA per score step and per state term).  d_o is
+// d_o comes as a bf16 pair hi + lo, both parts used in every pass (x of the dq pass, y of the dk pass, the value
+// operand of the dv pass: one more MFMA per score or product step and per state term).  d_o is
 // orthogonal to the recurrence output, which makes dq and dk small differences of larger terms
-// early in a sequence; a single bf16 there costs up to 0.15 of the RMS in single elements.
+// early in a sequence; a single bf16 there costs up to 0.15 of the RMS in single elements, and in dv, which for
+// the last tokens of a sequence is a multiple of a single d_o row, up to 0.02.
 template <int OUT_BF16, int TIED, int FUSED = 0>
 __global__ void __launch_bounds__(kWsThreads, 1)
 backward_gated_passes_kernel(PassSet ps)
@@ -75,7 +76,7 @@ backward_gated_passes_kernel(PassSet ps)
     if (bh >= ps.a[0].B * ps.a[0].Hh) return;                  // (the last group may be partly empty)
     const PassSet *kp = (const PassSet *)__builtin_amdgcn_kernarg_segment_ptr();
     if (pass == 0) pass_body<0, TIED ? 0 : 1, FUSED, 0, 1, 1, FUSED, 0>(ps.a[0], &kp->a[0], &kp->roles[0], bh, smem, sTot, sTrip);
-    else if (pass == 1) pass_body<OUT_BF16, 1, FUSED, 1, TIED ? 2 : 0, 0>(ps.a[1], &kp->a[1], &kp->roles[1], bh, smem, sTot, sTrip);
+    else if (pass == 1) pass_body<OUT_BF16, 1, FUSED, 1, TIED ? 2 : 0, 0, 0, FUSED>(ps.a[1], &kp->a[1], &kp->roles[1], bh, smem, sTot, sTrip);
     else pass_body<0, 1, FUSED, 1, 1, 1, 0, FUSED>(ps.a[2], &kp->a[2], &kp->roles[2], bh, smem, sTot, sTrip);
 }
 
@@ -94,7 +95,7 @@ hipError_t launch_backward_gated_passes(const ForwardArgs *a, const scan::ScanRo
     const dim3 grid((unsigned)((n_seq + 7) / 8 * 24)), block(kWsThreads);
     const bool out16 = a[1].out_dtype == LASAD_BF16;
     if (a[0].fused_act) {
-        if (!tied || !a[0].q_lo || !a[2].v_lo) return hipErrorInvalidValue;
+        if (!tied || !a[0].q_lo || !a[1].v_lo || !a[2].v_lo) return hipErrorInvalidValue;
         if (out16) hipLaunchKernelGGL((backward_gated_passes_kernel<1, 1, 1>), grid, block, 0, s, ps);
         else hipLaunchKernelGGL((backward_gated_passes_kernel<0, 1, 1>), grid, block, 0, s, ps);
     } else if (tied) {

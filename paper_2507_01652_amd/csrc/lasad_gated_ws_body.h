@@ -35,8 +35,11 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                                               int (*sTrip)[4], float *sSS, Fallback fallback_fn)
 {
     static_assert(!COL || (QMODE == 1 && !OUT_BF16 && !NORM), "column passes: query of ones, fp32 output, no norm");
-    static_assert(COL || (!XLO && !YLO), "two-part operands: column passes only");
+    static_assert(COL || !XLO, "a two-part x: column passes only");
     static_assert(TS >= RS, "the low-order Y tile sits in the output tile's place");
+    // the bf16 output tile goes through LDS for 16-byte stores unless its place holds the low-order Y tile (a row pass
+    // with a two-part value operand: then a lane stores its 8-byte pieces itself)
+    constexpr bool TILE_OUT = OUT_BF16 && !YLO;
     auto sQh = [&](int p) { return smem + p * kSetHalfs; };
     auto sQl = [&](int p) { return smem + p * kSetHalfs + C * RS; };
     auto sKh = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS; };
@@ -45,7 +48,7 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
     auto sSh = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS + 2 * C * KS + C * TS; };
     auto sSl = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS + 2 * C * KS + C * TS + D * RS; };
     auto sO = [&](int p) { return smem + p * kSetHalfs + 2 * C * RS + 2 * C * KS + C * TS + 2 * D * RS; };
-    auto sVl = sO;     // YLO: low-order part of the Y tile, row stride RS (a column pass stores fp32 from registers)
+    auto sVl = sO;     // YLO: low-order part of the Y tile, row stride RS (such a pass stores its output from registers)
 
     const int b = bh / a.Hh, h = bh - b * a.Hh;
     const int tid = threadIdx.x;
@@ -124,10 +127,10 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 stg.write(sQh(p), sQl(p), sKh(p), sKl(p), sV(p), l32, pcol);
             }
             // the output tile last: the wait for the next loads must not include these stores
-            if (OUT_BF16 && chunk > NORM) store_tile(chunk - 1 - NORM);
+            if (TILE_OUT && chunk > NORM) store_tile(chunk - 1 - NORM);
             if (barrier_flag(stg.trip)) return;
         }
-        if (OUT_BF16) {
+        if (TILE_OUT) {
             if (NORM) {
                 if (n_chunks > 1) store_tile(n_chunks - 2);
                 __syncthreads();                          // the output waves have written the last normalised tile
@@ -240,7 +243,18 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
     // the output tile of a chunk: a lane owns four consecutive value channels of its query per quad
     auto put_tile = [&](const f32x16 &acc, int chunk) {
         const int i_row = (wa ^ (chunk & 1)) * 32 + l32;
-        if (OUT_BF16) {                                   // via LDS; the loader waves store it during a later chunk
+        if (OUT_BF16 && !TILE_OUT) {                      // bf16 straight from the registers, 8-byte pieces
+            if (chunk * C + i_row < n) {
+                uint16_t *go = (uint16_t *)a.o + o_base + (int64_t)(chunk * C + i_row) * a.out.stride_n + wc * 32 + 4 * g;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    uint2 w2;
+                    w2.x = pack2(acc[4 * qd + 0], acc[4 * qd + 1]);
+                    w2.y = pack2(acc[4 * qd + 2], acc[4 * qd + 3]);
+                    *(uint2 *)(go + 8 * qd) = w2;
+                }
+            }
+        } else if (OUT_BF16) {                            // via LDS; the loader waves store it during a later chunk
             uint16_t *bO = sO(chunk & 1);
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
@@ -354,6 +368,13 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
                 for (int s = 0; s < 2; ++s) {
                     acc = mfma(fv[s], ph[s], acc);
                     acc = mfma(fv[s], pl[s], acc);
+                    if (YLO) {                                // the low-order part of V times P hi
+                        const uint16_t *bVl = sVl(p);
+                        Frag fvl;
+                        fvl.h[0] = tr_read(&bVl[(32 * jb + 16 * s + 4 * g + trow) * RS + tcol]);
+                        fvl.h[1] = tr_read(&bVl[(32 * jb + 16 * s + 8 + 4 * g + trow) * RS + tcol]);
+                        acc = mfma(fvl, ph[s], acc);
+                    }
                 }
                 return acc;
             };
@@ -478,7 +499,7 @@ __device__ __forceinline__ void gated_ws_body(const ForwardArgs &a, int bh, uint
     }
     if (NORM) {
         finish_tile(n_chunks - 1);
-        if (OUT_BF16) __syncthreads();                    // (the loader waves store the tile after it)
+        if (TILE_OUT) __syncthreads();                    // (the loader waves store the tile after it)
     }
 }
 
