@@ -45,6 +45,20 @@ def test_graph_replays_match_eager(lasad):
     lgrads = tuple(torch.empty_like(q) for _ in range(3))
     dwt = torch.empty(Hh, d, device="cuda")
     ws_l = torch.empty(lasad.lasad_backward_layer_workspace_bytes(q), dtype=torch.uint8, device="cuda")
+    # the entry points with carried states, the allocation-free forward, the vector-decay cache step
+    s_in = torch.randn(B, Hh, d, d, device="cuda", generator=gen) * 0.3
+    h_out = torch.randn(B, Hh, d, d, device="cuda", generator=gen) * 0.1
+    cgrads = tuple(torch.empty_like(q) for _ in range(3))
+    cdgam, cds = torch.empty(Hh, device="cuda"), torch.empty(B, Hh, d, d, device="cuda")
+    ws_c = torch.empty(lasad.lasad_backward_carried_workspace_bytes(B, Hh, n, d, lasad.BF16), dtype=torch.uint8, device="cuda")
+    cggrads = tuple(torch.empty_like(q) for _ in range(3))
+    cgds = torch.empty(B, Hh, d, d, device="cuda")
+    ws_cg = torch.empty(lasad.lasad_backward_gated_carried_workspace_bytes(B, Hh, n, d), dtype=torch.uint8, device="cuda")
+    o_static = torch.empty_like(q)
+    lams = torch.sigmoid(torch.randn(B, Hh, d, device="cuda", generator=gen) + 2).to(torch.bfloat16)
+    lc = torch.sigmoid(torch.randn(B, Hh, 8, d, device="cuda", generator=gen) + 2).to(torch.bfloat16)
+    vc2 = rnd(B, Hh, 8, d)
+    ogc = torch.empty_like(qs)
 
     def run():
         lasad.lasad_forward_chunked(q, k, v, gam, H, W, out=o, workspace=ws_f)
@@ -56,8 +70,15 @@ def test_graph_replays_match_eager(lasad):
         state.zero_()
         lasad.lasad_decode_step(qs, ks, vs, gam, state, H, W, 3, out=od)
         lasad.lasad_decode_step_cached(qs, ks, vs, gam, kc, vc, H, W, 3, out=oc)
+        lasad.lasad_backward_chunked_carried(q, k, v, g, gam, H, W, state_in=s_in, d_state_out=h_out, grads=cgrads, dgamma=cdgam,
+                                             d_state_in=cds, workspace=ws_c)
+        lasad.lasad_backward_gated_carried(q, lam, v, g, H, W, state_in=s_in, d_state_out=h_out, grads=cggrads, d_state_in=cgds,
+                                           workspace=ws_cg)
+        lasad.lasad_forward_chunked_static(q, k, v, gam, H, W, o_static)
+        lasad.lasad_decode_step_gated_cached(qs, lams, vs, lc, vc2, H, W, 3, out=ogc)
 
-    outputs = lambda: [t.clone() for t in (o, og, ol, *grads, dgam, *ggrads, *lgrads, dwt, od, oc, state, kc, vc)]
+    outputs = lambda: [t.clone() for t in (o, og, ol, *grads, dgam, *ggrads, *lgrads, dwt, od, oc, state, kc, vc,
+                                           *cgrads, cdgam, cds, *cggrads, cgds, o_static, ogc, lc, vc2)]
     run()                                   # warm-up (loads the code objects)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -70,7 +91,7 @@ def test_graph_replays_match_eager(lasad):
         run()                               # eager reference for these inputs
         torch.cuda.synchronize()
         want = outputs()
-        for t in (o, og, ol, *grads, dgam, *ggrads, od, oc):
+        for t in (o, og, ol, *grads, dgam, *ggrads, od, oc, *cgrads, cdgam, cds, *cggrads, cgds, o_static, ogc):
             t.fill_(float("nan"))
         graph.replay()
         torch.cuda.synchronize()
