@@ -33,10 +33,6 @@ using namespace fwd;
 constexpr int kWs12Threads = 768;     // SPLIT 1: 4 output + 4 state + 4 loader waves
 constexpr int kWs10Threads = 640;     // SPLIT 2: 4 output + 2 state + 4 loader waves
 constexpr int PS = RS / 2;            // row stride (floats) of an fp32 partial output tile [token][32 channels]
-#ifndef LASAD_WS12_PF
-#define LASAD_WS12_PF 1
-#endif
-constexpr int kPf = LASAD_WS12_PF;    // chunks between the global loads of K / V rows and their staging
 
 constexpr int kSetHalfs = C * RS + 3 * C * VS + 2 * D * RS + C * RS;   // one set of tiles
 
@@ -157,36 +153,29 @@ forward_mfma_ws12_kernel(ForwardArgs a, MultiPass m)
     };
     if (group == 2) {
         // ===================================== loader waves =====================================
-        // K and V rows travel through one of kPf register sets; the set of chunk c is loaded kPf chunks
-        // before its tiles are written (the loads of kPf - 1 chunks are in flight while one is staged)
-        uint4 rk[kPf][2], rv[kPf][2];
+        // K and V rows are loaded one chunk before their tiles are written.  (Deeper rings of register sets were
+        // measured: with loads that are issued under a condition the compiler's wait counts collapse the depth to one
+        // chunk anyway, and with unconditional loads the depth is real and gains nothing.)
+        uint4 rk[2], rv[2];
         StagedKeys sk;
         ChunkPos pos;
         pos.init(a.start_pos + seg_t0, a.grid_w, a.mode);
-#pragma unroll
-        for (int u = 0; u < kPf; ++u)
-            if (u == 0 || u < n_chunks) load_kv<NT>(rk[u], rv[u], gk, gv, u * C, n, a.in.stride_n, st);
-        prepare_keys(sk, rk[0], rv[0], st, min(C, n), pos, lg, sc);
+        load_kv<NT>(rk, rv, gk, gv, 0, n, a.in.stride_n, st);
+        prepare_keys(sk, rk, rv, st, min(C, n), pos, lg, sc);
         pos.advance();
-        write_tiles<true>(sK(0), sV(0), sKh(0), sKl(0), tabC2[0], rk[0], rv[0], sk, st);
-        if (kPf < n_chunks) load_kv<NT>(rk[0], rv[0], gk, gv, kPf * C, n, a.in.stride_n, st);
+        write_tiles<true>(sK(0), sV(0), sKh(0), sKl(0), tabC2[0], rk, rv, sk, st);
+        if (1 < n_chunks) load_kv<NT>(rk, rv, gk, gv, C, n, a.in.stride_n, st);
         __syncthreads();
-        for (int c0 = 0; c0 < n_chunks; c0 += kPf) {
-#pragma unroll
-            for (int u = 0; u < kPf; ++u) {
-                const int chunk = c0 + u;
-                if (chunk >= n_chunks) break;
-                const int r = (u + 1) % kPf;              // register set of chunk + 1
-                if ((OUT_BF16 || SPLIT == 2) && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
-                if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
-                    const int p = (chunk + 1) & 1;
-                    prepare_keys(sk, rk[r], rv[r], st, min(C, n - (chunk + 1) * C), pos, lg, sc);
-                    pos.advance();
-                    write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk[r], rv[r], sk, st);
-                    if (chunk + 1 + kPf < n_chunks) load_kv<NT>(rk[r], rv[r], gk, gv, (chunk + 1 + kPf) * C, n, a.in.stride_n, st);
-                }
-                __syncthreads();
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            if ((OUT_BF16 || SPLIT == 2) && chunk > 0) store_tile(chunk - 1);   // the output waves' finished tile
+            if (chunk + 1 < n_chunks) {                   // tiles of the next chunk into the other set
+                const int p = (chunk + 1) & 1;
+                prepare_keys(sk, rk, rv, st, min(C, n - (chunk + 1) * C), pos, lg, sc);
+                pos.advance();
+                write_tiles<true>(sK(p), sV(p), sKh(p), sKl(p), tabC2[p], rk, rv, sk, st);
+                if (chunk + 2 < n_chunks) load_kv<NT>(rk, rv, gk, gv, (chunk + 2) * C, n, a.in.stride_n, st);
             }
+            __syncthreads();
         }
         if (OUT_BF16 || SPLIT == 2) store_tile(n_chunks - 1);
         return;
