@@ -28,7 +28,7 @@ def _configs(count, seed):
         total = H * W
         start = int(rng.integers(0, total))
         n = int(rng.integers(1, total - start + 1))
-        B = int(rng.choice([1, 2, 3, 7, 50, 130]))
+        B = int(rng.choice([1, 2, 3, 7, 50, 130, 260]))      # (with 1-3 heads: both sides of the 128 / 256 / 512 sequence thresholds)
         Hh = int(rng.integers(1, 4))
         if B * Hh * n > 60000:           # keep the oracle fast
             B = 2
@@ -41,8 +41,8 @@ def _id(c):
     return f"B{c['B']}h{c['Hh']}_{c['H']}x{c['W']}_s{c['start']}n{c['n']}m{c['mode']}"
 
 
-SCALAR = _configs(24, 1)
-GATED = _configs(24, 2)
+SCALAR = _configs(40, 1)
+GATED = _configs(40, 2)
 
 
 @pytest.mark.parametrize("c", SCALAR, ids=[_id(c) for c in SCALAR])
