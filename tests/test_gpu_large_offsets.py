@@ -1,5 +1,5 @@
 """Tensors of more than 2^31 elements (the sizes 288 GB of device memory invite): the addressing of the forward,
-backward (scalar and vector decay), decode and cached-decode kernels must be 64-bit.  Inputs are drawn on the GPU
+backward (scalar and vector decay, fused layer), decode and cached-decode kernels must be 64-bit.  Inputs are drawn on the GPU
 from seeded generators (the host never holds a whole tensor); the oracle recomputes sampled (batch, head)
 sequences in full: the first, the last, the two on either side of element offset 2^31, and some in between.  Same
 tolerances as everywhere; the bf16 output of a sampled sequence must be the rounding of its fp32 output."""
@@ -124,6 +124,30 @@ def test_forward_and_backward_gated_beyond_2g_elements(lasad, oracle, seq_inputs
     want = oracle.gated_backward(_seqs(q, pairs), _seqs(lam, pairs), _seqs(v, pairs), _seqs(g, pairs), GRID_W, q_scale=0.5)
     for nm, got, r in zip(("dq", "dlam", "dv"), (dq, dlam, dv), want):
         assert rel_err(_seqs(got, pairs), r) <= TOL["bf16"], nm
+
+
+def test_layer_forward_and_backward_beyond_2g_elements(lasad, oracle, seq_inputs):
+    """Algorithm 1's fused layer (activations, tied key, recurrence, norm) and its backward at the same size."""
+    import torch
+    q, _, v, g, _, _ = seq_inputs
+    z = _normal((B_SEQ, N, HH, D), 105, mean=2.0)
+    cut_b = (1 << 31) // (N * HH * D)
+    pairs = [(0, 0), (cut_b - 1, HH - 1), (cut_b, 0), (cut_b, 41), (B_SEQ - 1, HH - 1)]
+    w = np.random.default_rng(8).uniform(0.5, 1.5, size=(HH, D)).astype(np.float32)
+    wt, wp = torch.from_numpy(w).cuda(), w[[h for _, h in pairs]]
+    o = lasad.lasad_forward_layer(q, z, v, GRID_H, GRID_W, norm_weight=wt, norm_eps=1e-5, q_scale=0.5, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    sq, sz, sv, sg = (_seqs(x, pairs) for x in (q, z, v, g))
+    ref = oracle.gated_layer(sq, sz, sv, GRID_W, norm_weight=wp, eps=1e-5, q_scale=0.5)
+    assert rel_err(_seqs(o, pairs), ref) <= TOL["bf16"]
+    del o
+    dq, dz, dv, dw = lasad.lasad_backward_layer(q, z, v, g, GRID_H, GRID_W, norm_weight=wt, norm_eps=1e-5, q_scale=0.5,
+                                                grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = oracle.gated_layer_backward(sq, sz, sv, sg, GRID_W, norm_weight=wp, eps=1e-5, q_scale=0.5)
+    for nm, got, r in zip(("dq_pre", "dz", "dv"), (dq, dz, dv), want):
+        assert rel_err(_seqs(got, pairs), r) <= TOL["bf16"], (nm, rel_err(_seqs(got, pairs), r))
+    assert bool(torch.isfinite(dw).all())
 
 
 def test_decode_states_beyond_2g_elements(lasad, oracle):
