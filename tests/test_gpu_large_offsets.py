@@ -218,3 +218,37 @@ def test_cached_decode_caches_beyond_2g_elements(lasad, oracle):
     assert rel_err(got, ref) <= TOL["bf16"]
     for b, h in pairs:
         assert torch.equal(lc[b, h, pos], lam[b, h])
+
+
+def test_carried_backward_states_beyond_2g_elements(lasad, oracle):
+    """Gradients through carried states with 8200 x 64 sequences of 8 tokens: the incoming state, the gradient of
+    the final state and the gradient of the incoming state are 2.15e9 fp32 elements each."""
+    import torch
+    B, Hh, H, W = 8200, 64, 2, 4
+    n = H * W
+    assert B * Hh * D * D > 1 << 31
+    pairs = _pairs(B, Hh, D * D)
+    q, k, v, g = (_normal((B, n, Hh, D), 400 + i, 0.125) for i in range(4))
+    lam = _normal((B, n, Hh, D), 404, mean=2.0).sigmoid_()
+    s0 = _normal((B, Hh, D, D), 405, 0.3, dtype=torch.float32)
+    h = _normal((B, Hh, D, D), 406, 0.1, dtype=torch.float32)
+    gam = np.random.default_rng(9).uniform(0.85, 0.999, size=(Hh,)).astype(np.float32)
+    sq, sk, sv, sg, sl = (_seqs(x, pairs) for x in (q, k, v, g, lam))
+    sel = lambda x: np.stack([x[b, hh].cpu().numpy() for b, hh in pairs])[None]
+    s0p, hp = sel(s0), sel(h)
+    dq, dk, dv, dgam, ds0 = lasad.lasad_backward_chunked_carried(q, k, v, g, torch.from_numpy(gam).cuda(), H, W, state_in=s0,
+                                                                 d_state_out=h, q_scale=0.5, grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    lam_t, _ = oracle.decay_factors(gam[[hh for _, hh in pairs]], H, W, 0, n)
+    rq, rk, rv, _, rs0 = oracle.backward_carried(sq, sk, sv, lam_t, sg, s0=s0p, d_state=hp, q_scale=0.5)
+    for nm, got, want in (("dq", _seqs(dq, pairs), rq), ("dk", _seqs(dk, pairs), rk), ("dv", _seqs(dv, pairs), rv),
+                          ("d_state_in", sel(ds0), rs0)):
+        assert rel_err(got, want) <= TOL["bf16"], nm
+    assert bool(torch.isfinite(dgam).all())
+    del dq, dk, dv, ds0
+    dq, dlam, dv, ds0 = lasad.lasad_backward_gated_carried(q, lam, v, g, H, W, state_in=s0, d_state_out=h, q_scale=0.5,
+                                                           grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = oracle.gated_backward_carried(sq, sl, sv, sg, W, s0=s0p, d_state=hp, q_scale=0.5)
+    for nm, got, r in zip(("dq", "dlam", "dv", "d_state_in"), (_seqs(dq, pairs), _seqs(dlam, pairs), _seqs(dv, pairs), sel(ds0)), want):
+        assert rel_err(got, r) <= TOL["bf16"], nm
