@@ -252,3 +252,39 @@ def test_carried_backward_states_beyond_2g_elements(lasad, oracle):
     want = oracle.gated_backward_carried(sq, sl, sv, sg, W, s0=s0p, d_state=hp, q_scale=0.5)
     for nm, got, r in zip(("dq", "dlam", "dv", "d_state_in"), (_seqs(dq, pairs), _seqs(dlam, pairs), _seqs(dv, pairs), sel(ds0)), want):
         assert rel_err(got, r) <= TOL["bf16"], nm
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_forward_quarter_million_tokens_per_sequence(lasad, oracle, mode):
+    """A 512 x 512 grid entered mid-row (262 000 tokens per sequence, 4096 chunks, the segment plan's long
+    segments), decays close to one: scalar and vector decay against the oracle's recurrence, outputs and final
+    states.  The call is also cut in two at an odd token and must give the same final state as the single call."""
+    import torch
+    H = W = 512
+    start = 3 * W + 77
+    n = H * W - start
+    B, Hh = 1, 2
+    q, k, v = (_normal((B, n, Hh, D), 500 + i, 0.125) for i in range(3))
+    lam = _normal((B, n, Hh, D), 504, mean=3.0).sigmoid_()
+    gam = np.array([0.9993, 0.99995], dtype=np.float32)
+    tg = torch.from_numpy(gam).cuda()
+    s1 = torch.empty((B, Hh, D, D), dtype=torch.float32, device="cuda")
+    o = lasad.lasad_forward_chunked(q, k, v, tg, H, W, start_pos=start, boundary_mode=mode, state_out=s1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    host = lambda x: x.float().cpu().numpy()
+    lam_t, _ = oracle.decay_factors(gam, H, W, start, n, mode)
+    ref, s_ref = oracle.recurrent(host(q), host(k), host(v), lam_t, want_state=True)
+    assert rel_err(host(o), ref) <= TOL["bf16"]
+    assert rel_err(host(s1), s_ref) <= TOL["bf16"]
+    cut = 100001
+    sa, sb = torch.empty_like(s1), torch.empty_like(s1)
+    lasad.lasad_forward_chunked(q[:, :cut], k[:, :cut], v[:, :cut], tg, H, W, start_pos=start, boundary_mode=mode, state_out=sa)
+    lasad.lasad_forward_chunked(q[:, cut:], k[:, cut:], v[:, cut:], tg, H, W, start_pos=start + cut, boundary_mode=mode,
+                                state_in=sa, state_out=sb)
+    torch.cuda.synchronize()
+    assert rel_err(host(sb), s_ref) <= TOL["bf16"]
+    og = lasad.lasad_forward_gated(q, lam, v, H, W, start_pos=start, boundary_mode=mode, state_out=s1, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ref, s_ref = oracle.gated_recurrent(host(q), host(lam), host(v), W, start_pos=start, mode=mode, want_state=True)
+    assert rel_err(host(og), ref) <= TOL["bf16"]
+    assert rel_err(host(s1), s_ref) <= TOL["bf16"]
