@@ -19,7 +19,7 @@ constexpr int kThreads = 256;
 constexpr int TS = 80;     // LDS row stride (bf16 elements) of the V tile (transpose reads): 160 B
 constexpr int KS = LASAD_GATED_KS;   // of the K~ tiles (16-byte row reads and transpose reads)
 constexpr int RS = 72;     // of the Q~, S^T and output tiles (16-byte row reads): 144 B
-constexpr float kMinChunkDecay = 8.6736174e-19f;   // 2^-60
+constexpr float kMinChunkDecay = 7.8886091e-31f;   // 2^-100
 
 // Running products of eight values along the 32 lanes of each half wavefront: on return x[c]
 // of lane l holds the product over lanes 0..l of its half (inclusive) and e[c] the product over

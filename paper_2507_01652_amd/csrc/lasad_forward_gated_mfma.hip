@@ -28,10 +28,15 @@
 // Precision: Q~, K~, P and S are computed operands and are each split into bf16 hi + lo (three
 // MFMAs for a product of two split operands, two when one side is exact); v is exact bf16.
 //
-// Range.  K~ grows like 1 / A.  A chunk whose total decay of some channel is below 2^-60 (or
-// zero) cannot be factored this way; the workgroup then abandons the chunked walk and redoes
-// its whole sequence with the token-serial fp32 routine (lasad_scan.h), which applies each
-// decay step by step.  Gates from a sigmoid stay many orders of magnitude above that limit.
+// Range.  K~ grows like 1 / A and Q~ shrinks like A.  Down to a chunk decay of 2^-100 per channel
+// both stay normal numbers in fp32 and in their bf16 hi and lo parts for inputs of ordinary size
+// (|k| 2^100 < 2^127; q_scale q 2^-100 and its low part, 2^-8 of it, > 2^-126), every valid score is
+// a sum of products A_i / A_j <= 1, and a state row mixes only terms of its own channel.  A chunk
+// whose total decay of some channel is below that (or zero) cannot be factored this way; the
+// workgroup then abandons the chunked walk and redoes its whole sequence with the token-serial
+// fp32 routine (lasad_scan.h), which applies each decay step by step.  Independent sigmoid gates
+// of logits N(m, 1) stay inside the range for m >= 0.5 (median gate 0.62: worst channel of a
+// chunk near 2^-73); at m = 0 the worst channels of a chunk straddle the limit.
 #include <stdlib.h>
 
 #include "lasad_forward_gated_common.h"
